@@ -1,0 +1,276 @@
+#!/usr/bin/env python3
+"""Decode benchmark of the multi-tenant BitDelta linear stack on one MI355X.
+
+Workload: the linears of Llama-2-7B (32 decoder layers x q,k,v,o,gate,up,down), one fp16 base model shared by
+B = 16 tenants, each tenant with its own 1-bit delta of every matrix, one decode token per tenant.  A step is
+one pass over the whole stack (224 calls of bd_linear_multitenant), i.e. B tokens decoded; every layer has its
+own weights (25.9 GB in total), so nothing is served from cache.  Deltas are produced by bd_compress from
+synthetic fine-tuned weights before the timed region (compression is offline in the paper; its rate is
+reported separately under "extras").
+
+Prints ONE JSON line: decode tokens/s, the HBM roofline of the decode kernel, and the CPU oracle timed on the
+host cores on one layer of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--tenants", type=int, default=16, help="B: tenants = decode tokens per step")
+    ap.add_argument("--layers", type=int, default=32, help="decoder layers in the stack (32 = Llama-2-7B)")
+    ap.add_argument("--model", choices=["7b", "70b"], default="7b")
+    ap.add_argument("--variant", type=int, default=0, help="kernel variant (0 = library's choice)")
+    ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
+    ap.add_argument("--no-extras", action="store_true", help="skip naive baseline, read probe, compress rate")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
+    ap.add_argument("--per-linear", action="store_true", help="also time each linear shape on its own")
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (the path has no collective); use --gpus 1. "
+              "How the path would shard over several GPUs is described in DESIGN.md.", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2402_10193_amd import binding as bd
+    from paper_2402_10193_amd import synth
+
+    if not os.path.exists(bd.LIB_PATH):
+        import __graft_entry__
+        __graft_entry__.build()
+    bd.lib()
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    B, n_layers = args.tenants, args.layers
+    shapes = synth.LLAMA2_7B_LAYER if args.model == "7b" else synth.LLAMA2_70B_LAYER
+    sigma = 0.002 if args.model == "7b" else 0.001
+    tok = synth.one_token_per_tenant(B)
+    tok_arr = bd._tok_array(tok)
+
+    # ---- build the stack: base weights + B compressed deltas per matrix, all resident in HBM
+    t_setup = time.time()
+    layers = []
+    ws = bd.new_workspace(bd.workspace_bytes(bd.OP_COMPRESS, 0, 1, 32, 1), dev)
+    compress_bytes, compress_ms = 0.0, 0.0
+    for li in range(n_layers):
+        mats = []
+        for name, out, inn in shapes:
+            base = synth.base_weight(out, inn, device=dev, tag=("L", li, name))
+            packed, alphas = [], []
+            for t in range(B):
+                ft = synth.finetuned_weight(base, sigma=sigma, tag=("L", li, name, t))
+                if li == 0:
+                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    e0.record()
+                p, a = bd.compress(base, ft, workspace=ws)
+                if li == 0:
+                    e1.record()
+                    e1.synchronize()
+                    compress_ms += e0.elapsed_time(e1)
+                    compress_bytes += out * inn * 4.125
+                packed.append(p)
+                alphas.append(a)
+                del ft
+            mats.append((name, out, inn, base, bd.TenantTable(packed, alphas)))
+        layers.append(mats)
+    xs = {inn: synth.activations(B, inn, device=dev, tag=("bench", inn)) for _, _, inn in shapes}
+    ys = {(name, out): torch.empty((B, out), dtype=torch.float16, device=dev) for name, out, _ in shapes}
+    torch.cuda.synchronize()
+    t_setup = time.time() - t_setup
+
+    def run_stack():
+        for mats in layers:
+            for name, out, inn, base, table in mats:
+                bd.linear_multitenant(xs[inn], base, table, tok, y=ys[(name, out)], variant=args.variant,
+                                      tok_array=tok_arr)
+
+    launches_per_step = n_layers * len(shapes)
+    P = sum(o * i for _, o, i in shapes)
+    xy_bytes = sum(B * (i + o) * 2 for _, o, i in shapes)
+    bytes_per_step = n_layers * (2.0 * P + B * P / 8.0 + xy_bytes)     # algorithmic: W once, each delta once, x, y
+
+    run_stack()                                   # first call sets kernel attributes; keep it out of any capture
+    torch.cuda.synchronize()
+    graph = None
+    if not args.no_graph:
+        try:
+            side = torch.cuda.Stream()
+            side.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.stream(side):
+                run_stack()
+            torch.cuda.current_stream().wait_stream(side)
+            torch.cuda.synchronize()
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph):
+                run_stack()
+        except Exception as e:   # noqa: BLE001
+            print(f"bench.py: graph capture failed ({e}); launching eagerly", file=sys.stderr)
+            graph = None
+    step = graph.replay if graph is not None else run_stack
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    wall0 = time.time()
+    e0.record()
+    for _ in range(args.steps):
+        step()
+    e1.record()
+    torch.cuda.synchronize()
+    wall = time.time() - wall0
+    ms_total = e0.elapsed_time(e1)
+    ms_per_step = ms_total / args.steps
+    tokens_per_s = B / (ms_per_step * 1e-3)
+    achieved_gbs = bytes_per_step / (ms_per_step * 1e-3) / 1e9
+
+    result = {
+        "metric": "decode tokens/s, fused fp16 base + 1-bit delta linear stack, B tenants",
+        "value": round(tokens_per_s, 2),
+        "unit": "tokens/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f16 in, f32 accumulate",
+        "data": "synthetic",
+        "config": {
+            "workload": f"llama-2-{args.model} linear stack: {n_layers} layers x (q,k,v,o,gate,up,down), "
+                        f"B={B} tenants, one decode token per tenant, distinct 1-bit delta per (tenant, matrix)",
+            "tenants": B, "layers": n_layers, "launches_per_step": launches_per_step,
+            "launch": "hip graph replay" if graph is not None else "eager",
+            "kernel_variant": args.variant,
+        },
+        "roofline": {
+            "bound": "hbm",
+            "achieved": round(achieved_gbs, 1),
+            "peak": HBM_PEAK_GBS,
+            "unit": "GB/s",
+            "frac": round(achieved_gbs / HBM_PEAK_GBS, 4),
+            "traffic": None,
+            "kernel": "linear_decode_mfma_kernel",
+            "bytes_per_launch": round(bytes_per_step / launches_per_step, 1),
+            "avg_launch_us": round(ms_per_step * 1e3 / launches_per_step, 3),
+        },
+        "wall_s_timed_region": round(wall, 4),
+        "setup_s": round(t_setup, 1),
+    }
+
+    extras = {}
+    if args.per_linear:
+        per = {}
+        for name, out, inn in [s for s in shapes if s[0] in ("q", "k", "gate", "down")]:
+            mats = [(m[3], m[4]) for L in layers for m in L if m[0] == name]
+            for base, table in mats[:2]:
+                bd.linear_multitenant(xs[inn], base, table, tok, y=ys[(name, out)], variant=args.variant, tok_array=tok_arr)
+            torch.cuda.synchronize()
+            e0.record()
+            reps = 0
+            for _ in range(4):
+                for base, table in mats:
+                    bd.linear_multitenant(xs[inn], base, table, tok, y=ys[(name, out)], variant=args.variant,
+                                          tok_array=tok_arr)
+                    reps += 1
+            e1.record()
+            e1.synchronize()
+            us = e0.elapsed_time(e1) * 1e3 / reps
+            nbytes = 2.0 * out * inn + B * out * inn / 8.0 + B * (inn + out) * 2
+            per[name] = {"us": round(us, 2), "GB/s": round(nbytes / us / 1e3, 1)}
+        extras["per_linear_eager"] = per
+
+    if not args.no_extras:
+        # (a) read ceiling: a pure 128-bit streaming read over 4 GiB
+        buf = torch.empty(1 << 30, dtype=torch.int32, device=dev)
+        buf.random_(0, 1 << 30)
+        sink = torch.zeros(4, dtype=torch.int32, device=dev)
+        bd.probe_read(buf, sink)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(5):
+            bd.probe_read(buf, sink)
+        e1.record()
+        e1.synchronize()
+        extras["read_probe_GBs"] = round(5 * buf.numel() * 4 / (e0.elapsed_time(e1) * 1e-3) / 1e9, 1)
+        del buf
+        # (b) the naive system of the paper: every tenant keeps a full fp16 copy.  One layer (B x 405 MB) timed.
+        mats0 = layers[0]
+        naive = []
+        for name, out, inn, base, table in mats0:
+            wts = [bd.materialize(base, table.packed[t], table.alpha[t:t + 1]) for t in range(B)]
+            naive.append((name, out, inn, bd.WeightTable(wts)))
+        # two copies of the layer so that the second pass does not find the first in the memory-side cache
+        naive2 = []
+        for name, out, inn, wt in naive:
+            naive2.append((name, out, inn, bd.WeightTable([w.clone() for w in wt.w])))
+
+        def run_naive(which):
+            for name, out, inn, wt in which:
+                bd.linear_naive(xs[inn], wt, tok, y=ys[(name, out)], tok_array=tok_arr)
+        run_naive(naive)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(3):
+            run_naive(naive2)
+            run_naive(naive)
+        e1.record()
+        e1.synchronize()
+        naive_ms_layer = e0.elapsed_time(e1) / 6
+        extras["naive_per_tenant_fp16"] = {
+            "ms_per_layer": round(naive_ms_layer, 4),
+            "tokens_per_s_stack": round(B / (naive_ms_layer * 1e-3 * n_layers), 2),
+            "GB/s": round(B * 2.0 * P / (naive_ms_layer * 1e-3) / 1e9, 1),
+            "bitdelta_speedup": round(naive_ms_layer / (ms_per_step / n_layers), 3),
+            "byte_ratio": round(B * 2.0 * P / (bytes_per_step / n_layers), 3),
+            "note": "one layer measured (B full fp16 copies), stack figure = x layers",
+        }
+        del naive, naive2
+        extras["compress_GBs"] = round(compress_bytes / (compress_ms * 1e-3) / 1e9, 1) if compress_ms > 0 else None
+    result["extras"] = extras
+
+    # ---- the oracle on the host cores, one layer of the same workload
+    if not args.no_cpu:
+        from oracle import ref
+        rng = np.random.default_rng(synth.DEFAULT_SEED)
+        t_cpu = 0.0
+        for name, out, inn in shapes:
+            wb = (rng.standard_normal((out, inn), dtype=np.float32) * 0.02).astype(np.float16)
+            xb = rng.standard_normal((B, inn), dtype=np.float32).astype(np.float16)
+            packed = [rng.integers(0, 2**32, size=(out, inn // 32), dtype=np.uint64).astype(np.uint32) for _ in range(B)]
+            alphas = np.full(B, 0.0016, dtype=np.float32)
+            t0 = time.time()
+            ref.linear_multitenant(xb, wb, packed, alphas, tok)
+            t_cpu += time.time() - t0
+        result["cpu_baseline"] = {
+            "value": round(B / (t_cpu * n_layers), 4),
+            "unit": "tokens/s",
+            "cores": ref.num_threads(),
+            "kind": "oracle",
+            "sample": f"1 of {n_layers} layers at full shape (7 linears, B={B}; iid weights and sign words), "
+                      f"{t_cpu:.2f} s of oracle time, stack rate = layer rate / {n_layers}",
+        }
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,161 @@
+/* bitdelta.h - C ABI of the MI355X (gfx950) BitDelta library.
+ *
+ * The library implements the data-parallel hot path of BitDelta (arxiv 2402.10193):
+ *   - the offline compressor of Sec. 3.1:  Delta = W_fine - W_base, sign bits (Eq. 1-2),
+ *     alpha = mean |Delta| (Eq. 4);
+ *   - the multi-tenant serving linear of Sec. 3.3, Eq. 6:
+ *         y_t = x_t . W_base^T + alpha_{tenant(t)} * ( x_t . Sign(Delta_{tenant(t)})^T )
+ *     for a batch of tokens that share one fp16 base matrix while each token uses the
+ *     1-bit delta of its own tenant (the batched W_INT1 A_FP16 product of Sec. 4.3).
+ *
+ * Conventions shared by every entry point
+ *   - Plain C, no exceptions.  Every call returns a bd_status; BD_OK is 0.
+ *   - Unless a parameter says HOST, pointers are DEVICE pointers owned by the caller.  The
+ *     library never allocates or frees device memory and keeps no state between calls.
+ *   - fp16 tensors are passed as uint16_t bit patterns (IEEE binary16).
+ *   - A weight matrix is [out, in] row-major: `in` (the reduction dimension) is contiguous.
+ *     `in` must be a multiple of 32, otherwise BD_ERR_SHAPE.
+ *   - Packed signs are uint32_t [out, in/32] row-major.  Bit j (least significant first) of
+ *     word w in row n is the sign of element k = 32*w + j:  1 means +1 (Delta > 0),
+ *     0 means -1 (Delta <= 0, so a zero delta is -1 as in Eq. 2; NaN also packs as 0).
+ *   - Tensor pointers must be 16-byte aligned (BD_ERR_ALIGN); rows are then aligned too.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only
+ *     enqueue work; they never synchronise.  Argument checks run on the host before anything
+ *     is enqueued, so a call that returns an error has launched nothing.
+ *   - Scratch memory comes from the caller: `workspace` must hold at least
+ *     bd_workspace_bytes(op, ...) bytes and be 256-byte aligned (BD_ERR_WORKSPACE otherwise).
+ *     It may be reused by the next call on the same stream.
+ *   - Results are deterministic: no floating-point atomics; the same inputs give the same bits.
+ */
+#ifndef BITDELTA_H
+#define BITDELTA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum bd_status {
+    BD_OK = 0,
+    BD_ERR_NULL = 1,        /* a required pointer is NULL */
+    BD_ERR_SHAPE = 2,       /* negative size, in % 32 != 0, or a size beyond the supported range */
+    BD_ERR_ALIGN = 3,       /* a tensor pointer is not 16-byte aligned */
+    BD_ERR_TENANT = 4,      /* a tenant id is outside [0, n_tenants) */
+    BD_ERR_WORKSPACE = 5,   /* workspace missing, too small or misaligned */
+    BD_ERR_DEVICE = 6,      /* the HIP runtime reported an error when enqueuing */
+    BD_ERR_UNSUPPORTED = 7, /* unknown kernel variant, or one that cannot run these sizes */
+    BD_ERR_ALIAS = 8        /* an output range overlaps an input range */
+} bd_status;
+
+typedef enum bd_op {
+    BD_OP_PACK_SIGNS = 0,
+    BD_OP_COMPRESS = 1,
+    BD_OP_LINEAR_MULTITENANT = 2
+} bd_op;
+
+/* Text for a status code (static storage, never NULL). */
+const char* bd_status_string(bd_status s);
+
+/* Library version: major*10000 + minor*100 + patch. */
+int bd_version(void);
+
+/* Bytes of workspace the given op needs for these sizes (0 if none).  Sizes that the op
+ * would reject give 0. */
+size_t bd_workspace_bytes(bd_op op, int64_t T, int64_t out, int64_t in, int32_t n_tenants);
+
+/* Eq. 2 applied to an explicit delta matrix.
+ *   delta_f16 [out, in] fp16  ->  packed [out, in/32].
+ * out == 0 or in == 0 is a no-op returning BD_OK. */
+bd_status bd_pack_signs(const uint16_t* delta_f16, int64_t out, int64_t in,
+                        uint32_t* packed, void* stream);
+
+/* The 1-bit quantiser of Sec. 3.1 for one matrix of one fine-tune.
+ *   Delta = f32(w_ft) - f32(w_base)                          (IEEE binary32)
+ *   packed <- sign bits of Delta                             (Eq. 2; equals w_ft > w_base)
+ *   *alpha <- fp16_rne( sum |Delta| / (out*in) ) as a float  (Eq. 4; the sum runs in binary64)
+ * w_base_f16, w_ft_f16: [out, in]; packed: [out, in/32]; alpha: one float on the device.
+ * Inf/NaN in the inputs propagate into alpha; they are not errors.
+ * out == 0 or in == 0: packed untouched, *alpha <- 0. */
+bd_status bd_compress(const uint16_t* w_base_f16, const uint16_t* w_ft_f16,
+                      int64_t out, int64_t in,
+                      uint32_t* packed, float* alpha,
+                      void* workspace, size_t workspace_bytes, void* stream);
+
+/* The multi-tenant linear of Eq. 6.
+ *   x_f16            [T, in]   fp16 activations, one row per token
+ *   w_base_f16       [out, in] fp16 base weight shared by every token
+ *   packed_by_tenant device array of n_tenants device pointers, each [out, in/32]
+ *   alpha_by_tenant  device array of n_tenants floats
+ *   tenant_of_token  HOST array of T ints in [0, n_tenants): which delta each token uses.
+ *                    Any order, repeats allowed; tokens of one tenant are grouped inside the
+ *                    call so that each delta is streamed once.  A tenant without a token costs
+ *                    nothing.
+ *   y_f16            [T, out]  fp16 result; must not overlap x or w_base (BD_ERR_ALIAS)
+ * Both products accumulate in binary32, alpha multiplies the finished +-1 sum in binary32 and
+ * the result is rounded once to fp16 (nearest even).
+ * T == 0 or out == 0 is a no-op returning BD_OK.  T up to 65535. */
+bd_status bd_linear_multitenant(const uint16_t* x_f16, const uint16_t* w_base_f16,
+                                const uint32_t* const* packed_by_tenant,
+                                const float* alpha_by_tenant,
+                                const int32_t* tenant_of_token,
+                                uint16_t* y_f16,
+                                int64_t T, int64_t out, int64_t in, int32_t n_tenants,
+                                void* workspace, size_t workspace_bytes, void* stream);
+
+/* Same operation with the kernel chosen by the caller instead of by the library; meant for
+ * benchmarking the kernel variants against each other.
+ *   variant 0  library's choice (identical to bd_linear_multitenant)
+ *   variant 1  plain vector-ALU kernel: one wavefront per output row, DPP reductions
+ *   variant 2+ matrix-core decode kernels (see the design notes); BD_ERR_UNSUPPORTED if the
+ *              variant cannot run these sizes. */
+bd_status bd_linear_multitenant_variant(const uint16_t* x_f16, const uint16_t* w_base_f16,
+                                        const uint32_t* const* packed_by_tenant,
+                                        const float* alpha_by_tenant,
+                                        const int32_t* tenant_of_token,
+                                        uint16_t* y_f16,
+                                        int64_t T, int64_t out, int64_t in, int32_t n_tenants,
+                                        void* workspace, size_t workspace_bytes, void* stream,
+                                        int32_t variant);
+
+/* The grouping step of the linear, exposed so that a scheduler (or a test) can see it: the
+ * tokens of one decode launch (T <= 32, all HOST arrays) sorted by tenant, stable, and cut
+ * into jobs.  A job is one tenant's run of columns inside one 16-column tile; the kernel
+ * streams a tenant's delta once per job, i.e. once per step unless a tenant's tokens straddle
+ * the tile boundary.
+ *   token_of_col[T]   column -> index into tenant_of_token
+ *   job_tenant, job_tile, job_col_begin, job_col_end: [T] each, first *n_jobs entries valid;
+ *   columns job_tile*16 + [job_col_begin, job_col_end) belong to the job.
+ * T outside 1..32 gives BD_ERR_SHAPE. */
+bd_status bd_group_tokens(const int32_t* tenant_of_token, int32_t T,
+                          int32_t* token_of_col, int32_t* job_tenant, int32_t* job_tile,
+                          int32_t* job_col_begin, int32_t* job_col_end, int32_t* n_jobs);
+
+/* ---- measurement helpers (the naive system of Sec. 4.3 and bandwidth probes) ------------- */
+
+/* w_out = fp16( f32(w_base) + alpha * s ), the full per-tenant matrix that the naive baseline
+ * of Sec. 4.3 keeps for every fine-tune.  alpha: one float on the device. */
+bd_status bd_materialize(const uint16_t* w_base_f16, const uint32_t* packed, const float* alpha,
+                         uint16_t* w_out_f16, int64_t out, int64_t in, void* stream);
+
+/* The naive forward pass of Sec. 4.3: token t is multiplied by its own tenant's full fp16
+ * matrix.  w_by_tenant: device array of n_tenants device pointers, each [out, in] fp16.
+ * tenant_of_token: HOST [T].  y_f16: [T, out]. */
+bd_status bd_linear_naive(const uint16_t* x_f16, const uint16_t* const* w_by_tenant,
+                          const int32_t* tenant_of_token, uint16_t* y_f16,
+                          int64_t T, int64_t out, int64_t in, int32_t n_tenants, void* stream);
+
+/* Streams `bytes` (a multiple of 16) from src with 128-bit loads and folds them into
+ * sink[0..3] (4 x uint32 on the device) so the loads cannot be elided: the read ceiling every
+ * bandwidth figure is also quoted against. */
+bd_status bd_probe_read(const void* src, size_t bytes, uint32_t* sink, void* stream);
+
+/* dst <- src, `bytes` a multiple of 16: a plain copy of known size, used to calibrate the
+ * profiler's HBM byte counters. */
+bd_status bd_probe_copy(void* dst, const void* src, size_t bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BITDELTA_H */

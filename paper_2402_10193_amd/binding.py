@@ -1,0 +1,254 @@
+"""Thin ctypes binding of libbitdelta.so: same names as the C ABI, argument marshalling only.
+
+PyTorch is used for device memory and streams; every step of the path runs in the library's
+kernels.  There is no CPU fallback: if the library is missing, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import List, Optional, Sequence
+
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libbitdelta.so")
+
+BD_OK = 0
+STATUS_NAMES = {0: "BD_OK", 1: "BD_ERR_NULL", 2: "BD_ERR_SHAPE", 3: "BD_ERR_ALIGN", 4: "BD_ERR_TENANT",
+                5: "BD_ERR_WORKSPACE", 6: "BD_ERR_DEVICE", 7: "BD_ERR_UNSUPPORTED", 8: "BD_ERR_ALIAS"}
+OP_PACK_SIGNS, OP_COMPRESS, OP_LINEAR_MULTITENANT = 0, 1, 2
+
+# every symbol include/bitdelta.h declares
+EXPORTS = ["bd_status_string", "bd_version", "bd_workspace_bytes", "bd_pack_signs", "bd_compress", "bd_group_tokens",
+           "bd_linear_multitenant", "bd_linear_multitenant_variant", "bd_materialize", "bd_linear_naive",
+           "bd_probe_read", "bd_probe_copy"]
+
+
+class BitDeltaError(RuntimeError):
+    def __init__(self, status: int, what: str):
+        self.status = status
+        super().__init__(f"{what}: {STATUS_NAMES.get(status, status)} ({status_string(status)})")
+
+
+_lib: Optional[ctypes.CDLL] = None
+
+
+def lib() -> ctypes.CDLL:
+    """Loads the built library; raises if it has not been built (python -m paper_2402_10193_amd.build)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(f"{LIB_PATH} is missing: run `python -m paper_2402_10193_amd.build` "
+                                    "(there is no fallback path)")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i64, i32, sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.c_size_t
+        L.bd_status_string.restype = ctypes.c_char_p
+        L.bd_status_string.argtypes = [ctypes.c_int]
+        L.bd_version.restype = ctypes.c_int
+        L.bd_version.argtypes = []
+        L.bd_workspace_bytes.restype = sz
+        L.bd_workspace_bytes.argtypes = [ctypes.c_int, i64, i64, i64, i32]
+        L.bd_pack_signs.argtypes = [vp, i64, i64, vp, vp]
+        L.bd_compress.argtypes = [vp, vp, i64, i64, vp, vp, vp, sz, vp]
+        L.bd_linear_multitenant.argtypes = [vp, vp, vp, vp, ctypes.POINTER(i32), vp, i64, i64, i64, i32, vp, sz, vp]
+        L.bd_linear_multitenant_variant.argtypes = [vp, vp, vp, vp, ctypes.POINTER(i32), vp, i64, i64, i64, i32, vp,
+                                                    sz, vp, i32]
+        pi = ctypes.POINTER(i32)
+        L.bd_group_tokens.argtypes = [pi, i32, pi, pi, pi, pi, pi, pi]
+        L.bd_group_tokens.restype = ctypes.c_int
+        L.bd_materialize.argtypes = [vp, vp, vp, vp, i64, i64, vp]
+        L.bd_linear_naive.argtypes = [vp, vp, ctypes.POINTER(i32), vp, i64, i64, i64, i32, vp]
+        L.bd_probe_read.argtypes = [vp, sz, vp, vp]
+        L.bd_probe_copy.argtypes = [vp, vp, sz, vp]
+        for name in ("bd_pack_signs", "bd_compress", "bd_linear_multitenant", "bd_linear_multitenant_variant",
+                     "bd_materialize", "bd_linear_naive", "bd_probe_read", "bd_probe_copy"):
+            getattr(L, name).restype = ctypes.c_int
+        _lib = L
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return lib().bd_status_string(int(status)).decode()
+
+
+def version() -> int:
+    return int(lib().bd_version())
+
+
+def workspace_bytes(op: int, T: int, out: int, inn: int, n_tenants: int) -> int:
+    return int(lib().bd_workspace_bytes(int(op), T, out, inn, n_tenants))
+
+
+def _stream(stream) -> int:
+    if stream is None:
+        return int(torch.cuda.current_stream().cuda_stream)
+    if isinstance(stream, torch.cuda.Stream):
+        return int(stream.cuda_stream)
+    return int(stream)
+
+
+def _ptr(t: Optional[torch.Tensor]) -> int:
+    return 0 if t is None else int(t.data_ptr())
+
+
+def _check(status: int, what: str) -> None:
+    if status != BD_OK:
+        raise BitDeltaError(status, what)
+
+
+def _dev(t: torch.Tensor, dtype, what: str) -> torch.Tensor:
+    if not t.is_cuda:
+        raise ValueError(f"{what} must be a device tensor")
+    if t.dtype != dtype:
+        raise TypeError(f"{what} must be {dtype}, got {t.dtype}")
+    if not t.is_contiguous():
+        raise ValueError(f"{what} must be contiguous")
+    return t
+
+
+def new_workspace(nbytes: int, device) -> torch.Tensor:
+    """Caller-owned scratch (torch's allocations are at least 256-byte aligned)."""
+    return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
+
+
+def pack_signs(delta: torch.Tensor, packed: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """bd_pack_signs: delta fp16 [out, in] -> packed int32 [out, in/32] (uint32 bit patterns)."""
+    _dev(delta, torch.float16, "delta")
+    out, inn = delta.shape
+    if packed is None:
+        packed = torch.empty((out, max(inn // 32, 0)), dtype=torch.int32, device=delta.device)
+    _dev(packed, torch.int32, "packed")
+    _check(lib().bd_pack_signs(_ptr(delta), out, inn, _ptr(packed), _stream(stream)), "bd_pack_signs")
+    return packed
+
+
+def compress(w_base: torch.Tensor, w_ft: torch.Tensor, packed: Optional[torch.Tensor] = None,
+             alpha: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None, stream=None):
+    """bd_compress: returns (packed int32 [out, in/32], alpha float32 [1]) on the device."""
+    _dev(w_base, torch.float16, "w_base")
+    _dev(w_ft, torch.float16, "w_ft")
+    if w_base.shape != w_ft.shape:
+        raise ValueError("w_base and w_ft differ in shape")
+    out, inn = w_base.shape
+    dev = w_base.device
+    if packed is None:
+        packed = torch.empty((out, max(inn // 32, 0)), dtype=torch.int32, device=dev)
+    if alpha is None:
+        alpha = torch.empty((1,), dtype=torch.float32, device=dev)
+    if workspace is None:
+        workspace = new_workspace(workspace_bytes(OP_COMPRESS, 0, out, inn, 1), dev)
+    _check(lib().bd_compress(_ptr(w_base), _ptr(w_ft), out, inn, _ptr(packed), _ptr(alpha), _ptr(workspace),
+                             workspace.numel(), _stream(stream)), "bd_compress")
+    return packed, alpha
+
+
+class TenantTable:
+    """Device-side arrays the linear takes: pointers to each tenant's packed delta and the scales."""
+
+    def __init__(self, packed_by_tenant: Sequence[torch.Tensor], alpha_by_tenant):
+        self.packed = list(packed_by_tenant)
+        for p in self.packed:
+            _dev(p, torch.int32, "packed delta")
+        dev = self.packed[0].device
+        self.ptrs = torch.tensor([p.data_ptr() for p in self.packed], dtype=torch.int64, device=dev)
+        if isinstance(alpha_by_tenant, torch.Tensor):
+            self.alpha = alpha_by_tenant.to(device=dev, dtype=torch.float32).reshape(-1).contiguous()
+        else:
+            self.alpha = torch.cat([a.reshape(1).to(torch.float32) for a in alpha_by_tenant]).to(dev).contiguous()
+        if self.alpha.numel() != len(self.packed):
+            raise ValueError("one alpha per tenant")
+
+    @property
+    def n_tenants(self) -> int:
+        return len(self.packed)
+
+
+def _tok_array(tenant_of_token: Sequence[int]):
+    n = len(tenant_of_token)
+    return (ctypes.c_int32 * max(n, 1))(*[int(t) for t in tenant_of_token])
+
+
+def linear_multitenant(x: torch.Tensor, w_base: torch.Tensor, tenants: TenantTable, tenant_of_token: Sequence[int],
+                       y: Optional[torch.Tensor] = None, stream=None, variant: int = 0,
+                       tok_array=None) -> torch.Tensor:
+    """bd_linear_multitenant (variant 0) or bd_linear_multitenant_variant: y fp16 [T, out]."""
+    _dev(x, torch.float16, "x")
+    _dev(w_base, torch.float16, "w_base")
+    T, inn = x.shape
+    out = w_base.shape[0]
+    if w_base.shape[1] != inn:
+        raise ValueError("x and w_base disagree on `in`")
+    if y is None:
+        y = torch.empty((T, out), dtype=torch.float16, device=x.device)
+    _dev(y, torch.float16, "y")
+    tok = tok_array if tok_array is not None else _tok_array(tenant_of_token)
+    L = lib()
+    if variant == 0:
+        st = L.bd_linear_multitenant(_ptr(x), _ptr(w_base), _ptr(tenants.ptrs), _ptr(tenants.alpha), tok, _ptr(y),
+                                     T, out, inn, tenants.n_tenants, 0, 0, _stream(stream))
+    else:
+        st = L.bd_linear_multitenant_variant(_ptr(x), _ptr(w_base), _ptr(tenants.ptrs), _ptr(tenants.alpha), tok,
+                                             _ptr(y), T, out, inn, tenants.n_tenants, 0, 0, _stream(stream),
+                                             int(variant))
+    _check(st, "bd_linear_multitenant")
+    return y
+
+
+def group_tokens(tenant_of_token: Sequence[int]):
+    """bd_group_tokens: returns (token_of_col, jobs) with jobs = [(tenant, tile, col_begin, col_end), ...]."""
+    T = len(tenant_of_token)
+    n = max(T, 1)
+    tok = _tok_array(tenant_of_token)
+    arrs = [(ctypes.c_int32 * n)() for _ in range(5)]
+    nj = ctypes.c_int32(0)
+    _check(lib().bd_group_tokens(tok, T, arrs[0], arrs[1], arrs[2], arrs[3], arrs[4], ctypes.byref(nj)),
+           "bd_group_tokens")
+    jobs = [(arrs[1][j], arrs[2][j], arrs[3][j], arrs[4][j]) for j in range(nj.value)]
+    return list(arrs[0][:T]), jobs
+
+
+def materialize(w_base: torch.Tensor, packed: torch.Tensor, alpha: torch.Tensor,
+                w_out: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    _dev(w_base, torch.float16, "w_base")
+    _dev(packed, torch.int32, "packed")
+    _dev(alpha, torch.float32, "alpha")
+    out, inn = w_base.shape
+    if w_out is None:
+        w_out = torch.empty_like(w_base)
+    _check(lib().bd_materialize(_ptr(w_base), _ptr(packed), _ptr(alpha), _ptr(w_out), out, inn, _stream(stream)),
+           "bd_materialize")
+    return w_out
+
+
+class WeightTable:
+    """Device array of pointers to full fp16 matrices, one per tenant (the naive system)."""
+
+    def __init__(self, w_by_tenant: Sequence[torch.Tensor]):
+        self.w = list(w_by_tenant)
+        for w in self.w:
+            _dev(w, torch.float16, "tenant weight")
+        self.ptrs = torch.tensor([w.data_ptr() for w in self.w], dtype=torch.int64, device=self.w[0].device)
+
+
+def linear_naive(x: torch.Tensor, weights: WeightTable, tenant_of_token: Sequence[int],
+                 y: Optional[torch.Tensor] = None, stream=None, tok_array=None) -> torch.Tensor:
+    _dev(x, torch.float16, "x")
+    T, inn = x.shape
+    out = weights.w[0].shape[0]
+    if y is None:
+        y = torch.empty((T, out), dtype=torch.float16, device=x.device)
+    tok = tok_array if tok_array is not None else _tok_array(tenant_of_token)
+    _check(lib().bd_linear_naive(_ptr(x), _ptr(weights.ptrs), tok, _ptr(y), T, out, inn, len(weights.w),
+                                 _stream(stream)), "bd_linear_naive")
+    return y
+
+
+def probe_read(buf: torch.Tensor, sink: torch.Tensor, stream=None) -> None:
+    nbytes = buf.numel() * buf.element_size()
+    _check(lib().bd_probe_read(_ptr(buf), nbytes, _ptr(sink), _stream(stream)), "bd_probe_read")
+
+
+def probe_copy(dst: torch.Tensor, src: torch.Tensor, stream=None) -> None:
+    nbytes = src.numel() * src.element_size()
+    _check(lib().bd_probe_copy(_ptr(dst), _ptr(src), nbytes, _stream(stream)), "bd_probe_copy")

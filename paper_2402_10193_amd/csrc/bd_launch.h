@@ -1,0 +1,35 @@
+// Host-side launch functions of the kernel translation units, called by the C ABI layer.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "bd_device.h"
+
+namespace bd {
+
+constexpr int kCompressMaxBlocks = 2048;   // also the number of binary64 partial sums in the workspace
+
+hipError_t launch_pack_signs(const uint16_t* delta, int64_t out, int64_t in, uint32_t* packed, hipStream_t st);
+hipError_t launch_compress(const uint16_t* base, const uint16_t* ft, int64_t out, int64_t in, uint32_t* packed,
+                           float* alpha, double* partial, hipStream_t st);
+
+// Plain vector-ALU linear: any T <= kMaxDecodeTokens per launch, tokens in caller order.
+hipError_t launch_linear_rowwave(const uint16_t* x, const uint16_t* w, const uint32_t* const* packed_by_tenant,
+                                 const float* alpha_by_tenant, const DecodeMeta& meta, uint16_t* y, int64_t out,
+                                 int64_t in, hipStream_t st);
+
+// Matrix-core decode kernel.  Returns hipErrorInvalidValue if `variant` is unknown.
+hipError_t launch_linear_decode_mfma(const uint16_t* x, const uint16_t* w, const uint32_t* const* packed_by_tenant,
+                                     const float* alpha_by_tenant, const DecodeMeta& meta, uint16_t* y, int64_t out,
+                                     int64_t in, int variant, hipStream_t st);
+bool decode_mfma_variant_known(int variant);
+
+hipError_t launch_materialize(const uint16_t* w_base, const uint32_t* packed, const float* alpha, uint16_t* w_out,
+                              int64_t out, int64_t in, hipStream_t st);
+hipError_t launch_linear_naive(const uint16_t* x, const uint16_t* const* w_by_tenant, const DecodeMeta& meta,
+                               uint16_t* y, int64_t out, int64_t in, hipStream_t st);
+hipError_t launch_probe_read(const void* src, size_t bytes, uint32_t* sink, hipStream_t st);
+hipError_t launch_probe_copy(void* dst, const void* src, size_t bytes, hipStream_t st);
+
+}  // namespace bd

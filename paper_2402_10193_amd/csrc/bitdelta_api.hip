@@ -1,0 +1,249 @@
+// C ABI of the library (include/bitdelta.h): argument checks, token grouping, kernel choice.
+// Everything here runs on the host; nothing is enqueued before the arguments have passed.
+#include "bitdelta.h"
+
+#include <algorithm>
+#include <cstring>
+
+#include "bd_launch.h"
+
+namespace {
+
+using bd::DecodeMeta;
+using bd::kMaxDecodeTokens;
+
+constexpr int kVersion = 100;   // 0.1.0
+constexpr int kVariantRowWave = 1;
+constexpr int kVariantDefaultMfma = 3;
+
+inline bool misaligned(const void* p, size_t a) { return ((uintptr_t)p & (a - 1)) != 0; }
+
+inline bool overlaps(const void* a, size_t abytes, const void* b, size_t bbytes) {
+    const uintptr_t a0 = (uintptr_t)a, b0 = (uintptr_t)b;
+    return a0 < b0 + bbytes && b0 < a0 + abytes;
+}
+
+// Tokens [t0, t0 + n) of the call -> one launch's bookkeeping: columns sorted by tenant
+// (stable), jobs = runs of equal tenant cut at the 16-column tile boundary.
+void build_meta(const int32_t* tenant_of_token, int64_t t0, int n, DecodeMeta* m) {
+    std::memset(m, 0, sizeof(*m));
+    m->T = n;
+    int order[kMaxDecodeTokens];
+    for (int i = 0; i < n; ++i) {
+        order[i] = i;
+        m->tenant_of_token[i] = tenant_of_token[t0 + i];
+    }
+    std::stable_sort(order, order + n, [&](int a, int b) { return m->tenant_of_token[a] < m->tenant_of_token[b]; });
+    int jobs = 0;
+    for (int col = 0; col < n; ++col) {
+        const int tok = order[col];
+        const int tenant = m->tenant_of_token[tok];
+        m->token_of_col[col] = (int32_t)tok;
+        const int tile = col >> 4, cin = col & 15;
+        if (jobs > 0 && m->job_tenant[jobs - 1] == tenant && m->job_tile[jobs - 1] == tile) {
+            m->job_col_end[jobs - 1] = (int32_t)(cin + 1);
+        } else {
+            m->job_tenant[jobs] = tenant;
+            m->job_tile[jobs] = (int32_t)tile;
+            m->job_col_begin[jobs] = (int32_t)cin;
+            m->job_col_end[jobs] = (int32_t)(cin + 1);
+            ++jobs;
+        }
+    }
+    m->n_jobs = jobs;
+}
+
+bd_status check_linear_args(const void* x, const void* w, const void* packed_by_tenant, const void* alpha_by_tenant,
+                            const int32_t* tenant_of_token, const void* y, int64_t T, int64_t out, int64_t in,
+                            int32_t n_tenants) {
+    if (T < 0 || out < 0 || in < 0 || n_tenants < 0 || T > 65535) return BD_ERR_SHAPE;
+    if (in % 32 != 0) return BD_ERR_SHAPE;
+    if (out > (int64_t)1 << 31 || in > (int64_t)1 << 31) return BD_ERR_SHAPE;
+    if (T == 0 || out == 0) return BD_OK;
+    if (!x || !w || !packed_by_tenant || !alpha_by_tenant || !tenant_of_token || !y) return BD_ERR_NULL;
+    if (misaligned(x, 16) || misaligned(w, 16) || misaligned(y, 16) || misaligned(packed_by_tenant, 8) ||
+        misaligned(alpha_by_tenant, 4))
+        return BD_ERR_ALIGN;
+    for (int64_t t = 0; t < T; ++t)
+        if (tenant_of_token[t] < 0 || tenant_of_token[t] >= n_tenants) return BD_ERR_TENANT;
+    const size_t ybytes = (size_t)T * out * 2;
+    if (overlaps(y, ybytes, x, (size_t)T * in * 2) || overlaps(y, ybytes, w, (size_t)out * in * 2)) return BD_ERR_ALIAS;
+    return BD_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* bd_status_string(bd_status s) {
+    switch (s) {
+        case BD_OK: return "ok";
+        case BD_ERR_NULL: return "a required pointer is NULL";
+        case BD_ERR_SHAPE: return "bad shape: negative, too large, or in not a multiple of 32";
+        case BD_ERR_ALIGN: return "a tensor pointer is not 16-byte aligned";
+        case BD_ERR_TENANT: return "tenant id outside [0, n_tenants)";
+        case BD_ERR_WORKSPACE: return "workspace missing, too small or misaligned";
+        case BD_ERR_DEVICE: return "the HIP runtime reported an error";
+        case BD_ERR_UNSUPPORTED: return "unsupported op or kernel variant for these sizes";
+        case BD_ERR_ALIAS: return "the output overlaps an input";
+    }
+    return "unknown status";
+}
+
+int bd_version(void) { return kVersion; }
+
+size_t bd_workspace_bytes(bd_op op, int64_t T, int64_t out, int64_t in, int32_t n_tenants) {
+    (void)T;
+    (void)n_tenants;
+    if (out < 0 || in < 0 || in % 32 != 0) return 0;
+    switch (op) {
+        case BD_OP_COMPRESS: return (size_t)bd::kCompressMaxBlocks * sizeof(double);
+        case BD_OP_PACK_SIGNS: return 0;
+        case BD_OP_LINEAR_MULTITENANT: return 0;
+    }
+    return 0;
+}
+
+bd_status bd_pack_signs(const uint16_t* delta_f16, int64_t out, int64_t in, uint32_t* packed, void* stream) {
+    if (out < 0 || in < 0 || in % 32 != 0) return BD_ERR_SHAPE;
+    if (out == 0 || in == 0) return BD_OK;
+    if (!delta_f16 || !packed) return BD_ERR_NULL;
+    if (misaligned(delta_f16, 16) || misaligned(packed, 16)) return BD_ERR_ALIGN;
+    if (overlaps(packed, (size_t)out * in / 8, delta_f16, (size_t)out * in * 2)) return BD_ERR_ALIAS;
+    return bd::launch_pack_signs(delta_f16, out, in, packed, (hipStream_t)stream) == hipSuccess ? BD_OK : BD_ERR_DEVICE;
+}
+
+bd_status bd_compress(const uint16_t* w_base_f16, const uint16_t* w_ft_f16, int64_t out, int64_t in, uint32_t* packed,
+                      float* alpha, void* workspace, size_t workspace_bytes, void* stream) {
+    if (out < 0 || in < 0 || in % 32 != 0) return BD_ERR_SHAPE;
+    if (!alpha) return BD_ERR_NULL;
+    if (misaligned(alpha, 4)) return BD_ERR_ALIGN;
+    const bool empty = (out == 0 || in == 0);
+    if (!empty) {
+        if (!w_base_f16 || !w_ft_f16 || !packed) return BD_ERR_NULL;
+        if (misaligned(w_base_f16, 16) || misaligned(w_ft_f16, 16) || misaligned(packed, 16)) return BD_ERR_ALIGN;
+        const size_t wbytes = (size_t)out * in * 2, pbytes = (size_t)out * in / 8;
+        if (overlaps(packed, pbytes, w_base_f16, wbytes) || overlaps(packed, pbytes, w_ft_f16, wbytes)) return BD_ERR_ALIAS;
+    }
+    const size_t need = bd_workspace_bytes(BD_OP_COMPRESS, 0, out, in, 1);
+    if (!workspace || workspace_bytes < need || misaligned(workspace, 256)) return BD_ERR_WORKSPACE;
+    return bd::launch_compress(w_base_f16, w_ft_f16, out, in, packed, alpha, (double*)workspace,
+                               (hipStream_t)stream) == hipSuccess
+               ? BD_OK
+               : BD_ERR_DEVICE;
+}
+
+bd_status bd_linear_multitenant_variant(const uint16_t* x_f16, const uint16_t* w_base_f16,
+                                        const uint32_t* const* packed_by_tenant, const float* alpha_by_tenant,
+                                        const int32_t* tenant_of_token, uint16_t* y_f16, int64_t T, int64_t out,
+                                        int64_t in, int32_t n_tenants, void* workspace, size_t workspace_bytes,
+                                        void* stream, int32_t variant) {
+    (void)workspace;
+    (void)workspace_bytes;   // this op needs none (bd_workspace_bytes returns 0)
+    const bd_status st = check_linear_args(x_f16, w_base_f16, packed_by_tenant, alpha_by_tenant, tenant_of_token, y_f16,
+                                           T, out, in, n_tenants);
+    if (st != BD_OK) return st;
+    if (variant != 0 && variant != kVariantRowWave && !bd::decode_mfma_variant_known(variant)) return BD_ERR_UNSUPPORTED;
+    if (T == 0 || out == 0) return BD_OK;
+    // 128-bit sign loads need whole, aligned 4-word groups; 32-bit lane offsets need tensors below 4 GiB
+    const bool mfma_ok = (in % 128 == 0) && in > 0 && (uint64_t)out * (uint64_t)in * 2 < ((uint64_t)1 << 32) &&
+                         (uint64_t)T * (uint64_t)in * 2 < ((uint64_t)1 << 32);
+    if (variant >= 2 && !mfma_ok) return BD_ERR_UNSUPPORTED;
+    int use = variant;
+    if (use == 0) use = mfma_ok ? kVariantDefaultMfma : kVariantRowWave;
+
+    hipStream_t hs = (hipStream_t)stream;
+    for (int64_t t0 = 0; t0 < T; t0 += kMaxDecodeTokens) {
+        const int n = (int)std::min<int64_t>(kMaxDecodeTokens, T - t0);
+        DecodeMeta meta;
+        build_meta(tenant_of_token, t0, n, &meta);
+        const uint16_t* xs = x_f16 + t0 * in;
+        uint16_t* ys = y_f16 + t0 * out;
+        hipError_t e;
+        if (in == 0) {
+            // empty reduction: y = 0.  The row-wave kernel handles it (its loop body never runs).
+            e = bd::launch_linear_rowwave(xs, w_base_f16, packed_by_tenant, alpha_by_tenant, meta, ys, out, in, hs);
+        } else if (use == kVariantRowWave) {
+            e = bd::launch_linear_rowwave(xs, w_base_f16, packed_by_tenant, alpha_by_tenant, meta, ys, out, in, hs);
+        } else {
+            e = bd::launch_linear_decode_mfma(xs, w_base_f16, packed_by_tenant, alpha_by_tenant, meta, ys, out, in, use, hs);
+        }
+        if (e != hipSuccess) return BD_ERR_DEVICE;
+    }
+    return BD_OK;
+}
+
+bd_status bd_linear_multitenant(const uint16_t* x_f16, const uint16_t* w_base_f16,
+                                const uint32_t* const* packed_by_tenant, const float* alpha_by_tenant,
+                                const int32_t* tenant_of_token, uint16_t* y_f16, int64_t T, int64_t out, int64_t in,
+                                int32_t n_tenants, void* workspace, size_t workspace_bytes, void* stream) {
+    return bd_linear_multitenant_variant(x_f16, w_base_f16, packed_by_tenant, alpha_by_tenant, tenant_of_token, y_f16, T,
+                                         out, in, n_tenants, workspace, workspace_bytes, stream, 0);
+}
+
+bd_status bd_group_tokens(const int32_t* tenant_of_token, int32_t T, int32_t* token_of_col, int32_t* job_tenant,
+                          int32_t* job_tile, int32_t* job_col_begin, int32_t* job_col_end, int32_t* n_jobs) {
+    if (T < 1 || T > kMaxDecodeTokens) return BD_ERR_SHAPE;
+    if (!tenant_of_token || !token_of_col || !job_tenant || !job_tile || !job_col_begin || !job_col_end || !n_jobs)
+        return BD_ERR_NULL;
+    DecodeMeta m;
+    build_meta(tenant_of_token, 0, T, &m);
+    for (int i = 0; i < T; ++i) token_of_col[i] = m.token_of_col[i];
+    for (int j = 0; j < m.n_jobs; ++j) {
+        job_tenant[j] = m.job_tenant[j];
+        job_tile[j] = m.job_tile[j];
+        job_col_begin[j] = m.job_col_begin[j];
+        job_col_end[j] = m.job_col_end[j];
+    }
+    *n_jobs = m.n_jobs;
+    return BD_OK;
+}
+
+bd_status bd_materialize(const uint16_t* w_base_f16, const uint32_t* packed, const float* alpha, uint16_t* w_out_f16,
+                         int64_t out, int64_t in, void* stream) {
+    if (out < 0 || in < 0 || in % 32 != 0) return BD_ERR_SHAPE;
+    if (out == 0 || in == 0) return BD_OK;
+    if (!w_base_f16 || !packed || !alpha || !w_out_f16) return BD_ERR_NULL;
+    if (misaligned(w_base_f16, 16) || misaligned(packed, 16) || misaligned(w_out_f16, 16)) return BD_ERR_ALIGN;
+    return bd::launch_materialize(w_base_f16, packed, alpha, w_out_f16, out, in, (hipStream_t)stream) == hipSuccess
+               ? BD_OK
+               : BD_ERR_DEVICE;
+}
+
+bd_status bd_linear_naive(const uint16_t* x_f16, const uint16_t* const* w_by_tenant, const int32_t* tenant_of_token,
+                          uint16_t* y_f16, int64_t T, int64_t out, int64_t in, int32_t n_tenants, void* stream) {
+    if (T < 0 || out < 0 || in < 0 || n_tenants < 0 || in % 8 != 0 || T > 65535) return BD_ERR_SHAPE;
+    if (T == 0 || out == 0) return BD_OK;
+    if (!x_f16 || !w_by_tenant || !tenant_of_token || !y_f16) return BD_ERR_NULL;
+    if (misaligned(x_f16, 16) || misaligned(y_f16, 2)) return BD_ERR_ALIGN;
+    for (int64_t t = 0; t < T; ++t)
+        if (tenant_of_token[t] < 0 || tenant_of_token[t] >= n_tenants) return BD_ERR_TENANT;
+    for (int64_t t0 = 0; t0 < T; t0 += kMaxDecodeTokens) {
+        const int n = (int)std::min<int64_t>(kMaxDecodeTokens, T - t0);
+        DecodeMeta meta;
+        build_meta(tenant_of_token, t0, n, &meta);
+        if (bd::launch_linear_naive(x_f16 + t0 * in, w_by_tenant, meta, y_f16 + t0 * out, out, in,
+                                    (hipStream_t)stream) != hipSuccess)
+            return BD_ERR_DEVICE;
+    }
+    return BD_OK;
+}
+
+bd_status bd_probe_read(const void* src, size_t bytes, uint32_t* sink, void* stream) {
+    if (bytes % 16 != 0) return BD_ERR_SHAPE;
+    if (bytes == 0) return BD_OK;
+    if (!src || !sink) return BD_ERR_NULL;
+    if (misaligned(src, 16) || misaligned(sink, 4)) return BD_ERR_ALIGN;
+    return bd::launch_probe_read(src, bytes, sink, (hipStream_t)stream) == hipSuccess ? BD_OK : BD_ERR_DEVICE;
+}
+
+bd_status bd_probe_copy(void* dst, const void* src, size_t bytes, void* stream) {
+    if (bytes % 16 != 0) return BD_ERR_SHAPE;
+    if (bytes == 0) return BD_OK;
+    if (!dst || !src) return BD_ERR_NULL;
+    if (misaligned(src, 16) || misaligned(dst, 16)) return BD_ERR_ALIGN;
+    if (overlaps(dst, bytes, src, bytes)) return BD_ERR_ALIAS;
+    return bd::launch_probe_copy(dst, src, bytes, (hipStream_t)stream) == hipSuccess ? BD_OK : BD_ERR_DEVICE;
+}
+
+}  // extern "C"

@@ -1,0 +1,124 @@
+// Offline compressor kernels (Sec. 3.1 of the paper): delta, sign bits (Eq. 2), mean |delta| (Eq. 4).
+//
+// Both kernels are pure streams: every lane reads 8 consecutive fp16 (one 128-bit load per
+// matrix), forms one byte of sign bits, and four neighbouring lanes merge their bytes into one
+// uint32 word with two cross-lane ORs.  HBM traffic is 4 B read + 1/8 B written per element for
+// the compressor, 2 B + 1/8 B for the packer.
+#include "bd_device.h"
+#include "bd_launch.h"
+
+namespace bd {
+
+constexpr int kCompressThreads = 256;
+
+__device__ __forceinline__ uint32_t merge_quad_bytes(uint32_t byte, int lane) {
+    uint32_t v = byte << (8 * (lane & 3));
+    v |= __shfl_xor(v, 1, kWave);
+    v |= __shfl_xor(v, 2, kWave);
+    return v;
+}
+
+// delta [n_vec * 8] fp16 -> packed [n_vec / 4] words.  n_vec is a multiple of 4.
+__global__ __launch_bounds__(kCompressThreads) void pack_signs_kernel(
+    const u32x4* __restrict__ delta, uint32_t* __restrict__ packed, int64_t n_vec) {
+    const int lane = threadIdx.x & (kWave - 1);
+    const int64_t stride = (int64_t)gridDim.x * kCompressThreads;
+    for (int64_t i = (int64_t)blockIdx.x * kCompressThreads + threadIdx.x; i < n_vec; i += stride) {
+        const u32x4 d = __builtin_nontemporal_load(delta + i);
+        const uint32_t w[4] = {d[0], d[1], d[2], d[3]};
+        uint32_t byte = 0;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const float v = h2f((uint16_t)(w[e >> 1] >> (16 * (e & 1))));
+            byte |= (v > 0.0f ? 1u : 0u) << e;
+        }
+        const uint32_t word = merge_quad_bytes(byte, lane);
+        if ((lane & 3) == 0) packed[i >> 2] = word;
+    }
+}
+
+// base, ft [n_vec * 8] fp16 -> packed [n_vec / 4], partial[gridDim.x] = this block's sum |delta|.
+__global__ __launch_bounds__(kCompressThreads) void compress_kernel(
+    const u32x4* __restrict__ base, const u32x4* __restrict__ ft, uint32_t* __restrict__ packed,
+    double* __restrict__ partial, int64_t n_vec) {
+    __shared__ double wave_part[kCompressThreads / kWave];
+    const int lane = threadIdx.x & (kWave - 1);
+    const int64_t stride = (int64_t)gridDim.x * kCompressThreads;
+    double s = 0.0;
+    for (int64_t i = (int64_t)blockIdx.x * kCompressThreads + threadIdx.x; i < n_vec; i += stride) {
+        const u32x4 b = __builtin_nontemporal_load(base + i);
+        const u32x4 f = __builtin_nontemporal_load(ft + i);
+        const uint32_t bw[4] = {b[0], b[1], b[2], b[3]};
+        const uint32_t fw[4] = {f[0], f[1], f[2], f[3]};
+        uint32_t byte = 0;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const float vb = h2f((uint16_t)(bw[e >> 1] >> (16 * (e & 1))));
+            const float vf = h2f((uint16_t)(fw[e >> 1] >> (16 * (e & 1))));
+            const float d = vf - vb;                // the delta of Sec. 3.1, IEEE binary32
+            byte |= (d > 0.0f ? 1u : 0u) << e;      // Eq. 2: +1 only for d > 0
+            s += (double)__builtin_fabsf(d);
+        }
+        const uint32_t word = merge_quad_bytes(byte, lane);
+        if ((lane & 3) == 0) packed[i >> 2] = word;
+    }
+    s = wave_sum(s);
+    if (lane == 0) wave_part[threadIdx.x / kWave] = s;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        double t = 0.0;
+#pragma unroll
+        for (int w = 0; w < kCompressThreads / kWave; ++w) t += wave_part[w];
+        partial[blockIdx.x] = t;
+    }
+}
+
+// alpha = fp16_rne( sum(partial) / count ), one block, fixed summation order.
+__global__ __launch_bounds__(256) void alpha_finalize_kernel(const double* __restrict__ partial, int n_partial,
+                                                             double count, float* __restrict__ alpha) {
+    __shared__ double sm[256];
+    double t = 0.0;
+    for (int i = threadIdx.x; i < n_partial; i += 256) t += partial[i];
+    sm[threadIdx.x] = t;
+    __syncthreads();
+    for (int w = 128; w >= 1; w >>= 1) {
+        if ((int)threadIdx.x < w) sm[threadIdx.x] += sm[threadIdx.x + w];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) {
+        const double mean = count > 0.0 ? sm[0] / count : 0.0;
+        const float m32 = (float)mean;
+        *alpha = (float)(_Float16)m32;   // one rounding to fp16, carried as a float
+    }
+}
+
+int compress_grid_blocks(int64_t n_vec) {
+    // enough blocks to fill 256 CUs several times over, few enough that the partial sums stay tiny
+    const int64_t want = (n_vec + kCompressThreads - 1) / kCompressThreads;
+    return (int)(want < 1 ? 1 : (want > kCompressMaxBlocks ? kCompressMaxBlocks : want));
+}
+
+hipError_t launch_pack_signs(const uint16_t* delta, int64_t out, int64_t in, uint32_t* packed, hipStream_t st) {
+    const int64_t n_vec = out * in / 8;
+    hipLaunchKernelGGL(pack_signs_kernel, dim3(compress_grid_blocks(n_vec)), dim3(kCompressThreads), 0, st,
+                       (const u32x4*)delta, packed, n_vec);
+    return hipGetLastError();
+}
+
+hipError_t launch_compress(const uint16_t* base, const uint16_t* ft, int64_t out, int64_t in, uint32_t* packed,
+                           float* alpha, double* partial, hipStream_t st) {
+    const int64_t n_vec = out * in / 8;
+    int blocks = 0;
+    if (n_vec > 0) {
+        blocks = compress_grid_blocks(n_vec);
+        hipLaunchKernelGGL(compress_kernel, dim3(blocks), dim3(kCompressThreads), 0, st, (const u32x4*)base,
+                           (const u32x4*)ft, packed, partial, n_vec);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL(alpha_finalize_kernel, dim3(1), dim3(256), 0, st, (const double*)partial, blocks,
+                       (double)out * (double)in, alpha);
+    return hipGetLastError();
+}
+
+}  // namespace bd

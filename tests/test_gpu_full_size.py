@@ -1,0 +1,80 @@
+"""GPU parity at the benchmark's full sizes (Llama-2-7B and 70B layer shapes), in the launch configuration
+bench.py times.  The 7B layer is compared in full; the 70B matrices on sampled output rows, which the oracle
+computes one by one (rows of a linear are independent, so a row slice of W and of the packed deltas is a
+complete problem)."""
+import numpy as np
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+from paper_2402_10193_amd import binding as bd   # noqa: E402
+from paper_2402_10193_amd import synth           # noqa: E402
+from gpu_util import check_close, packed_to_np, to_np   # noqa: E402
+
+DEV = "cuda"
+
+
+def _gpu_layer(out, inn, B, sigma, tag):
+    base = synth.base_weight(out, inn, device=DEV, tag=(tag, "base"))
+    ws = bd.new_workspace(bd.workspace_bytes(bd.OP_COMPRESS, 0, out, inn, 1), DEV)
+    packed, alphas, fts = [], [], []
+    for t in range(B):
+        ft = synth.finetuned_weight(base, sigma=sigma, tag=(tag, t))
+        p, a = bd.compress(base, ft, workspace=ws)
+        packed.append(p)
+        alphas.append(a)
+        fts.append(ft)
+    return base, fts, bd.TenantTable(packed, alphas)
+
+
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("name,out,inn", [("q", 4096, 4096), ("gate", 11008, 4096), ("down", 4096, 11008)])
+def test_llama2_7b_layer_b16_full_output(ref, name, out, inn):
+    B = 16
+    print(f"7B {name} {out}x{inn} B={B}", flush=True)
+    base, fts, table = _gpu_layer(out, inn, B, 0.002, ("7b", name))
+    x = synth.activations(B, inn, device=DEV, tag=("7b", name))
+    tok = synth.one_token_per_tenant(B)
+    y = bd.linear_multitenant(x, base, table, tok)
+    torch.cuda.synchronize()
+    base_np = to_np(base)
+    refc = []
+    for t in range(B):
+        p, a, _ = ref.compress(base_np, to_np(fts[t]))
+        assert np.array_equal(packed_to_np(table.packed[t]), p)          # full-size compression parity, bit-exact
+        assert float(table.alpha[t].item()) == a
+        refc.append((p, a))
+    del fts
+    _, y32 = ref.linear_multitenant(to_np(x), base_np, [c[0] for c in refc], [c[1] for c in refc], tok)
+    err = check_close(y, y32, f"7B {name}")
+    print(f"   max rel err {err:.2e}", flush=True)
+
+
+@pytest.mark.timeout(900)
+@pytest.mark.parametrize("name,out,inn", [("kv", 1024, 8192), ("gate", 28672, 8192), ("down", 8192, 28672)])
+def test_llama2_70b_b32_sampled_rows(ref, name, out, inn):
+    B, n_rows = 32, 256
+    print(f"70B {name} {out}x{inn} B={B}", flush=True)
+    base, fts, table = _gpu_layer(out, inn, B, 0.001, ("70b", name))
+    x = synth.activations(B, inn, device=DEV, tag=("70b", name))
+    tok = synth.one_token_per_tenant(B)
+    y = bd.linear_multitenant(x, base, table, tok)
+    torch.cuda.synchronize()
+    g = torch.Generator().manual_seed(7)
+    rows = torch.sort(torch.randperm(out, generator=g)[:n_rows]).values
+    rows[0], rows[-1] = 0, out - 1
+    rows_d = rows.to(DEV)
+    base_full = to_np(base)
+    refc, alphas = [], []
+    for t in range(B):
+        p, a, _ = ref.compress(base_full, to_np(fts[t]))                   # oracle compression of the full matrix
+        assert np.array_equal(packed_to_np(table.packed[t]), p)
+        assert float(table.alpha[t].item()) == a
+        refc.append(np.ascontiguousarray(p[rows.numpy()]))
+        alphas.append(a)
+        fts[t] = None
+    base_np = np.ascontiguousarray(base_full[rows.numpy()])
+    _, y32 = ref.linear_multitenant(to_np(x), base_np, refc, alphas, tok)
+    err = check_close(y[:, rows_d], y32, f"70B {name}")
+    print(f"   max rel err {err:.2e}", flush=True)

@@ -1,0 +1,132 @@
+"""CPU-side checks of the C-ABI library: it loads, exports every declared symbol, and rejects bad
+arguments on the host before anything is enqueued (no GPU needed, no compute call is made)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def bd():
+    from paper_2402_10193_amd import binding
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2402_10193_amd import build
+        build.build_library()
+    binding.lib()
+    return binding
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "bitdelta.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(bd_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol(bd):
+    names = _declared_functions()
+    assert set(names) == set(bd.EXPORTS)
+    L = bd.lib()
+    for n in names:
+        assert hasattr(L, n), n
+
+
+def test_version_and_status_strings(bd):
+    assert bd.version() >= 100
+    seen = set()
+    for code in range(9):
+        s = bd.status_string(code)
+        assert s and s not in seen
+        seen.add(s)
+    assert bd.status_string(99) == "unknown status"
+
+
+def test_workspace_bytes(bd):
+    assert bd.workspace_bytes(bd.OP_COMPRESS, 0, 4096, 4096, 1) >= 2048 * 8
+    assert bd.workspace_bytes(bd.OP_LINEAR_MULTITENANT, 16, 4096, 4096, 16) == 0
+    assert bd.workspace_bytes(bd.OP_PACK_SIGNS, 0, 4096, 4096, 1) == 0
+    assert bd.workspace_bytes(bd.OP_COMPRESS, 0, 4096, 4100, 1) == 0   # rejected shape
+
+
+def _tok(*ids):
+    return (ctypes.c_int32 * max(len(ids), 1))(*ids)
+
+
+A = 0x10000  # a fake, 16-byte aligned, never dereferenced device address
+
+
+def test_linear_argument_errors_are_caught_on_the_host(bd):
+    L = bd.lib()
+    f = L.bd_linear_multitenant
+    ok_args = dict(x=A, w=2 * A, pk=3 * A, al=4 * A, tok=_tok(0), y=5 * A, T=1, out=16, inn=128, nt=1)
+
+    def call(**kw):
+        a = dict(ok_args, **kw)
+        return f(a["x"], a["w"], a["pk"], a["al"], a["tok"], a["y"], a["T"], a["out"], a["inn"], a["nt"], 0, 0, 0)
+
+    assert call(inn=48) == 2 and call(T=-1) == 2 and call(out=-1) == 2 and call(T=70000) == 2
+    assert call(x=0) == 1 and call(w=0) == 1 and call(pk=0) == 1 and call(al=0) == 1 and call(y=0) == 1
+    assert call(x=A + 2) == 3 and call(w=2 * A + 8) == 3 and call(y=5 * A + 4) == 3
+    assert call(tok=_tok(1)) == 4 and call(tok=_tok(-1)) == 4 and call(tok=_tok(0, 0, 5), T=3, nt=5) == 4
+    assert call(y=A) == 8 and call(y=2 * A + 64) == 8            # y overlapping x / w
+    # no-ops succeed without touching any pointer
+    assert call(T=0, x=0, y=0) == 0 and call(out=0, w=0, y=0) == 0
+    # unknown kernel variant, and a matrix-core variant on a shape it cannot run
+    fv = L.bd_linear_multitenant_variant
+    assert fv(A, 2 * A, 3 * A, 4 * A, _tok(0), 5 * A, 1, 16, 128, 1, 0, 0, 0, 99) == 7
+    assert fv(A, 2 * A, 3 * A, 4 * A, _tok(0), 5 * A, 1, 16, 96, 1, 0, 0, 0, 3) == 7
+
+
+def test_compress_and_pack_argument_errors(bd):
+    L = bd.lib()
+    need = bd.workspace_bytes(bd.OP_COMPRESS, 0, 16, 128, 1)
+    c = L.bd_compress
+    assert c(A, 2 * A, 16, 100, 3 * A, 4 * A, 5 * A, need, 0) == 2
+    assert c(0, 2 * A, 16, 128, 3 * A, 4 * A, 5 * A, need, 0) == 1
+    assert c(A, 2 * A, 16, 128, 3 * A, 0, 5 * A, need, 0) == 1
+    assert c(A + 4, 2 * A, 16, 128, 3 * A, 4 * A, 5 * A, need, 0) == 3
+    assert c(A, 2 * A, 16, 128, 3 * A, 4 * A, 0, need, 0) == 5
+    assert c(A, 2 * A, 16, 128, 3 * A, 4 * A, 5 * A, need - 1, 0) == 5
+    assert c(A, 2 * A, 16, 128, 3 * A, 4 * A, 5 * A + 16, need, 0) == 5
+    assert c(A, 2 * A, 16, 128, A + 1024, 4 * A, 5 * A, need, 0) == 8
+    p = L.bd_pack_signs
+    assert p(A, 16, 40, 2 * A, 0) == 2 and p(0, 16, 64, 2 * A, 0) == 1 and p(A, 16, 64, 2 * A + 4, 0) == 3
+    assert p(0, 0, 64, 0, 0) == 0
+    assert L.bd_probe_read(A, 24, 2 * A, 0) == 2 and L.bd_probe_copy(A, A + 16, 64, 0) == 8
+    assert L.bd_linear_naive(A, 2 * A, _tok(3), 3 * A, 1, 16, 64, 2, 0) == 4
+    assert L.bd_materialize(A, 2 * A, 0, 3 * A, 16, 64, 0) == 1
+
+
+def test_group_tokens_sorts_stably_and_cuts_jobs_at_the_tile_boundary(bd):
+    import random
+    rng = random.Random(5)
+    for T in [1, 2, 5, 16, 17, 31, 32]:
+        for n_tenants in [1, 3, 40]:
+            tok = [rng.randrange(n_tenants) for _ in range(T)]
+            cols, jobs = bd.group_tokens(tok)
+            assert sorted(cols) == list(range(T))                      # a permutation
+            keys = [(tok[t], t) for t in cols]
+            assert keys == sorted(keys)                                # sorted by tenant, stable
+            covered = []
+            for tenant, tile, cb, ce in jobs:
+                assert 0 <= cb < ce <= 16 and tile in (0, 1)
+                for c in range(cb, ce):
+                    assert tok[cols[tile * 16 + c]] == tenant
+                    covered.append(tile * 16 + c)
+            assert covered == list(range(T))                           # every column in exactly one job, in order
+            per_tile = {}
+            for tenant, tile, _, _ in jobs:
+                assert (tenant, tile) not in per_tile                  # a delta is streamed once per tile
+                per_tile[(tenant, tile)] = True
+            assert len(jobs) <= len(set(tok)) + 1                      # at most one tenant straddles the boundary
+    assert bd.lib().bd_group_tokens(_tok(0), 0, _tok(0), _tok(0), _tok(0), _tok(0), _tok(0), _tok(0)) == 2
+    assert bd.lib().bd_group_tokens(_tok(0), 33, _tok(0), _tok(0), _tok(0), _tok(0), _tok(0), _tok(0)) == 2
+
+
+def test_loading_fails_loudly_without_the_library(bd, tmp_path, monkeypatch):
+    monkeypatch.setattr(bd, "_lib", None)
+    monkeypatch.setattr(bd, "LIB_PATH", str(tmp_path / "nope.so"))
+    with pytest.raises(FileNotFoundError):
+        bd.lib()
