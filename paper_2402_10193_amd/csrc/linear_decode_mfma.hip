@@ -15,19 +15,20 @@
 // order k is visited, every operand is loaded in the layout its memory wants:
 //   base   lane (r,g), slice v: W[n0+r][k0 + 32v + 8g .. +8]   (64 contiguous bytes per row and load)
 //   signs  lane (r,g): the four words covering k0 + 128g .. +128 of row n0+r (one 128-bit load)
-//   x      staged once per step and wavefront in LDS, read back in either order.
+//   x      staged once per step and wavefront in LDS (direct global->LDS loads), read back in either order.
 // A delta "job" is one tenant's run of columns in a tile; its MFMA result is only valid in
 // those columns, which are selected once per pass.  Jobs are processed in passes of 8/4/2/1 so
 // that every pass is straight-line code.  Partial sums of the wavefronts are added in a fixed
 // order through LDS, so results are deterministic and y is written exactly once.
+#include <type_traits>
+
 #include "bd_device.h"
 #include "bd_launch.h"
 
 namespace bd {
 
 constexpr int kStepK = 512;            // reduction elements one wavefront consumes per step
-constexpr int kXsBlockBytes = 264;     // 128 fp16 of one column + 8 B pad (2 banks)
-constexpr int kXsRowBytes = 1072;      // 4 blocks + 16 B pad: row stride = 4 * odd banks
+constexpr int kXsRowBytes = 1040;      // 512 fp16 of one column + 16 B pad: row stride = 4 * odd banks
 constexpr int kXsWaveBytes = 16 * kXsRowBytes;
 constexpr int kMaxWaves = 8;
 
@@ -118,6 +119,10 @@ __device__ __forceinline__ half8 as_half8(uint32_t a, uint32_t b, uint32_t c, ui
     return __builtin_bit_cast(half8, v);
 }
 
+// s_waitcnt immediate that waits only for the vector-memory counter (gfx9 encoding: vmcnt in
+// bits 3:0 and 15:14, expcnt 6:4 and lgkmcnt 11:8 left at "no wait").
+__device__ __forceinline__ constexpr int vmcnt_only(int n) { return (n & 0xF) | ((n >> 4) << 14) | (0x7 << 4) | (0xF << 8); }
+
 __device__ __forceinline__ void lds_wave_sync() {
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
@@ -126,181 +131,131 @@ __device__ __forceinline__ void lds_wave_sync() {
 
 // All global loads are "uniform 64-bit base + 32-bit lane offset", the form that needs one
 // address register per lane; the host guarantees every tensor is below 4 GiB.
-__device__ __forceinline__ u32x4 load16(const void* base, uint32_t lane_off) {
-    return *(const u32x4*)((const unsigned char*)base + lane_off);
-}
 __device__ __forceinline__ u32x4 load16_stream(const void* base, uint32_t lane_off) {
     return __builtin_nontemporal_load((const u32x4*)((const unsigned char*)base + lane_off));
 }
+
+typedef const void __attribute__((address_space(1)))* gptr_t;
+typedef void __attribute__((address_space(3)))* lptr_t;
 
 struct LaneCtx {
     const uint16_t* x;
     const uint16_t* w;
     const uint32_t* const* packed_by_tenant;
-    int64_t in;
+    int in;                                // reduction length (below 2^31)
     uint32_t woff;                         // byte offset of W[row][8 g]
     uint32_t soff;                         // byte offset of packed[row][4 g]
     uint32_t xoff;                         // byte offset 16 * lane inside a 512-element chunk of x
-    unsigned char* xs;                     // this wavefront's LDS region
-    unsigned char* xs_wr;                  // + column * kXsRowBytes
-    const unsigned char* xs_base_rd;       // + (v/4)*264 + (v%4)*64
-    const unsigned char* xs_delta_rd;      // + u*64 + m*8 (+32)
-    int g, wave, n_waves, n_steps, n_tiles;
+    unsigned char* xs;                     // this wavefront's LDS region: [16 columns][kXsRowBytes]
+    const unsigned char* xs_base_rd;       // + 64 v
+    const unsigned char* xs_delta_rd;      // + 64 u + 8 m (+32)
+    int lane, g, wave, n_waves, n_steps;
 };
 
-// x of one column tile, 512 reduction elements from k0 -> this wavefront's LDS region.
-// Two batches of eight columns keep the transient registers at 32.  Columns beyond T and
-// elements beyond `in` are written as zeros, so whatever the weight registers hold there
-// multiplies zero.
-__device__ __forceinline__ void stage_x(const LaneCtx& cx, const DecodeMeta& meta, int tile, int64_t k0, bool full,
-                                        uint32_t xoff) {
-    const bool kvalid = full || (k0 + (xoff >> 1) < cx.in);
+// x of one column tile, 512 reduction elements from k0 -> this wavefront's LDS region, by
+// direct global->LDS loads (no registers; lane l's 16 bytes land at row + 16 l).  Rows of
+// columns beyond T are never written and stay zero from the start of the kernel; elements
+// beyond `in` are written as zeros, so whatever the weight registers hold there multiplies 0.
+template <bool FULL>
+__device__ __forceinline__ void stage_x(const LaneCtx& cx, const DecodeMeta& meta, int tile, int k0, uint32_t xoff) {
+    const bool kvalid = FULL || (k0 + (int)(xoff >> 1) < cx.in);
 #pragma unroll
-    for (int half = 0; half < 2; ++half) {
-        u32x4 v[8];
-#pragma unroll
-        for (int c = 0; c < 8; ++c) {
-            const int col = tile * 16 + half * 8 + c;
-            v[c] = u32x4{0u, 0u, 0u, 0u};
-            if (col < meta.T) {
-                const uint16_t* colbase = cx.x + (int64_t)meta.token_of_col[col] * cx.in + k0;
-                if (kvalid) v[c] = load16(colbase, xoff);
+    for (int c = 0; c < 16; ++c) {
+        const int col = tile * 16 + c;
+        if (col < meta.T) {
+            const unsigned char* colbase = (const unsigned char*)(cx.x + (int64_t)meta.token_of_col[col] * cx.in + k0);
+            unsigned char* row = cx.xs + c * kXsRowBytes;
+            if constexpr (FULL) {
+                __builtin_amdgcn_global_load_lds((gptr_t)(colbase + xoff), (lptr_t)row, 16, 0, 0);
+            } else {
+                if (kvalid) __builtin_amdgcn_global_load_lds((gptr_t)(colbase + xoff), (lptr_t)row, 16, 0, 0);
+                else *(u32x4*)(row + xoff) = u32x4{0u, 0u, 0u, 0u};
             }
         }
-#pragma unroll
-        for (int c = 0; c < 8; ++c) *(u32x4*)(cx.xs_wr + (half * 8 + c) * kXsRowBytes) = v[c];
-        __builtin_amdgcn_sched_barrier(0);
     }
 }
 
-// One pass: JP delta jobs of column tile `tile` over all of this wavefront's steps.  A BASE
-// pass also streams W (once per call) and builds the base product of tile 0, and of tile 1
-// when there is one.  In mantissa mode every pass rebuilds the H term of its tile (one MFMA
-// per slice, the same value each time), which keeps the pass free of flags.
-template <int JP, int MODE, bool BASE>
-__device__ __forceinline__ void run_pass(const LaneCtx& cx, const DecodeMeta& meta, const ExpandConsts<MODE>& kc,
-                                         int tile, int job0, float4v (&accb)[2], float4v& accb1, float4v& acch,
-                                         float4v (&acc)[JP]) {
-    const uint32_t* sptr[JP];
-#pragma unroll
-    for (int j = 0; j < JP; ++j) {
-        acc[j] = float4v{0.f, 0.f, 0.f, 0.f};
-        sptr[j] = cx.packed_by_tenant[meta.job_tenant[job0 + j]];
+// The JG delta jobs [job0, job0 + JG) of one step: expand their sign words and multiply them
+// with the staged x.  Slots at or beyond job_end are padding (they re-read the first job's
+// words and are never selected).  On return `sel` holds, per lane, the partial sum of the job
+// that owns the lane's column (unchanged if none of these jobs does).
+// The B operand (x) of delta slice (u, m): elements (4m+q, 4m+q+16), q = 0..3, of word u of
+// this lane's 128-element block, as four fp16 pairs.
+struct DeltaB {
+    u32x2 lo, hi;
+    __device__ __forceinline__ void read(const LaneCtx& cx, int u, int m) {
+        lo = *(const u32x2*)(cx.xs_delta_rd + u * 64 + m * 8);
+        hi = *(const u32x2*)(cx.xs_delta_rd + u * 64 + m * 8 + 32);
     }
-    acch = float4v{0.f, 0.f, 0.f, 0.f};
-    for (int step = cx.wave; step < cx.n_steps; step += cx.n_waves) {
-        const int64_t k0 = (int64_t)step * kStepK;
-        const bool full = k0 + kStepK <= cx.in;
-        // Lane offsets are re-read through an empty asm every step: otherwise the compiler hoists
-        // "uniform base + lane offset" of every load out of the loop as 64-bit register pairs.
-        uint32_t woff = cx.woff, soff = cx.soff, xoff = cx.xoff;
-        asm volatile("" : "+v"(woff), "+v"(soff), "+v"(xoff));
-        // ---- long-latency loads first: base slices and sign words
-        u32x4 wreg[BASE ? 16 : 1];
-        if constexpr (BASE) {
-            const uint16_t* wk = cx.w + k0;
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                wreg[v] = u32x4{0u, 0u, 0u, 0u};
-                if (full || k0 + 32 * v < cx.in) wreg[v] = load16_stream(wk + 32 * v, woff);
-            }
-        }
-        u32x4 sreg[JP];
-        const bool svalid = full || (k0 + 128 * cx.g < cx.in);
-#pragma unroll
-        for (int j = 0; j < JP; ++j) {
-            sreg[j] = u32x4{0u, 0u, 0u, 0u};
-            if (svalid) sreg[j] = load16_stream(sptr[j] + (k0 >> 5), soff);
-        }
-        __builtin_amdgcn_sched_barrier(0);
-        // ---- x of this tile and step -> LDS
-        stage_x(cx, meta, tile, k0, full, xoff);
-        lds_wave_sync();
+    __device__ __forceinline__ half8 operand() const {
+        return as_half8(__builtin_amdgcn_perm(hi[0], lo[0], 0x05040100u), __builtin_amdgcn_perm(hi[0], lo[0], 0x07060302u),
+                        __builtin_amdgcn_perm(hi[1], lo[1], 0x05040100u), __builtin_amdgcn_perm(hi[1], lo[1], 0x07060302u));
+    }
+};
 
-        if constexpr (BASE) {
+template <int JG, int MODE>
+__device__ __forceinline__ void delta_group(const LaneCtx& cx, const DecodeMeta& meta, const ExpandConsts<MODE>& kc,
+                                            int job0, int job_end, int c, const u32x4 (&sreg)[JG], float4v& sel) {
+    float4v acc[JG];
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const half8 b = *(const half8*)(cx.xs_base_rd + (v >> 2) * kXsBlockBytes + (v & 3) * 64);
-                accb[v & 1] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8, wreg[v]), b, accb[v & 1], 0, 0, 0);
+    for (int j = 0; j < JG; ++j) acc[j] = float4v{0.f, 0.f, 0.f, 0.f};
+    DeltaB nxt;
+    nxt.read(cx, 0, 0);
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        WordState<MODE> ws[JG];
+#pragma unroll
+        for (int j = 0; j < JG; ++j) ws[j].set(sreg[j][u]);
+#pragma unroll
+        for (int m = 0; m < 4; ++m) {
+            const half8 bd = nxt.operand();
+            if (u * 4 + m + 1 < 16) nxt.read(cx, (u * 4 + m + 1) >> 2, (u * 4 + m + 1) & 3);   // LDS latency hides under this slice
+#pragma unroll
+            for (int j = 0; j < JG; ++j) {
+                const half8 a = as_half8(ws[j].reg(4 * m, kc), ws[j].reg(4 * m + 1, kc), ws[j].reg(4 * m + 2, kc),
+                                         ws[j].reg(4 * m + 3, kc));
+                acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, bd, acc[j], 0, 0, 0);
             }
-            __builtin_amdgcn_sched_barrier(0);
+            __builtin_amdgcn_sched_barrier(0);   // keep the expansion of one slice next to its MFMAs
         }
+    }
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            WordState<MODE> ws[JP];
+    for (int j = 0; j < JG; ++j) {
+        const int jj = job0 + j;
+        const bool mine = jj < job_end && c >= meta.job_col_begin[jj] && c < meta.job_col_end[jj];
 #pragma unroll
-            for (int j = 0; j < JP; ++j) ws[j].set(sreg[j][u]);
-#pragma unroll
-            for (int m = 0; m < 4; ++m) {
-                const u32x2 lo = *(const u32x2*)(cx.xs_delta_rd + u * 64 + m * 8);
-                const u32x2 hi = *(const u32x2*)(cx.xs_delta_rd + u * 64 + m * 8 + 32);
-                const half8 bd = as_half8(__builtin_amdgcn_perm(hi[0], lo[0], 0x05040100u),
-                                          __builtin_amdgcn_perm(hi[0], lo[0], 0x07060302u),
-                                          __builtin_amdgcn_perm(hi[1], lo[1], 0x05040100u),
-                                          __builtin_amdgcn_perm(hi[1], lo[1], 0x07060302u));
-                if constexpr (MODE == kMantissa) {
-                    const int pb = (m & 1) * 4 + 2;
-                    const half8 hop = as_half8(kc.hreg[pb - 2], kc.hreg[pb - 1], kc.hreg[pb], kc.hreg[pb + 1]);
-                    acch = __builtin_amdgcn_mfma_f32_16x16x32_f16(hop, bd, acch, 0, 0, 0);
-                }
-#pragma unroll
-                for (int j = 0; j < JP; ++j) {
-                    const half8 a = as_half8(ws[j].reg(4 * m, kc), ws[j].reg(4 * m + 1, kc), ws[j].reg(4 * m + 2, kc),
-                                             ws[j].reg(4 * m + 3, kc));
-                    acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, bd, acc[j], 0, 0, 0);
-                }
-                __builtin_amdgcn_sched_barrier(0);   // keep the expansion of one slice next to its MFMAs
-            }
-        }
-        // ---- second column tile's base product while this step's W is still in registers
-        if constexpr (BASE) {
-            if (cx.n_tiles > 1) {
-                __builtin_amdgcn_wave_barrier();
-                stage_x(cx, meta, 1, k0, full, xoff);
-                lds_wave_sync();
-#pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const half8 b = *(const half8*)(cx.xs_base_rd + (v >> 2) * kXsBlockBytes + (v & 3) * 64);
-                    accb1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8, wreg[v]), b, accb1, 0, 0, 0);
-                }
-            }
-        }
-        __builtin_amdgcn_wave_barrier();   // the next step's staging must not overtake these reads
+        for (int i = 0; i < 4; ++i) sel[i] = mine ? acc[j][i] : sel[i];
     }
 }
 
-// Keep, per lane, the result of the job that owns this lane's column.
-template <int JP>
-__device__ __forceinline__ void select_columns(const DecodeMeta& meta, const float* __restrict__ alpha_by_tenant, int job0,
-                                               int c, const float4v (&acc)[JP], float4v& dsel, float& alpha_c) {
+// H = sum_k (2^(11-p(k)) + 1) x_k of one step (mantissa mode only): the same four B operands
+// per word as the delta product, against a constant A operand.
+__device__ __forceinline__ void h_term(const LaneCtx& cx, const ExpandConsts<kMantissa>& kc, float4v& acch) {
 #pragma unroll
-    for (int j = 0; j < JP; ++j) {
-        const bool mine = c >= meta.job_col_begin[job0 + j] && c < meta.job_col_end[job0 + j];
-        const float a = alpha_by_tenant[meta.job_tenant[job0 + j]];
-        dsel = mine ? acc[j] : dsel;
-        alpha_c = mine ? a : alpha_c;
+    for (int u = 0; u < 4; ++u) {
+        DeltaB b[4];
+#pragma unroll
+        for (int m = 0; m < 4; ++m) b[m].read(cx, u, m);
+#pragma unroll
+        for (int m = 0; m < 4; ++m) {
+            const int pb = (m & 1) * 4;
+            const half8 hop = as_half8(kc.hreg[pb], kc.hreg[pb + 1], kc.hreg[pb + 2], kc.hreg[pb + 3]);
+            acch = __builtin_amdgcn_mfma_f32_16x16x32_f16(hop, b[m].operand(), acch, 0, 0, 0);
+        }
     }
 }
 
-template <int JP, int MODE>
-__device__ __forceinline__ void pass_and_select(const LaneCtx& cx, const DecodeMeta& meta, const ExpandConsts<MODE>& kc,
-                                                const float* __restrict__ alpha_by_tenant, int tile, int job0, bool base,
-                                                int c, float4v (&accb)[2], float4v& accb1, float4v& acch, float4v& dsel,
-                                                float& alpha_c) {
-    float4v acc[JP];
-    if (base) run_pass<JP, MODE, true>(cx, meta, kc, tile, job0, accb, accb1, acch, acc);
-    else run_pass<JP, MODE, false>(cx, meta, kc, tile, job0, accb, accb1, acch, acc);
-    select_columns<JP>(meta, alpha_by_tenant, job0, c, acc, dsel, alpha_c);
-}
-
-template <int MODE>
+// NG groups of JG job slots per column tile: (1,4) up to 4 jobs, (1,8) up to 8, (2,8) up to 16.
+template <int MODE, int TILES, int NG, int JG>
 __global__ __launch_bounds__(kMaxWaves * kWave) void linear_decode_mfma_kernel(
     const uint16_t* __restrict__ x, const uint16_t* __restrict__ w,
     const uint32_t* const* __restrict__ packed_by_tenant, const float* __restrict__ alpha_by_tenant,
-    const DecodeMeta meta, uint16_t* __restrict__ y, const int64_t out, const int64_t in) {
+    const DecodeMeta meta, uint16_t* __restrict__ y, const int64_t out, const int64_t in64) {
+    const int in = (int)in64;
     extern __shared__ __align__(16) unsigned char smem[];
     LaneCtx cx;
     const int lane = threadIdx.x & (kWave - 1);
+    cx.lane = lane;
     cx.wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform, and the compiler knows it
     cx.n_waves = blockDim.x >> 6;
     const int c = lane & 15;          // A row (output row) for loads, B/D column (token) for MFMA results
@@ -309,63 +264,151 @@ __global__ __launch_bounds__(kMaxWaves * kWave) void linear_decode_mfma_kernel(
     const int64_t n0 = (int64_t)blockIdx.x * 16;
     const int64_t nrow = (n0 + c < out) ? n0 + c : out - 1;   // clamp: padded rows repeat the last row
     cx.n_steps = (int)((in + kStepK - 1) / kStepK);
-    cx.n_tiles = (meta.T + 15) >> 4;
     cx.in = in;
     cx.x = x;
     cx.w = w;
     cx.packed_by_tenant = packed_by_tenant;
-    cx.woff = (uint32_t)((nrow * in + 8 * cx.g) * 2);
-    cx.soff = (uint32_t)((nrow * (in >> 5) + 4 * cx.g) * 4);
+    cx.woff = (uint32_t)((nrow * in64 + 8 * cx.g) * 2);
+    cx.soff = (uint32_t)((nrow * (in64 >> 5) + 4 * cx.g) * 4);
     cx.xoff = (uint32_t)(16 * lane);
-    cx.xs_wr = cx.xs + (lane >> 4) * kXsBlockBytes + (lane & 15) * 16;
     cx.xs_base_rd = cx.xs + c * kXsRowBytes + cx.g * 16;
-    cx.xs_delta_rd = cx.xs + c * kXsRowBytes + cx.g * kXsBlockBytes;
+    cx.xs_delta_rd = cx.xs + c * kXsRowBytes + cx.g * 256;
     const ExpandConsts<MODE> kc;
 
-    float4v ypart0 = {0.f, 0.f, 0.f, 0.f}, ypart1 = {0.f, 0.f, 0.f, 0.f};
-    float4v accb1 = {0.f, 0.f, 0.f, 0.f};   // base product of the second column tile, built during the first pass
+    // zero this wavefront's staging rows once: rows of absent columns are never written again
+#pragma unroll
+    for (int i = 0; i < kXsWaveBytes / (kWave * 16); ++i) *(u32x4*)(cx.xs + (i * kWave + lane) * 16) = u32x4{0u, 0u, 0u, 0u};
+    if (lane < (kXsWaveBytes % (kWave * 16)) / 16)
+        *(u32x4*)(cx.xs + ((kXsWaveBytes / (kWave * 16)) * kWave + lane) * 16) = u32x4{0u, 0u, 0u, 0u};
 
-    int job = 0;
-    for (int tile = 0; tile < cx.n_tiles; ++tile) {
-        int job_end = job;
-        while (job_end < meta.n_jobs && meta.job_tile[job_end] == tile) ++job_end;
-        float4v accb[2] = {float4v{0.f, 0.f, 0.f, 0.f}, float4v{0.f, 0.f, 0.f, 0.f}};
-        float4v acch = {0.f, 0.f, 0.f, 0.f};
-        float4v dsel = {0.f, 0.f, 0.f, 0.f};
-        float alpha_c = 0.f;
-        bool base = (tile == 0);     // W streams exactly once, in the first pass of the first tile
-        while (job < job_end) {      // the host guarantees at least one job per tile
-            const int left = job_end - job;
-            if (left >= 8) {
-                pass_and_select<8, MODE>(cx, meta, kc, alpha_by_tenant, tile, job, base, c, accb, accb1, acch, dsel, alpha_c);
-                job += 8;
-            } else if (left >= 4) {
-                pass_and_select<4, MODE>(cx, meta, kc, alpha_by_tenant, tile, job, base, c, accb, accb1, acch, dsel, alpha_c);
-                job += 4;
-            } else if (left >= 2) {
-                pass_and_select<2, MODE>(cx, meta, kc, alpha_by_tenant, tile, job, base, c, accb, accb1, acch, dsel, alpha_c);
-                job += 2;
-            } else {
-                pass_and_select<1, MODE>(cx, meta, kc, alpha_by_tenant, tile, job, base, c, accb, accb1, acch, dsel, alpha_c);
-                job += 1;
+    // per tile: first job, one past the last job, and this lane's scale (alpha of the job owning its column)
+    int job_begin[TILES], job_stop[TILES];
+    float alpha_c[TILES];
+    {
+        int job = 0;
+#pragma unroll
+        for (int tile = 0; tile < TILES; ++tile) {
+            job_begin[tile] = job;
+            alpha_c[tile] = 0.f;
+            while (job < meta.n_jobs && meta.job_tile[job] == tile) {
+                const bool mine = c >= meta.job_col_begin[job] && c < meta.job_col_end[job];
+                const float a = alpha_by_tenant[meta.job_tenant[job]];
+                alpha_c[tile] = mine ? a : alpha_c[tile];
+                ++job;
             }
-            base = false;
+            job_stop[tile] = job;
         }
-        float4v bsum = accb[0] + accb[1];
-        if (tile == 1) bsum = accb1;
-        float4v d = dsel;
-        if constexpr (MODE == kMantissa) d = 4.0f * dsel - acch;
-        if (tile == 0) ypart0 = bsum + alpha_c * d;
-        else ypart1 = bsum + alpha_c * d;
     }
+
+    float4v accb[TILES], acch[TILES], dsel[TILES];
+#pragma unroll
+    for (int tile = 0; tile < TILES; ++tile) accb[tile] = acch[tile] = dsel[tile] = float4v{0.f, 0.f, 0.f, 0.f};
+
+    // One step of this wavefront: 512 reduction elements from k0.  FULL steps carry no guards at
+    // all; the (at most one) ragged last step of the matrix takes the guarded instantiation.
+    auto do_step = [&](auto full_tag, const int k0) {
+        constexpr bool FULL = decltype(full_tag)::value;
+        // Lane offsets are re-read through an empty asm every step: otherwise the compiler hoists
+        // "uniform base + lane offset" of every load out of the loop as 64-bit register pairs.
+        uint32_t woff = cx.woff, soff = cx.soff, xoff = cx.xoff;
+        asm volatile("" : "+v"(woff), "+v"(soff), "+v"(xoff));
+        const bool svalid = FULL || (k0 + 128 * cx.g < in);
+
+        // ---- issue order = arrival order: x (L2 hits, straight into LDS), the sign words (their
+        // expansion is the bulk of the work), W last (its 16 MFMAs per tile are the short tail)
+        lds_wave_sync();                         // the previous step's LDS reads are done
+        stage_x<FULL>(cx, meta, 0, k0, xoff);
+        __builtin_amdgcn_sched_barrier(0);
+        u32x4 sreg[NG][JG];
+        auto load_signs = [&](const int tile) {
+#pragma unroll
+            for (int gi = 0; gi < NG; ++gi) {
+#pragma unroll
+                for (int j = 0; j < JG; ++j) {
+                    const int jj = job_begin[tile] + gi * JG + j;
+                    const int tenant = meta.job_tenant[jj < job_stop[tile] ? jj : job_begin[tile]];
+                    if constexpr (FULL) {
+                        sreg[gi][j] = load16_stream(packed_by_tenant[tenant] + (k0 >> 5), soff);
+                    } else {
+                        sreg[gi][j] = u32x4{0u, 0u, 0u, 0u};
+                        if (svalid) sreg[gi][j] = load16_stream(packed_by_tenant[tenant] + (k0 >> 5), soff);
+                    }
+                }
+            }
+        };
+        load_signs(0);
+        u32x4 wreg[16];
+        {
+            const uint16_t* wk = w + k0;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                if constexpr (FULL) {
+                    wreg[v] = load16_stream(wk + 32 * v, woff);
+                } else {
+                    wreg[v] = u32x4{0u, 0u, 0u, 0u};
+                    if (k0 + 32 * v < in) wreg[v] = load16_stream(wk + 32 * v, woff);
+                }
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        // The direct-to-LDS loads are older than the NG*JG + 16 register loads above and memory
+        // loads return in order: "at most that many outstanding" means x has landed.  (The guarded
+        // instantiation may have skipped loads, so it waits for everything.)
+        if constexpr (FULL) __builtin_amdgcn_s_waitcnt(vmcnt_only(NG * JG + 16));
+        else __builtin_amdgcn_s_waitcnt(vmcnt_only(0));
+#pragma unroll
+        for (int tile = 0; tile < TILES; ++tile) {
+            if (tile > 0) {
+                // second column tile: new sign words, and its x over the same LDS rows
+                lds_wave_sync();
+                stage_x<FULL>(cx, meta, tile, k0, xoff);
+                __builtin_amdgcn_sched_barrier(0);
+                load_signs(tile);
+                __builtin_amdgcn_sched_barrier(0);
+                if constexpr (FULL) __builtin_amdgcn_s_waitcnt(vmcnt_only(NG * JG));
+                else __builtin_amdgcn_s_waitcnt(vmcnt_only(0));
+            }
+            lds_wave_sync();
+            if constexpr (MODE == kMantissa) {
+                h_term(cx, kc, acch[tile]);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            // ---- delta jobs, one group of JG at a time; keep the job owning this lane's column
+            float4v sel = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int gi = 0; gi < NG; ++gi) {
+                if (gi == 0 || job_begin[tile] + gi * JG < job_stop[tile])
+                    delta_group<JG, MODE>(cx, meta, kc, job_begin[tile] + gi * JG, job_stop[tile], c, sreg[gi], sel);
+            }
+            dsel[tile] += sel;
+            // ---- base product of this tile, four B operands in flight
+#pragma unroll
+            for (int vb = 0; vb < 16; vb += 4) {
+                half8 b[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) b[i] = *(const half8*)(cx.xs_base_rd + (vb + i) * 64);
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    accb[tile] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8, wreg[vb + i]), b[i], accb[tile], 0, 0, 0);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+    const int n_full = in / kStepK;
+    for (int step = cx.wave; step < n_full; step += cx.n_waves) do_step(std::true_type{}, step * kStepK);
+    if (n_full < cx.n_steps && (n_full % cx.n_waves) == cx.wave) do_step(std::false_type{}, n_full * kStepK);
 
     // ---- add the wavefronts' partial tiles in a fixed order and write y once
     __syncthreads();   // every wavefront is done with its staging region
     float* red = (float*)cx.xs;   // [tile][col][row] of this wavefront
-    *(float4v*)(red + c * 16 + 4 * cx.g) = ypart0;
-    if (cx.n_tiles > 1) *(float4v*)(red + 256 + c * 16 + 4 * cx.g) = ypart1;
+#pragma unroll
+    for (int tile = 0; tile < TILES; ++tile) {
+        float4v d = dsel[tile];
+        if constexpr (MODE == kMantissa) d = 4.0f * dsel[tile] - acch[tile];
+        *(float4v*)(red + tile * 256 + c * 16 + 4 * cx.g) = accb[tile] + alpha_c[tile] * d;
+    }
     __syncthreads();
-    for (int idx = threadIdx.x; idx < cx.n_tiles * 256; idx += blockDim.x) {
+    for (int idx = threadIdx.x; idx < TILES * 256; idx += blockDim.x) {
         const int tile = idx >> 8, col = (idx >> 4) & 15, row = idx & 15;
         const int gcol = tile * 16 + col;
         if (gcol < meta.T && n0 + row < out) {
@@ -379,14 +422,14 @@ __global__ __launch_bounds__(kMaxWaves * kWave) void linear_decode_mfma_kernel(
 
 bool decode_mfma_variant_known(int variant) { return variant == 2 || variant == 3; }
 
-template <int MODE>
+template <int MODE, int TILES, int NG, int JG>
 static hipError_t launch_one(const uint16_t* x, const uint16_t* w, const uint32_t* const* packed_by_tenant,
                              const float* alpha_by_tenant, const DecodeMeta& meta, uint16_t* y, int64_t out, int64_t in,
                              hipStream_t st) {
     const int n_steps = (int)((in + kStepK - 1) / kStepK);
     const int n_waves = n_steps < kMaxWaves ? n_steps : kMaxWaves;
     const size_t lds = (size_t)n_waves * kXsWaveBytes;
-    auto kernel = linear_decode_mfma_kernel<MODE>;
+    auto kernel = linear_decode_mfma_kernel<MODE, TILES, NG, JG>;
     static bool attr_set = false;   // raising the dynamic LDS limit is idempotent; a race only repeats it
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -399,14 +442,35 @@ static hipError_t launch_one(const uint16_t* x, const uint16_t* w, const uint32_
     return hipGetLastError();
 }
 
+template <int MODE>
+static hipError_t launch_mode(const uint16_t* x, const uint16_t* w, const uint32_t* const* packed_by_tenant,
+                              const float* alpha_by_tenant, const DecodeMeta& meta, uint16_t* y, int64_t out, int64_t in,
+                              hipStream_t st) {
+    int max_jobs = 0, cur = 0;   // most jobs in one column tile
+    for (int j = 0; j < meta.n_jobs; ++j) {
+        cur = (j > 0 && meta.job_tile[j] == meta.job_tile[j - 1]) ? cur + 1 : 1;
+        max_jobs = cur > max_jobs ? cur : max_jobs;
+    }
+#define BD_ARGS x, w, packed_by_tenant, alpha_by_tenant, meta, y, out, in, st
+    if (meta.T <= 16) {
+        if (max_jobs <= 4) return launch_one<MODE, 1, 1, 4>(BD_ARGS);
+        if (max_jobs <= 8) return launch_one<MODE, 1, 1, 8>(BD_ARGS);
+        return launch_one<MODE, 1, 2, 8>(BD_ARGS);
+    }
+    if (max_jobs <= 4) return launch_one<MODE, 2, 1, 4>(BD_ARGS);
+    if (max_jobs <= 8) return launch_one<MODE, 2, 1, 8>(BD_ARGS);
+    return launch_one<MODE, 2, 2, 8>(BD_ARGS);
+#undef BD_ARGS
+}
+
 // variant 2 = plain +-1 expansion, variant 3 = mantissa expansion.
 // Requires in % 128 == 0 and every tensor (W, x, each packed delta) below 4 GiB.
 hipError_t launch_linear_decode_mfma(const uint16_t* x, const uint16_t* w, const uint32_t* const* packed_by_tenant,
                                      const float* alpha_by_tenant, const DecodeMeta& meta, uint16_t* y, int64_t out,
                                      int64_t in, int variant, hipStream_t st) {
     switch (variant) {
-        case 2: return launch_one<kPlain>(x, w, packed_by_tenant, alpha_by_tenant, meta, y, out, in, st);
-        case 3: return launch_one<kMantissa>(x, w, packed_by_tenant, alpha_by_tenant, meta, y, out, in, st);
+        case 2: return launch_mode<kPlain>(x, w, packed_by_tenant, alpha_by_tenant, meta, y, out, in, st);
+        case 3: return launch_mode<kMantissa>(x, w, packed_by_tenant, alpha_by_tenant, meta, y, out, in, st);
         default: return hipErrorInvalidValue;
     }
 }
