@@ -252,22 +252,26 @@ def main():
     if not args.no_cpu:
         from oracle import ref
         rng = np.random.default_rng(synth.DEFAULT_SEED)
-        t_cpu = 0.0
+        t_cpu, layer_passes = 0.0, 0
+        cpu_inputs = []
         for name, out, inn in shapes:
             wb = (rng.standard_normal((out, inn), dtype=np.float32) * 0.02).astype(np.float16)
             xb = rng.standard_normal((B, inn), dtype=np.float32).astype(np.float16)
             packed = [rng.integers(0, 2**32, size=(out, inn // 32), dtype=np.uint64).astype(np.uint32) for _ in range(B)]
-            alphas = np.full(B, 0.0016, dtype=np.float32)
-            t0 = time.time()
-            ref.linear_multitenant(xb, wb, packed, alphas, tok)
-            t_cpu += time.time() - t0
+            cpu_inputs.append((xb, wb, packed, np.full(B, 0.0016, dtype=np.float32)))
+        while t_cpu < 10.0 and layer_passes < 64:      # about 10 s of oracle work
+            for xb, wb, packed, alphas in cpu_inputs:
+                t0 = time.time()
+                ref.linear_multitenant(xb, wb, packed, alphas, tok)
+                t_cpu += time.time() - t0
+            layer_passes += 1
         result["cpu_baseline"] = {
-            "value": round(B / (t_cpu * n_layers), 4),
+            "value": round(B * layer_passes / (t_cpu * n_layers), 4),
             "unit": "tokens/s",
             "cores": ref.num_threads(),
             "kind": "oracle",
-            "sample": f"1 of {n_layers} layers at full shape (7 linears, B={B}; iid weights and sign words), "
-                      f"{t_cpu:.2f} s of oracle time, stack rate = layer rate / {n_layers}",
+            "sample": f"one decoder layer at full shape (7 linears, B={B}; iid weights and sign words), {layer_passes} passes, "
+                      f"{t_cpu:.2f} s of oracle time; stack rate = layer rate / {n_layers}",
         }
     print(json.dumps(result))
 

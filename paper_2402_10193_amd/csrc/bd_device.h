@@ -28,6 +28,15 @@ struct DecodeMeta {
     int32_t job_tile[kMaxDecodeTokens];         // which 16-column tile the job's columns are in
     int32_t job_col_begin[kMaxDecodeTokens];    // first column (0..15, inside the tile)
     int32_t job_col_end[kMaxDecodeTokens];      // one past the last column (inside the tile)
+    int32_t tenant_of_col[kMaxDecodeTokens];    // tenant of each sorted column
+    int32_t tile_job_begin[2];                  // first job of each 16-column tile
+    int32_t tile_job_end[2];                    // one past its last job
+    // The same jobs laid out per tile in 16 fixed slots, so that the kernel reads them with
+    // constant indices: slot s of tile t is job tile_job_begin[t] + s; slots beyond the tile's
+    // jobs repeat its first tenant with an empty column range (never selected).
+    int32_t slot_tenant[2][16];
+    int32_t slot_col_begin[2][16];
+    int32_t slot_col_end[2][16];
 };
 
 __device__ __forceinline__ float h2f(uint16_t bits) {

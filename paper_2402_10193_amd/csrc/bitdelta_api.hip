@@ -39,6 +39,7 @@ void build_meta(const int32_t* tenant_of_token, int64_t t0, int n, DecodeMeta* m
         const int tok = order[col];
         const int tenant = m->tenant_of_token[tok];
         m->token_of_col[col] = (int32_t)tok;
+        m->tenant_of_col[col] = tenant;
         const int tile = col >> 4, cin = col & 15;
         if (jobs > 0 && m->job_tenant[jobs - 1] == tenant && m->job_tile[jobs - 1] == tile) {
             m->job_col_end[jobs - 1] = (int32_t)(cin + 1);
@@ -51,6 +52,20 @@ void build_meta(const int32_t* tenant_of_token, int64_t t0, int n, DecodeMeta* m
         }
     }
     m->n_jobs = jobs;
+    for (int tile = 0; tile < 2; ++tile) {
+        int b = 0;
+        while (b < jobs && m->job_tile[b] < tile) ++b;
+        int e = b;
+        while (e < jobs && m->job_tile[e] == tile) ++e;
+        m->tile_job_begin[tile] = b;
+        m->tile_job_end[tile] = e;
+        for (int sl = 0; sl < 16; ++sl) {
+            const bool real = b + sl < e;
+            m->slot_tenant[tile][sl] = real ? m->job_tenant[b + sl] : (b < e ? m->job_tenant[b] : 0);
+            m->slot_col_begin[tile][sl] = real ? m->job_col_begin[b + sl] : 0;
+            m->slot_col_end[tile][sl] = real ? m->job_col_end[b + sl] : 0;
+        }
+    }
 }
 
 bd_status check_linear_args(const void* x, const void* w, const void* packed_by_tenant, const void* alpha_by_tenant,

@@ -27,6 +27,18 @@
 
 namespace bd {
 
+#ifdef BD_EXPERIMENT_STAMPS
+// experiment only: shader-clock stamps of the first workgroups' wavefronts
+__device__ unsigned long long bd_stamps[64 * 8 * 16];
+#define BD_STAMP(i)                                                                                   \
+    do {                                                                                              \
+        if (blockIdx.x < 64 && (threadIdx.x & 63) == 0)                                               \
+            bd_stamps[(blockIdx.x * 8 + (threadIdx.x >> 6)) * 16 + (i)] = __builtin_readcyclecounter(); \
+    } while (0)
+#else
+#define BD_STAMP(i) do { } while (0)
+#endif
+
 constexpr int kStepK = 512;            // reduction elements one wavefront consumes per step
 constexpr int kXsRowBytes = 1040;      // 512 fp16 of one column + 16 B pad: row stride = 4 * odd banks
 constexpr int kXsWaveBytes = 16 * kXsRowBytes;
@@ -132,7 +144,7 @@ __device__ __forceinline__ void lds_wave_sync() {
 // All global loads are "uniform 64-bit base + 32-bit lane offset", the form that needs one
 // address register per lane; the host guarantees every tensor is below 4 GiB.
 __device__ __forceinline__ u32x4 load16_stream(const void* base, uint32_t lane_off) {
-    return __builtin_nontemporal_load((const u32x4*)((const unsigned char*)base + lane_off));
+    return *(const u32x4*)((const unsigned char*)base + lane_off);
 }
 
 typedef const void __attribute__((address_space(1)))* gptr_t;
@@ -175,9 +187,9 @@ __device__ __forceinline__ void stage_x(const LaneCtx& cx, const DecodeMeta& met
     }
 }
 
-// The JG delta jobs [job0, job0 + JG) of one step: expand their sign words and multiply them
-// with the staged x.  Slots at or beyond job_end are padding (they re-read the first job's
-// words and are never selected).  On return `sel` holds, per lane, the partial sum of the job
+// The JG delta jobs in slots [slot0, slot0 + JG) of a tile, one step: expand their sign words and
+// multiply them with the staged x.  Padding slots re-read the first job's words and are never
+// selected.  On return `sel` holds, per lane, the partial sum of the job
 // that owns the lane's column (unchanged if none of these jobs does).
 // The B operand (x) of delta slice (u, m): elements (4m+q, 4m+q+16), q = 0..3, of word u of
 // this lane's 128-element block, as four fp16 pairs.
@@ -195,7 +207,7 @@ struct DeltaB {
 
 template <int JG, int MODE>
 __device__ __forceinline__ void delta_group(const LaneCtx& cx, const DecodeMeta& meta, const ExpandConsts<MODE>& kc,
-                                            int job0, int job_end, int c, const u32x4 (&sreg)[JG], float4v& sel) {
+                                            int tile, int slot0, int c, const u32x4 (&sreg)[JG], float4v& sel) {
     float4v acc[JG];
 #pragma unroll
     for (int j = 0; j < JG; ++j) acc[j] = float4v{0.f, 0.f, 0.f, 0.f};
@@ -216,13 +228,23 @@ __device__ __forceinline__ void delta_group(const LaneCtx& cx, const DecodeMeta&
                                          ws[j].reg(4 * m + 3, kc));
                 acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, bd, acc[j], 0, 0, 0);
             }
+            // Issue order inside the slice: the expansion of job j+1 (4 and-or) goes between the
+            // MFMAs of jobs j and j+1, so the vector ALU and the matrix pipe run at the same time
+            // even with a single wavefront on the SIMD.
+            __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);   // next slice's LDS reads
+            __builtin_amdgcn_sched_group_barrier(0x002, 8, 0);   // perms + expansion of job 0
+#pragma unroll
+            for (int j = 0; j + 1 < JG; ++j) {
+                __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);   // expansion of job j+1 ...
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // ... ahead of the MFMA of job j
+            }
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
             __builtin_amdgcn_sched_barrier(0);   // keep the expansion of one slice next to its MFMAs
         }
     }
 #pragma unroll
     for (int j = 0; j < JG; ++j) {
-        const int jj = job0 + j;
-        const bool mine = jj < job_end && c >= meta.job_col_begin[jj] && c < meta.job_col_end[jj];
+        const bool mine = (c >= meta.slot_col_begin[tile][slot0 + j]) & (c < meta.slot_col_end[tile][slot0 + j]);
 #pragma unroll
         for (int i = 0; i < 4; ++i) sel[i] = mine ? acc[j][i] : sel[i];
     }
@@ -256,6 +278,7 @@ __global__ __launch_bounds__(kMaxWaves * kWave) void linear_decode_mfma_kernel(
     LaneCtx cx;
     const int lane = threadIdx.x & (kWave - 1);
     cx.lane = lane;
+    BD_STAMP(0);
     cx.wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform, and the compiler knows it
     cx.n_waves = blockDim.x >> 6;
     const int c = lane & 15;          // A row (output row) for loads, B/D column (token) for MFMA results
@@ -281,25 +304,32 @@ __global__ __launch_bounds__(kMaxWaves * kWave) void linear_decode_mfma_kernel(
     if (lane < (kXsWaveBytes % (kWave * 16)) / 16)
         *(u32x4*)(cx.xs + ((kXsWaveBytes / (kWave * 16)) * kWave + lane) * 16) = u32x4{0u, 0u, 0u, 0u};
 
-    // per tile: first job, one past the last job, and this lane's scale (alpha of the job owning its column)
-    int job_begin[TILES], job_stop[TILES];
+    // per tile: the packed-delta pointer of every job slot and this lane's scale = alpha of the
+    // tenant owning its column.  The slot tenants arrive with the kernel arguments (fixed slots,
+    // constant indices).  Lane j of `slot_ptr_*` fetches the pointer of slot j with ONE vector load
+    // (sixteen dependent scalar loads would serialise for microseconds); the step loop reads the
+    // lanes back as uniform values.  The alpha load is issued here and first used in the epilogue.
+    int n_jobs_tile[TILES];
+    uint32_t slot_ptr_lo[TILES], slot_ptr_hi[TILES];
     float alpha_c[TILES];
-    {
-        int job = 0;
 #pragma unroll
-        for (int tile = 0; tile < TILES; ++tile) {
-            job_begin[tile] = job;
-            alpha_c[tile] = 0.f;
-            while (job < meta.n_jobs && meta.job_tile[job] == tile) {
-                const bool mine = c >= meta.job_col_begin[job] && c < meta.job_col_end[job];
-                const float a = alpha_by_tenant[meta.job_tenant[job]];
-                alpha_c[tile] = mine ? a : alpha_c[tile];
-                ++job;
-            }
-            job_stop[tile] = job;
+    for (int tile = 0; tile < TILES; ++tile) {
+        n_jobs_tile[tile] = meta.tile_job_end[tile] - meta.tile_job_begin[tile];
+        int my_tenant = 0, lane_tenant = 0;
+#pragma unroll
+        for (int j = 0; j < NG * JG; ++j) {
+            const int t = meta.slot_tenant[tile][j];
+            lane_tenant = (lane == j) ? t : lane_tenant;
+            const bool mine = (c >= meta.slot_col_begin[tile][j]) & (c < meta.slot_col_end[tile][j]);
+            my_tenant = mine ? t : my_tenant;
         }
+        const uint64_t p = (uint64_t)packed_by_tenant[lane_tenant];   // lanes >= NG*JG fetch slot-0-like tenant 0: valid, unused
+        slot_ptr_lo[tile] = (uint32_t)p;
+        slot_ptr_hi[tile] = (uint32_t)(p >> 32);
+        alpha_c[tile] = (tile * 16 + c < meta.T) ? alpha_by_tenant[my_tenant] : 0.f;
     }
 
+    BD_STAMP(9);
     float4v accb[TILES], acch[TILES], dsel[TILES];
 #pragma unroll
     for (int tile = 0; tile < TILES; ++tile) accb[tile] = acch[tile] = dsel[tile] = float4v{0.f, 0.f, 0.f, 0.f};
@@ -317,26 +347,30 @@ __global__ __launch_bounds__(kMaxWaves * kWave) void linear_decode_mfma_kernel(
         // ---- issue order = arrival order: x (L2 hits, straight into LDS), the sign words (their
         // expansion is the bulk of the work), W last (its 16 MFMAs per tile are the short tail)
         lds_wave_sync();                         // the previous step's LDS reads are done
+        BD_STAMP(10);
         stage_x<FULL>(cx, meta, 0, k0, xoff);
         __builtin_amdgcn_sched_barrier(0);
+        BD_STAMP(11);
         u32x4 sreg[NG][JG];
         auto load_signs = [&](const int tile) {
 #pragma unroll
             for (int gi = 0; gi < NG; ++gi) {
 #pragma unroll
                 for (int j = 0; j < JG; ++j) {
-                    const int jj = job_begin[tile] + gi * JG + j;
-                    const int tenant = meta.job_tenant[jj < job_stop[tile] ? jj : job_begin[tile]];
+                    const uint64_t pj = (uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)slot_ptr_lo[tile], gi * JG + j) |
+                                        ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)slot_ptr_hi[tile], gi * JG + j) << 32);
+                    const uint32_t* sp = (const uint32_t*)pj + (k0 >> 5);
                     if constexpr (FULL) {
-                        sreg[gi][j] = load16_stream(packed_by_tenant[tenant] + (k0 >> 5), soff);
+                        sreg[gi][j] = load16_stream(sp, soff);
                     } else {
                         sreg[gi][j] = u32x4{0u, 0u, 0u, 0u};
-                        if (svalid) sreg[gi][j] = load16_stream(packed_by_tenant[tenant] + (k0 >> 5), soff);
+                        if (svalid) sreg[gi][j] = load16_stream(sp, soff);
                     }
                 }
             }
         };
         load_signs(0);
+        BD_STAMP(12);
         u32x4 wreg[16];
         {
             const uint16_t* wk = w + k0;
@@ -350,6 +384,7 @@ __global__ __launch_bounds__(kMaxWaves * kWave) void linear_decode_mfma_kernel(
                 }
             }
         }
+        BD_STAMP(1);
         __builtin_amdgcn_sched_barrier(0);
         // The direct-to-LDS loads are older than the NG*JG + 16 register loads above and memory
         // loads return in order: "at most that many outstanding" means x has landed.  (The guarded
@@ -369,18 +404,32 @@ __global__ __launch_bounds__(kMaxWaves * kWave) void linear_decode_mfma_kernel(
                 else __builtin_amdgcn_s_waitcnt(vmcnt_only(0));
             }
             lds_wave_sync();
+            BD_STAMP(2);
             if constexpr (MODE == kMantissa) {
                 h_term(cx, kc, acch[tile]);
                 __builtin_amdgcn_sched_barrier(0);
             }
+            BD_STAMP(3);
             // ---- delta jobs, one group of JG at a time; keep the job owning this lane's column
             float4v sel = {0.f, 0.f, 0.f, 0.f};
+#ifdef BD_EXPERIMENT_NO_DELTA_MATH
+            {   // experiment only: consume the sign words without expanding them
+                uint32_t fold = 0;
+#pragma unroll
+                for (int gi = 0; gi < NG; ++gi)
+#pragma unroll
+                    for (int j = 0; j < JG; ++j) fold ^= sreg[gi][j][0] ^ sreg[gi][j][1] ^ sreg[gi][j][2] ^ sreg[gi][j][3];
+                sel[0] = (fold == 0x12345u) ? 1.f : 0.f;
+            }
+#else
 #pragma unroll
             for (int gi = 0; gi < NG; ++gi) {
-                if (gi == 0 || job_begin[tile] + gi * JG < job_stop[tile])
-                    delta_group<JG, MODE>(cx, meta, kc, job_begin[tile] + gi * JG, job_stop[tile], c, sreg[gi], sel);
+                if (gi == 0 || gi * JG < n_jobs_tile[tile])
+                    delta_group<JG, MODE>(cx, meta, kc, tile, gi * JG, c, sreg[gi], sel);
             }
+#endif
             dsel[tile] += sel;
+            BD_STAMP(4);
             // ---- base product of this tile, four B operands in flight
 #pragma unroll
             for (int vb = 0; vb < 16; vb += 4) {
@@ -392,6 +441,7 @@ __global__ __launch_bounds__(kMaxWaves * kWave) void linear_decode_mfma_kernel(
                     accb[tile] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8, wreg[vb + i]), b[i], accb[tile], 0, 0, 0);
             }
             __builtin_amdgcn_sched_barrier(0);
+            BD_STAMP(5);
         }
     };
     const int n_full = in / kStepK;
@@ -399,7 +449,9 @@ __global__ __launch_bounds__(kMaxWaves * kWave) void linear_decode_mfma_kernel(
     if (n_full < cx.n_steps && (n_full % cx.n_waves) == cx.wave) do_step(std::false_type{}, n_full * kStepK);
 
     // ---- add the wavefronts' partial tiles in a fixed order and write y once
+    BD_STAMP(6);
     __syncthreads();   // every wavefront is done with its staging region
+    BD_STAMP(7);
     float* red = (float*)cx.xs;   // [tile][col][row] of this wavefront
 #pragma unroll
     for (int tile = 0; tile < TILES; ++tile) {
@@ -418,7 +470,14 @@ __global__ __launch_bounds__(kMaxWaves * kWave) void linear_decode_mfma_kernel(
             y[(int64_t)meta.token_of_col[gcol] * out + n0 + row] = f2h_rne(s);
         }
     }
+    BD_STAMP(8);
 }
+
+#ifdef BD_EXPERIMENT_STAMPS
+extern "C" int bd_debug_read_stamps(unsigned long long* host, int n) {
+    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(bd_stamps), sizeof(unsigned long long) * n);
+}
+#endif
 
 bool decode_mfma_variant_known(int variant) { return variant == 2 || variant == 3; }
 
