@@ -119,6 +119,60 @@ bd_status bd_linear_multitenant_variant(const uint16_t* x_f16, const uint16_t* w
                                         void* workspace, size_t workspace_bytes, void* stream,
                                         int32_t variant);
 
+/* ---- serving layout ---------------------------------------------------------------------
+ * Sec. 4.3 of the paper serves every fine-tune from one shared base plus packed 1-bit deltas
+ * that stay packed until they are on the chip.  For that stream the library keeps both in a
+ * TILED layout whose bytes are already in matrix-core operand order, so that every load of the
+ * decode kernel is one contiguous 512 B or 1 KiB run.  Re-laying a tensor is done once, offline,
+ * like compression.  The layout (tiles of 16 rows x 256 reduction elements, ordered [row block][k tile]):
+ *   base   Wt[rb][kt][v][l][e] fp16 = W[16 rb + l%16][256 kt + 32 v + 8 (l/16) + e]    v<8, l<64, e<8
+ *   signs  St[rb][kt][l][v]    byte,  bit e = packed sign of the same element
+ * Rows beyond out and elements beyond in are zero.  Sizes come from bd_tiled_*_bytes (0 for
+ * shapes the tiled path rejects: in % 32 != 0, or a tiled base of 4 GiB or more). */
+size_t bd_tiled_base_bytes(int64_t out, int64_t in);
+size_t bd_tiled_signs_bytes(int64_t out, int64_t in);
+
+/* w_f16 [out, in] fp16 row-major -> w_tiled (bd_tiled_base_bytes(out, in) bytes). */
+bd_status bd_tile_base(const uint16_t* w_f16, int64_t out, int64_t in, uint16_t* w_tiled, void* stream);
+
+/* packed [out, in/32] as written by bd_compress / bd_pack_signs -> signs_tiled
+ * (bd_tiled_signs_bytes(out, in) bytes). */
+bd_status bd_tile_signs(const uint32_t* packed, int64_t out, int64_t in, uint32_t* signs_tiled, void* stream);
+
+/* The multi-tenant linear of Eq. 6 over the serving layout; same arithmetic and rounding as
+ * bd_linear_multitenant.
+ *   w_tiled          tiled base (bd_tile_base)
+ *   tiled_by_tenant  HOST array of n_tenants DEVICE pointers to tiled deltas (bd_tile_signs); the
+ *                    pointers travel in the kernel arguments, so no device-side pointer table is read.
+ *                    Entries of tenants without a token in this call may be NULL.
+ *   alpha_by_tenant  device array of n_tenants floats
+ *   tenant_of_token  HOST [T]; x_f16 [T, in]; y_f16 [T, out], must not overlap x or w_tiled.
+ * Tokens are grouped by tenant inside the call; more than 16 tokens run as several launches of 16
+ * (the base is then streamed once per launch).  Needs no workspace. */
+bd_status bd_linear_multitenant_tiled(const uint16_t* x_f16, const uint16_t* w_tiled,
+                                      const uint32_t* const* tiled_by_tenant,
+                                      const float* alpha_by_tenant,
+                                      const int32_t* tenant_of_token,
+                                      uint16_t* y_f16,
+                                      int64_t T, int64_t out, int64_t in, int32_t n_tenants,
+                                      void* stream);
+
+/* Up to 3 linears that read the same activations (q, k, v or gate, up of one decoder layer) in
+ * ONE launch: y_m = Eq. 6 with matrix m's base, deltas and scales, for m < n_mats.
+ *   w_tiled             HOST [n_mats] of device pointers
+ *   tiled_by_mat_tenant HOST [n_mats * n_tenants], entry m * n_tenants + e = tenant e's delta of matrix m
+ *   alpha_by_mat        HOST [n_mats] of device arrays [n_tenants]
+ *   y_f16               HOST [n_mats] of device pointers, y_m is [T, out[m]]
+ *   out                 HOST [n_mats]; `in`, x, T and tenant_of_token are shared. */
+bd_status bd_linear_multitenant_tiled_group(int32_t n_mats, const uint16_t* x_f16,
+                                            const uint16_t* const* w_tiled,
+                                            const uint32_t* const* tiled_by_mat_tenant,
+                                            const float* const* alpha_by_mat,
+                                            const int32_t* tenant_of_token,
+                                            uint16_t* const* y_f16,
+                                            int64_t T, const int64_t* out, int64_t in, int32_t n_tenants,
+                                            void* stream);
+
 /* The grouping step of the linear, exposed so that a scheduler (or a test) can see it: the
  * tokens of one decode launch (T <= 32, all HOST arrays) sorted by tenant, stable, and cut
  * into jobs.  A job is one tenant's run of columns inside one 16-column tile; the kernel

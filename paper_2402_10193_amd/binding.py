@@ -22,7 +22,8 @@ OP_PACK_SIGNS, OP_COMPRESS, OP_LINEAR_MULTITENANT = 0, 1, 2
 # every symbol include/bitdelta.h declares
 EXPORTS = ["bd_status_string", "bd_version", "bd_workspace_bytes", "bd_pack_signs", "bd_compress", "bd_group_tokens",
            "bd_linear_multitenant", "bd_linear_multitenant_variant", "bd_materialize", "bd_linear_naive",
-           "bd_probe_read", "bd_probe_copy"]
+           "bd_probe_read", "bd_probe_copy", "bd_tiled_base_bytes", "bd_tiled_signs_bytes", "bd_tile_base",
+           "bd_tile_signs", "bd_linear_multitenant_tiled", "bd_linear_multitenant_tiled_group"]
 
 
 class BitDeltaError(RuntimeError):
@@ -61,8 +62,18 @@ def lib() -> ctypes.CDLL:
         L.bd_linear_naive.argtypes = [vp, vp, ctypes.POINTER(i32), vp, i64, i64, i64, i32, vp]
         L.bd_probe_read.argtypes = [vp, sz, vp, vp]
         L.bd_probe_copy.argtypes = [vp, vp, sz, vp]
+        L.bd_tiled_base_bytes.restype = sz
+        L.bd_tiled_base_bytes.argtypes = [i64, i64]
+        L.bd_tiled_signs_bytes.restype = sz
+        L.bd_tiled_signs_bytes.argtypes = [i64, i64]
+        L.bd_tile_base.argtypes = [vp, i64, i64, vp, vp]
+        L.bd_tile_signs.argtypes = [vp, i64, i64, vp, vp]
+        pvp, pi64 = ctypes.POINTER(vp), ctypes.POINTER(i64)
+        L.bd_linear_multitenant_tiled.argtypes = [vp, vp, pvp, vp, pi, vp, i64, i64, i64, i32, vp]
+        L.bd_linear_multitenant_tiled_group.argtypes = [i32, vp, pvp, pvp, pvp, pi, pvp, i64, pi64, i64, i32, vp]
         for name in ("bd_pack_signs", "bd_compress", "bd_linear_multitenant", "bd_linear_multitenant_variant",
-                     "bd_materialize", "bd_linear_naive", "bd_probe_read", "bd_probe_copy"):
+                     "bd_materialize", "bd_linear_naive", "bd_probe_read", "bd_probe_copy", "bd_tile_base",
+                     "bd_tile_signs", "bd_linear_multitenant_tiled", "bd_linear_multitenant_tiled_group"):
             getattr(L, name).restype = ctypes.c_int
         _lib = L
     return _lib
@@ -252,3 +263,106 @@ def probe_read(buf: torch.Tensor, sink: torch.Tensor, stream=None) -> None:
 def probe_copy(dst: torch.Tensor, src: torch.Tensor, stream=None) -> None:
     nbytes = src.numel() * src.element_size()
     _check(lib().bd_probe_copy(_ptr(dst), _ptr(src), nbytes, _stream(stream)), "bd_probe_copy")
+
+
+# ---- tiled serving layout ------------------------------------------------------------------
+
+def tiled_base_bytes(out: int, inn: int) -> int:
+    return int(lib().bd_tiled_base_bytes(out, inn))
+
+
+def tiled_signs_bytes(out: int, inn: int) -> int:
+    return int(lib().bd_tiled_signs_bytes(out, inn))
+
+
+def tile_base(w: torch.Tensor, w_tiled: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """bd_tile_base: fp16 [out, in] -> flat fp16 tensor in the serving layout."""
+    _dev(w, torch.float16, "w")
+    out, inn = w.shape
+    if w_tiled is None:
+        w_tiled = torch.empty((max(tiled_base_bytes(out, inn) // 2, 8),), dtype=torch.float16, device=w.device)
+    _check(lib().bd_tile_base(_ptr(w), out, inn, _ptr(w_tiled), _stream(stream)), "bd_tile_base")
+    return w_tiled
+
+
+def tile_signs(packed: torch.Tensor, out: int, inn: int, signs_tiled: Optional[torch.Tensor] = None,
+               stream=None) -> torch.Tensor:
+    """bd_tile_signs: int32 [out, in/32] -> flat int32 tensor in the serving layout."""
+    _dev(packed, torch.int32, "packed")
+    if signs_tiled is None:
+        signs_tiled = torch.empty((max(tiled_signs_bytes(out, inn) // 4, 4),), dtype=torch.int32, device=packed.device)
+    _check(lib().bd_tile_signs(_ptr(packed), out, inn, _ptr(signs_tiled), _stream(stream)), "bd_tile_signs")
+    return signs_tiled
+
+
+class TiledTenantTable:
+    """What the tiled linear takes for one matrix: a HOST array of device pointers to each tenant's
+    tiled delta (None = tenant absent) and the device array of scales."""
+
+    def __init__(self, tiled_by_tenant: Sequence[Optional[torch.Tensor]], alpha_by_tenant):
+        self.tiled = list(tiled_by_tenant)
+        dev = next(t for t in self.tiled if t is not None).device
+        for t in self.tiled:
+            if t is not None:
+                _dev(t, torch.int32, "tiled delta")
+        self.host_ptrs = (ctypes.c_void_p * max(len(self.tiled), 1))(*[_ptr(t) or None for t in self.tiled])
+        if isinstance(alpha_by_tenant, torch.Tensor):
+            self.alpha = alpha_by_tenant.to(device=dev, dtype=torch.float32).reshape(-1).contiguous()
+        else:
+            self.alpha = torch.cat([a.reshape(1).to(torch.float32) for a in alpha_by_tenant]).to(dev).contiguous()
+        if self.alpha.numel() != len(self.tiled):
+            raise ValueError("one alpha per tenant")
+
+    @property
+    def n_tenants(self) -> int:
+        return len(self.tiled)
+
+
+def linear_multitenant_tiled(x: torch.Tensor, w_tiled: torch.Tensor, out: int, tenants: TiledTenantTable,
+                             tenant_of_token: Sequence[int], y: Optional[torch.Tensor] = None, stream=None,
+                             tok_array=None) -> torch.Tensor:
+    """bd_linear_multitenant_tiled: y fp16 [T, out]."""
+    _dev(x, torch.float16, "x")
+    _dev(w_tiled, torch.float16, "w_tiled")
+    T, inn = x.shape
+    if y is None:
+        y = torch.empty((T, out), dtype=torch.float16, device=x.device)
+    _dev(y, torch.float16, "y")
+    tok = tok_array if tok_array is not None else _tok_array(tenant_of_token)
+    _check(lib().bd_linear_multitenant_tiled(_ptr(x), _ptr(w_tiled), tenants.host_ptrs, _ptr(tenants.alpha), tok,
+                                             _ptr(y), T, out, inn, tenants.n_tenants, _stream(stream)),
+           "bd_linear_multitenant_tiled")
+    return y
+
+
+class TiledGroup:
+    """Marshalled arguments of bd_linear_multitenant_tiled_group for a fixed set of matrices."""
+
+    def __init__(self, w_tiled: Sequence[torch.Tensor], outs: Sequence[int], tables: Sequence[TiledTenantTable]):
+        self.n = len(w_tiled)
+        self.keep = (list(w_tiled), list(tables))
+        self.outs = [int(o) for o in outs]
+        nt = tables[0].n_tenants
+        if any(t.n_tenants != nt for t in tables):
+            raise ValueError("every matrix needs the same tenants")
+        self.n_tenants = nt
+        self.w = (ctypes.c_void_p * self.n)(*[_ptr(w) for w in w_tiled])
+        self.signs = (ctypes.c_void_p * (self.n * max(nt, 1)))(
+            *[_ptr(t) or None for tab in tables for t in tab.tiled])
+        self.alpha = (ctypes.c_void_p * self.n)(*[_ptr(tab.alpha) for tab in tables])
+        self.out_arr = (ctypes.c_int64 * self.n)(*self.outs)
+
+
+def linear_multitenant_tiled_group(x: torch.Tensor, group: TiledGroup, tenant_of_token: Sequence[int],
+                                   ys: Optional[Sequence[torch.Tensor]] = None, stream=None, tok_array=None):
+    """bd_linear_multitenant_tiled_group: list of y_m fp16 [T, out_m]."""
+    _dev(x, torch.float16, "x")
+    T, inn = x.shape
+    if ys is None:
+        ys = [torch.empty((T, o), dtype=torch.float16, device=x.device) for o in group.outs]
+    yarr = (ctypes.c_void_p * group.n)(*[_ptr(_dev(y, torch.float16, "y")) for y in ys])
+    tok = tok_array if tok_array is not None else _tok_array(tenant_of_token)
+    _check(lib().bd_linear_multitenant_tiled_group(group.n, _ptr(x), group.w, group.signs, group.alpha, tok, yarr, T,
+                                                   group.out_arr, inn, group.n_tenants, _stream(stream)),
+           "bd_linear_multitenant_tiled_group")
+    return list(ys)

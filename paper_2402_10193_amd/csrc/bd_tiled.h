@@ -1,0 +1,54 @@
+// The serving ("tiled") layout of the base weight and of a packed 1-bit delta, and the kernel
+// arguments of the decode kernel that reads it.
+//
+// A weight matrix [out, in] is cut into tiles of 16 output rows x 256 reduction elements, the
+// unit one wavefront consumes per step.  Inside a tile every byte sits where the matrix-core
+// instruction v_mfma_f32_16x16x32_f16 wants it: MFMA slice v (0..7) covers k = 32 v .. 32 v + 31
+// of the tile, and lane l = (r, g) = (l % 16, l / 16) supplies row r, elements 8 g .. 8 g + 7 of the slice.
+//
+//   base   Wt[rb][kt][v][l][e]  fp16  = W[16 rb + r][256 kt + 32 v + 8 g + e]          (8 KiB per tile)
+//   signs  St[rb][kt][l][v]     byte, bit e = sign of element (16 rb + r, 256 kt + 32 v + 8 g + e)  (512 B per tile)
+//
+// so one 128-bit load per lane fetches a whole slice of the base (1 KiB contiguous per wavefront)
+// and one 64-bit load per lane fetches a tenant's signs of the whole tile (512 B contiguous).
+// Rows beyond `out` and elements beyond `in` are stored as zeros.  Tiles are ordered [rb][kt], kt fastest.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace bd {
+
+constexpr int kTileRows = 16;
+constexpr int kTileK = 256;
+constexpr int kTileBaseBytes = kTileRows * kTileK * 2;   // 8192
+constexpr int kTileSignBytes = kTileRows * kTileK / 8;   // 512
+constexpr int kTiledMaxMats = 3;                         // matrices one launch can cover (q,k,v or gate,up)
+constexpr int kTiledMaxJobs = 16;                        // delta jobs (distinct tenants) per launch
+constexpr int kTiledMaxTokens = 16;                      // one 16-column MFMA tile
+
+inline int64_t tiled_row_blocks(int64_t out) { return (out + kTileRows - 1) / kTileRows; }
+inline int64_t tiled_k_tiles(int64_t in) { return (in + kTileK - 1) / kTileK; }
+
+// Everything the kernel needs arrives in the kernel arguments (scalar loads, no dependent
+// fetch of a pointer table from memory before the first weight load can be issued).
+struct TiledArgs {
+    const uint16_t* x;                                        // [T, in] fp16
+    const uint16_t* wt[kTiledMaxMats];                        // tiled base of each matrix
+    uint16_t* y[kTiledMaxMats];                               // [T, out_m] fp16
+    const float* alpha[kTiledMaxMats];                        // device array indexed by tenant id
+    const uint32_t* signs[kTiledMaxMats][kTiledMaxJobs];      // tiled delta of job slot j, matrix m
+    int32_t out[kTiledMaxMats];
+    int32_t rb_end[kTiledMaxMats];                            // cumulative row blocks: matrix m owns blocks [rb_end[m-1], rb_end[m])
+    int32_t col_token[kTiledMaxTokens];                       // sorted column -> token (row of x and y)
+    int32_t col_job[kTiledMaxTokens];                         // sorted column -> job slot owning it
+    int32_t col_tenant[kTiledMaxTokens];                      // sorted column -> tenant id (for alpha)
+    int32_t T, in, KT, n_mats;
+};
+
+hipError_t launch_tile_base(const uint16_t* w, int64_t out, int64_t in, uint16_t* wt, hipStream_t st);
+hipError_t launch_tile_signs(const uint32_t* packed, int64_t out, int64_t in, uint32_t* st_out, hipStream_t st);
+// n_jobs real job slots (1..16); slots up to the next instantiated count must repeat slot 0's pointers.
+hipError_t launch_linear_decode_tiled(const TiledArgs& args, int n_jobs, hipStream_t st);
+
+}  // namespace bd

@@ -6,13 +6,14 @@
 #include <cstring>
 
 #include "bd_launch.h"
+#include "bd_tiled.h"
 
 namespace {
 
 using bd::DecodeMeta;
 using bd::kMaxDecodeTokens;
 
-constexpr int kVersion = 100;   // 0.1.0
+constexpr int kVersion = 200;   // 0.2.0
 constexpr int kVariantRowWave = 1;
 constexpr int kVariantDefaultMfma = 3;
 
@@ -194,6 +195,130 @@ bd_status bd_linear_multitenant(const uint16_t* x_f16, const uint16_t* w_base_f1
                                 int32_t n_tenants, void* workspace, size_t workspace_bytes, void* stream) {
     return bd_linear_multitenant_variant(x_f16, w_base_f16, packed_by_tenant, alpha_by_tenant, tenant_of_token, y_f16, T,
                                          out, in, n_tenants, workspace, workspace_bytes, stream, 0);
+}
+
+// ---- tiled serving layout ------------------------------------------------------------------
+
+namespace {
+
+bool tiled_shape_ok(int64_t out, int64_t in) {
+    if (out < 0 || in < 0 || in % 32 != 0) return false;
+    if (out > ((int64_t)1 << 31) - 16 || in > ((int64_t)1 << 31) - 256) return false;
+    // 32-bit byte offsets inside one tiled tensor
+    const uint64_t tiles = (uint64_t)bd::tiled_row_blocks(out) * (uint64_t)bd::tiled_k_tiles(in);
+    return tiles * (uint64_t)bd::kTileBaseBytes < ((uint64_t)1 << 32);
+}
+
+}  // namespace
+
+size_t bd_tiled_base_bytes(int64_t out, int64_t in) {
+    if (!tiled_shape_ok(out, in)) return 0;
+    return (size_t)(bd::tiled_row_blocks(out) * bd::tiled_k_tiles(in)) * bd::kTileBaseBytes;
+}
+
+size_t bd_tiled_signs_bytes(int64_t out, int64_t in) {
+    if (!tiled_shape_ok(out, in)) return 0;
+    return (size_t)(bd::tiled_row_blocks(out) * bd::tiled_k_tiles(in)) * bd::kTileSignBytes;
+}
+
+bd_status bd_tile_base(const uint16_t* w_f16, int64_t out, int64_t in, uint16_t* w_tiled, void* stream) {
+    if (!tiled_shape_ok(out, in)) return BD_ERR_SHAPE;
+    if (out == 0 || in == 0) return BD_OK;
+    if (!w_f16 || !w_tiled) return BD_ERR_NULL;
+    if (misaligned(w_f16, 16) || misaligned(w_tiled, 16)) return BD_ERR_ALIGN;
+    if (overlaps(w_tiled, bd_tiled_base_bytes(out, in), w_f16, (size_t)out * in * 2)) return BD_ERR_ALIAS;
+    return bd::launch_tile_base(w_f16, out, in, w_tiled, (hipStream_t)stream) == hipSuccess ? BD_OK : BD_ERR_DEVICE;
+}
+
+bd_status bd_tile_signs(const uint32_t* packed, int64_t out, int64_t in, uint32_t* signs_tiled, void* stream) {
+    if (!tiled_shape_ok(out, in)) return BD_ERR_SHAPE;
+    if (out == 0 || in == 0) return BD_OK;
+    if (!packed || !signs_tiled) return BD_ERR_NULL;
+    if (misaligned(packed, 16) || misaligned(signs_tiled, 16)) return BD_ERR_ALIGN;
+    if (overlaps(signs_tiled, bd_tiled_signs_bytes(out, in), packed, (size_t)out * in / 8)) return BD_ERR_ALIAS;
+    return bd::launch_tile_signs(packed, out, in, signs_tiled, (hipStream_t)stream) == hipSuccess ? BD_OK : BD_ERR_DEVICE;
+}
+
+bd_status bd_linear_multitenant_tiled_group(int32_t n_mats, const uint16_t* x_f16, const uint16_t* const* w_tiled,
+                                            const uint32_t* const* tiled_by_mat_tenant,
+                                            const float* const* alpha_by_mat, const int32_t* tenant_of_token,
+                                            uint16_t* const* y_f16, int64_t T, const int64_t* out, int64_t in,
+                                            int32_t n_tenants, void* stream) {
+    if (n_mats < 1 || n_mats > bd::kTiledMaxMats) return BD_ERR_SHAPE;
+    if (!out) return BD_ERR_NULL;
+    if (T < 0 || n_tenants < 0 || T > 65535) return BD_ERR_SHAPE;
+    int64_t row_blocks = 0;
+    for (int m = 0; m < n_mats; ++m) {
+        if (!tiled_shape_ok(out[m], in)) return BD_ERR_SHAPE;
+        row_blocks += bd::tiled_row_blocks(out[m]);
+    }
+    if (row_blocks > 0x7fffffff) return BD_ERR_SHAPE;
+    if ((uint64_t)T * (uint64_t)in * 2 >= ((uint64_t)1 << 32)) return BD_ERR_SHAPE;   // 32-bit byte offsets into x
+    if (T == 0 || row_blocks == 0) return BD_OK;
+    if (!x_f16 || !w_tiled || !tiled_by_mat_tenant || !alpha_by_mat || !tenant_of_token || !y_f16) return BD_ERR_NULL;
+    if (misaligned(x_f16, 16)) return BD_ERR_ALIGN;
+    for (int64_t t = 0; t < T; ++t)
+        if (tenant_of_token[t] < 0 || tenant_of_token[t] >= n_tenants) return BD_ERR_TENANT;
+    for (int m = 0; m < n_mats; ++m) {
+        if (out[m] == 0) continue;
+        if (!w_tiled[m] || !alpha_by_mat[m] || !y_f16[m]) return BD_ERR_NULL;
+        if (misaligned(w_tiled[m], 16) || misaligned(y_f16[m], 2) || misaligned(alpha_by_mat[m], 4)) return BD_ERR_ALIGN;
+        const size_t ybytes = (size_t)T * out[m] * 2;
+        if (overlaps(y_f16[m], ybytes, x_f16, (size_t)T * in * 2) ||
+            overlaps(y_f16[m], ybytes, w_tiled[m], bd_tiled_base_bytes(out[m], in)))
+            return BD_ERR_ALIAS;
+        for (int64_t t = 0; t < T; ++t) {
+            const uint32_t* p = tiled_by_mat_tenant[(size_t)m * n_tenants + tenant_of_token[t]];
+            if (!p) return BD_ERR_NULL;
+            if (misaligned(p, 16)) return BD_ERR_ALIGN;
+        }
+    }
+    // in == 0 (empty reduction) needs no special case: the kernel runs zero steps and writes y = 0
+
+    for (int64_t t0 = 0; t0 < T; t0 += bd::kTiledMaxTokens) {
+        const int n = (int)std::min<int64_t>(bd::kTiledMaxTokens, T - t0);
+        DecodeMeta meta;
+        build_meta(tenant_of_token, t0, n, &meta);   // n <= 16: everything is in column tile 0
+        bd::TiledArgs a;
+        std::memset(&a, 0, sizeof(a));
+        a.x = x_f16 + t0 * in;
+        a.T = n;
+        a.in = (int32_t)in;
+        a.KT = (int32_t)bd::tiled_k_tiles(in);
+        int32_t rb = 0;
+        int mats = 0;
+        const int n_jobs = meta.tile_job_end[0] - meta.tile_job_begin[0];
+        for (int m = 0; m < n_mats; ++m) {
+            if (out[m] == 0) continue;
+            a.wt[mats] = w_tiled[m];
+            a.y[mats] = y_f16[m] + t0 * out[m];
+            a.alpha[mats] = alpha_by_mat[m];
+            a.out[mats] = (int32_t)out[m];
+            rb += (int32_t)bd::tiled_row_blocks(out[m]);
+            a.rb_end[mats] = rb;
+            for (int sl = 0; sl < bd::kTiledMaxJobs; ++sl)   // slots beyond the jobs repeat slot 0 (never selected)
+                a.signs[mats][sl] = tiled_by_mat_tenant[(size_t)m * n_tenants + meta.slot_tenant[0][sl < n_jobs ? sl : 0]];
+            ++mats;
+        }
+        a.n_mats = mats;
+        for (int col = 0; col < bd::kTiledMaxTokens; ++col) {
+            a.col_token[col] = col < n ? meta.token_of_col[col] : 0;
+            a.col_tenant[col] = col < n ? meta.tenant_of_col[col] : 0;
+            a.col_job[col] = -1;
+            for (int sl = 0; sl < n_jobs; ++sl)
+                if (col >= meta.slot_col_begin[0][sl] && col < meta.slot_col_end[0][sl]) a.col_job[col] = sl;
+        }
+        if (bd::launch_linear_decode_tiled(a, n_jobs, (hipStream_t)stream) != hipSuccess) return BD_ERR_DEVICE;
+    }
+    return BD_OK;
+}
+
+bd_status bd_linear_multitenant_tiled(const uint16_t* x_f16, const uint16_t* w_tiled,
+                                      const uint32_t* const* tiled_by_tenant, const float* alpha_by_tenant,
+                                      const int32_t* tenant_of_token, uint16_t* y_f16, int64_t T, int64_t out, int64_t in,
+                                      int32_t n_tenants, void* stream) {
+    return bd_linear_multitenant_tiled_group(1, x_f16, &w_tiled, tiled_by_tenant, &alpha_by_tenant, tenant_of_token, &y_f16,
+                                             T, &out, in, n_tenants, stream);
 }
 
 bd_status bd_group_tokens(const int32_t* tenant_of_token, int32_t T, int32_t* token_of_col, int32_t* job_tenant,

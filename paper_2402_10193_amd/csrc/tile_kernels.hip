@@ -1,0 +1,65 @@
+// Row-major -> tiled serving layout (see bd_tiled.h).  Offline, like the compressor: run once
+// per base matrix and once per (tenant, matrix) delta.
+#include "bd_device.h"
+#include "bd_tiled.h"
+
+namespace bd {
+
+// One thread per 16-byte unit of the tiled base: unit ((rb KT + kt) 8 + v) 64 + l holds
+// W[16 rb + l % 16][256 kt + 32 v + 8 (l / 16) .. + 8].
+__global__ __launch_bounds__(256) void tile_base_kernel(const uint16_t* __restrict__ w, u32x4* __restrict__ wt,
+                                                         const int64_t out, const int64_t in, const int64_t KT,
+                                                         const int64_t n_units) {
+    for (int64_t u = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; u < n_units; u += (int64_t)gridDim.x * blockDim.x) {
+        const int l = (int)(u & 63), v = (int)((u >> 6) & 7);
+        const int64_t tile = u >> 9, kt = tile % KT, rb = tile / KT;
+        const int64_t row = rb * kTileRows + (l & 15), k = kt * kTileK + 32 * v + 8 * (l >> 4);
+        u32x4 val = {0u, 0u, 0u, 0u};
+        if (row < out && k < in) val = *(const u32x4*)(w + row * in + k);   // in % 8 == 0: the 8 elements are all inside
+        wt[u] = val;
+    }
+}
+
+// One thread per lane slot of the tiled signs: slot (rb KT + kt) 64 + l holds 8 bytes, byte v =
+// bits 8 g .. 8 g + 7 of packed word 8 kt + v of row 16 rb + l % 16   (g = l / 16).
+__global__ __launch_bounds__(256) void tile_signs_kernel(const uint32_t* __restrict__ packed, u32x2* __restrict__ st,
+                                                          const int64_t out, const int64_t in, const int64_t KT,
+                                                          const int64_t n_slots) {
+    const int64_t words_per_row = in >> 5;
+    for (int64_t u = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; u < n_slots; u += (int64_t)gridDim.x * blockDim.x) {
+        const int l = (int)(u & 63);
+        const int64_t tile = u >> 6, kt = tile % KT, rb = tile / KT;
+        const int64_t row = rb * kTileRows + (l & 15);
+        const int sh = 8 * (l >> 4);
+        u32x2 val = {0u, 0u};
+        if (row < out) {
+#pragma unroll
+            for (int v = 0; v < 8; ++v) {
+                const int64_t wi = kt * 8 + v;
+                const uint32_t byte = wi < words_per_row ? ((packed[row * words_per_row + wi] >> sh) & 0xFFu) : 0u;
+                val[v >> 2] |= byte << (8 * (v & 3));
+            }
+        }
+        st[u] = val;
+    }
+}
+
+static unsigned grid_for(int64_t n, int block) {
+    int64_t g = (n + block - 1) / block;
+    return (unsigned)(g < 1 ? 1 : (g > 65536 ? 65536 : g));
+}
+
+hipError_t launch_tile_base(const uint16_t* w, int64_t out, int64_t in, uint16_t* wt, hipStream_t st) {
+    const int64_t KT = tiled_k_tiles(in), n_units = tiled_row_blocks(out) * KT * (kTileBaseBytes / 16);
+    hipLaunchKernelGGL(tile_base_kernel, dim3(grid_for(n_units, 256)), dim3(256), 0, st, w, (u32x4*)wt, out, in, KT, n_units);
+    return hipGetLastError();
+}
+
+hipError_t launch_tile_signs(const uint32_t* packed, int64_t out, int64_t in, uint32_t* st_out, hipStream_t st) {
+    const int64_t KT = tiled_k_tiles(in), n_slots = tiled_row_blocks(out) * KT * 64;
+    hipLaunchKernelGGL(tile_signs_kernel, dim3(grid_for(n_slots, 256)), dim3(256), 0, st, packed, (u32x2*)st_out, out, in, KT,
+                       n_slots);
+    return hipGetLastError();
+}
+
+}  // namespace bd
