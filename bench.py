@@ -3,10 +3,13 @@
 
 Workload: the linears of Llama-2-7B (32 decoder layers x q,k,v,o,gate,up,down), one fp16 base model shared by
 B = 16 tenants, each tenant with its own 1-bit delta of every matrix, one decode token per tenant.  A step is
-one pass over the whole stack (224 calls of bd_linear_multitenant), i.e. B tokens decoded; every layer has its
-own weights (25.9 GB in total), so nothing is served from cache.  Deltas are produced by bd_compress from
-synthetic fine-tuned weights before the timed region (compression is offline in the paper; its rate is
-reported separately under "extras").
+one pass over the whole stack, i.e. B tokens decoded; every layer has its own weights (25.9 GB in total), so
+nothing is served from cache.  Deltas are produced by bd_compress from synthetic fine-tuned weights and, like
+the base, re-laid into the serving layout (bd_tile_signs / bd_tile_base) before the timed region: compression
+and re-layout are offline (their rate is reported under "extras").  --path chooses the serving path:
+  tiled-fused  (default) 4 launches per layer: q,k,v in one grouped call, o, gate+up in one grouped call, down
+  tiled        7 launches per layer, bd_linear_multitenant_tiled
+  rowmajor     7 launches per layer, bd_linear_multitenant on the row-major tensors
 
 Prints ONE JSON line: decode tokens/s, the HBM roofline of the decode kernel, and the CPU oracle timed on the
 host cores on one layer of the same workload.
@@ -32,7 +35,8 @@ def parse():
     ap.add_argument("--tenants", type=int, default=16, help="B: tenants = decode tokens per step")
     ap.add_argument("--layers", type=int, default=32, help="decoder layers in the stack (32 = Llama-2-7B)")
     ap.add_argument("--model", choices=["7b", "70b"], default="7b")
-    ap.add_argument("--variant", type=int, default=0, help="kernel variant (0 = library's choice)")
+    ap.add_argument("--variant", type=int, default=0, help="row-major path: kernel variant (0 = library's choice)")
+    ap.add_argument("--path", choices=["tiled-fused", "tiled", "rowmajor"], default="tiled-fused")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
     ap.add_argument("--no-extras", action="store_true", help="skip naive baseline, read probe, compress rate")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
@@ -89,20 +93,52 @@ def main():
                 packed.append(p)
                 alphas.append(a)
                 del ft
-            mats.append((name, out, inn, base, bd.TenantTable(packed, alphas)))
+            table = bd.TenantTable(packed, alphas)
+            wt = ttable = None
+            if args.path != "rowmajor":
+                wt = bd.tile_base(base)
+                ttable = bd.TiledTenantTable([bd.tile_signs(p, out, inn) for p in packed], table.alpha)
+                if li > 0:          # layer 0 keeps its row-major tensors for the naive baseline below
+                    base = table = None
+            mats.append((name, out, inn, base, table, wt, ttable))
         layers.append(mats)
     xs = {inn: synth.activations(B, inn, device=dev, tag=("bench", inn)) for _, _, inn in shapes}
     ys = {(name, out): torch.empty((B, out), dtype=torch.float16, device=dev) for name, out, _ in shapes}
     torch.cuda.synchronize()
     t_setup = time.time() - t_setup
 
-    def run_stack():
-        for mats in layers:
-            for name, out, inn, base, table in mats:
-                bd.linear_multitenant(xs[inn], base, table, tok, y=ys[(name, out)], variant=args.variant,
-                                      tok_array=tok_arr)
+    plans = []          # one list of launch closures per layer
+    for mats in layers:
+        by = {m[0]: m for m in mats}
+        plan = []
+        if args.path == "rowmajor":
+            for name, out, inn, base, table, _, _ in mats:
+                plan.append(lambda inn=inn, base=base, table=table, y=ys[(name, out)]: bd.linear_multitenant(
+                    xs[inn], base, table, tok, y=y, variant=args.variant, tok_array=tok_arr))
+        elif args.path == "tiled":
+            for name, out, inn, _, _, wt, ttable in mats:
+                plan.append(lambda inn=inn, out=out, wt=wt, ttable=ttable, y=ys[(name, out)]: bd.linear_multitenant_tiled(
+                    xs[inn], wt, out, ttable, tok, y=y, tok_array=tok_arr))
+        else:
+            def grouped(names):
+                ms = [by[n] for n in names]
+                g = bd.TiledGroup([m[5] for m in ms], [m[1] for m in ms], [m[6] for m in ms])
+                yl = [ys[(m[0], m[1])] for m in ms]
+                return lambda g=g, yl=yl, inn=ms[0][2]: bd.linear_multitenant_tiled_group(xs[inn], g, tok, ys=yl,
+                                                                                           tok_array=tok_arr)
+            def single(n):
+                m = by[n]
+                return lambda m=m: bd.linear_multitenant_tiled(xs[m[2]], m[5], m[1], m[6], tok, y=ys[(m[0], m[1])],
+                                                               tok_array=tok_arr)
+            plan = [grouped(["q", "k", "v"]), single("o"), grouped(["gate", "up"]), single("down")]
+        plans.append(plan)
 
-    launches_per_step = n_layers * len(shapes)
+    def run_stack():
+        for plan in plans:
+            for launch in plan:
+                launch()
+
+    launches_per_step = sum(len(p) for p in plans)
     P = sum(o * i for _, o, i in shapes)
     xy_bytes = sum(B * (i + o) * 2 for _, o, i in shapes)
     bytes_per_step = n_layers * (2.0 * P + B * P / 8.0 + xy_bytes)     # algorithmic: W once, each delta once, x, y
@@ -160,7 +196,7 @@ def main():
                         f"B={B} tenants, one decode token per tenant, distinct 1-bit delta per (tenant, matrix)",
             "tenants": B, "layers": n_layers, "launches_per_step": launches_per_step,
             "launch": "hip graph replay" if graph is not None else "eager",
-            "kernel_variant": args.variant,
+            "path": args.path, "kernel_variant": args.variant,
         },
         "roofline": {
             "bound": "hbm",
@@ -169,7 +205,7 @@ def main():
             "unit": "GB/s",
             "frac": round(achieved_gbs / HBM_PEAK_GBS, 4),
             "traffic": None,
-            "kernel": "linear_decode_mfma_kernel",
+            "kernel": "linear_decode_mfma_kernel" if args.path == "rowmajor" else "linear_decode_tiled_kernel",
             "bytes_per_launch": round(bytes_per_step / launches_per_step, 1),
             "avg_launch_us": round(ms_per_step * 1e3 / launches_per_step, 3),
         },
@@ -181,7 +217,7 @@ def main():
     if args.per_linear:
         per = {}
         for name, out, inn in [s for s in shapes if s[0] in ("q", "k", "gate", "down")]:
-            mats = [(m[3], m[4]) for L in layers for m in L if m[0] == name]
+            mats = [(m[3], m[4]) for L in layers for m in L if m[0] == name and m[3] is not None]
             for base, table in mats[:2]:
                 bd.linear_multitenant(xs[inn], base, table, tok, y=ys[(name, out)], variant=args.variant, tok_array=tok_arr)
             torch.cuda.synchronize()
@@ -216,7 +252,7 @@ def main():
         # (b) the naive system of the paper: every tenant keeps a full fp16 copy.  One layer (B x 405 MB) timed.
         mats0 = layers[0]
         naive = []
-        for name, out, inn, base, table in mats0:
+        for name, out, inn, base, table, _, _ in mats0:
             wts = [bd.materialize(base, table.packed[t], table.alpha[t:t + 1]) for t in range(B)]
             naive.append((name, out, inn, bd.WeightTable(wts)))
         # two copies of the layer so that the second pass does not find the first in the memory-side cache
