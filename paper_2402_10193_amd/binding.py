@@ -12,7 +12,8 @@ from typing import List, Optional, Sequence
 import torch
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_PKG, "libbitdelta.so")
+# BITDELTA_LIB may name another build of the same library (e.g. an instrumented one)
+LIB_PATH = os.environ.get("BITDELTA_LIB") or os.path.join(_PKG, "libbitdelta.so")
 
 BD_OK = 0
 STATUS_NAMES = {0: "BD_OK", 1: "BD_ERR_NULL", 2: "BD_ERR_SHAPE", 3: "BD_ERR_ALIGN", 4: "BD_ERR_TENANT",

@@ -15,13 +15,19 @@
 // matrix pipe.  (Expanding with and-or instructions costs >= 8 per 8 signs and, at one token per
 // tenant, makes the vector ALU the bottleneck long before HBM.)
 //
-// Decomposition.  A workgroup owns 16 output rows; its wavefronts split the k tiles into
-// contiguous ranges.  Per tile a wavefront needs 8 KiB of base (8 loads), 512 B of signs per
-// job (one 64-bit load per lane) and the 16 x 256 block of x, which each lane loads straight
-// from global memory (L2 hits) in B-operand order: no staging, no barrier in the loop.
-// Everything of step s+1 is requested while step s is being multiplied: W[v] right after its
-// MFMA, the signs of job j right after their addresses are formed, x into a second register
-// set.  Partial sums of the wavefronts are added in a fixed order through LDS; y is written once.
+// Decomposition.  The grid is persistent: one workgroup per compute unit, each owning a
+// contiguous range of the launch's 16-row blocks (all matrices of a grouped launch laid end to
+// end); its wavefronts split the k tiles into contiguous ranges.  A task = one (row block, k tile):
+// 8 KiB of base (8 loads of 1 KiB), 512 B of signs per job (one 64-bit load per lane) and the
+// 16 x 256 block of x, which each lane loads straight from global memory (L2 hits) in B-operand
+// order: no staging, no barrier in the loop.  When a wavefront has at most two k tiles its x
+// stays in registers for all of its row blocks (x is then fetched once per workgroup instead
+// of once per task; the L1 is an in-order queue, so every x request it does not carry leaves
+// room for a weight request).  Otherwise x is double-buffered per task.
+// Everything of task t+1 is requested while task t is being multiplied: W[v] right after its
+// MFMA, the signs of job j right after their addresses are formed.  Per row block the
+// wavefronts' partial tiles go to LDS slots and are added in a fixed order when the slots are
+// full or the work is done; y is written once.
 #include <type_traits>
 
 #include "bd_device.h"
@@ -34,6 +40,23 @@ namespace {
 constexpr int kLutBytes = 256 * 16 * 16;          // 256 entries x 16 copies x 16 B
 constexpr int kRedBytesPerWave = 16 * 16 * 4;     // one 16 x 16 fp32 tile
 constexpr int kMaxWavesTiled = 8;
+// x staging of one wavefront: 16 token rows x (512 B + 16 B pad), the pad spreads the 16 rows over all banks
+constexpr int kStageRowBytes = kTileK * 2 + 16;
+constexpr int kStageBytes = 16 * kStageRowBytes;
+// LDS after the table: one region per wavefront = slots for the partial tiles of finished row blocks.
+// Resident x is staged there before the first task (the slots overlay the staging rows).
+template <int XSTEPS> struct LdsPlan {
+    static constexpr int kRedSlots = 8;
+    static constexpr int kRegion = (XSTEPS > 0 && kStageBytes > kRedSlots * kRedBytesPerWave) ? kStageBytes : kRedSlots * kRedBytesPerWave;
+    static constexpr int kTotal = kLutBytes + kMaxWavesTiled * kRegion;
+};
+static_assert(LdsPlan<0>::kTotal <= 160 * 1024 && LdsPlan<2>::kTotal <= 160 * 1024, "LDS budget");
+
+__device__ __forceinline__ void lds_wave_sync() {   // order this wavefront's LDS writes before its later reads
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
 
 typedef const void __attribute__((address_space(1)))* gptr_t;
 typedef const u32x4 __attribute__((address_space(3)))* lds_u32x4_ptr;
@@ -48,88 +71,84 @@ __device__ __forceinline__ u32x4 ldg16(const unsigned char* base, uint32_t off) 
     return *(const u32x4*)(base + off);
 }
 
-// The eight operands of one job's tile: byte v of the lane's sign words -> table entry.
+// The MFMA operand of slice v of a job's tile: byte v of the lane's sign words -> table entry.
 // `lanebits` = 16 * (lane % 16) in byte 0; the selector puts sign byte (v % 4) of word v / 4
 // into byte 1 and zeros above: address = 256 * byte + 16 * copy (the table starts at LDS address 0).
-__device__ __forceinline__ void lut_issue(const u32x2 s, const uint32_t lanebits, u32x4 (&a)[8]) {
-#pragma unroll
-    for (int v = 0; v < 8; ++v) {
-        const uint32_t addr = __builtin_amdgcn_perm(s[v >> 2], lanebits, 0x0C0C0000u | ((4u + (v & 3)) << 8));
-        a[v] = *(lds_u32x4_ptr)(uintptr_t)addr;
-    }
+__device__ __forceinline__ u32x4 lut_read(const u32x2 s, const int v, const uint32_t lanebits) {
+    const uint32_t addr = __builtin_amdgcn_perm(s[v >> 2], lanebits, 0x0C0C0000u | ((4u + (v & 3)) << 8));
+    return *(lds_u32x4_ptr)(uintptr_t)addr;
 }
 
 }  // namespace
 
-template <int NJ>
+// XSTEPS = 1 or 2: every wavefront has exactly that many k tiles and keeps their x in registers.
+// XSTEPS = 0: any number of k tiles per wavefront, x double-buffered per task.
+template <int NJ, int XSTEPS>
 __global__ __launch_bounds__(kMaxWavesTiled * kWave) void linear_decode_tiled_kernel(const TiledArgs a) {
-    extern __shared__ __align__(16) unsigned char smem[];   // [0, 64 KiB): table; then one fp32 tile per wavefront
+    extern __shared__ __align__(16) unsigned char smem[];   // [0, 64 KiB): table; then one region per wavefront
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int nw = blockDim.x >> 6;
     const int c = lane & 15;   // A row (output row) for loads, B/D column (token) for MFMA operands and results
     const int g = lane >> 4;
-
-    // which matrix of the launch this workgroup belongs to
-    int m = 0, rb = blockIdx.x;
-    if (a.n_mats > 1 && rb >= a.rb_end[0]) m = 1;
-    if (a.n_mats > 2 && rb >= a.rb_end[1]) m = 2;
-    if (m > 0) rb -= a.rb_end[m - 1];
-    const int KT = a.KT;
-    const int kb = wave * KT / nw, ke = (wave + 1) * KT / nw;   // this wavefront's k tiles
-    const int steps = ke - kb;
-
-    const unsigned char* wt = (const unsigned char*)a.wt[m];
-    const unsigned char* xg = (const unsigned char*)a.x;
-    const unsigned char* sp[NJ];
-#pragma unroll
-    for (int j = 0; j < NJ; ++j) sp[j] = (const unsigned char*)a.signs[m][j];
-    uint32_t woff = (uint32_t)(rb * KT + kb) * (uint32_t)kTileBaseBytes + (uint32_t)lane * 16u;
-    uint32_t soff = (uint32_t)(rb * KT + kb) * (uint32_t)kTileSignBytes + (uint32_t)lane * 8u;
-
-    // this lane's column: token row of x, owning job, scale
-    int tok = a.col_token[0], myjob = -1, tenant = 0;
-#pragma unroll
-    for (int i = 0; i < kTiledMaxTokens; ++i) {
-        tok = (c == i && i < a.T) ? a.col_token[i] : tok;
-        myjob = (c == i && i < a.T) ? a.col_job[i] : myjob;
-        tenant = (c == i && i < a.T) ? a.col_tenant[i] : tenant;
+    using Plan = LdsPlan<XSTEPS>;
+    // Touch every 64-byte line of the kernel arguments at once: the first read of a line is a trip
+    // to memory, and taken one after the other (pointer tables are indexed by values read before)
+    // those trips would delay the first weight request by microseconds.
+    {
+        const unsigned char __attribute__((address_space(4)))* ka =
+            (const unsigned char __attribute__((address_space(4)))*)__builtin_amdgcn_kernarg_segment_ptr();
+        uint32_t t0, t1, t2, t3, t4, t5, t6, t7, t8, t9, t10;
+        asm volatile(
+            "s_load_dword %0, %11, 0x0\n s_load_dword %1, %11, 0x40\n s_load_dword %2, %11, 0x80\n"
+            "s_load_dword %3, %11, 0xc0\n s_load_dword %4, %11, 0x100\n s_load_dword %5, %11, 0x140\n"
+            "s_load_dword %6, %11, 0x180\n s_load_dword %7, %11, 0x1c0\n s_load_dword %8, %11, 0x200\n"
+            "s_load_dword %9, %11, 0x240\n s_load_dword %10, %11, 0x280\n s_waitcnt lgkmcnt(0)"
+            : "=&s"(t0), "=&s"(t1), "=&s"(t2), "=&s"(t3), "=&s"(t4), "=&s"(t5), "=&s"(t6), "=&s"(t7), "=&s"(t8), "=&s"(t9),
+              "=&s"(t10)
+            : "s"(ka));
+        static_assert(sizeof(TiledArgs) <= 0x2c0, "touch every line of the arguments");
     }
-    // columns beyond T read token col_token[0]'s x (valid memory); their results are never stored
-    uint32_t xoff = (uint32_t)tok * (uint32_t)a.in * 2u + (uint32_t)g * 16u + (uint32_t)kb * (uint32_t)(kTileK * 2);
-    const int k_ragged = (a.in % kTileK != 0) ? KT - 1 : -1;   // the tile that reaches beyond `in`, if any
+    const int KT = a.KT;
+    const int rb_total = a.rb_end[a.n_mats - 1];
+    // this workgroup's row blocks [r0, r1) of the concatenated matrices (the host keeps grid <= rb_total)
+    const int r0 = (int)((int64_t)blockIdx.x * rb_total / gridDim.x);
+    const int r1 = (int)((int64_t)(blockIdx.x + 1) * rb_total / gridDim.x);
+    const int n_rb = r1 - r0;
+    const int kb = wave * KT / nw, ke = (wave + 1) * KT / nw;   // this wavefront's k tiles
+    const int steps = XSTEPS > 0 ? XSTEPS : ke - kb;
+    const bool have_work = n_rb > 0 && steps > 0;
 
-    auto load_x = [&](u32x4 (&xr)[8], const int kt, const uint32_t off) {
-        if (kt != k_ragged) {
-#pragma unroll
-            for (int v = 0; v < 8; ++v) xr[v] = ldg16(xg, off + v * 64);
-        } else {
-#pragma unroll
-            for (int v = 0; v < 8; ++v) {
-                xr[v] = u32x4{0u, 0u, 0u, 0u};
-                if (kt * kTileK + 32 * v + 8 * g < a.in) xr[v] = ldg16(xg, off + v * 64);
-            }
-        }
+    auto mat_of = [&](const int rbg, int& m, int& rb) {
+        m = 0;
+        if (a.n_mats > 1 && rbg >= a.rb_end[0]) m = 1;
+        if (a.n_mats > 2 && rbg >= a.rb_end[1]) m = 2;
+        rb = rbg - (m > 0 ? a.rb_end[m - 1] : 0);
     };
 
-    // ---- requests of the first step, in the order they are consumed
-    u32x4 wr[8], xc[8];
-    u32x2 sr[NJ];
-    if (steps > 0) {
+    // ---- pointers of the matrix whose tiles are being REQUESTED (the task being multiplied only
+    // needs registers); reloaded from the kernel arguments when the requests cross into the next matrix
+    int m_req, rb_req;
+    mat_of(r0, m_req, rb_req);
+    const unsigned char* wt = (const unsigned char*)a.wt[m_req];
+    const unsigned char* sp[NJ];
 #pragma unroll
-        for (int v = 0; v < 8; ++v) wr[v] = ldg16_stream(wt, woff + v * 1024);
-        load_x(xc, kb, xoff);
-#pragma unroll
-        for (int j = 0; j < NJ; ++j) sr[j] = ldg8_stream(sp[j], soff);
-    } else {
-#pragma unroll
-        for (int v = 0; v < 8; ++v) wr[v] = xc[v] = u32x4{0u, 0u, 0u, 0u};
-#pragma unroll
-        for (int j = 0; j < NJ; ++j) sr[j] = u32x2{0u, 0u};
-    }
-    const float alpha_c = a.alpha[m][tenant];
+    for (int j = 0; j < NJ; ++j) sp[j] = (const unsigned char*)a.signs[m_req][j];
+    const uint32_t lane16 = (uint32_t)lane * 16u, lane8 = (uint32_t)lane * 8u;
 
-    // ---- the table: entry b, copy cp at 256 b + 16 cp; element e = bit e of b ? +1.0 : -1.0
+    // ---- requests of the first task: base first, (table,) then x, then the signs
+    u32x4 wr[8];
+    u32x2 sr[NJ];
+    const uint32_t tile0 = (uint32_t)(rb_req * KT + kb);
+    if (have_work) {
+#pragma unroll
+        for (int v = 0; v < 8; ++v) wr[v] = ldg16_stream(wt, tile0 * (uint32_t)kTileBaseBytes + lane16 + v * 1024);
+    }
+
+    // ---- the table: entry b, copy cp at 256 b + 16 cp; element e = bit e of b ? +1.0 : -1.0.
+    // Built (and the workgroup synchronised) while only the first base requests are in flight: the
+    // later requests queue up behind the memory system, and a barrier behind them would hold the
+    // first multiplications back by microseconds.
     for (int idx = threadIdx.x; idx < 256 * 16; idx += blockDim.x) {
         const uint32_t b = (uint32_t)idx >> 4;
         u32x4 e;
@@ -139,86 +158,233 @@ __global__ __launch_bounds__(kMaxWavesTiled * kWave) void linear_decode_tiled_ke
         *(u32x4*)(smem + idx * 16) = e;
     }
     __syncthreads();
+
+
+    // x of one k tile is a [16 tokens][256] fp16 block.  It is fetched with loads whose lanes are
+    // contiguous in memory (load i: token rows 2i and 2i+1, 512 B each) and brought into B-operand
+    // order (lane (c, g): row c, elements 32 v + 8 g ..) through this wavefront's LDS staging rows:
+    // fetching it in operand order directly would make every lane its own 16-byte access.
+    // Rows of columns beyond T read token col_token[0] (valid memory); their results are never stored.
+    const unsigned char* xg = (const unsigned char*)a.x;
+    const int xh = lane >> 5;                                   // which of the two rows of a load
+    const uint32_t xcol = (uint32_t)(lane & 31) * 16u;          // byte inside the tile row
+    const int k_ragged = (a.in % kTileK != 0) ? KT - 1 : -1;    // the tile that reaches beyond `in`, if any
+    const uint32_t row_bytes = (uint32_t)a.in * 2u;
+    auto x_fetch = [&](u32x4 (&xraw)[8], const int kt) {
+        uint32_t xc = xcol;
+        asm volatile("" : "+v"(xc));   // keep "base + lane offset" a 32-bit offset (see task())
+        const uint32_t off = xc + (uint32_t)kt * (uint32_t)(kTileK * 2);
+        const bool inside = (kt != k_ragged) || (kt * kTileK + (lane & 31) * 8 < a.in);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int ra = 2 * i < a.T ? a.col_token[2 * i] : a.col_token[0];
+            const int rbw = 2 * i + 1 < a.T ? a.col_token[2 * i + 1] : a.col_token[0];
+            const uint32_t tokoff = (uint32_t)(xh ? rbw : ra) * row_bytes;
+            xraw[i] = u32x4{0u, 0u, 0u, 0u};
+            if (inside) xraw[i] = ldg16(xg, tokoff + off);
+        }
+    };
+    // Streamed x (a fresh tile per task) is fetched in operand order directly: lane (c, g), slice v reads
+    // x[token of column c][256 kt + 32 v + 8 g ..]; a trip through LDS per task would sit on the critical path.
+    int tok_c = a.col_token[0];
+#pragma unroll
+    for (int i = 0; i < kTiledMaxTokens; ++i) tok_c = (c == i && i < a.T) ? a.col_token[i] : tok_c;
+    const uint32_t xlane = (uint32_t)tok_c * row_bytes + (uint32_t)g * 16u;
+    auto x_fetch_operands = [&](u32x4 (&xop)[8], const int kt) {
+        uint32_t xl = xlane;
+        asm volatile("" : "+v"(xl));
+        const uint32_t off = xl + (uint32_t)kt * (uint32_t)(kTileK * 2);
+        if (kt != k_ragged) {
+#pragma unroll
+            for (int v = 0; v < 8; ++v) xop[v] = ldg16(xg, off + v * 64);
+        } else {
+#pragma unroll
+            for (int v = 0; v < 8; ++v) {
+                xop[v] = u32x4{0u, 0u, 0u, 0u};
+                if (kt * kTileK + 32 * v + 8 * g < a.in) xop[v] = ldg16(xg, off + v * 64);
+            }
+        }
+    };
+    unsigned char* const region = smem + kLutBytes + wave * Plan::kRegion;
+    auto x_to_operands = [&](const u32x4 (&xraw)[8], u32x4 (&xop)[8]) {
+        lds_wave_sync();   // earlier reads of the staging rows are done
+#pragma unroll
+        for (int i = 0; i < 8; ++i) *(u32x4*)(region + (2 * i + xh) * kStageRowBytes + xcol) = xraw[i];
+        lds_wave_sync();
+#pragma unroll
+        for (int v = 0; v < 8; ++v) xop[v] = *(const u32x4*)(region + c * kStageRowBytes + 64 * v + 16 * g);
+    };
+
+    constexpr int XR = XSTEPS > 0 ? XSTEPS : 1;   // x register sets in operand order
+    u32x4 xs[XR][8];
+    u32x4 xraw[XR][8];                            // resident x as fetched; streamed x: the next task's operands
+    if (have_work) {
+        if constexpr (XSTEPS > 0) x_fetch(xraw[0], kb);
+        else x_fetch_operands(xs[0], kb);
+        const uint32_t soff0 = tile0 * (uint32_t)kTileSignBytes + lane8;
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) sr[j] = ldg8_stream(sp[j], soff0);
+        if constexpr (XSTEPS == 2) x_fetch(xraw[1], kb + 1);
+    }
+
+    // this lane's column: owning job, tenant (for the scale)
+    int myjob = -1, tenant = 0;
+#pragma unroll
+    for (int i = 0; i < kTiledMaxTokens; ++i) {
+        myjob = (c == i && i < a.T) ? a.col_job[i] : myjob;
+        tenant = (c == i && i < a.T) ? a.col_tenant[i] : tenant;
+    }
+    float alpha_m[kTiledMaxMats];
+#pragma unroll
+    for (int m = 0; m < kTiledMaxMats; ++m) alpha_m[m] = m < a.n_mats ? a.alpha[m][tenant] : 0.f;
+
+    if (!have_work) return;   // uniform per workgroup (n_rb) / never true for steps (host: waves <= k tiles)
+#pragma unroll
+    for (int i = 0; i < (XSTEPS > 0 ? XR : 0); ++i) x_to_operands(xraw[i], xs[i]);
     const uint32_t lanebits = (uint32_t)c << 4;
 
     float4v accb = {0.f, 0.f, 0.f, 0.f}, dsel = {0.f, 0.f, 0.f, 0.f};
 
-    // One step = one tile.  MORE: there is a next tile, request it while this one is multiplied.
-    auto step = [&](auto more_tag, const int kt) {
+    // One task.  MORE: there is a next task; its tile index is tile_next and its pointers are
+    // current (wt, sp).  xr: this task's x in operand order; with streamed x the next tile (kt_next) is
+    // fetched into xnext during the task and replaces xr at its end.
+    auto task = [&](auto more_tag, u32x4 (&xr)[8], const uint32_t tile_next, u32x4 (&xnext)[8], const int kt_next) {
         constexpr bool MORE = decltype(more_tag)::value;
-        // ---- base product; W[v] of the next tile goes into the register group just read
-        if constexpr (MORE) woff += kTileBaseBytes;
+        // The lane offsets pass through an empty asm in every task: otherwise the compiler hoists
+        // "uniform base + lane offset" of every load out of the loop as a 64-bit register pair per load.
+        uint32_t l16 = lane16, l8 = lane8;
+        asm volatile("" : "+v"(l16), "+v"(l8));
+        const uint32_t woff = tile_next * (uint32_t)kTileBaseBytes + l16, soff = tile_next * (uint32_t)kTileSignBytes + l8;
+        // ---- base product; W[v] of the next task goes into the register group just read
 #pragma unroll
         for (int v = 0; v < 8; ++v) {
-            accb = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8, wr[v]), __builtin_bit_cast(half8, xc[v]),
+            accb = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8, wr[v]), __builtin_bit_cast(half8, xr[v]),
                                                           accb, 0, 0, 0);
             if constexpr (MORE) wr[v] = ldg16_stream(wt, woff + v * 1024);
+            __builtin_amdgcn_sched_barrier(0);   // keep each request behind the MFMA that frees its registers
         }
-        u32x4 xn[8];
-        if constexpr (MORE) {
-            xoff += kTileK * 2;
-            load_x(xn, kt + 1, xoff);
-            soff += kTileSignBytes;
-        }
+        if constexpr (MORE && XSTEPS == 0) x_fetch_operands(xnext, kt_next);
         __builtin_amdgcn_sched_barrier(0);
-        // ---- delta jobs: table look-ups of job j+1 are in flight while job j is multiplied
-        u32x4 cur[8], nxt[8];
+        // ---- delta jobs.  The 8 NJ (job, slice) pairs of the task form one sequence; the table
+        // look-up of pair i + kLookAhead is issued before the MFMA of pair i, through a ring of
+        // operand registers, and a job's sign words are re-requested as soon as its last address exists.
+        constexpr int kLookAhead = 6, kRing = kLookAhead + 2, kPairs = 8 * NJ;
+        u32x4 ring[kRing];
         float4v sel = {0.f, 0.f, 0.f, 0.f};   // the job owning this lane's column, this tile
-        lut_issue(sr[0], lanebits, cur);
-        if constexpr (MORE) sr[0] = ldg8_stream(sp[0], soff);
-#pragma unroll
-        for (int j = 0; j < NJ; ++j) {
-            if (j + 1 < NJ) {
-                lut_issue(sr[j + 1], lanebits, nxt);
-                if constexpr (MORE) sr[j + 1] = ldg8_stream(sp[j + 1], soff);
+        auto look_up = [&](const int i) {      // i = 8 * job + slice
+            const int j = i >> 3, v = i & 7;
+            ring[i % kRing] = lut_read(sr[j], v, lanebits);
+            if constexpr (MORE) {
+                if (v == 7) sr[j] = ldg8_stream(sp[j], soff);
             }
-            float4v acc = {0.f, 0.f, 0.f, 0.f};
+        };
 #pragma unroll
-            for (int v = 0; v < 8; ++v)
-                acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8, cur[v]),
-                                                             __builtin_bit_cast(half8, xc[v]), acc, 0, 0, 0);
-            const bool mine = (myjob == j);
+        for (int i = 0; i < kLookAhead; ++i) look_up(i);
+        float4v acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int i = 0; i < 4; ++i) sel[i] = mine ? acc[i] : sel[i];
-            __builtin_amdgcn_sched_barrier(0);
+        for (int i = 0; i < kPairs; ++i) {
+            if (i + kLookAhead < kPairs) look_up(i + kLookAhead);
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8, ring[i % kRing]),
+                                                         __builtin_bit_cast(half8, xr[i & 7]), acc, 0, 0, 0);
+            if ((i & 7) == 7) {
+                const bool mine = (myjob == (i >> 3));
 #pragma unroll
-            for (int v = 0; v < 8; ++v) cur[v] = nxt[v];
+                for (int q = 0; q < 4; ++q) sel[q] = mine ? acc[q] : sel[q];
+                // pin the selection here: left alone, the compiler sinks all of them below the last job
+                // and keeps one live accumulator per job
+                asm volatile("" : "+v"(sel[0]), "+v"(sel[1]), "+v"(sel[2]), "+v"(sel[3]));
+                acc = float4v{0.f, 0.f, 0.f, 0.f};
+                __builtin_amdgcn_sched_barrier(0);
+            }
         }
         dsel += sel;
-        if constexpr (MORE) {
+        if constexpr (MORE && XSTEPS == 0) {   // this task's x is spent: move the next one in
 #pragma unroll
-            for (int v = 0; v < 8; ++v) xc[v] = xn[v];
+            for (int v = 0; v < 8; ++v) xr[v] = xnext[v];
         }
     };
-    for (int s = 0; s + 1 < steps; ++s) step(std::true_type{}, kb + s);
-    if (steps > 0) step(std::false_type{}, ke - 1);
 
-    // ---- add the wavefronts' partial tiles in a fixed order and write y once
-    float* red = (float*)(smem + kLutBytes);
-    {
-        float4v r;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) r[i] = accb[i] + alpha_c * dsel[i];
-        *(float4v*)(red + wave * 256 + c * 16 + 4 * g) = r;   // [column][row]
-    }
-    __syncthreads();
-    const int n0 = rb * kTileRows;
-    const int out = a.out[m];
-    uint16_t* y = a.y[m];
-    for (int idx = threadIdx.x; idx < 256; idx += blockDim.x) {
-        const int col = idx >> 4, row = idx & 15;
-        if (col < a.T && n0 + row < out) {
-            float s = 0.f;
-            for (int wv = 0; wv < nw; ++wv) s += red[wv * 256 + idx];
-            y[(int64_t)a.col_token[col] * out + n0 + row] = f2h_rne(s);
+    // The partial tiles of `n` finished row blocks, first one rbg0: add the wavefronts in a fixed order, write y.
+    auto flush = [&](const int rbg0, const int n, const bool more_follow) {
+        __syncthreads();
+        for (int idx = threadIdx.x; idx < n * 256; idx += blockDim.x) {
+            const int slot = idx >> 8, e = idx & 255, col = e >> 4, row = e & 15;
+            int m, rb;
+            mat_of(rbg0 + slot, m, rb);
+            const int out = a.out[m], n_row = rb * kTileRows + row;
+            if (col < a.T && n_row < out) {
+                float s = 0.f;
+                for (int wv = 0; wv < nw; ++wv)
+                    s += *(const float*)(smem + kLutBytes + wv * Plan::kRegion + (slot * 256 + e) * 4);
+                a.y[m][(int64_t)a.col_token[col] * out + n_row] = f2h_rne(s);
+            }
         }
+        if (more_follow) __syncthreads();
+    };
+
+    int slot = 0, flush_base = r0;
+    int m_cur = m_req;
+    for (int rbi = 0; rbi < n_rb; ++rbi) {
+        const bool last_rb = rbi + 1 == n_rb;
+        // where the requests go after this row block's last task
+        int m_nx = m_req, rb_nx = 0;
+        if (!last_rb) mat_of(r0 + rbi + 1, m_nx, rb_nx);
+        const uint32_t tile_rb = (uint32_t)(rb_req * KT + kb);            // first tile of this wavefront in this row block
+        const uint32_t tile_nx = (uint32_t)(rb_nx * KT + kb);             // ... and in the next one
+        auto cross = [&]() {   // requests move on to the next row block: switch the pointers if it is in another matrix
+            if (m_nx != m_req) {
+                wt = (const unsigned char*)a.wt[m_nx];
+#pragma unroll
+                for (int j = 0; j < NJ; ++j) sp[j] = (const unsigned char*)a.signs[m_nx][j];
+            }
+        };
+        if constexpr (XSTEPS > 0) {
+#pragma unroll
+            for (int ki = 0; ki < XSTEPS; ++ki) {
+                if (ki + 1 < XSTEPS) {
+                    task(std::true_type{}, xs[ki], tile_rb + ki + 1, xraw[0], 0);
+                } else if (!last_rb) {
+                    cross();
+                    task(std::true_type{}, xs[ki], tile_nx, xraw[0], 0);
+                } else {
+                    task(std::false_type{}, xs[ki], 0u, xraw[0], 0);
+                }
+            }
+        } else {
+            for (int ki = 0; ki < steps; ++ki) {
+                const bool inner = ki + 1 < steps;
+                if (!inner && !last_rb) cross();
+                if (inner || !last_rb)
+                    task(std::true_type{}, xs[0], inner ? tile_rb + ki + 1 : tile_nx, xraw[0], inner ? kb + ki + 1 : kb);
+                else
+                    task(std::false_type{}, xs[0], 0u, xraw[0], 0);
+            }
+        }
+        // ---- row block done: this wavefront's partial tile -> slot
+        {
+            const float al = m_cur == 0 ? alpha_m[0] : (m_cur == 1 ? alpha_m[1] : alpha_m[2]);
+            float4v r;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) r[i] = accb[i] + al * dsel[i];
+            *(float4v*)(region + (slot * 256 + c * 16 + 4 * g) * 4) = r;   // [column][row]
+            accb = dsel = float4v{0.f, 0.f, 0.f, 0.f};
+        }
+        ++slot;
+        if (slot == Plan::kRedSlots || last_rb) {
+            flush(flush_base, slot, !last_rb);
+            flush_base += slot;
+            slot = 0;
+        }
+        m_cur = m_nx;
+        m_req = m_nx;
+        rb_req = rb_nx;
     }
 }
 
-template <int NJ>
-static hipError_t launch_nj(const TiledArgs& args, int n_waves, unsigned grid, hipStream_t st) {
-    auto kernel = linear_decode_tiled_kernel<NJ>;
-    const size_t lds = (size_t)kLutBytes + (size_t)kMaxWavesTiled * kRedBytesPerWave;
+template <int NJ, int XSTEPS>
+static hipError_t launch_inst(const TiledArgs& args, int n_waves, unsigned grid, hipStream_t st) {
+    auto kernel = linear_decode_tiled_kernel<NJ, XSTEPS>;
+    const size_t lds = (size_t)LdsPlan<XSTEPS>::kTotal;
     static bool attr_set = false;   // raising the dynamic LDS limit is idempotent; a race only repeats it
     if (!attr_set) {
         hipFuncAttributes fa;
@@ -233,12 +399,17 @@ static hipError_t launch_nj(const TiledArgs& args, int n_waves, unsigned grid, h
     return hipGetLastError();
 }
 
+template <int NJ>
+static hipError_t launch_nj(const TiledArgs& args, int n_waves, int xsteps, unsigned grid, hipStream_t st) {
+    if (xsteps == 1) return launch_inst<NJ, 1>(args, n_waves, grid, st);
+    if (xsteps == 2) return launch_inst<NJ, 2>(args, n_waves, grid, st);
+    return launch_inst<NJ, 0>(args, n_waves, grid, st);
+}
+
 hipError_t launch_linear_decode_tiled(const TiledArgs& args, int n_jobs, hipStream_t st) {
     if (n_jobs < 1 || n_jobs > kTiledMaxJobs || args.n_mats < 1 || args.n_mats > kTiledMaxMats) return hipErrorInvalidValue;
-    const unsigned grid = (unsigned)args.rb_end[args.n_mats - 1];
-    // One workgroup of 8 wavefronts per compute unit while the grid fits in one round; beyond
-    // that, workgroups of 4 so that two are resident per unit and one's epilogue overlaps the
-    // other's stream.  Never more wavefronts than k tiles.
+    const int rb_total = args.rb_end[args.n_mats - 1];
+    if (rb_total < 1 || args.KT < 0) return hipErrorInvalidValue;
     static int cus = 0;   // compute units of the current device, asked once
     if (cus == 0) {
         int dev = 0, v = 0;
@@ -248,11 +419,16 @@ hipError_t launch_linear_decode_tiled(const TiledArgs& args, int n_jobs, hipStre
         else
             cus = 256;
     }
-    int n_waves = grid <= (unsigned)cus ? 8 : 4;
+    // persistent grid: one workgroup per compute unit, never more workgroups than row blocks;
+    // 8 wavefronts, never more than k tiles (KT == 0: one idle-looping wavefront writes y = 0)
+    const unsigned grid = (unsigned)(rb_total < cus ? rb_total : cus);
+    int n_waves = kMaxWavesTiled;
     while (n_waves > 1 && n_waves > args.KT) n_waves >>= 1;
-    if (n_jobs <= 4) return launch_nj<4>(args, n_waves, grid, st);
-    if (n_jobs <= 8) return launch_nj<8>(args, n_waves, grid, st);
-    return launch_nj<16>(args, n_waves, grid, st);
+    int xsteps = 0;
+    if (args.KT > 0 && args.KT % n_waves == 0 && args.KT / n_waves <= 2) xsteps = args.KT / n_waves;
+    if (n_jobs <= 4) return launch_nj<4>(args, n_waves, xsteps, grid, st);
+    if (n_jobs <= 8) return launch_nj<8>(args, n_waves, xsteps, grid, st);
+    return launch_nj<16>(args, n_waves, xsteps, grid, st);
 }
 
 }  // namespace bd
