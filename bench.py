@@ -25,6 +25,10 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+# HBM bytes per launch of the decode kernel measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by what the
+# same counters read for a plain copy of known size (summary and commands: profiles/*_hbm_traffic.md).
+# Key: (model, tenants, path).  Other configurations report null.
+MEASURED_TRAFFIC_BYTES_PER_LAUNCH = {("7b", 16, "tiled-fused"): 204.5e6}
 
 
 def parse():
@@ -41,6 +45,9 @@ def parse():
     ap.add_argument("--no-extras", action="store_true", help="skip naive baseline, read probe, compress rate")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
     ap.add_argument("--per-linear", action="store_true", help="also time each linear shape on its own")
+    ap.add_argument("--calibrate", action="store_true",
+                    help="only run a 1 GiB copy and a 1 GiB read three times: known sizes against which the "
+                         "profiler's HBM byte counters are scaled")
     return ap.parse_args()
 
 
@@ -63,6 +70,16 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs the GPU"
     dev = "cuda:0"
     torch.cuda.set_device(0)
+    if args.calibrate:
+        src = torch.empty(1 << 28, dtype=torch.int32, device=dev).random_(0, 1 << 30)
+        dst = torch.empty_like(src)
+        sink = torch.zeros(4, dtype=torch.int32, device=dev)
+        for _ in range(3):
+            bd.probe_copy(dst, src)
+            bd.probe_read(src, sink)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibrate": "3 x bd_probe_copy and bd_probe_read of 1 GiB"}))
+        return
     B, n_layers = args.tenants, args.layers
     shapes = synth.LLAMA2_7B_LAYER if args.model == "7b" else synth.LLAMA2_70B_LAYER
     sigma = 0.002 if args.model == "7b" else 0.001
@@ -204,7 +221,7 @@ def main():
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
             "frac": round(achieved_gbs / HBM_PEAK_GBS, 4),
-            "traffic": None,
+            "traffic": MEASURED_TRAFFIC_BYTES_PER_LAUNCH.get((args.model, B, args.path)) if n_layers == 32 else None,
             "kernel": "linear_decode_mfma_kernel" if args.path == "rowmajor" else "linear_decode_tiled_kernel",
             "bytes_per_launch": round(bytes_per_step / launches_per_step, 1),
             "avg_launch_us": round(ms_per_step * 1e3 / launches_per_step, 3),

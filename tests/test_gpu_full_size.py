@@ -1,5 +1,6 @@
 """GPU parity at the benchmark's full sizes (Llama-2-7B and 70B layer shapes), in the launch configuration
-bench.py times.  The 7B layer is compared in full; the 70B matrices on sampled output rows, which the oracle
+bench.py times: the row-major entry point, the tiled entry point and the grouped (q,k,v / gate,up) tiled
+launches.  The 7B layer is compared in full; the 70B matrices on sampled output rows, which the oracle
 computes one by one (rows of a linear are independent, so a row slice of W and of the packed deltas is a
 complete problem)."""
 import numpy as np
@@ -37,6 +38,8 @@ def test_llama2_7b_layer_b16_full_output(ref, name, out, inn):
     x = synth.activations(B, inn, device=DEV, tag=("7b", name))
     tok = synth.one_token_per_tenant(B)
     y = bd.linear_multitenant(x, base, table, tok)
+    ttable = bd.TiledTenantTable([bd.tile_signs(p, out, inn) for p in table.packed], table.alpha)
+    y_tiled = bd.linear_multitenant_tiled(x, bd.tile_base(base), out, ttable, tok)
     torch.cuda.synchronize()
     base_np = to_np(base)
     refc = []
@@ -48,7 +51,34 @@ def test_llama2_7b_layer_b16_full_output(ref, name, out, inn):
     del fts
     _, y32 = ref.linear_multitenant(to_np(x), base_np, [c[0] for c in refc], [c[1] for c in refc], tok)
     err = check_close(y, y32, f"7B {name}")
-    print(f"   max rel err {err:.2e}", flush=True)
+    err_t = check_close(y_tiled, y32, f"7B {name} tiled")
+    print(f"   max rel err {err:.2e} (row-major)  {err_t:.2e} (tiled)", flush=True)
+
+
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("names,outs,inn", [(("q", "k", "v"), (4096, 4096, 4096), 4096),
+                                            (("gate", "up"), (11008, 11008), 4096)])
+def test_llama2_7b_grouped_launch_b16_full_output(ref, names, outs, inn):
+    """The launches bench.py times: several matrices over the same x in one call."""
+    B = 16
+    print(f"7B grouped {names} B={B}", flush=True)
+    x = synth.activations(B, inn, device=DEV, tag=("7bg", names[0]))
+    tok = synth.one_token_per_tenant(B)
+    wts, tables, keep = [], [], []
+    for name, out in zip(names, outs):
+        base, fts, table = _gpu_layer(out, inn, B, 0.002, ("7bg", name))
+        del fts
+        wts.append(bd.tile_base(base))
+        tables.append(bd.TiledTenantTable([bd.tile_signs(p, out, inn) for p in table.packed], table.alpha))
+        keep.append((base, table))
+    ys = bd.linear_multitenant_tiled_group(x, bd.TiledGroup(wts, list(outs), tables), tok)
+    torch.cuda.synchronize()
+    for i, (base, table) in enumerate(keep):
+        packed = [packed_to_np(p) for p in table.packed]          # bit-exactness of these is covered above
+        alphas = [float(a) for a in to_np(table.alpha)]
+        _, y32 = ref.linear_multitenant(to_np(x), to_np(base), packed, alphas, tok)
+        err = check_close(ys[i], y32, f"7B grouped {names[i]}")
+        print(f"   {names[i]}: max rel err {err:.2e}", flush=True)
 
 
 @pytest.mark.timeout(900)
@@ -60,6 +90,8 @@ def test_llama2_70b_b32_sampled_rows(ref, name, out, inn):
     x = synth.activations(B, inn, device=DEV, tag=("70b", name))
     tok = synth.one_token_per_tenant(B)
     y = bd.linear_multitenant(x, base, table, tok)
+    ttable = bd.TiledTenantTable([bd.tile_signs(p, out, inn) for p in table.packed], table.alpha)
+    y_tiled = bd.linear_multitenant_tiled(x, bd.tile_base(base), out, ttable, tok)   # 32 tokens: two launches of 16
     torch.cuda.synchronize()
     g = torch.Generator().manual_seed(7)
     rows = torch.sort(torch.randperm(out, generator=g)[:n_rows]).values
@@ -77,4 +109,5 @@ def test_llama2_70b_b32_sampled_rows(ref, name, out, inn):
     base_np = np.ascontiguousarray(base_full[rows.numpy()])
     _, y32 = ref.linear_multitenant(to_np(x), base_np, refc, alphas, tok)
     err = check_close(y[:, rows_d], y32, f"70B {name}")
-    print(f"   max rel err {err:.2e}", flush=True)
+    err_t = check_close(y_tiled[:, rows_d], y32, f"70B {name} tiled")
+    print(f"   max rel err {err:.2e} (row-major)  {err_t:.2e} (tiled)", flush=True)

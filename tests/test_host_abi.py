@@ -99,6 +99,38 @@ def test_compress_and_pack_argument_errors(bd):
     assert L.bd_materialize(A, 2 * A, 0, 3 * A, 16, 64, 0) == 1
 
 
+def test_tiled_sizes_and_argument_errors(bd):
+    L = bd.lib()
+    # sizes: tiles of 16 rows x 256 k, 8 KiB of base and 512 B of signs each; zero for rejected shapes
+    assert bd.tiled_base_bytes(4096, 4096) == 4096 * 4096 * 2 and bd.tiled_signs_bytes(4096, 4096) == 4096 * 4096 // 8
+    assert bd.tiled_base_bytes(50, 640) == 4 * 3 * 8192 and bd.tiled_signs_bytes(50, 640) == 4 * 3 * 512
+    assert bd.tiled_base_bytes(16, 40) == 0 and bd.tiled_signs_bytes(-1, 64) == 0
+    assert bd.tiled_base_bytes(1 << 20, 1 << 20) == 0          # a tiled tensor of 4 GiB or more is rejected
+    tb, ts = L.bd_tile_base, L.bd_tile_signs
+    assert tb(A, 16, 40, 2 * A, 0) == 2 and tb(0, 16, 64, 2 * A, 0) == 1 and tb(A, 16, 64, 2 * A + 8, 0) == 3
+    assert tb(A, 16, 256, A + 4096, 0) == 8 and tb(0, 0, 64, 0, 0) == 0
+    assert ts(A, 16, 40, 2 * A, 0) == 2 and ts(A, 16, 64, 0, 0) == 1 and ts(A + 4, 16, 64, 2 * A, 0) == 3
+    vp = ctypes.c_void_p
+    f = L.bd_linear_multitenant_tiled
+    ok = dict(x=A, w=2 * A, pk=(vp * 1)(3 * A), al=4 * A, tok=_tok(0), y=5 * A, T=1, out=16, inn=128, nt=1)
+
+    def call(**kw):
+        a = dict(ok, **kw)
+        return f(a["x"], a["w"], a["pk"], a["al"], a["tok"], a["y"], a["T"], a["out"], a["inn"], a["nt"], 0)
+
+    assert call(inn=48) == 2 and call(T=-1) == 2 and call(T=70000) == 2
+    assert call(x=0) == 1 and call(w=0) == 1 and call(al=0) == 1 and call(y=0) == 1
+    assert call(pk=(vp * 1)(None)) == 1                          # the token's tenant has no delta
+    assert call(x=A + 2) == 3 and call(w=2 * A + 8) == 3 and call(pk=(vp * 1)(3 * A + 4)) == 3
+    assert call(tok=_tok(1)) == 4 and call(tok=_tok(-1)) == 4
+    assert call(y=A) == 8 and call(y=2 * A + 64) == 8
+    assert call(T=0, x=0, y=0) == 0 and call(out=0, w=0, y=0) == 0
+    g = L.bd_linear_multitenant_tiled_group
+    i64 = ctypes.c_int64
+    args = [A, (vp * 1)(2 * A), (vp * 1)(3 * A), (vp * 1)(4 * A), _tok(0), (vp * 1)(5 * A), 1, (i64 * 1)(16), 128, 1, 0]
+    assert g(0, *args) == 2 and g(4, *args) == 2                 # 1..3 matrices per launch
+
+
 def test_group_tokens_sorts_stably_and_cuts_jobs_at_the_tile_boundary(bd):
     import random
     rng = random.Random(5)
