@@ -183,8 +183,10 @@ def _tok_array(tenant_of_token: Sequence[int]):
 
 def linear_multitenant(x: torch.Tensor, w_base: torch.Tensor, tenants: TenantTable, tenant_of_token: Sequence[int],
                        y: Optional[torch.Tensor] = None, stream=None, variant: int = 0,
-                       tok_array=None) -> torch.Tensor:
-    """bd_linear_multitenant (variant 0) or bd_linear_multitenant_variant: y fp16 [T, out]."""
+                       tok_array=None, workspace="auto") -> torch.Tensor:
+    """bd_linear_multitenant (variant 0) or bd_linear_multitenant_variant: y fp16 [T, out].
+    workspace: "auto" allocates what bd_workspace_bytes asks for (more than 32 tokens: the prefill GEMM),
+    None passes no workspace (the call then runs as decode launches), or a caller-owned uint8 tensor."""
     _dev(x, torch.float16, "x")
     _dev(w_base, torch.float16, "w_base")
     T, inn = x.shape
@@ -196,9 +198,13 @@ def linear_multitenant(x: torch.Tensor, w_base: torch.Tensor, tenants: TenantTab
     _dev(y, torch.float16, "y")
     tok = tok_array if tok_array is not None else _tok_array(tenant_of_token)
     L = lib()
+    if isinstance(workspace, str):
+        need = workspace_bytes(OP_LINEAR_MULTITENANT, T, out, inn, tenants.n_tenants)
+        workspace = new_workspace(need, x.device) if need > 0 else None
+    ws_ptr, ws_bytes = (_ptr(workspace), workspace.numel()) if workspace is not None else (0, 0)
     if variant == 0:
         st = L.bd_linear_multitenant(_ptr(x), _ptr(w_base), _ptr(tenants.ptrs), _ptr(tenants.alpha), tok, _ptr(y),
-                                     T, out, inn, tenants.n_tenants, 0, 0, _stream(stream))
+                                     T, out, inn, tenants.n_tenants, ws_ptr, ws_bytes, _stream(stream))
     else:
         st = L.bd_linear_multitenant_variant(_ptr(x), _ptr(w_base), _ptr(tenants.ptrs), _ptr(tenants.alpha), tok,
                                              _ptr(y), T, out, inn, tenants.n_tenants, 0, 0, _stream(stream),

@@ -13,7 +13,7 @@ OBJ = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "libbitdelta.so")
 
 SOURCES = ["bitdelta_api.hip", "compress_kernels.hip", "linear_rowwave.hip", "linear_decode_mfma.hip",
-           "linear_decode_tiled.hip", "tile_kernels.hip", "baseline_kernels.hip"]
+           "linear_decode_tiled.hip", "tile_kernels.hip", "linear_prefill.hip", "baseline_kernels.hip"]
 
 HIPCC_FLAGS = [
     "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-ffp-contract=off",
@@ -44,7 +44,7 @@ def _compile(src: str, extra) -> str:
     return obj
 
 
-def build_library(extra_flags=(), jobs: int = 7) -> str:
+def build_library(extra_flags=(), jobs: int = 8) -> str:
     os.makedirs(OBJ, exist_ok=True)
     with ThreadPoolExecutor(max_workers=jobs) as ex:
         objs = list(ex.map(lambda s: _compile(s, list(extra_flags)), SOURCES))

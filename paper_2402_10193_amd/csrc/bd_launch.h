@@ -25,6 +25,16 @@ hipError_t launch_linear_decode_mfma(const uint16_t* x, const uint16_t* w, const
                                      int64_t in, int variant, hipStream_t st);
 bool decode_mfma_variant_known(int variant);
 
+// Prefill GEMM (many tokens per tenant).  row_token: n_mtiles * kPrefillTile ints, the token of every
+// tile row or -1 for padding; tile_tenant: n_mtiles ints.  Both in device memory (the workspace).
+constexpr int kPrefillTile = 128;   // tile of y: 128 tokens x 128 output features
+constexpr int kPrefillK = 32;       // reduction elements per step
+struct PrefillMetaChunk { int32_t v[960]; };
+hipError_t launch_prefill_meta(const PrefillMetaChunk& chunk, int32_t* dst, int n, hipStream_t st);
+hipError_t launch_linear_prefill(const uint16_t* x, const uint16_t* w, const uint32_t* const* packed_by_tenant,
+                                 const float* alpha_by_tenant, const int32_t* row_token, const int32_t* tile_tenant,
+                                 int n_mtiles, uint16_t* y, int64_t out, int64_t in, hipStream_t st);
+
 hipError_t launch_materialize(const uint16_t* w_base, const uint32_t* packed, const float* alpha, uint16_t* w_out,
                               int64_t out, int64_t in, hipStream_t st);
 hipError_t launch_linear_naive(const uint16_t* x, const uint16_t* const* w_by_tenant, const DecodeMeta& meta,

@@ -4,6 +4,7 @@
 
 #include <algorithm>
 #include <cstring>
+#include <vector>
 
 #include "bd_launch.h"
 #include "bd_tiled.h"
@@ -87,6 +88,51 @@ bd_status check_linear_args(const void* x, const void* w, const void* packed_by_
     return BD_OK;
 }
 
+// Prefill (T > 32): the token permutation and the tenant of every 128-row tile live in the workspace.
+// At most ceil(T / 128) full tiles plus one ragged tile per tenant that has a token.
+size_t prefill_workspace_bytes(int64_t T, int32_t n_tenants) {
+    if (T <= kMaxDecodeTokens || n_tenants < 0) return 0;
+    const int64_t tiles = (T + bd::kPrefillTile - 1) / bd::kPrefillTile + std::min<int64_t>(n_tenants, T);
+    const size_t bytes = (size_t)tiles * (bd::kPrefillTile + 1) * sizeof(int32_t);
+    return (bytes + 255) & ~(size_t)255;
+}
+
+// Sorts the tokens by tenant (stable), cuts them into tiles of 128 rows that never mix tenants, writes
+// the two tables into the workspace (through kernel arguments: no host-to-device copy call) and runs the GEMM.
+hipError_t run_prefill(const uint16_t* x, const uint16_t* w, const uint32_t* const* packed_by_tenant,
+                       const float* alpha_by_tenant, const int32_t* tenant_of_token, uint16_t* y, int64_t T, int64_t out,
+                       int64_t in, void* workspace, hipStream_t st) {
+    std::vector<int32_t> order((size_t)T);
+    for (int64_t i = 0; i < T; ++i) order[(size_t)i] = (int32_t)i;
+    std::stable_sort(order.begin(), order.end(),
+                     [&](int32_t a, int32_t b) { return tenant_of_token[a] < tenant_of_token[b]; });
+    std::vector<int32_t> row_token, tile_tenant;
+    for (int64_t i = 0; i < T;) {
+        const int32_t tenant = tenant_of_token[order[(size_t)i]];
+        int64_t e = i;
+        while (e < T && tenant_of_token[order[(size_t)e]] == tenant) ++e;
+        for (int64_t t0 = i; t0 < e; t0 += bd::kPrefillTile) {
+            tile_tenant.push_back(tenant);
+            for (int64_t rrow = 0; rrow < bd::kPrefillTile; ++rrow)
+                row_token.push_back(t0 + rrow < e ? order[(size_t)(t0 + rrow)] : -1);
+        }
+        i = e;
+    }
+    const int n_mtiles = (int)tile_tenant.size();
+    std::vector<int32_t> all(row_token);
+    all.insert(all.end(), tile_tenant.begin(), tile_tenant.end());
+    int32_t* dst = (int32_t*)workspace;
+    for (size_t off = 0; off < all.size(); off += 960) {
+        bd::PrefillMetaChunk c;
+        const int n = (int)std::min<size_t>(960, all.size() - off);
+        std::memcpy(c.v, all.data() + off, (size_t)n * sizeof(int32_t));
+        const hipError_t e = bd::launch_prefill_meta(c, dst + off, n, st);
+        if (e != hipSuccess) return e;
+    }
+    return bd::launch_linear_prefill(x, w, packed_by_tenant, alpha_by_tenant, dst, dst + row_token.size(), n_mtiles, y, out,
+                                     in, st);
+}
+
 }  // namespace
 
 extern "C" {
@@ -109,13 +155,11 @@ const char* bd_status_string(bd_status s) {
 int bd_version(void) { return kVersion; }
 
 size_t bd_workspace_bytes(bd_op op, int64_t T, int64_t out, int64_t in, int32_t n_tenants) {
-    (void)T;
-    (void)n_tenants;
     if (out < 0 || in < 0 || in % 32 != 0) return 0;
     switch (op) {
         case BD_OP_COMPRESS: return (size_t)bd::kCompressMaxBlocks * sizeof(double);
         case BD_OP_PACK_SIGNS: return 0;
-        case BD_OP_LINEAR_MULTITENANT: return 0;
+        case BD_OP_LINEAR_MULTITENANT: return prefill_workspace_bytes(T, n_tenants);
     }
     return 0;
 }
@@ -154,8 +198,6 @@ bd_status bd_linear_multitenant_variant(const uint16_t* x_f16, const uint16_t* w
                                         const int32_t* tenant_of_token, uint16_t* y_f16, int64_t T, int64_t out,
                                         int64_t in, int32_t n_tenants, void* workspace, size_t workspace_bytes,
                                         void* stream, int32_t variant) {
-    (void)workspace;
-    (void)workspace_bytes;   // this op needs none (bd_workspace_bytes returns 0)
     const bd_status st = check_linear_args(x_f16, w_base_f16, packed_by_tenant, alpha_by_tenant, tenant_of_token, y_f16,
                                            T, out, in, n_tenants);
     if (st != BD_OK) return st;
@@ -169,6 +211,14 @@ bd_status bd_linear_multitenant_variant(const uint16_t* x_f16, const uint16_t* w
     if (use == 0) use = mfma_ok ? kVariantDefaultMfma : kVariantRowWave;
 
     hipStream_t hs = (hipStream_t)stream;
+    // More than one decode launch worth of tokens: the prefill GEMM, if the caller brought its workspace
+    // (without one the call still works, as a sequence of decode launches that re-read the base).
+    const size_t need = prefill_workspace_bytes(T, n_tenants);
+    if (variant == 0 && need > 0 && in > 0 && workspace && workspace_bytes >= need && !misaligned(workspace, 256))
+        return run_prefill(x_f16, w_base_f16, packed_by_tenant, alpha_by_tenant, tenant_of_token, y_f16, T, out, in,
+                           workspace, hs) == hipSuccess
+                   ? BD_OK
+                   : BD_ERR_DEVICE;
     for (int64_t t0 = 0; t0 < T; t0 += kMaxDecodeTokens) {
         const int n = (int)std::min<int64_t>(kMaxDecodeTokens, T - t0);
         DecodeMeta meta;

@@ -111,3 +111,26 @@ def test_llama2_70b_b32_sampled_rows(ref, name, out, inn):
     err = check_close(y[:, rows_d], y32, f"70B {name}")
     err_t = check_close(y_tiled[:, rows_d], y32, f"70B {name} tiled")
     print(f"   max rel err {err:.2e} (row-major)  {err_t:.2e} (tiled)", flush=True)
+
+
+@pytest.mark.timeout(900)
+@pytest.mark.parametrize("name,out,inn", [("up", 11008, 4096), ("down", 4096, 11008)])
+def test_prefill_8_tenants_x_512_tokens_sampled_rows(ref, name, out, inn):
+    """The prefill configuration: 8 tenants x 512 tokens through one GEMM launch, checked on sampled output rows."""
+    B, per, n_rows = 8, 512, 96
+    print(f"prefill {name} {out}x{inn} T={B * per}", flush=True)
+    base, fts, table = _gpu_layer(out, inn, B, 0.002, ("pf", name))
+    del fts
+    tok = [t for t in range(B) for _ in range(per)]
+    x = synth.activations(B * per, inn, device=DEV, tag=("pf", name))
+    y = bd.linear_multitenant(x, base, table, tok)
+    torch.cuda.synchronize()
+    g = torch.Generator().manual_seed(11)
+    rows = torch.sort(torch.randperm(out, generator=g)[:n_rows]).values
+    rows[0], rows[-1] = 0, out - 1
+    packed = [np.ascontiguousarray(packed_to_np(p)[rows.numpy()]) for p in table.packed]
+    alphas = [float(a) for a in to_np(table.alpha)]
+    base_np = np.ascontiguousarray(to_np(base)[rows.numpy()])
+    _, y32 = ref.linear_multitenant(to_np(x), base_np, packed, alphas, tok)
+    err = check_close(y[:, rows.to(DEV)], y32, f"prefill {name}")
+    print(f"   max rel err {err:.2e}", flush=True)

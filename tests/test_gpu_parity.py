@@ -107,6 +107,35 @@ def test_linear_matches_oracle(ref, case, variant):
     assert np.mean((ulp <= 1) | ~same_sign) > 0.99
 
 
+PREFILL_CASES = [
+    # out, in, n_tenants, tokens per tenant (tokens are then shuffled)
+    (300, 512, 5, [70, 1, 0, 129, 40]),          # ragged rows, an idle tenant, a tenant with more than one tile
+    (130, 96, 3, [11, 11, 11]),                  # 33 tokens: just beyond one decode launch; two N tiles, 3 k steps
+    (128, 1024, 2, [128, 256]),                  # exact tiles
+    (1024, 2048, 8, [160] * 8),                  # 1280 tokens
+    (64, 32, 4, [9, 9, 9, 9]),                   # a single k step
+]
+
+
+@pytest.mark.parametrize("case", range(len(PREFILL_CASES)))
+def test_prefill_gemm_matches_oracle(ref, case):
+    """More than 32 tokens with a workspace: one matrix-core GEMM launch; without: decode launches.  Same oracle."""
+    out, inn, nt, counts = PREFILL_CASES[case]
+    tok = [t for t, c in enumerate(counts) for _ in range(c)]
+    perm = torch.randperm(len(tok), generator=torch.Generator().manual_seed(case)).tolist()
+    tok = [tok[i] for i in perm]
+    _p(f"prefill case={case} out={out} in={inn} tenants={nt} T={len(tok)}")
+    prob = Problem(ref, out, inn, nt, tag=("pf", case))
+    x = prob.x(len(tok))
+    y = bd.linear_multitenant(x, prob.w_base, prob.table, tok)                       # workspace allocated: GEMM
+    y_dec = bd.linear_multitenant(x, prob.w_base, prob.table, tok, workspace=None)   # no workspace: decode launches
+    torch.cuda.synchronize()
+    _, y32 = ref.linear_multitenant(to_np(x), prob.w_base_np, prob.packed_np, prob.alpha_np, tok)
+    check_close(y, y32, f"prefill case {case}")
+    check_close(y_dec, y32, f"prefill case {case}, decode launches")
+    assert torch.equal(bd.linear_multitenant(x, prob.w_base, prob.table, tok), y)    # bitwise reproducible
+
+
 @pytest.mark.parametrize("variant", VARIANTS)
 def test_linear_special_inputs(ref, variant):
     """alpha = 0, all-ones / all-zero sign words, one-hot x: exact consequences of Eq. 6."""

@@ -46,6 +46,10 @@ def test_version_and_status_strings(bd):
 def test_workspace_bytes(bd):
     assert bd.workspace_bytes(bd.OP_COMPRESS, 0, 4096, 4096, 1) >= 2048 * 8
     assert bd.workspace_bytes(bd.OP_LINEAR_MULTITENANT, 16, 4096, 4096, 16) == 0
+    assert bd.workspace_bytes(bd.OP_LINEAR_MULTITENANT, 32, 4096, 4096, 16) == 0
+    # prefill: (ceil(T / 128) + min(tenants, T)) tiles x 129 ints, rounded up to 256 bytes
+    assert bd.workspace_bytes(bd.OP_LINEAR_MULTITENANT, 4096, 11008, 4096, 8) == (40 * 129 * 4 + 255) // 256 * 256
+    assert bd.workspace_bytes(bd.OP_LINEAR_MULTITENANT, 33, 64, 64, 100) == (34 * 129 * 4 + 255) // 256 * 256
     assert bd.workspace_bytes(bd.OP_PACK_SIGNS, 0, 4096, 4096, 1) == 0
     assert bd.workspace_bytes(bd.OP_COMPRESS, 0, 4096, 4100, 1) == 0   # rejected shape
 
