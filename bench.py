@@ -45,10 +45,66 @@ def parse():
     ap.add_argument("--no-extras", action="store_true", help="skip naive baseline, read probe, compress rate")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
     ap.add_argument("--per-linear", action="store_true", help="also time each linear shape on its own")
+    ap.add_argument("--workload", choices=["decode", "prefill"], default="decode",
+                    help="prefill: 8 tenants x 512 tokens on the 4096x11008 and 11008x4096 linears (matrix-core GEMM)")
     ap.add_argument("--calibrate", action="store_true",
                     help="only run a 1 GiB copy and a 1 GiB read three times: known sizes against which the "
                          "profiler's HBM byte counters are scaled")
     return ap.parse_args()
+
+
+MFMA_F16_PEAK_TFLOPS = 2500.0
+
+
+def run_prefill(args, torch, bd, synth, dev):
+    """8 tenants x 512 tokens through bd_linear_multitenant on an up- and a down-projection of Llama-2-7B: one
+    step = both linears; reports TFLOP/s of the two products (base and delta) against the dense fp16 MFMA peak."""
+    B, per = 8, 512
+    T = B * per
+    tok = [t for t in range(B) for _ in range(per)]
+    tok_arr = bd._tok_array(tok)
+    mats = []
+    ws_c = bd.new_workspace(bd.workspace_bytes(bd.OP_COMPRESS, 0, 1, 32, 1), dev)
+    for name, out, inn in [("up", 11008, 4096), ("down", 4096, 11008)]:
+        base = synth.base_weight(out, inn, device=dev, tag=("pf", name))
+        packed, alphas = [], []
+        for t in range(B):
+            ft = synth.finetuned_weight(base, tag=("pf", name, t))
+            p, a = bd.compress(base, ft, workspace=ws_c)
+            packed.append(p)
+            alphas.append(a)
+        x = synth.activations(T, inn, device=dev, tag=("pf", name))
+        y = torch.empty((T, out), dtype=torch.float16, device=dev)
+        ws = bd.new_workspace(bd.workspace_bytes(bd.OP_LINEAR_MULTITENANT, T, out, inn, B), dev)
+        mats.append((x, base, bd.TenantTable(packed, alphas), y, ws, out, inn))
+
+    def step():
+        for x, base, table, y, ws, _, _ in mats:
+            bd.linear_multitenant(x, base, table, tok, y=y, tok_array=tok_arr, workspace=ws)
+    for _ in range(max(args.warmup, 1)):
+        step()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(args.steps):
+        step()
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / args.steps
+    flops = sum(2.0 * 2.0 * T * inn * out for *_, out, inn in mats)      # base + delta products
+    tflops = flops / (ms * 1e-3) / 1e12
+    print(json.dumps({
+        "metric": "prefill tokens/s, fused fp16 base + 1-bit delta linear, 8 tenants x 512 tokens",
+        "value": round(T / (ms * 1e-3), 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f16 in, f32 accumulate", "data": "synthetic",
+        "config": {"workload": "prefill: 8 tenants x 512 tokens, linears 4096->11008 and 11008->4096 (one step = both)",
+                   "tenants": B, "tokens": T},
+        "roofline": {"bound": "mfma", "achieved": round(tflops, 1), "peak": MFMA_F16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": round(tflops / MFMA_F16_PEAK_TFLOPS, 4), "traffic": None, "kernel": "linear_prefill_kernel",
+                     "flops_per_launch": flops / 2, "avg_launch_us": round(ms * 1e3 / 2, 2),
+                     "useful_fraction_note": "half of the flops are the base product, half the +-1 delta product"},
+    }))
 
 
 def main():
@@ -79,6 +135,9 @@ def main():
             bd.probe_read(src, sink)
         torch.cuda.synchronize()
         print(json.dumps({"calibrate": "3 x bd_probe_copy and bd_probe_read of 1 GiB"}))
+        return
+    if args.workload == "prefill":
+        run_prefill(args, torch, bd, synth, dev)
         return
     B, n_layers = args.tenants, args.layers
     shapes = synth.LLAMA2_7B_LAYER if args.model == "7b" else synth.LLAMA2_70B_LAYER
