@@ -28,7 +28,7 @@ bool decode_mfma_variant_known(int variant);
 // Prefill GEMM (many tokens per tenant).  row_token: n_mtiles * kPrefillTile ints, the token of every
 // tile row or -1 for padding; tile_tenant: n_mtiles ints.  Both in device memory (the workspace).
 constexpr int kPrefillTile = 128;   // tile of y: 128 tokens x 128 output features
-constexpr int kPrefillK = 32;       // reduction elements per step
+constexpr int kPrefillK = 64;       // reduction elements per step
 struct PrefillMetaChunk { int32_t v[960]; };
 hipError_t launch_prefill_meta(const PrefillMetaChunk& chunk, int32_t* dst, int n, hipStream_t st);
 hipError_t launch_linear_prefill(const uint16_t* x, const uint16_t* w, const uint32_t* const* packed_by_tenant,

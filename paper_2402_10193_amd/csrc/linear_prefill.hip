@@ -5,15 +5,15 @@
 // With hundreds of tokens per tenant both products are dense contractions, so this is a tiled
 // matrix-core GEMM.  Tokens are sorted by tenant on the host and cut into M tiles of 128 rows
 // that never mix tenants (the last tile of a tenant is padded with empty rows).  A workgroup
-// (4 wavefronts, 2 x 2) owns one 128 x 128 tile of y and walks k in steps of 32:
-//   x tile   128 tokens x 32 k   fp16, gathered through the token permutation
-//   W tile   128 rows   x 32 k   fp16
-//   s tile   128 rows   x 32 k   one packed word per row, expanded to +-1.0 fp16 on the way into
+// (4 wavefronts, 2 x 2) owns one 128 x 128 tile of y and walks k in steps of 64 (32 for the last step of in % 64 == 32):
+//   x tile   128 tokens x 64 k   fp16, gathered through the token permutation
+//   W tile   128 rows   x 64 k   fp16
+//   s tile   128 rows   x 64 k   two packed words per row, expanded to +-1.0 fp16 on the way into
 //                                LDS (four 16-byte entries of a 256-entry byte table per word)
 // and every wavefront accumulates its 64 x 64 corner twice with v_mfma_f32_16x16x32_f16: x.W^T
 // and x.s^T in separate binary32 accumulators, combined as acc_b + alpha * acc_d at the end (alpha
 // multiplies the finished +-1 sum, as in the decode kernels).  Global loads of step k+1 are in
-// registers while step k is multiplied; LDS rows are padded to 80 bytes so that the 16-byte
+// registers while step k is multiplied; LDS rows are padded to 144 bytes so that the 16-byte
 // operand reads of 16 lanes fall into 16 different bank groups.
 #include "bd_device.h"
 #include "bd_launch.h"
@@ -22,8 +22,10 @@ namespace bd {
 
 namespace {
 
-constexpr int kPfRowBytes = kPrefillK * 2 + 16;            // 80
-constexpr int kPfTileBytes = kPrefillTile * kPfRowBytes;   // 10240
+constexpr int kPfRowBytes = kPrefillK * 2 + 16;            // 144
+constexpr int kPfTileBytes = kPrefillTile * kPfRowBytes;   // 18432
+constexpr int kPfChunks = kPrefillK / 8;                   // 16-byte chunks per tile row
+constexpr int kPfPerThread = kPrefillTile * kPfChunks / 256;
 constexpr int kPfLutBytes = 256 * 16;
 
 }  // namespace
@@ -34,7 +36,7 @@ __global__ __launch_bounds__(256) void prefill_meta_kernel(const PrefillMetaChun
     for (int i = threadIdx.x; i < n; i += blockDim.x) dst[i] = c.v[i];
 }
 
-__global__ __launch_bounds__(256) void linear_prefill_kernel(
+__global__ __launch_bounds__(256, 2) void linear_prefill_kernel(
     const uint16_t* __restrict__ x, const uint16_t* __restrict__ w, const uint32_t* const* __restrict__ packed_by_tenant,
     const float* __restrict__ alpha_by_tenant, const int32_t* __restrict__ row_token, const int32_t* __restrict__ tile_tenant,
     uint16_t* __restrict__ y, const int64_t out, const int64_t in) {
@@ -64,45 +66,53 @@ __global__ __launch_bounds__(256) void linear_prefill_kernel(
         *(u32x4*)(lut + tid * 16) = e;
     }
 
-    // what this thread fetches per step: two 16-byte chunks of x, two of W, (threads < 128) one sign word
-    const unsigned char* xsrc[2];
-    const unsigned char* wsrc[2];
-    bool xok[2];
-    int soff_lds[2];
+    // what this thread fetches per step: four 16-byte chunks of x, four of W, (threads < 128) the sign words of one row
+    const unsigned char* xsrc[kPfPerThread];
+    const unsigned char* wsrc[kPfPerThread];
+    bool xok[kPfPerThread];
+    int soff_lds[kPfPerThread], kofs[kPfPerThread];
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-        const int q = tid + 256 * i, row = q >> 2, c4 = q & 3;
+    for (int i = 0; i < kPfPerThread; ++i) {
+        const int q = tid + 256 * i, row = q / kPfChunks, c8 = q % kPfChunks;
         const int tok = row_token[mt * kPrefillTile + row];
         xok[i] = tok >= 0;
-        xsrc[i] = (const unsigned char*)(x + (int64_t)(tok >= 0 ? tok : 0) * in) + c4 * 16;
+        xsrc[i] = (const unsigned char*)(x + (int64_t)(tok >= 0 ? tok : 0) * in) + c8 * 16;
         const int64_t wrow = n0 + row < out ? n0 + row : out - 1;   // rows beyond out repeat the last row; never stored
-        wsrc[i] = (const unsigned char*)(w + wrow * in) + c4 * 16;
-        soff_lds[i] = row * kPfRowBytes + c4 * 16;
+        wsrc[i] = (const unsigned char*)(w + wrow * in) + c8 * 16;
+        soff_lds[i] = row * kPfRowBytes + c8 * 16;
+        kofs[i] = c8 * 8;
     }
     const int64_t srow = n0 + (tid & 127) < out ? n0 + (tid & 127) : out - 1;
     const uint32_t* ssrc = packed + srow * words_per_row;
 
-    u32x4 xg[2], wg[2];
-    uint32_t sw = 0;
+    u32x4 xg[kPfPerThread], wg[kPfPerThread];
+    uint32_t sw[kPrefillK / 32];
+    // elements beyond `in` (second half of the last step when in % 64 == 32) are fetched as zeros
     auto fetch = [&](const int64_t k0) {
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            xg[i] = u32x4{0u, 0u, 0u, 0u};
-            if (xok[i]) xg[i] = *(const u32x4*)(xsrc[i] + k0 * 2);
-            wg[i] = *(const u32x4*)(wsrc[i] + k0 * 2);
+        for (int i = 0; i < kPfPerThread; ++i) {
+            const bool kin = k0 + kofs[i] < in;
+            xg[i] = wg[i] = u32x4{0u, 0u, 0u, 0u};
+            if (xok[i] && kin) xg[i] = *(const u32x4*)(xsrc[i] + k0 * 2);
+            if (kin) wg[i] = *(const u32x4*)(wsrc[i] + k0 * 2);
         }
-        if (tid < 128) sw = ssrc[k0 >> 5];
+        if (tid < 128) {
+#pragma unroll
+            for (int h = 0; h < kPrefillK / 32; ++h) sw[h] = (k0 >> 5) + h < words_per_row ? ssrc[(k0 >> 5) + h] : 0u;
+        }
     };
     auto stage = [&]() {
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
+        for (int i = 0; i < kPfPerThread; ++i) {
             *(u32x4*)(xs + soff_lds[i]) = xg[i];
             *(u32x4*)(ws + soff_lds[i]) = wg[i];
         }
         if (tid < 128) {
 #pragma unroll
-            for (int q = 0; q < 4; ++q)
-                *(u32x4*)(ss + tid * kPfRowBytes + q * 16) = *(const u32x4*)(lut + ((sw >> (8 * q)) & 0xFFu) * 16);
+            for (int h = 0; h < kPrefillK / 32; ++h)
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    *(u32x4*)(ss + tid * kPfRowBytes + h * 64 + q * 16) = *(const u32x4*)(lut + ((sw[h] >> (8 * q)) & 0xFFu) * 16);
         }
     };
 
@@ -118,20 +128,23 @@ __global__ __launch_bounds__(256) void linear_prefill_kernel(
         stage();
         __syncthreads();
         if (k0 + kPrefillK < in) fetch(k0 + kPrefillK);
-        half8 a[4], bw[4], bs[4];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            a[i] = *(const half8*)(xs + (wm * 64 + i * 16 + r) * kPfRowBytes + g * 16);
-            bw[i] = *(const half8*)(ws + (wn * 64 + i * 16 + r) * kPfRowBytes + g * 16);
-            bs[i] = *(const half8*)(ss + (wn * 64 + i * 16 + r) * kPfRowBytes + g * 16);
-        }
+        for (int h = 0; h < kPrefillK / 32; ++h) {
+            half8 a[4], bw[4], bs[4];
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                accb[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[i], bw[j], accb[i][j], 0, 0, 0);
-                accd[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[i], bs[j], accd[i][j], 0, 0, 0);
+            for (int i = 0; i < 4; ++i) {
+                a[i] = *(const half8*)(xs + (wm * 64 + i * 16 + r) * kPfRowBytes + h * 64 + g * 16);
+                bw[i] = *(const half8*)(ws + (wn * 64 + i * 16 + r) * kPfRowBytes + h * 64 + g * 16);
+                bs[i] = *(const half8*)(ss + (wn * 64 + i * 16 + r) * kPfRowBytes + h * 64 + g * 16);
             }
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    accb[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[i], bw[j], accb[i][j], 0, 0, 0);
+                    accd[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[i], bs[j], accd[i][j], 0, 0, 0);
+                }
+        }
         __syncthreads();   // everybody is done reading this step's tiles
     }
 
