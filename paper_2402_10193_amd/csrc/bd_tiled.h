@@ -26,6 +26,7 @@ constexpr int kTileSignBytes = kTileRows * kTileK / 8;   // 512
 constexpr int kTiledMaxMats = 3;                         // matrices one launch can cover (q,k,v or gate,up)
 constexpr int kTiledMaxJobs = 16;                        // delta jobs (distinct tenants) per launch
 constexpr int kTiledMaxTokens = 16;                      // one 16-column MFMA tile
+constexpr int kTiledMaxCt = 2;                           // column tiles one launch can cover (32 tokens)
 
 inline int64_t tiled_row_blocks(int64_t out) { return (out + kTileRows - 1) / kTileRows; }
 inline int64_t tiled_k_tiles(int64_t in) { return (in + kTileK - 1) / kTileK; }
@@ -37,18 +38,20 @@ struct TiledArgs {
     const uint16_t* wt[kTiledMaxMats];                        // tiled base of each matrix
     uint16_t* y[kTiledMaxMats];                               // [T, out_m] fp16
     const float* alpha[kTiledMaxMats];                        // device array indexed by tenant id
-    const uint32_t* signs[kTiledMaxMats][kTiledMaxJobs];      // tiled delta of job slot j, matrix m
     int32_t out[kTiledMaxMats];
     int32_t rb_end[kTiledMaxMats];                            // cumulative row blocks: matrix m owns blocks [rb_end[m-1], rb_end[m])
-    int32_t col_token[kTiledMaxTokens];                       // sorted column -> token (row of x and y)
-    int32_t col_job[kTiledMaxTokens];                         // sorted column -> job slot owning it
-    int32_t col_tenant[kTiledMaxTokens];                      // sorted column -> tenant id (for alpha)
-    int32_t T, in, KT, n_mats;
+    int32_t in, KT, n_mats, n_ct;                             // n_ct column tiles of up to 16 tokens each
+    int32_t T[kTiledMaxCt];                                   // tokens (columns in use) of each column tile
+    // per column tile ct: its job slots and its sorted columns
+    const uint32_t* signs[kTiledMaxCt][kTiledMaxMats][kTiledMaxJobs];   // tiled delta of job slot j, matrix m
+    int32_t col_token[kTiledMaxCt][kTiledMaxTokens];          // sorted column -> token (row of x and y)
+    int32_t col_job[kTiledMaxCt][kTiledMaxTokens];            // sorted column -> job slot owning it
+    int32_t col_tenant[kTiledMaxCt][kTiledMaxTokens];         // sorted column -> tenant id (for alpha)
 };
 
 hipError_t launch_tile_base(const uint16_t* w, int64_t out, int64_t in, uint16_t* wt, hipStream_t st);
 hipError_t launch_tile_signs(const uint32_t* packed, int64_t out, int64_t in, uint32_t* st_out, hipStream_t st);
-// n_jobs real job slots (1..16); slots up to the next instantiated count must repeat slot 0's pointers.
+// n_jobs real job slots per column tile (1..16, the larger of the two); unused slots must repeat slot 0's pointers.
 hipError_t launch_linear_decode_tiled(const TiledArgs& args, int n_jobs, hipStream_t st);
 
 }  // namespace bd

@@ -325,19 +325,19 @@ bd_status bd_linear_multitenant_tiled_group(int32_t n_mats, const uint16_t* x_f1
     }
     // in == 0 (empty reduction) needs no special case: the kernel runs zero steps and writes y = 0
 
-    for (int64_t t0 = 0; t0 < T; t0 += bd::kTiledMaxTokens) {
-        const int n = (int)std::min<int64_t>(bd::kTiledMaxTokens, T - t0);
+    constexpr int kPerLaunch = bd::kTiledMaxTokens * bd::kTiledMaxCt;   // 32 tokens: two 16-column tiles
+    for (int64_t t0 = 0; t0 < T; t0 += kPerLaunch) {
+        const int n = (int)std::min<int64_t>(kPerLaunch, T - t0);
         DecodeMeta meta;
-        build_meta(tenant_of_token, t0, n, &meta);   // n <= 16: everything is in column tile 0
+        build_meta(tenant_of_token, t0, n, &meta);
         bd::TiledArgs a;
         std::memset(&a, 0, sizeof(a));
         a.x = x_f16 + t0 * in;
-        a.T = n;
         a.in = (int32_t)in;
         a.KT = (int32_t)bd::tiled_k_tiles(in);
+        a.n_ct = n > bd::kTiledMaxTokens ? 2 : 1;
         int32_t rb = 0;
         int mats = 0;
-        const int n_jobs = meta.tile_job_end[0] - meta.tile_job_begin[0];
         for (int m = 0; m < n_mats; ++m) {
             if (out[m] == 0) continue;
             a.wt[mats] = w_tiled[m];
@@ -346,19 +346,35 @@ bd_status bd_linear_multitenant_tiled_group(int32_t n_mats, const uint16_t* x_f1
             a.out[mats] = (int32_t)out[m];
             rb += (int32_t)bd::tiled_row_blocks(out[m]);
             a.rb_end[mats] = rb;
-            for (int sl = 0; sl < bd::kTiledMaxJobs; ++sl)   // slots beyond the jobs repeat slot 0 (never selected)
-                a.signs[mats][sl] = tiled_by_mat_tenant[(size_t)m * n_tenants + meta.slot_tenant[0][sl < n_jobs ? sl : 0]];
             ++mats;
         }
         a.n_mats = mats;
-        for (int col = 0; col < bd::kTiledMaxTokens; ++col) {
-            a.col_token[col] = col < n ? meta.token_of_col[col] : 0;
-            a.col_tenant[col] = col < n ? meta.tenant_of_col[col] : 0;
-            a.col_job[col] = -1;
-            for (int sl = 0; sl < n_jobs; ++sl)
-                if (col >= meta.slot_col_begin[0][sl] && col < meta.slot_col_end[0][sl]) a.col_job[col] = sl;
+        int max_jobs = 1;
+        for (int ct = 0; ct < bd::kTiledMaxCt; ++ct) {
+            // a column tile beyond n_ct mirrors tile 0 (never read by the kernel, but every pointer stays valid)
+            const int src = ct < a.n_ct ? ct : 0;
+            const int n_jobs = meta.tile_job_end[src] - meta.tile_job_begin[src];
+            const int n_cols = std::min(n - src * bd::kTiledMaxTokens, (int)bd::kTiledMaxTokens);
+            max_jobs = std::max(max_jobs, n_jobs);
+            a.T[ct] = n_cols;
+            mats = 0;
+            for (int m = 0; m < n_mats; ++m) {
+                if (out[m] == 0) continue;
+                for (int sl = 0; sl < bd::kTiledMaxJobs; ++sl)   // slots beyond the jobs repeat slot 0 (never selected)
+                    a.signs[ct][mats][sl] =
+                        tiled_by_mat_tenant[(size_t)m * n_tenants + meta.slot_tenant[src][sl < n_jobs ? sl : 0]];
+                ++mats;
+            }
+            for (int col = 0; col < bd::kTiledMaxTokens; ++col) {
+                const int gcol = src * bd::kTiledMaxTokens + col;
+                a.col_token[ct][col] = col < n_cols ? meta.token_of_col[gcol] : 0;
+                a.col_tenant[ct][col] = col < n_cols ? meta.tenant_of_col[gcol] : 0;
+                a.col_job[ct][col] = -1;
+                for (int sl = 0; sl < n_jobs; ++sl)
+                    if (col >= meta.slot_col_begin[src][sl] && col < meta.slot_col_end[src][sl]) a.col_job[ct][col] = sl;
+            }
         }
-        if (bd::launch_linear_decode_tiled(a, n_jobs, (hipStream_t)stream) != hipSuccess) return BD_ERR_DEVICE;
+        if (bd::launch_linear_decode_tiled(a, max_jobs, (hipStream_t)stream) != hipSuccess) return BD_ERR_DEVICE;
     }
     return BD_OK;
 }

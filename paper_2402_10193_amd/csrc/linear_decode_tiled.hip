@@ -46,7 +46,7 @@ constexpr int kStageBytes = 16 * kStageRowBytes;
 // LDS after the table: one region per wavefront = slots for the partial tiles of finished row blocks.
 // Resident x is staged there before the first task (the slots overlay the staging rows).
 template <int XSTEPS> struct LdsPlan {
-    static constexpr int kRedSlots = 8;
+    static constexpr int kRedSlots = 8;   // 16 x 16 tiles; a row block takes one per column tile
     static constexpr int kRegion = (XSTEPS > 0 && kStageBytes > kRedSlots * kRedBytesPerWave) ? kStageBytes : kRedSlots * kRedBytesPerWave;
     static constexpr int kTotal = kLutBytes + kMaxWavesTiled * kRegion;
 };
@@ -83,7 +83,9 @@ __device__ __forceinline__ u32x4 lut_read(const u32x2 s, const int v, const uint
 
 // XSTEPS = 1 or 2: every wavefront has exactly that many k tiles and keeps their x in registers.
 // XSTEPS = 0: any number of k tiles per wavefront, x double-buffered per task.
-template <int NJ, int XSTEPS>
+// NCT = 2 (streamed x only): 17..32 tokens as two column tiles; the tasks of one (row block, k tile)
+// then come in pairs that share the base registers, so the base is still read once.
+template <int NJ, int XSTEPS, int NCT>
 __global__ __launch_bounds__(kMaxWavesTiled * kWave) void linear_decode_tiled_kernel(const TiledArgs a) {
     extern __shared__ __align__(16) unsigned char smem[];   // [0, 64 KiB): table; then one region per wavefront
     const int lane = threadIdx.x & (kWave - 1);
@@ -92,22 +94,23 @@ __global__ __launch_bounds__(kMaxWavesTiled * kWave) void linear_decode_tiled_ke
     const int c = lane & 15;   // A row (output row) for loads, B/D column (token) for MFMA operands and results
     const int g = lane >> 4;
     using Plan = LdsPlan<XSTEPS>;
+    static_assert(NCT == 1 || XSTEPS == 0, "two column tiles only with streamed x");
     // Touch every 64-byte line of the kernel arguments at once: the first read of a line is a trip
     // to memory, and taken one after the other (pointer tables are indexed by values read before)
     // those trips would delay the first weight request by microseconds.
     {
         const unsigned char __attribute__((address_space(4)))* ka =
             (const unsigned char __attribute__((address_space(4)))*)__builtin_amdgcn_kernarg_segment_ptr();
-        uint32_t t0, t1, t2, t3, t4, t5, t6, t7, t8, t9, t10;
-        asm volatile(
-            "s_load_dword %0, %11, 0x0\n s_load_dword %1, %11, 0x40\n s_load_dword %2, %11, 0x80\n"
-            "s_load_dword %3, %11, 0xc0\n s_load_dword %4, %11, 0x100\n s_load_dword %5, %11, 0x140\n"
-            "s_load_dword %6, %11, 0x180\n s_load_dword %7, %11, 0x1c0\n s_load_dword %8, %11, 0x200\n"
-            "s_load_dword %9, %11, 0x240\n s_load_dword %10, %11, 0x280\n s_waitcnt lgkmcnt(0)"
-            : "=&s"(t0), "=&s"(t1), "=&s"(t2), "=&s"(t3), "=&s"(t4), "=&s"(t5), "=&s"(t6), "=&s"(t7), "=&s"(t8), "=&s"(t9),
-              "=&s"(t10)
-            : "s"(ka));
-        static_assert(sizeof(TiledArgs) <= 0x2c0, "touch every line of the arguments");
+        constexpr int kLines = (int)((sizeof(TiledArgs) + 63) / 64);
+        uint32_t touched[kLines];
+#pragma unroll
+        for (int i = 0; i < kLines; ++i) {
+            const uint32_t off = (uint32_t)i * 64u;
+            asm volatile("s_load_dword %0, %1, %2" : "=s"(touched[i]) : "s"(ka), "s"(off));
+        }
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#pragma unroll
+        for (int i = 0; i < kLines; ++i) asm volatile("" ::"s"(touched[i]));
     }
     const int KT = a.KT;
     const int rb_total = a.rb_end[a.n_mats - 1];
@@ -131,9 +134,11 @@ __global__ __launch_bounds__(kMaxWavesTiled * kWave) void linear_decode_tiled_ke
     int m_req, rb_req;
     mat_of(r0, m_req, rb_req);
     const unsigned char* wt = (const unsigned char*)a.wt[m_req];
-    const unsigned char* sp[NJ];
+    const unsigned char* sp[NCT][NJ];
 #pragma unroll
-    for (int j = 0; j < NJ; ++j) sp[j] = (const unsigned char*)a.signs[m_req][j];
+    for (int ct = 0; ct < NCT; ++ct)
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) sp[ct][j] = (const unsigned char*)a.signs[ct][m_req][j];
     const uint32_t lane16 = (uint32_t)lane * 16u, lane8 = (uint32_t)lane * 8u;
 
     // ---- requests of the first task: base first, (table,) then x, then the signs
@@ -179,8 +184,8 @@ __global__ __launch_bounds__(kMaxWavesTiled * kWave) void linear_decode_tiled_ke
         const bool inside = (kt != k_ragged) || (kt * kTileK + (lane & 31) * 8 < a.in);
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
-            const int ra = 2 * i < a.T ? a.col_token[2 * i] : a.col_token[0];
-            const int rbw = 2 * i + 1 < a.T ? a.col_token[2 * i + 1] : a.col_token[0];
+            const int ra = 2 * i < a.T[0] ? a.col_token[0][2 * i] : a.col_token[0][0];
+            const int rbw = 2 * i + 1 < a.T[0] ? a.col_token[0][2 * i + 1] : a.col_token[0][0];
             const uint32_t tokoff = (uint32_t)(xh ? rbw : ra) * row_bytes;
             xraw[i] = u32x4{0u, 0u, 0u, 0u};
             if (inside) xraw[i] = ldg16(xg, tokoff + off);
@@ -188,12 +193,16 @@ __global__ __launch_bounds__(kMaxWavesTiled * kWave) void linear_decode_tiled_ke
     };
     // Streamed x (a fresh tile per task) is fetched in operand order directly: lane (c, g), slice v reads
     // x[token of column c][256 kt + 32 v + 8 g ..]; a trip through LDS per task would sit on the critical path.
-    int tok_c = a.col_token[0];
+    uint32_t xlane[NCT];
 #pragma unroll
-    for (int i = 0; i < kTiledMaxTokens; ++i) tok_c = (c == i && i < a.T) ? a.col_token[i] : tok_c;
-    const uint32_t xlane = (uint32_t)tok_c * row_bytes + (uint32_t)g * 16u;
-    auto x_fetch_operands = [&](u32x4 (&xop)[8], const int kt) {
-        uint32_t xl = xlane;
+    for (int ct = 0; ct < NCT; ++ct) {
+        int tok_c = a.col_token[ct][0];
+#pragma unroll
+        for (int i = 0; i < kTiledMaxTokens; ++i) tok_c = (c == i && i < a.T[ct]) ? a.col_token[ct][i] : tok_c;
+        xlane[ct] = (uint32_t)tok_c * row_bytes + (uint32_t)g * 16u;
+    }
+    auto x_fetch_operands = [&](u32x4 (&xop)[8], const int kt, const int ct) {
+        uint32_t xl = ct == 0 ? xlane[0] : xlane[NCT - 1];
         asm volatile("" : "+v"(xl));
         const uint32_t off = xl + (uint32_t)kt * (uint32_t)(kTileK * 2);
         if (kt != k_ragged) {
@@ -222,36 +231,49 @@ __global__ __launch_bounds__(kMaxWavesTiled * kWave) void linear_decode_tiled_ke
     u32x4 xraw[XR][8];                            // resident x as fetched; streamed x: the next task's operands
     if (have_work) {
         if constexpr (XSTEPS > 0) x_fetch(xraw[0], kb);
-        else x_fetch_operands(xs[0], kb);
+        else x_fetch_operands(xs[0], kb, 0);
         const uint32_t soff0 = tile0 * (uint32_t)kTileSignBytes + lane8;
 #pragma unroll
-        for (int j = 0; j < NJ; ++j) sr[j] = ldg8_stream(sp[j], soff0);
+        for (int j = 0; j < NJ; ++j) sr[j] = ldg8_stream(sp[0][j], soff0);
         if constexpr (XSTEPS == 2) x_fetch(xraw[1], kb + 1);
     }
 
     // this lane's column: owning job, tenant (for the scale)
-    int myjob = -1, tenant = 0;
+    int myjob[NCT];
+    float alpha_m[NCT][kTiledMaxMats];
 #pragma unroll
-    for (int i = 0; i < kTiledMaxTokens; ++i) {
-        myjob = (c == i && i < a.T) ? a.col_job[i] : myjob;
-        tenant = (c == i && i < a.T) ? a.col_tenant[i] : tenant;
+    for (int ct = 0; ct < NCT; ++ct) {
+        int tenant = 0;
+        myjob[ct] = -1;
+#pragma unroll
+        for (int i = 0; i < kTiledMaxTokens; ++i) {
+            myjob[ct] = (c == i && i < a.T[ct]) ? a.col_job[ct][i] : myjob[ct];
+            tenant = (c == i && i < a.T[ct]) ? a.col_tenant[ct][i] : tenant;
+        }
+#pragma unroll
+        for (int m = 0; m < kTiledMaxMats; ++m) alpha_m[ct][m] = m < a.n_mats ? a.alpha[m][tenant] : 0.f;
     }
-    float alpha_m[kTiledMaxMats];
-#pragma unroll
-    for (int m = 0; m < kTiledMaxMats; ++m) alpha_m[m] = m < a.n_mats ? a.alpha[m][tenant] : 0.f;
 
     if (!have_work) return;   // uniform per workgroup (n_rb) / never true for steps (host: waves <= k tiles)
 #pragma unroll
     for (int i = 0; i < (XSTEPS > 0 ? XR : 0); ++i) x_to_operands(xraw[i], xs[i]);
     const uint32_t lanebits = (uint32_t)c << 4;
 
-    float4v accb = {0.f, 0.f, 0.f, 0.f}, dsel = {0.f, 0.f, 0.f, 0.f};
+    float4v accb[NCT], dsel[NCT];
+#pragma unroll
+    for (int ct = 0; ct < NCT; ++ct) accb[ct] = dsel[ct] = float4v{0.f, 0.f, 0.f, 0.f};
 
-    // One task.  MORE: there is a next task; its tile index is tile_next and its pointers are
-    // current (wt, sp).  xr: this task's x in operand order; with streamed x the next tile (kt_next) is
-    // fetched into xnext during the task and replaces xr at its end.
-    auto task = [&](auto more_tag, u32x4 (&xr)[8], const uint32_t tile_next, u32x4 (&xnext)[8], const int kt_next) {
+    // One task = (row block, k tile, column tile CT).  MORE: there is a next task; its tile index is
+    // tile_next and its pointers are current (wt, sp).  The base registers are re-requested by the
+    // last column tile of a (row block, k tile) only.  xr: this task's x in operand order; with
+    // streamed x the next task's (kt_next, next column tile) is fetched into xnext during the task
+    // and replaces xr at its end.
+    auto task = [&](auto more_tag, auto ct_tag, u32x4 (&xr)[8], const uint32_t tile_next, u32x4 (&xnext)[8],
+                    const int kt_next) {
         constexpr bool MORE = decltype(more_tag)::value;
+        constexpr int CT = decltype(ct_tag)::value;
+        constexpr int CT_NEXT = (CT + 1) % NCT;
+        constexpr bool NEW_BASE = CT == NCT - 1;   // the next task is on another tile of W
         // The lane offsets pass through an empty asm in every task: otherwise the compiler hoists
         // "uniform base + lane offset" of every load out of the loop as a 64-bit register pair per load.
         uint32_t l16 = lane16, l8 = lane8;
@@ -260,24 +282,24 @@ __global__ __launch_bounds__(kMaxWavesTiled * kWave) void linear_decode_tiled_ke
         // ---- base product; W[v] of the next task goes into the register group just read
 #pragma unroll
         for (int v = 0; v < 8; ++v) {
-            accb = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8, wr[v]), __builtin_bit_cast(half8, xr[v]),
-                                                          accb, 0, 0, 0);
-            if constexpr (MORE) wr[v] = ldg16_stream(wt, woff + v * 1024);
+            accb[CT] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8, wr[v]),
+                                                              __builtin_bit_cast(half8, xr[v]), accb[CT], 0, 0, 0);
+            if constexpr (MORE && NEW_BASE) wr[v] = ldg16_stream(wt, woff + v * 1024);
             __builtin_amdgcn_sched_barrier(0);   // keep each request behind the MFMA that frees its registers
         }
-        if constexpr (MORE && XSTEPS == 0) x_fetch_operands(xnext, kt_next);
+        if constexpr (MORE && XSTEPS == 0) x_fetch_operands(xnext, kt_next, CT_NEXT);
         __builtin_amdgcn_sched_barrier(0);
         // ---- delta jobs.  The 8 NJ (job, slice) pairs of the task form one sequence; the table
         // look-up of pair i + kLookAhead is issued before the MFMA of pair i, through a ring of
         // operand registers, and a job's sign words are re-requested as soon as its last address exists.
-        constexpr int kLookAhead = 6, kRing = kLookAhead + 2, kPairs = 8 * NJ;
+        constexpr int kLookAhead = NCT == 2 ? 4 : 6, kRing = kLookAhead + 2, kPairs = 8 * NJ;
         u32x4 ring[kRing];
         float4v sel = {0.f, 0.f, 0.f, 0.f};   // the job owning this lane's column, this tile
         auto look_up = [&](const int i) {      // i = 8 * job + slice
             const int j = i >> 3, v = i & 7;
             ring[i % kRing] = lut_read(sr[j], v, lanebits);
             if constexpr (MORE) {
-                if (v == 7) sr[j] = ldg8_stream(sp[j], soff);
+                if (v == 7) sr[j] = ldg8_stream(sp[CT_NEXT][j], soff);
             }
         };
 #pragma unroll
@@ -289,7 +311,7 @@ __global__ __launch_bounds__(kMaxWavesTiled * kWave) void linear_decode_tiled_ke
             acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8, ring[i % kRing]),
                                                          __builtin_bit_cast(half8, xr[i & 7]), acc, 0, 0, 0);
             if ((i & 7) == 7) {
-                const bool mine = (myjob == (i >> 3));
+                const bool mine = (myjob[CT] == (i >> 3));
 #pragma unroll
                 for (int q = 0; q < 4; ++q) sel[q] = mine ? acc[q] : sel[q];
                 // pin the selection here: left alone, the compiler sinks all of them below the last job
@@ -299,7 +321,7 @@ __global__ __launch_bounds__(kMaxWavesTiled * kWave) void linear_decode_tiled_ke
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
-        dsel += sel;
+        dsel[CT] += sel;
         if constexpr (MORE && XSTEPS == 0) {   // this task's x is spent: move the next one in
 #pragma unroll
             for (int v = 0; v < 8; ++v) xr[v] = xnext[v];
@@ -309,16 +331,17 @@ __global__ __launch_bounds__(kMaxWavesTiled * kWave) void linear_decode_tiled_ke
     // The partial tiles of `n` finished row blocks, first one rbg0: add the wavefronts in a fixed order, write y.
     auto flush = [&](const int rbg0, const int n, const bool more_follow) {
         __syncthreads();
-        for (int idx = threadIdx.x; idx < n * 256; idx += blockDim.x) {
+        for (int idx = threadIdx.x; idx < n * 256; idx += blockDim.x) {   // n slots = n / NCT row blocks
             const int slot = idx >> 8, e = idx & 255, col = e >> 4, row = e & 15;
+            const int ct = slot % NCT;
             int m, rb;
-            mat_of(rbg0 + slot, m, rb);
+            mat_of(rbg0 + slot / NCT, m, rb);
             const int out = a.out[m], n_row = rb * kTileRows + row;
-            if (col < a.T && n_row < out) {
+            if (col < a.T[ct] && n_row < out) {
                 float s = 0.f;
                 for (int wv = 0; wv < nw; ++wv)
                     s += *(const float*)(smem + kLutBytes + wv * Plan::kRegion + (slot * 256 + e) * 4);
-                a.y[m][(int64_t)a.col_token[col] * out + n_row] = f2h_rne(s);
+                a.y[m][(int64_t)a.col_token[ct][col] * out + n_row] = f2h_rne(s);
             }
         }
         if (more_follow) __syncthreads();
@@ -337,44 +360,51 @@ __global__ __launch_bounds__(kMaxWavesTiled * kWave) void linear_decode_tiled_ke
             if (m_nx != m_req) {
                 wt = (const unsigned char*)a.wt[m_nx];
 #pragma unroll
-                for (int j = 0; j < NJ; ++j) sp[j] = (const unsigned char*)a.signs[m_nx][j];
+                for (int ct = 0; ct < NCT; ++ct)
+#pragma unroll
+                    for (int j = 0; j < NJ; ++j) sp[ct][j] = (const unsigned char*)a.signs[ct][m_nx][j];
             }
         };
+        using Ct0 = std::integral_constant<int, 0>;
+        using CtL = std::integral_constant<int, NCT - 1>;
         if constexpr (XSTEPS > 0) {
 #pragma unroll
             for (int ki = 0; ki < XSTEPS; ++ki) {
                 if (ki + 1 < XSTEPS) {
-                    task(std::true_type{}, xs[ki], tile_rb + ki + 1, xraw[0], 0);
+                    task(std::true_type{}, Ct0{}, xs[ki], tile_rb + ki + 1, xraw[0], 0);
                 } else if (!last_rb) {
                     cross();
-                    task(std::true_type{}, xs[ki], tile_nx, xraw[0], 0);
+                    task(std::true_type{}, Ct0{}, xs[ki], tile_nx, xraw[0], 0);
                 } else {
-                    task(std::false_type{}, xs[ki], 0u, xraw[0], 0);
+                    task(std::false_type{}, Ct0{}, xs[ki], 0u, xraw[0], 0);
                 }
             }
         } else {
             for (int ki = 0; ki < steps; ++ki) {
                 const bool inner = ki + 1 < steps;
+                // all but the last column tile: the next task stays on this tile (same k tile, next columns)
+                if constexpr (NCT == 2) task(std::true_type{}, Ct0{}, xs[0], tile_rb + ki, xraw[0], kb + ki);
                 if (!inner && !last_rb) cross();
                 if (inner || !last_rb)
-                    task(std::true_type{}, xs[0], inner ? tile_rb + ki + 1 : tile_nx, xraw[0], inner ? kb + ki + 1 : kb);
+                    task(std::true_type{}, CtL{}, xs[0], inner ? tile_rb + ki + 1 : tile_nx, xraw[0], inner ? kb + ki + 1 : kb);
                 else
-                    task(std::false_type{}, xs[0], 0u, xraw[0], 0);
+                    task(std::false_type{}, CtL{}, xs[0], 0u, xraw[0], 0);
             }
         }
-        // ---- row block done: this wavefront's partial tile -> slot
-        {
-            const float al = m_cur == 0 ? alpha_m[0] : (m_cur == 1 ? alpha_m[1] : alpha_m[2]);
+        // ---- row block done: this wavefront's partial tiles -> slots
+#pragma unroll
+        for (int ct = 0; ct < NCT; ++ct) {
+            const float al = m_cur == 0 ? alpha_m[ct][0] : (m_cur == 1 ? alpha_m[ct][1] : alpha_m[ct][2]);
             float4v r;
 #pragma unroll
-            for (int i = 0; i < 4; ++i) r[i] = accb[i] + al * dsel[i];
-            *(float4v*)(region + (slot * 256 + c * 16 + 4 * g) * 4) = r;   // [column][row]
-            accb = dsel = float4v{0.f, 0.f, 0.f, 0.f};
+            for (int i = 0; i < 4; ++i) r[i] = accb[ct][i] + al * dsel[ct][i];
+            *(float4v*)(region + ((slot + ct) * 256 + c * 16 + 4 * g) * 4) = r;   // [column][row]
+            accb[ct] = dsel[ct] = float4v{0.f, 0.f, 0.f, 0.f};
         }
-        ++slot;
+        slot += NCT;
         if (slot == Plan::kRedSlots || last_rb) {
             flush(flush_base, slot, !last_rb);
-            flush_base += slot;
+            flush_base += slot / NCT;
             slot = 0;
         }
         m_cur = m_nx;
@@ -383,9 +413,9 @@ __global__ __launch_bounds__(kMaxWavesTiled * kWave) void linear_decode_tiled_ke
     }
 }
 
-template <int NJ, int XSTEPS>
+template <int NJ, int XSTEPS, int NCT = 1>
 static hipError_t launch_inst(const TiledArgs& args, int n_waves, unsigned grid, hipStream_t st) {
-    auto kernel = linear_decode_tiled_kernel<NJ, XSTEPS>;
+    auto kernel = linear_decode_tiled_kernel<NJ, XSTEPS, NCT>;
     const size_t lds = (size_t)LdsPlan<XSTEPS>::kTotal;
     static bool attr_set = false;   // raising the dynamic LDS limit is idempotent; a race only repeats it
     if (!attr_set) {
@@ -409,7 +439,9 @@ static hipError_t launch_nj(const TiledArgs& args, int n_waves, int xsteps, unsi
 }
 
 hipError_t launch_linear_decode_tiled(const TiledArgs& args, int n_jobs, hipStream_t st) {
-    if (n_jobs < 1 || n_jobs > kTiledMaxJobs || args.n_mats < 1 || args.n_mats > kTiledMaxMats) return hipErrorInvalidValue;
+    if (n_jobs < 1 || n_jobs > kTiledMaxJobs || args.n_mats < 1 || args.n_mats > kTiledMaxMats || args.n_ct < 1 ||
+        args.n_ct > kTiledMaxCt)
+        return hipErrorInvalidValue;
     const int rb_total = args.rb_end[args.n_mats - 1];
     if (rb_total < 1 || args.KT < 0) return hipErrorInvalidValue;
     static int cus = 0;   // compute units of the current device, asked once
@@ -426,6 +458,10 @@ hipError_t launch_linear_decode_tiled(const TiledArgs& args, int n_jobs, hipStre
     const unsigned grid = (unsigned)(rb_total < cus ? rb_total : cus);
     int n_waves = kMaxWavesTiled;
     while (n_waves > 1 && n_waves > args.KT) n_waves >>= 1;
+    if (args.n_ct == 2) {   // 17..32 tokens: two column tiles, streamed x
+        if (n_jobs <= 8) return launch_inst<8, 0, 2>(args, n_waves, grid, st);
+        return launch_inst<16, 0, 2>(args, n_waves, grid, st);
+    }
     int xsteps = 0;
     if (args.KT > 0 && args.KT % n_waves == 0 && args.KT / n_waves <= 2) xsteps = args.KT / n_waves;
     if (n_jobs <= 4) return launch_nj<4>(args, n_waves, xsteps, grid, st);
