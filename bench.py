@@ -47,6 +47,9 @@ def parse():
     ap.add_argument("--per-linear", action="store_true", help="also time each linear shape on its own")
     ap.add_argument("--workload", choices=["decode", "prefill"], default="decode",
                     help="prefill: 8 tenants x 512 tokens on the 4096x11008 and 11008x4096 linears (matrix-core GEMM)")
+    ap.add_argument("--mix", type=str, default="",
+                    help="mixed decode batch: tokens per active tenant, e.g. 6,4,3,1,1,1 (tenants 0.. of the B resident "
+                         "ones; the others stay idle); default: one token per tenant")
     ap.add_argument("--calibrate", action="store_true",
                     help="only run a 1 GiB copy and a 1 GiB read three times: known sizes against which the "
                          "profiler's HBM byte counters are scaled")
@@ -143,6 +146,12 @@ def main():
     shapes = synth.LLAMA2_7B_LAYER if args.model == "7b" else synth.LLAMA2_70B_LAYER
     sigma = 0.002 if args.model == "7b" else 0.001
     tok = synth.one_token_per_tenant(B)
+    if args.mix:
+        counts = [int(c) for c in args.mix.split(",")]
+        assert len(counts) <= B and all(c > 0 for c in counts), "--mix: at most B positive counts"
+        tok = [t for t, c in enumerate(counts) for _ in range(c)]
+        args.no_extras = args.no_cpu = True      # the baselines below are defined for one token per tenant
+    T, n_active = len(tok), len(set(tok))
     tok_arr = bd._tok_array(tok)
 
     # ---- build the stack: base weights + B compressed deltas per matrix, all resident in HBM
@@ -178,8 +187,8 @@ def main():
                     base = table = None
             mats.append((name, out, inn, base, table, wt, ttable))
         layers.append(mats)
-    xs = {inn: synth.activations(B, inn, device=dev, tag=("bench", inn)) for _, _, inn in shapes}
-    ys = {(name, out): torch.empty((B, out), dtype=torch.float16, device=dev) for name, out, _ in shapes}
+    xs = {inn: synth.activations(T, inn, device=dev, tag=("bench", inn)) for _, _, inn in shapes}
+    ys = {(name, out): torch.empty((T, out), dtype=torch.float16, device=dev) for name, out, _ in shapes}
     torch.cuda.synchronize()
     t_setup = time.time() - t_setup
 
@@ -216,8 +225,8 @@ def main():
 
     launches_per_step = sum(len(p) for p in plans)
     P = sum(o * i for _, o, i in shapes)
-    xy_bytes = sum(B * (i + o) * 2 for _, o, i in shapes)
-    bytes_per_step = n_layers * (2.0 * P + B * P / 8.0 + xy_bytes)     # algorithmic: W once, each delta once, x, y
+    xy_bytes = sum(T * (i + o) * 2 for _, o, i in shapes)
+    bytes_per_step = n_layers * (2.0 * P + n_active * P / 8.0 + xy_bytes)   # algorithmic: W once, each active delta once, x, y
 
     run_stack()                                   # first call sets kernel attributes; keep it out of any capture
     torch.cuda.synchronize()
@@ -251,7 +260,7 @@ def main():
     wall = time.time() - wall0
     ms_total = e0.elapsed_time(e1)
     ms_per_step = ms_total / args.steps
-    tokens_per_s = B / (ms_per_step * 1e-3)
+    tokens_per_s = T / (ms_per_step * 1e-3)
     achieved_gbs = bytes_per_step / (ms_per_step * 1e-3) / 1e9
 
     result = {
@@ -269,8 +278,10 @@ def main():
         "data": "synthetic",
         "config": {
             "workload": f"llama-2-{args.model} linear stack: {n_layers} layers x (q,k,v,o,gate,up,down), "
-                        f"B={B} tenants, one decode token per tenant, distinct 1-bit delta per (tenant, matrix)",
-            "tenants": B, "layers": n_layers, "launches_per_step": launches_per_step,
+                        f"B={B} tenants, " + (f"mixed decode batch of {T} tokens ({args.mix} per active tenant), "
+                                               if args.mix else "one decode token per tenant, ")
+                        + "distinct 1-bit delta per (tenant, matrix)",
+            "tenants": B, "tokens": T, "active_tenants": n_active, "layers": n_layers, "launches_per_step": launches_per_step,
             "launch": "hip graph replay" if graph is not None else "eager",
             "path": args.path, "kernel_variant": args.variant,
         },
@@ -280,7 +291,8 @@ def main():
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
             "frac": round(achieved_gbs / HBM_PEAK_GBS, 4),
-            "traffic": MEASURED_TRAFFIC_BYTES_PER_LAUNCH.get((args.model, B, args.path)) if n_layers == 32 else None,
+            "traffic": MEASURED_TRAFFIC_BYTES_PER_LAUNCH.get((args.model, B, args.path))
+                       if n_layers == 32 and not args.mix else None,
             "kernel": "linear_decode_mfma_kernel" if args.path == "rowmajor" else "linear_decode_tiled_kernel",
             "bytes_per_launch": round(bytes_per_step / launches_per_step, 1),
             "avg_launch_us": round(ms_per_step * 1e3 / launches_per_step, 3),

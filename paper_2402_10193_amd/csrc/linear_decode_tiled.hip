@@ -459,6 +459,7 @@ hipError_t launch_linear_decode_tiled(const TiledArgs& args, int n_jobs, hipStre
     int n_waves = kMaxWavesTiled;
     while (n_waves > 1 && n_waves > args.KT) n_waves >>= 1;
     if (args.n_ct == 2) {   // 17..32 tokens: two column tiles, streamed x
+        if (n_jobs <= 4) return launch_inst<4, 0, 2>(args, n_waves, grid, st);
         if (n_jobs <= 8) return launch_inst<8, 0, 2>(args, n_waves, grid, st);
         return launch_inst<16, 0, 2>(args, n_waves, grid, st);
     }

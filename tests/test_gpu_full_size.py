@@ -81,6 +81,48 @@ def test_llama2_7b_grouped_launch_b16_full_output(ref, names, outs, inn):
         print(f"   {names[i]}: max rel err {err:.2e}", flush=True)
 
 
+MIXED_BATCHES = [
+    # resident tenants, tenant of each token (continuous batching: several tokens of some tenants, most tenants idle)
+    (24, [3, 3, 3, 3, 3, 3, 0, 0, 0, 0, 7, 7, 7, 9, 12, 20]),                                  # 16 tokens, 6 of 24 tenants
+    (40, [5] * 9 + [31] * 7 + [2, 2, 2, 39, 39, 17, 8, 11, 23, 30, 1]),                        # 27 tokens: two column tiles
+]
+
+
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("case", range(len(MIXED_BATCHES)))
+def test_llama2_7b_mixed_batch_gate_up_full_output(ref, case):
+    """A mixed decode batch on the grouped gate,up launch at full size: only the active tenants' deltas exist
+    (idle tenants have no pointer), each is streamed once for all of its tokens."""
+    n_res, tok = MIXED_BATCHES[case]
+    out, inn = 11008, 4096
+    active = sorted(set(tok))
+    print(f"7B mixed batch case={case} T={len(tok)} active={len(active)} of {n_res}", flush=True)
+    x = synth.activations(len(tok), inn, device=DEV, tag=("7bmix", case))
+    ws = bd.new_workspace(bd.workspace_bytes(bd.OP_COMPRESS, 0, out, inn, 1), DEV)
+    wts, tables, keep = [], [], []
+    for name in ("gate", "up"):
+        base = synth.base_weight(out, inn, device=DEV, tag=("7bmix", case, name))
+        tiled, packed = [None] * n_res, [None] * n_res
+        alpha = torch.zeros(n_res, dtype=torch.float32, device=DEV)
+        for t in active:
+            ft = synth.finetuned_weight(base, sigma=0.002, tag=("7bmix", case, name, t))
+            p, a = bd.compress(base, ft, workspace=ws)
+            del ft
+            packed[t], alpha[t] = p, a
+            tiled[t] = bd.tile_signs(p, out, inn)
+        wts.append(bd.tile_base(base))
+        tables.append(bd.TiledTenantTable(tiled, alpha))
+        keep.append((base, packed, alpha))
+    ys = bd.linear_multitenant_tiled_group(x, bd.TiledGroup(wts, [out, out], tables), tok)
+    torch.cuda.synchronize()
+    for i, (base, packed, alpha) in enumerate(keep):
+        dummy = np.zeros((out, inn // 32), dtype=np.uint32)              # never selected: idle tenants have no token
+        packed_np = [packed_to_np(p) if p is not None else dummy for p in packed]   # bit-exactness is covered above
+        _, y32 = ref.linear_multitenant(to_np(x), to_np(base), packed_np, [float(a) for a in to_np(alpha)], tok)
+        err = check_close(ys[i], y32, f"7B mixed batch {i}")
+        print(f"   matrix {i}: max rel err {err:.2e}", flush=True)
+
+
 @pytest.mark.timeout(900)
 @pytest.mark.parametrize("name,out,inn", [("kv", 1024, 8192), ("gate", 28672, 8192), ("down", 8192, 28672)])
 def test_llama2_70b_b32_sampled_rows(ref, name, out, inn):

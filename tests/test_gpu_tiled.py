@@ -79,6 +79,7 @@ CASES = [
     (64, 1536, 32, list(range(32))),                                 # 32 tenants
     (40, 96, 2, [1, 0, 1]),                                          # K % 128 != 0
     (64, 11008, 16, list(range(15, -1, -1))),                        # the down-projection's K: 43 tiles
+    (80, 2048, 6, [5] * 6 + [1] * 5 + [2] * 5 + [0] * 4 + [1] * 3),  # 23 tokens of 4 tenants: two column tiles, few jobs each
 ]
 
 
