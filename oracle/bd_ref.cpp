@@ -13,6 +13,9 @@
 //   * scale                   alpha = mean |Delta_ij|                 (Eq. 4)
 //   * serving decomposition   X'_i = W_base X_i + alpha_i Sign(Delta_i) X_i
 //                                                                     (Eq. 6)
+//   * iterated compression   the compressor applied again with the compressed
+//                             model as the base: k sign planes, k scales
+//                                        (Sec. 4.2, ablation over the fidelity of Delta)
 // Readings where the paper is silent (all listed in the design notes):
 //   * weights are [out, in] row-major, the reduction runs along `in`;
 //   * 32 signs per uint32 along `in`, least significant bit first,
@@ -24,6 +27,12 @@
 //     ascending k, alpha is applied to the finished +-1 sum in binary32, and the
 //     result is rounded once (nearest even) to binary16.  A binary64 variant
 //     exists to bound the oracle's own rounding noise.
+//
+//   * iterated compression: the residual W_fine - (W_base + sum_i alpha_i S_i)
+//     is carried in binary32 (one rounding per iteration: r <- r - alpha * s),
+//     never re-rounded to binary16; every alpha_j is rounded to binary16 like
+//     the first; the k-plane linear accumulates each plane's +-1 sum separately
+//     in binary32 and adds alpha_j * sum_j to the base product in ascending j.
 //
 // Parity pins live in tests/test_oracle_*.py (closed forms, brute force,
 // library special cases, hand-written words).  No function here is unpinned.
@@ -238,6 +247,125 @@ int bd_ref_linear_multitenant_f64(const uint16_t* x_f16, const uint16_t* w_base_
                 acc_delta += (double)sign_of_bit(srow, k) * xv;
             }
             y_f64[t * out + n] = acc_base + (double)alpha_by_tenant[tenant_of_token[t]] * acc_delta;
+        }
+    }
+    return 0;
+}
+
+// ---- Sec. 4.2 (fidelity of Delta): the compressor iterated k times ----------
+// Iteration j treats W_base + sum_{i<j} alpha_i S_i as the base model: its delta is the residual
+//   r_0 = f32(W_fine) - f32(W_base),   r_{j+1} = r_j - alpha_j * Sign(r_j)      (binary32)
+// and it emits plane j = sign bits of r_j (Eq. 2) and alpha_j = mean |r_j| (Eq. 4, binary64 sum,
+// one rounding to binary16).  packed: [k][out][in/32]; alpha, alpha_unrounded: [k];
+// residual_sq (may be null): [k+1], sum of r_j^2 in binary64 before each iteration and after the last.
+int bd_ref_compress_iterated(const uint16_t* w_base_f16, const uint16_t* w_ft_f16, int64_t out, int64_t in,
+                             int32_t k, uint32_t* packed, float* alpha_f16_as_float, double* alpha_unrounded,
+                             double* residual_sq) {
+    if (in % 32 != 0 || k < 1) return -1;
+    const int64_t words = in / 32, count = out * in;
+    std::vector<float> r((size_t)count);
+    for (int64_t i = 0; i < count; ++i) r[(size_t)i] = half_bits_to_float(w_ft_f16[i]) - half_bits_to_float(w_base_f16[i]);
+    std::vector<double> row_abs((size_t)out), row_sq((size_t)out);
+    for (int32_t j = 0; j <= k; ++j) {
+#pragma omp parallel for schedule(static)
+        for (int64_t n = 0; n < out; ++n) {
+            double sa = 0.0, sq = 0.0;
+            for (int64_t c = 0; c < in; ++c) {
+                const double v = (double)r[(size_t)(n * in + c)];
+                sa += std::fabs(v);
+                sq += v * v;
+            }
+            row_abs[(size_t)n] = sa;
+            row_sq[(size_t)n] = sq;
+        }
+        double total_abs = 0.0, total_sq = 0.0;
+        for (int64_t n = 0; n < out; ++n) {
+            total_abs += row_abs[(size_t)n];
+            total_sq += row_sq[(size_t)n];
+        }
+        if (residual_sq) residual_sq[j] = total_sq;
+        if (j == k) break;
+        const double mean = count > 0 ? total_abs / (double)count : 0.0;
+        const float a = half_bits_to_float(float_to_half_bits((float)mean));
+        if (alpha_unrounded) alpha_unrounded[j] = mean;
+        alpha_f16_as_float[j] = a;
+        uint32_t* plane = packed + (int64_t)j * out * words;
+#pragma omp parallel for schedule(static)
+        for (int64_t n = 0; n < out; ++n) {
+            for (int64_t w = 0; w < words; ++w) {
+                uint32_t word = 0;
+                for (int b = 0; b < 32; ++b) {
+                    float& v = r[(size_t)(n * in + w * 32 + b)];
+                    const bool plus = v > 0.0f;
+                    if (plus) word |= (1u << b);
+                    v = plus ? v - a : v + a;          // r - alpha * (+-1)
+                }
+                plane[n * words + w] = word;
+            }
+        }
+    }
+    return 0;
+}
+
+// ---- Eq. 6 with k sign planes per tenant -------------------------------------
+//   y[t,n] = sum_k x W_base  +  sum_{j<k} alpha_{e,j} * (sum_k x s_{e,j}),   e = tenant(t)
+// planes[e * k + j]: [out, in/32]; alpha[e * k + j].  Every sum over the reduction index is binary32,
+// ascending; the planes are added to the base product in ascending j; one rounding to binary16.
+int bd_ref_linear_multitenant_kbit(const uint16_t* x_f16, const uint16_t* w_base_f16,
+                                   const uint32_t* const* planes, const float* alpha,
+                                   const int32_t* tenant_of_token, uint16_t* y_f16, float* y_f32,
+                                   int64_t T, int64_t out, int64_t in, int32_t n_tenants, int32_t k) {
+    if (in % 32 != 0 || k < 1) return -1;
+    for (int64_t t = 0; t < T; ++t)
+        if (tenant_of_token[t] < 0 || tenant_of_token[t] >= n_tenants) return -2;
+    const int64_t words = in / 32;
+#pragma omp parallel for schedule(static)
+    for (int64_t n = 0; n < out; ++n) {
+        for (int64_t t = 0; t < T; ++t) {
+            const int64_t e = tenant_of_token[t];
+            float y = 0.0f;
+            for (int64_t c = 0; c < in; ++c)
+                y += half_bits_to_float(x_f16[t * in + c]) * half_bits_to_float(w_base_f16[n * in + c]);
+            for (int32_t j = 0; j < k; ++j) {
+                const uint32_t* srow = planes[e * k + j] + n * words;
+                float acc = 0.0f;
+                for (int64_t c = 0; c < in; ++c) {
+                    const float xv = half_bits_to_float(x_f16[t * in + c]);
+                    acc += sign_of_bit(srow, c) > 0 ? xv : -xv;
+                }
+                y += alpha[e * k + j] * acc;
+            }
+            if (y_f32) y_f32[t * out + n] = y;
+            if (y_f16) y_f16[t * out + n] = float_to_half_bits(y);
+        }
+    }
+    return 0;
+}
+
+// binary64 accumulation, no output rounding
+int bd_ref_linear_multitenant_kbit_f64(const uint16_t* x_f16, const uint16_t* w_base_f16,
+                                       const uint32_t* const* planes, const float* alpha,
+                                       const int32_t* tenant_of_token, double* y_f64,
+                                       int64_t T, int64_t out, int64_t in, int32_t n_tenants, int32_t k) {
+    if (in % 32 != 0 || k < 1) return -1;
+    for (int64_t t = 0; t < T; ++t)
+        if (tenant_of_token[t] < 0 || tenant_of_token[t] >= n_tenants) return -2;
+    const int64_t words = in / 32;
+#pragma omp parallel for schedule(static)
+    for (int64_t n = 0; n < out; ++n) {
+        for (int64_t t = 0; t < T; ++t) {
+            const int64_t e = tenant_of_token[t];
+            double y = 0.0;
+            for (int64_t c = 0; c < in; ++c)
+                y += (double)half_bits_to_float(x_f16[t * in + c]) * (double)half_bits_to_float(w_base_f16[n * in + c]);
+            for (int32_t j = 0; j < k; ++j) {
+                const uint32_t* srow = planes[e * k + j] + n * words;
+                double acc = 0.0;
+                for (int64_t c = 0; c < in; ++c)
+                    acc += (double)sign_of_bit(srow, c) * (double)half_bits_to_float(x_f16[t * in + c]);
+                y += (double)alpha[e * k + j] * acc;
+            }
+            y_f64[t * out + n] = y;
         }
     }
     return 0;

@@ -57,6 +57,11 @@ def lib() -> ctypes.CDLL:
                                                 c_u16p, c_f32p, i64, i64, i64, ctypes.c_int32]
         L.bd_ref_linear_multitenant_f64.argtypes = [c_u16p, c_u16p, ctypes.POINTER(c_u32p), c_f32p, c_i32p,
                                                     c_f64p, i64, i64, i64, ctypes.c_int32]
+        L.bd_ref_compress_iterated.argtypes = [c_u16p, c_u16p, i64, i64, ctypes.c_int32, c_u32p, c_f32p, c_f64p, c_f64p]
+        L.bd_ref_linear_multitenant_kbit.argtypes = [c_u16p, c_u16p, ctypes.POINTER(c_u32p), c_f32p, c_i32p,
+                                                     c_u16p, c_f32p, i64, i64, i64, ctypes.c_int32, ctypes.c_int32]
+        L.bd_ref_linear_multitenant_kbit_f64.argtypes = [c_u16p, c_u16p, ctypes.POINTER(c_u32p), c_f32p, c_i32p,
+                                                         c_f64p, i64, i64, i64, ctypes.c_int32, ctypes.c_int32]
         L.bd_ref_linear_materialised.argtypes = [c_u16p, c_u16p, c_u32p, ctypes.c_float, c_f32p, c_f32p,
                                                  i64, i64, i64]
         L.bd_ref_linear_naive.argtypes = [c_u16p, ctypes.POINTER(c_u16p), c_i32p, c_u16p, c_f32p,
@@ -125,6 +130,79 @@ def compress(w_base: np.ndarray, w_ft: np.ndarray):
                                _p(packed, ctypes.c_uint32), ctypes.byref(alpha), ctypes.byref(mean))
     assert rc == 0
     return packed, float(alpha.value), float(mean.value)
+
+
+def compress_iterated(w_base: np.ndarray, w_ft: np.ndarray, k: int):
+    """The compressor iterated k times (Sec. 4.2, fidelity of Delta).  Returns (packed uint32 [k,out,in/32],
+    alpha float32 [k] (binary16-representable), means before rounding float64 [k], residual sum of squares
+    float64 [k+1] before each iteration and after the last)."""
+    b, f = _u16(w_base), _u16(w_ft)
+    assert b.shape == f.shape
+    out, inn = b.shape
+    if inn % 32 != 0 or k < 1:
+        raise ValueError("in must be a multiple of 32 and k >= 1")
+    packed = np.empty((k, out, inn // 32), dtype=np.uint32)
+    alpha = np.empty(k, dtype=np.float32)
+    mean = np.empty(k, dtype=np.float64)
+    rsq = np.empty(k + 1, dtype=np.float64)
+    rc = lib().bd_ref_compress_iterated(_p(b, ctypes.c_uint16), _p(f, ctypes.c_uint16), out, inn, k,
+                                        _p(packed, ctypes.c_uint32), _p(alpha, ctypes.c_float),
+                                        _p(mean, ctypes.c_double), _p(rsq, ctypes.c_double))
+    assert rc == 0
+    return packed, alpha, mean, rsq
+
+
+def _kbit_args(x, w_base, planes_by_tenant, alpha_by_tenant, tenant_of_token):
+    xb, wb = _u16(x), _u16(w_base)
+    T, inn = xb.shape
+    out = wb.shape[0]
+    assert wb.shape[1] == inn
+    k = len(planes_by_tenant[0])
+    flat = []
+    for planes in planes_by_tenant:
+        assert len(planes) == k
+        for p in planes:
+            p = np.ascontiguousarray(p, dtype=np.uint32)
+            assert p.shape == (out, inn // 32)
+            flat.append(p)
+    ptrs, keep = _tenant_ptrs(flat, ctypes.c_uint32)
+    alpha = np.ascontiguousarray(alpha_by_tenant, dtype=np.float32)
+    assert alpha.shape == (len(planes_by_tenant), k)
+    tok = np.ascontiguousarray(tenant_of_token, dtype=np.int32)
+    assert tok.shape == (T,)
+    return xb, wb, T, out, inn, k, ptrs, keep, alpha, tok
+
+
+def linear_multitenant_kbit(x, w_base, planes_by_tenant, alpha_by_tenant, tenant_of_token):
+    """Eq. 6 with k sign planes per tenant: planes_by_tenant[e][j] uint32 [out,in/32], alpha_by_tenant [n_tenants,k].
+    Returns (y float16 [T,out], y float32 before rounding)."""
+    xb, wb, T, out, inn, k, ptrs, keep, alpha, tok = _kbit_args(x, w_base, planes_by_tenant, alpha_by_tenant, tenant_of_token)
+    y16 = np.empty((T, out), dtype=np.uint16)
+    y32 = np.empty((T, out), dtype=np.float32)
+    rc = lib().bd_ref_linear_multitenant_kbit(_p(xb, ctypes.c_uint16), _p(wb, ctypes.c_uint16), ptrs,
+                                              _p(alpha, ctypes.c_float), _p(tok, ctypes.c_int32),
+                                              _p(y16, ctypes.c_uint16), _p(y32, ctypes.c_float),
+                                              T, out, inn, len(planes_by_tenant), k)
+    if rc == -1:
+        raise ValueError("in must be a multiple of 32")
+    if rc == -2:
+        raise IndexError("tenant id out of range")
+    del keep
+    return y16.view(np.float16), y32
+
+
+def linear_multitenant_kbit_f64(x, w_base, planes_by_tenant, alpha_by_tenant, tenant_of_token):
+    xb, wb, T, out, inn, k, ptrs, keep, alpha, tok = _kbit_args(x, w_base, planes_by_tenant, alpha_by_tenant, tenant_of_token)
+    y = np.empty((T, out), dtype=np.float64)
+    rc = lib().bd_ref_linear_multitenant_kbit_f64(_p(xb, ctypes.c_uint16), _p(wb, ctypes.c_uint16), ptrs,
+                                                  _p(alpha, ctypes.c_float), _p(tok, ctypes.c_int32),
+                                                  _p(y, ctypes.c_double), T, out, inn, len(planes_by_tenant), k)
+    if rc == -1:
+        raise ValueError("in must be a multiple of 32")
+    if rc == -2:
+        raise IndexError("tenant id out of range")
+    del keep
+    return y
 
 
 def _tenant_ptrs(arrs: Sequence[np.ndarray], ctype):
