@@ -179,6 +179,50 @@ bd_status bd_linear_multitenant_tiled_group(int32_t n_mats, const uint16_t* x_f1
                                             int64_t T, const int64_t* out, int64_t in, int32_t n_tenants,
                                             void* stream);
 
+/* ---- several sign planes per tenant (Sec. 4.2 of the paper, ablation over the fidelity of Delta) ----
+ * Applying the compressor again with the compressed model as the base gives a second 1-bit mask
+ * with a scale of its own, and so on: W_fine ~ W_base + sum_{j<k} alpha_j S_j.  The residual
+ *   r_0 = f32(w_ft) - f32(w_base),   r_{j+1} = r_j - alpha_j * Sign(r_j)          (IEEE binary32)
+ * is never re-rounded to fp16; plane j = sign bits of r_j (Eq. 2), alpha_j = fp16_rne(mean |r_j|)
+ * (Eq. 4, binary64 sum).  k = 1 is bd_compress.
+ *   packed [k][out][in/32]; alpha: k floats on the device (also read back by later iterations);
+ *   workspace as for bd_compress; 1 <= k <= BD_MAX_PLANES, else BD_ERR_SHAPE.  (Plane j starts
+ *   j * out * in / 8 bytes into packed: 16-byte aligned, as bd_tile_signs wants it, when out*in % 128 == 0.)
+ * Asynchronous: k compress launches, each reading the scales the earlier ones left in `alpha`. */
+#define BD_MAX_PLANES 8
+bd_status bd_compress_iterated(const uint16_t* w_base_f16, const uint16_t* w_ft_f16,
+                               int64_t out, int64_t in, int32_t k,
+                               uint32_t* packed, float* alpha,
+                               void* workspace, size_t workspace_bytes, void* stream);
+
+/* Eq. 6 with k planes per tenant over the serving layout:
+ *   y[t] = x[t] W_base^T + sum_{j<k} alpha[e*k+j] * (x[t] S_{e,j}^T),   e = tenant_of_token[t]
+ * (each +-1 sum accumulated in binary32, scaled, added to the base product; one rounding to fp16).
+ *   planes_by_tenant  HOST [n_tenants * k] of DEVICE pointers, entry e*k + j = tiled plane j of tenant e
+ *                     (bd_tile_signs of packed plane j); NULL allowed for tenants without a token
+ *   alpha_by_tenant   device [n_tenants * k]
+ * A token occupies k of a launch's 32 columns, so one launch covers 2 * floor(16 / k) tokens; more
+ * tokens run as several launches.  k = 1 is bd_linear_multitenant_tiled.  Other arguments and errors
+ * as there; k outside 1..BD_MAX_PLANES gives BD_ERR_SHAPE. */
+bd_status bd_linear_multitenant_tiled_kbit(const uint16_t* x_f16, const uint16_t* w_tiled,
+                                           const uint32_t* const* planes_by_tenant,
+                                           const float* alpha_by_tenant,
+                                           const int32_t* tenant_of_token,
+                                           uint16_t* y_f16,
+                                           int64_t T, int64_t out, int64_t in, int32_t n_tenants, int32_t k,
+                                           void* stream);
+
+/* The grouped launch with k planes per tenant: planes_by_mat_tenant HOST [n_mats * n_tenants * k],
+ * entry (m * n_tenants + e) * k + j; alpha_by_mat HOST [n_mats] of device arrays [n_tenants * k]. */
+bd_status bd_linear_multitenant_tiled_group_kbit(int32_t n_mats, const uint16_t* x_f16,
+                                                 const uint16_t* const* w_tiled,
+                                                 const uint32_t* const* planes_by_mat_tenant,
+                                                 const float* const* alpha_by_mat,
+                                                 const int32_t* tenant_of_token,
+                                                 uint16_t* const* y_f16,
+                                                 int64_t T, const int64_t* out, int64_t in, int32_t n_tenants,
+                                                 int32_t k, void* stream);
+
 /* The grouping step of the linear, exposed so that a scheduler (or a test) can see it: the
  * tokens of one decode launch (T <= 32, all HOST arrays) sorted by tenant, stable, and cut
  * into jobs.  A job is one tenant's run of columns inside one 16-column tile; the kernel

@@ -24,7 +24,8 @@ OP_PACK_SIGNS, OP_COMPRESS, OP_LINEAR_MULTITENANT = 0, 1, 2
 EXPORTS = ["bd_status_string", "bd_version", "bd_workspace_bytes", "bd_pack_signs", "bd_compress", "bd_group_tokens",
            "bd_linear_multitenant", "bd_linear_multitenant_variant", "bd_materialize", "bd_linear_naive",
            "bd_probe_read", "bd_probe_copy", "bd_tiled_base_bytes", "bd_tiled_signs_bytes", "bd_tile_base",
-           "bd_tile_signs", "bd_linear_multitenant_tiled", "bd_linear_multitenant_tiled_group"]
+           "bd_tile_signs", "bd_linear_multitenant_tiled", "bd_linear_multitenant_tiled_group", "bd_compress_iterated",
+           "bd_linear_multitenant_tiled_kbit", "bd_linear_multitenant_tiled_group_kbit"]
 
 
 class BitDeltaError(RuntimeError):
@@ -72,6 +73,9 @@ def lib() -> ctypes.CDLL:
         pvp, pi64 = ctypes.POINTER(vp), ctypes.POINTER(i64)
         L.bd_linear_multitenant_tiled.argtypes = [vp, vp, pvp, vp, pi, vp, i64, i64, i64, i32, vp]
         L.bd_linear_multitenant_tiled_group.argtypes = [i32, vp, pvp, pvp, pvp, pi, pvp, i64, pi64, i64, i32, vp]
+        L.bd_compress_iterated.argtypes = [vp, vp, i64, i64, i32, vp, vp, vp, sz, vp]
+        L.bd_linear_multitenant_tiled_kbit.argtypes = [vp, vp, pvp, vp, pi, vp, i64, i64, i64, i32, i32, vp]
+        L.bd_linear_multitenant_tiled_group_kbit.argtypes = [i32, vp, pvp, pvp, pvp, pi, pvp, i64, pi64, i64, i32, i32, vp]
         for name in ("bd_pack_signs", "bd_compress", "bd_linear_multitenant", "bd_linear_multitenant_variant",
                      "bd_materialize", "bd_linear_naive", "bd_probe_read", "bd_probe_copy", "bd_tile_base",
                      "bd_tile_signs", "bd_linear_multitenant_tiled", "bd_linear_multitenant_tiled_group"):
@@ -152,6 +156,29 @@ def compress(w_base: torch.Tensor, w_ft: torch.Tensor, packed: Optional[torch.Te
         workspace = new_workspace(workspace_bytes(OP_COMPRESS, 0, out, inn, 1), dev)
     _check(lib().bd_compress(_ptr(w_base), _ptr(w_ft), out, inn, _ptr(packed), _ptr(alpha), _ptr(workspace),
                              workspace.numel(), _stream(stream)), "bd_compress")
+    return packed, alpha
+
+
+MAX_PLANES = 8
+
+
+def compress_iterated(w_base: torch.Tensor, w_ft: torch.Tensor, k: int, packed: Optional[torch.Tensor] = None,
+                      alpha: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None, stream=None):
+    """bd_compress_iterated: returns (packed int32 [k, out, in/32], alpha float32 [k]) on the device."""
+    _dev(w_base, torch.float16, "w_base")
+    _dev(w_ft, torch.float16, "w_ft")
+    if w_base.shape != w_ft.shape:
+        raise ValueError("w_base and w_ft differ in shape")
+    out, inn = w_base.shape
+    dev = w_base.device
+    if packed is None:
+        packed = torch.empty((max(k, 0), out, max(inn // 32, 0)), dtype=torch.int32, device=dev)
+    if alpha is None:
+        alpha = torch.empty((max(k, 1),), dtype=torch.float32, device=dev)
+    if workspace is None:
+        workspace = new_workspace(workspace_bytes(OP_COMPRESS, 0, out, inn, 1), dev)
+    _check(lib().bd_compress_iterated(_ptr(w_base), _ptr(w_ft), out, inn, k, _ptr(packed), _ptr(alpha), _ptr(workspace),
+                                      workspace.numel(), _stream(stream)), "bd_compress_iterated")
     return packed, alpha
 
 
@@ -340,6 +367,83 @@ def linear_multitenant_tiled(x: torch.Tensor, w_tiled: torch.Tensor, out: int, t
                                              _ptr(y), T, out, inn, tenants.n_tenants, _stream(stream)),
            "bd_linear_multitenant_tiled")
     return y
+
+
+class TiledPlaneTable:
+    """What the k-plane tiled linear takes for one matrix: a HOST array [n_tenants * k] of device pointers to
+    every tenant's tiled planes (None = tenant absent) and the device array [n_tenants * k] of scales."""
+
+    def __init__(self, planes_by_tenant: Sequence[Optional[Sequence[torch.Tensor]]], alpha_by_tenant: torch.Tensor):
+        present = [p for p in planes_by_tenant if p is not None]
+        self.k = len(present[0])
+        if any(len(p) != self.k for p in present):
+            raise ValueError("every tenant needs the same number of planes")
+        self.planes = [list(p) if p is not None else None for p in planes_by_tenant]
+        flat = []
+        for p in self.planes:
+            for j in range(self.k):
+                t = p[j] if p is not None else None
+                if t is not None:
+                    _dev(t, torch.int32, "tiled plane")
+                flat.append(t)
+        dev = present[0][0].device
+        self.host_ptrs = (ctypes.c_void_p * max(len(flat), 1))(*[_ptr(t) or None for t in flat])
+        self.alpha = alpha_by_tenant.to(device=dev, dtype=torch.float32).reshape(-1).contiguous()
+        if self.alpha.numel() != len(self.planes) * self.k:
+            raise ValueError("one alpha per tenant and plane")
+
+    @property
+    def n_tenants(self) -> int:
+        return len(self.planes)
+
+
+def linear_multitenant_tiled_kbit(x: torch.Tensor, w_tiled: torch.Tensor, out: int, tenants: TiledPlaneTable,
+                                  tenant_of_token: Sequence[int], y: Optional[torch.Tensor] = None, stream=None,
+                                  tok_array=None) -> torch.Tensor:
+    """bd_linear_multitenant_tiled_kbit: y fp16 [T, out]."""
+    _dev(x, torch.float16, "x")
+    _dev(w_tiled, torch.float16, "w_tiled")
+    T, inn = x.shape
+    if y is None:
+        y = torch.empty((T, out), dtype=torch.float16, device=x.device)
+    _dev(y, torch.float16, "y")
+    tok = tok_array if tok_array is not None else _tok_array(tenant_of_token)
+    _check(lib().bd_linear_multitenant_tiled_kbit(_ptr(x), _ptr(w_tiled), tenants.host_ptrs, _ptr(tenants.alpha), tok,
+                                                  _ptr(y), T, out, inn, tenants.n_tenants, tenants.k, _stream(stream)),
+           "bd_linear_multitenant_tiled_kbit")
+    return y
+
+
+class TiledPlaneGroup:
+    """Marshalled arguments of bd_linear_multitenant_tiled_group_kbit for a fixed set of matrices."""
+
+    def __init__(self, w_tiled: Sequence[torch.Tensor], outs: Sequence[int], tables: Sequence[TiledPlaneTable]):
+        self.n = len(w_tiled)
+        self.keep = (list(w_tiled), list(tables))
+        self.outs = [int(o) for o in outs]
+        nt, k = tables[0].n_tenants, tables[0].k
+        if any(t.n_tenants != nt or t.k != k for t in tables):
+            raise ValueError("every matrix needs the same tenants and planes")
+        self.n_tenants, self.k = nt, k
+        self.w = (ctypes.c_void_p * self.n)(*[_ptr(w) for w in w_tiled])
+        self.signs = (ctypes.c_void_p * (self.n * max(nt * k, 1)))(*[p for tab in tables for p in tab.host_ptrs])
+        self.alpha = (ctypes.c_void_p * self.n)(*[_ptr(tab.alpha) for tab in tables])
+        self.out_arr = (ctypes.c_int64 * self.n)(*self.outs)
+
+
+def linear_multitenant_tiled_group_kbit(x: torch.Tensor, group: TiledPlaneGroup, tenant_of_token: Sequence[int],
+                                        ys: Optional[Sequence[torch.Tensor]] = None, stream=None, tok_array=None):
+    """bd_linear_multitenant_tiled_group_kbit: list of y_m fp16 [T, out_m]."""
+    _dev(x, torch.float16, "x")
+    T, inn = x.shape
+    if ys is None:
+        ys = [torch.empty((T, o), dtype=torch.float16, device=x.device) for o in group.outs]
+    yarr = (ctypes.c_void_p * group.n)(*[_ptr(_dev(y, torch.float16, "y")) for y in ys])
+    tok = tok_array if tok_array is not None else _tok_array(tenant_of_token)
+    _check(lib().bd_linear_multitenant_tiled_group_kbit(group.n, _ptr(x), group.w, group.signs, group.alpha, tok, yarr, T,
+                                                        group.out_arr, inn, group.n_tenants, group.k, _stream(stream)),
+           "bd_linear_multitenant_tiled_group_kbit")
+    return list(ys)
 
 
 class TiledGroup:

@@ -8,11 +8,13 @@
 
 namespace bd {
 
+constexpr int kCompressMaxPlanes = 8;      // iterations of the compressor one call can run
 constexpr int kCompressMaxBlocks = 2048;   // also the number of binary64 partial sums in the workspace
 
 hipError_t launch_pack_signs(const uint16_t* delta, int64_t out, int64_t in, uint32_t* packed, hipStream_t st);
+// alpha_prev[0 .. n_prev): the scales of the iterations already done (device memory); n_prev = 0: the plain compressor
 hipError_t launch_compress(const uint16_t* base, const uint16_t* ft, int64_t out, int64_t in, uint32_t* packed,
-                           float* alpha, double* partial, hipStream_t st);
+                           float* alpha, double* partial, hipStream_t st, const float* alpha_prev = nullptr, int n_prev = 0);
 
 // Plain vector-ALU linear: any T <= kMaxDecodeTokens per launch, tokens in caller order.
 hipError_t launch_linear_rowwave(const uint16_t* x, const uint16_t* w, const uint32_t* const* packed_by_tenant,

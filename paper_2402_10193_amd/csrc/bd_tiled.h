@@ -27,6 +27,7 @@ constexpr int kTiledMaxMats = 3;                         // matrices one launch 
 constexpr int kTiledMaxJobs = 16;                        // delta jobs (distinct tenants) per launch
 constexpr int kTiledMaxTokens = 16;                      // one 16-column MFMA tile
 constexpr int kTiledMaxCt = 2;                           // column tiles one launch can cover (32 tokens)
+constexpr int kTiledMaxPlanes = 8;                       // sign planes per tenant (iterated compression)
 
 inline int64_t tiled_row_blocks(int64_t out) { return (out + kTileRows - 1) / kTileRows; }
 inline int64_t tiled_k_tiles(int64_t in) { return (in + kTileK - 1) / kTileK; }
@@ -46,7 +47,12 @@ struct TiledArgs {
     const uint32_t* signs[kTiledMaxCt][kTiledMaxMats][kTiledMaxJobs];   // tiled delta of job slot j, matrix m
     int32_t col_token[kTiledMaxCt][kTiledMaxTokens];          // sorted column -> token (row of x and y)
     int32_t col_job[kTiledMaxCt][kTiledMaxTokens];            // sorted column -> job slot owning it
-    int32_t col_tenant[kTiledMaxCt][kTiledMaxTokens];         // sorted column -> tenant id (for alpha)
+    int32_t col_tenant[kTiledMaxCt][kTiledMaxTokens];         // sorted column -> index into alpha[m] (tenant, or tenant * k + plane)
+    // Several sign planes per tenant (iterated compression): a token occupies `span` consecutive columns
+    // that all carry its x, one per plane; the first holds span, the others 0.  Their results are added
+    // when y is written and only the first contributes the base product.  One plane: all 1.
+    int32_t col_span[kTiledMaxCt][kTiledMaxTokens];
+    int32_t planes;                                           // k: 1 = plain 1-bit deltas
 };
 
 hipError_t launch_tile_base(const uint16_t* w, int64_t out, int64_t in, uint16_t* wt, hipStream_t st);

@@ -193,6 +193,29 @@ bd_status bd_compress(const uint16_t* w_base_f16, const uint16_t* w_ft_f16, int6
                : BD_ERR_DEVICE;
 }
 
+bd_status bd_compress_iterated(const uint16_t* w_base_f16, const uint16_t* w_ft_f16, int64_t out, int64_t in, int32_t k,
+                               uint32_t* packed, float* alpha, void* workspace, size_t workspace_bytes, void* stream) {
+    if (out < 0 || in < 0 || in % 32 != 0 || k < 1 || k > bd::kCompressMaxPlanes) return BD_ERR_SHAPE;
+    if (!alpha) return BD_ERR_NULL;
+    if (misaligned(alpha, 4)) return BD_ERR_ALIGN;
+    const bool empty = (out == 0 || in == 0);
+    const size_t plane_words = (size_t)out * in / 32;
+    if (!empty) {
+        if (!w_base_f16 || !w_ft_f16 || !packed) return BD_ERR_NULL;
+        if (misaligned(w_base_f16, 16) || misaligned(w_ft_f16, 16) || misaligned(packed, 16)) return BD_ERR_ALIGN;
+        const size_t wbytes = (size_t)out * in * 2, pbytes = plane_words * 4 * (size_t)k;
+        if (overlaps(packed, pbytes, w_base_f16, wbytes) || overlaps(packed, pbytes, w_ft_f16, wbytes)) return BD_ERR_ALIAS;
+    }
+    const size_t need = bd_workspace_bytes(BD_OP_COMPRESS, 0, out, in, 1);
+    if (!workspace || workspace_bytes < need || misaligned(workspace, 256)) return BD_ERR_WORKSPACE;
+    // iteration j reads the scales 0 .. j-1 that the iterations before it left in `alpha` (same stream)
+    for (int j = 0; j < k; ++j)
+        if (bd::launch_compress(w_base_f16, w_ft_f16, out, in, packed + (size_t)j * plane_words, alpha + j, (double*)workspace,
+                                (hipStream_t)stream, alpha, j) != hipSuccess)
+            return BD_ERR_DEVICE;
+    return BD_OK;
+}
+
 bd_status bd_linear_multitenant_variant(const uint16_t* x_f16, const uint16_t* w_base_f16,
                                         const uint32_t* const* packed_by_tenant, const float* alpha_by_tenant,
                                         const int32_t* tenant_of_token, uint16_t* y_f16, int64_t T, int64_t out,
@@ -289,12 +312,16 @@ bd_status bd_tile_signs(const uint32_t* packed, int64_t out, int64_t in, uint32_
     return bd::launch_tile_signs(packed, out, in, signs_tiled, (hipStream_t)stream) == hipSuccess ? BD_OK : BD_ERR_DEVICE;
 }
 
-bd_status bd_linear_multitenant_tiled_group(int32_t n_mats, const uint16_t* x_f16, const uint16_t* const* w_tiled,
-                                            const uint32_t* const* tiled_by_mat_tenant,
-                                            const float* const* alpha_by_mat, const int32_t* tenant_of_token,
-                                            uint16_t* const* y_f16, int64_t T, const int64_t* out, int64_t in,
-                                            int32_t n_tenants, void* stream) {
+namespace {
+
+// The tiled linear over n_mats matrices that share x, with k sign planes per tenant (k = 1: plain 1-bit
+// deltas).  Pointer table index: (m * n_tenants + tenant) * k + plane; scale index: tenant * k + plane.
+bd_status tiled_linear_impl(int32_t n_mats, const uint16_t* x_f16, const uint16_t* const* w_tiled,
+                            const uint32_t* const* tiled_by_mat_tenant, const float* const* alpha_by_mat,
+                            const int32_t* tenant_of_token, uint16_t* const* y_f16, int64_t T, const int64_t* out,
+                            int64_t in, int32_t n_tenants, int32_t k, void* stream) {
     if (n_mats < 1 || n_mats > bd::kTiledMaxMats) return BD_ERR_SHAPE;
+    if (k < 1 || k > bd::kTiledMaxPlanes) return BD_ERR_SHAPE;
     if (!out) return BD_ERR_NULL;
     if (T < 0 || n_tenants < 0 || T > 65535) return BD_ERR_SHAPE;
     int64_t row_blocks = 0;
@@ -317,27 +344,33 @@ bd_status bd_linear_multitenant_tiled_group(int32_t n_mats, const uint16_t* x_f1
         if (overlaps(y_f16[m], ybytes, x_f16, (size_t)T * in * 2) ||
             overlaps(y_f16[m], ybytes, w_tiled[m], bd_tiled_base_bytes(out[m], in)))
             return BD_ERR_ALIAS;
-        for (int64_t t = 0; t < T; ++t) {
-            const uint32_t* p = tiled_by_mat_tenant[(size_t)m * n_tenants + tenant_of_token[t]];
-            if (!p) return BD_ERR_NULL;
-            if (misaligned(p, 16)) return BD_ERR_ALIGN;
-        }
+        for (int64_t t = 0; t < T; ++t)
+            for (int j = 0; j < k; ++j) {
+                const uint32_t* p = tiled_by_mat_tenant[((size_t)m * n_tenants + tenant_of_token[t]) * k + j];
+                if (!p) return BD_ERR_NULL;
+                if (misaligned(p, 16)) return BD_ERR_ALIGN;
+            }
     }
     // in == 0 (empty reduction) needs no special case: the kernel runs zero steps and writes y = 0
 
-    constexpr int kPerLaunch = bd::kTiledMaxTokens * bd::kTiledMaxCt;   // 32 tokens: two 16-column tiles
-    for (int64_t t0 = 0; t0 < T; t0 += kPerLaunch) {
-        const int n = (int)std::min<int64_t>(kPerLaunch, T - t0);
-        DecodeMeta meta;
-        build_meta(tenant_of_token, t0, n, &meta);
+    // A token takes k columns (one per plane) of a 16-column tile; a launch covers two tiles.
+    const int per_tile = bd::kTiledMaxTokens / k;
+    const int per_launch = per_tile * bd::kTiledMaxCt;
+    for (int64_t t0 = 0; t0 < T; t0 += per_launch) {
+        const int n = (int)std::min<int64_t>(per_launch, T - t0);
+        int order[bd::kTiledMaxTokens * bd::kTiledMaxCt];
+        for (int i = 0; i < n; ++i) order[i] = i;
+        std::stable_sort(order, order + n, [&](int p, int q) { return tenant_of_token[t0 + p] < tenant_of_token[t0 + q]; });
         bd::TiledArgs a;
         std::memset(&a, 0, sizeof(a));
         a.x = x_f16 + t0 * in;
         a.in = (int32_t)in;
         a.KT = (int32_t)bd::tiled_k_tiles(in);
-        a.n_ct = n > bd::kTiledMaxTokens ? 2 : 1;
+        a.n_ct = n > per_tile ? 2 : 1;
+        a.planes = k;
         int32_t rb = 0;
         int mats = 0;
+        int mat_of[bd::kTiledMaxMats] = {0, 0, 0};
         for (int m = 0; m < n_mats; ++m) {
             if (out[m] == 0) continue;
             a.wt[mats] = w_tiled[m];
@@ -346,6 +379,7 @@ bd_status bd_linear_multitenant_tiled_group(int32_t n_mats, const uint16_t* x_f1
             a.out[mats] = (int32_t)out[m];
             rb += (int32_t)bd::tiled_row_blocks(out[m]);
             a.rb_end[mats] = rb;
+            mat_of[mats] = m;
             ++mats;
         }
         a.n_mats = mats;
@@ -353,38 +387,69 @@ bd_status bd_linear_multitenant_tiled_group(int32_t n_mats, const uint16_t* x_f1
         for (int ct = 0; ct < bd::kTiledMaxCt; ++ct) {
             // a column tile beyond n_ct mirrors tile 0 (never read by the kernel, but every pointer stays valid)
             const int src = ct < a.n_ct ? ct : 0;
-            const int n_jobs = meta.tile_job_end[src] - meta.tile_job_begin[src];
-            const int n_cols = std::min(n - src * bd::kTiledMaxTokens, (int)bd::kTiledMaxTokens);
+            const int tok_begin = src * per_tile, tok_end = std::min(n, tok_begin + per_tile);
+            int n_runs = 0, run_tenant[bd::kTiledMaxTokens];
+            int col = 0;
+            for (int i = tok_begin; i < tok_end; ++i) {
+                const int tok = order[i];
+                const int tenant = tenant_of_token[t0 + tok];
+                if (n_runs == 0 || run_tenant[n_runs - 1] != tenant) run_tenant[n_runs++] = tenant;
+                for (int j = 0; j < k; ++j, ++col) {   // the token's columns: plane j is job slot (run, j)
+                    a.col_token[ct][col] = tok;
+                    a.col_tenant[ct][col] = tenant * k + j;
+                    a.col_job[ct][col] = (n_runs - 1) * k + j;
+                    a.col_span[ct][col] = j == 0 ? k : 0;
+                }
+            }
+            a.T[ct] = col;
+            for (; col < bd::kTiledMaxTokens; ++col) a.col_job[ct][col] = -1;
+            const int n_jobs = n_runs * k;
             max_jobs = std::max(max_jobs, n_jobs);
-            a.T[ct] = n_cols;
-            mats = 0;
-            for (int m = 0; m < n_mats; ++m) {
-                if (out[m] == 0) continue;
-                for (int sl = 0; sl < bd::kTiledMaxJobs; ++sl)   // slots beyond the jobs repeat slot 0 (never selected)
-                    a.signs[ct][mats][sl] =
-                        tiled_by_mat_tenant[(size_t)m * n_tenants + meta.slot_tenant[src][sl < n_jobs ? sl : 0]];
-                ++mats;
-            }
-            for (int col = 0; col < bd::kTiledMaxTokens; ++col) {
-                const int gcol = src * bd::kTiledMaxTokens + col;
-                a.col_token[ct][col] = col < n_cols ? meta.token_of_col[gcol] : 0;
-                a.col_tenant[ct][col] = col < n_cols ? meta.tenant_of_col[gcol] : 0;
-                a.col_job[ct][col] = -1;
-                for (int sl = 0; sl < n_jobs; ++sl)
-                    if (col >= meta.slot_col_begin[src][sl] && col < meta.slot_col_end[src][sl]) a.col_job[ct][col] = sl;
-            }
+            for (int mi = 0; mi < mats; ++mi)
+                for (int sl = 0; sl < bd::kTiledMaxJobs; ++sl) {   // slots beyond the jobs repeat slot 0 (never selected)
+                    const int s = sl < n_jobs ? sl : 0;
+                    a.signs[ct][mi][sl] = tiled_by_mat_tenant[((size_t)mat_of[mi] * n_tenants + run_tenant[s / k]) * k + s % k];
+                }
         }
         if (bd::launch_linear_decode_tiled(a, max_jobs, (hipStream_t)stream) != hipSuccess) return BD_ERR_DEVICE;
     }
     return BD_OK;
 }
 
+}  // namespace
+
+bd_status bd_linear_multitenant_tiled_group(int32_t n_mats, const uint16_t* x_f16, const uint16_t* const* w_tiled,
+                                            const uint32_t* const* tiled_by_mat_tenant,
+                                            const float* const* alpha_by_mat, const int32_t* tenant_of_token,
+                                            uint16_t* const* y_f16, int64_t T, const int64_t* out, int64_t in,
+                                            int32_t n_tenants, void* stream) {
+    return tiled_linear_impl(n_mats, x_f16, w_tiled, tiled_by_mat_tenant, alpha_by_mat, tenant_of_token, y_f16, T, out, in,
+                             n_tenants, 1, stream);
+}
+
 bd_status bd_linear_multitenant_tiled(const uint16_t* x_f16, const uint16_t* w_tiled,
                                       const uint32_t* const* tiled_by_tenant, const float* alpha_by_tenant,
                                       const int32_t* tenant_of_token, uint16_t* y_f16, int64_t T, int64_t out, int64_t in,
                                       int32_t n_tenants, void* stream) {
-    return bd_linear_multitenant_tiled_group(1, x_f16, &w_tiled, tiled_by_tenant, &alpha_by_tenant, tenant_of_token, &y_f16,
-                                             T, &out, in, n_tenants, stream);
+    return tiled_linear_impl(1, x_f16, &w_tiled, tiled_by_tenant, &alpha_by_tenant, tenant_of_token, &y_f16, T, &out, in,
+                             n_tenants, 1, stream);
+}
+
+bd_status bd_linear_multitenant_tiled_group_kbit(int32_t n_mats, const uint16_t* x_f16, const uint16_t* const* w_tiled,
+                                                 const uint32_t* const* planes_by_mat_tenant,
+                                                 const float* const* alpha_by_mat, const int32_t* tenant_of_token,
+                                                 uint16_t* const* y_f16, int64_t T, const int64_t* out, int64_t in,
+                                                 int32_t n_tenants, int32_t k, void* stream) {
+    return tiled_linear_impl(n_mats, x_f16, w_tiled, planes_by_mat_tenant, alpha_by_mat, tenant_of_token, y_f16, T, out, in,
+                             n_tenants, k, stream);
+}
+
+bd_status bd_linear_multitenant_tiled_kbit(const uint16_t* x_f16, const uint16_t* w_tiled,
+                                           const uint32_t* const* planes_by_tenant, const float* alpha_by_tenant,
+                                           const int32_t* tenant_of_token, uint16_t* y_f16, int64_t T, int64_t out,
+                                           int64_t in, int32_t n_tenants, int32_t k, void* stream) {
+    return tiled_linear_impl(1, x_f16, &w_tiled, planes_by_tenant, &alpha_by_tenant, tenant_of_token, &y_f16, T, &out, in,
+                             n_tenants, k, stream);
 }
 
 bd_status bd_group_tokens(const int32_t* tenant_of_token, int32_t T, int32_t* token_of_col, int32_t* job_tenant,

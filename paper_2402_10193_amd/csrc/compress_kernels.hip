@@ -38,10 +38,16 @@ __global__ __launch_bounds__(kCompressThreads) void pack_signs_kernel(
 }
 
 // base, ft [n_vec * 8] fp16 -> packed [n_vec / 4], partial[gridDim.x] = this block's sum |delta|.
+// Iterated compression (Sec. 4.2, fidelity of Delta): with n_prev > 0 the element's delta is first
+// carried through the n_prev earlier iterations, r <- r - alpha_i * Sign(r) in binary32, so that
+// plane n_prev is the sign of the residual left by the planes before it.
 __global__ __launch_bounds__(kCompressThreads) void compress_kernel(
     const u32x4* __restrict__ base, const u32x4* __restrict__ ft, uint32_t* __restrict__ packed,
-    double* __restrict__ partial, int64_t n_vec) {
+    double* __restrict__ partial, int64_t n_vec, const float* __restrict__ alpha_prev, const int n_prev) {
     __shared__ double wave_part[kCompressThreads / kWave];
+    float ap[kCompressMaxPlanes - 1];
+#pragma unroll
+    for (int i = 0; i < kCompressMaxPlanes - 1; ++i) ap[i] = i < n_prev ? alpha_prev[i] : 0.0f;
     const int lane = threadIdx.x & (kWave - 1);
     const int64_t stride = (int64_t)gridDim.x * kCompressThreads;
     double s = 0.0;
@@ -55,7 +61,10 @@ __global__ __launch_bounds__(kCompressThreads) void compress_kernel(
         for (int e = 0; e < 8; ++e) {
             const float vb = h2f((uint16_t)(bw[e >> 1] >> (16 * (e & 1))));
             const float vf = h2f((uint16_t)(fw[e >> 1] >> (16 * (e & 1))));
-            const float d = vf - vb;                // the delta of Sec. 3.1, IEEE binary32
+            float d = vf - vb;                      // the delta of Sec. 3.1, IEEE binary32
+#pragma unroll
+            for (int i = 0; i < kCompressMaxPlanes - 1; ++i)
+                if (i < n_prev) d = d > 0.0f ? d - ap[i] : d + ap[i];
             byte |= (d > 0.0f ? 1u : 0u) << e;      // Eq. 2: +1 only for d > 0
             s += (double)__builtin_fabsf(d);
         }
@@ -106,13 +115,14 @@ hipError_t launch_pack_signs(const uint16_t* delta, int64_t out, int64_t in, uin
 }
 
 hipError_t launch_compress(const uint16_t* base, const uint16_t* ft, int64_t out, int64_t in, uint32_t* packed,
-                           float* alpha, double* partial, hipStream_t st) {
+                           float* alpha, double* partial, hipStream_t st, const float* alpha_prev, int n_prev) {
+    if (n_prev < 0 || n_prev > kCompressMaxPlanes - 1 || (n_prev > 0 && !alpha_prev)) return hipErrorInvalidValue;
     const int64_t n_vec = out * in / 8;
     int blocks = 0;
     if (n_vec > 0) {
         blocks = compress_grid_blocks(n_vec);
         hipLaunchKernelGGL(compress_kernel, dim3(blocks), dim3(kCompressThreads), 0, st, (const u32x4*)base,
-                           (const u32x4*)ft, packed, partial, n_vec);
+                           (const u32x4*)ft, packed, partial, n_vec, alpha_prev, n_prev);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }

@@ -337,10 +337,12 @@ __global__ __launch_bounds__(kMaxWavesTiled * kWave) void linear_decode_tiled_ke
             int m, rb;
             mat_of(rbg0 + slot / NCT, m, rb);
             const int out = a.out[m], n_row = rb * kTileRows + row;
-            if (col < a.T[ct] && n_row < out) {
+            const int span = a.col_span[ct][col];   // columns of this token (its planes); 0: not a token's first column
+            if (col < a.T[ct] && n_row < out && span > 0) {
                 float s = 0.f;
-                for (int wv = 0; wv < nw; ++wv)
-                    s += *(const float*)(smem + kLutBytes + wv * Plan::kRegion + (slot * 256 + e) * 4);
+                for (int p = 0; p < span; ++p)
+                    for (int wv = 0; wv < nw; ++wv)
+                        s += *(const float*)(smem + kLutBytes + wv * Plan::kRegion + (slot * 256 + e + p * 16) * 4);
                 a.y[m][(int64_t)a.col_token[ct][col] * out + n_row] = f2h_rne(s);
             }
         }
@@ -395,6 +397,14 @@ __global__ __launch_bounds__(kMaxWavesTiled * kWave) void linear_decode_tiled_ke
 #pragma unroll
         for (int ct = 0; ct < NCT; ++ct) {
             const float al = m_cur == 0 ? alpha_m[ct][0] : (m_cur == 1 ? alpha_m[ct][1] : alpha_m[ct][2]);
+            if (a.planes > 1) {   // several planes per token: only a token's first column carries the base product
+                int cc = c;
+                asm volatile("" : "+v"(cc));   // derived here, once per row block, instead of living in a register
+                bool first = false;
+#pragma unroll
+                for (int i = 0; i < kTiledMaxTokens; ++i) first = (cc == i && a.col_span[ct][i] > 0) ? true : first;
+                if (!first) accb[ct] = float4v{0.f, 0.f, 0.f, 0.f};
+            }
             float4v r;
 #pragma unroll
             for (int i = 0; i < 4; ++i) r[i] = accb[ct][i] + al * dsel[ct][i];
