@@ -50,6 +50,8 @@ def parse():
     ap.add_argument("--mix", type=str, default="",
                     help="mixed decode batch: tokens per active tenant, e.g. 6,4,3,1,1,1 (tenants 0.. of the B resident "
                          "ones; the others stay idle); default: one token per tenant")
+    ap.add_argument("--planes", type=int, default=1,
+                    help="sign planes per tenant (iterated compression); a token then takes that many of a launch's columns")
     ap.add_argument("--calibrate", action="store_true",
                     help="only run a 1 GiB copy and a 1 GiB read three times: known sizes against which the "
                          "profiler's HBM byte counters are scaled")
@@ -152,6 +154,10 @@ def main():
         tok = [t for t, c in enumerate(counts) for _ in range(c)]
         args.no_extras = args.no_cpu = True      # the baselines below are defined for one token per tenant
     T, n_active = len(tok), len(set(tok))
+    k = args.planes
+    if k != 1:
+        assert args.path == "tiled-fused", "--planes needs the tiled-fused path"
+        args.no_extras = args.no_cpu = True
     tok_arr = bd._tok_array(tok)
 
     # ---- build the stack: base weights + B compressed deltas per matrix, all resident in HBM
@@ -169,18 +175,23 @@ def main():
                 if li == 0:
                     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
                     e0.record()
-                p, a = bd.compress(base, ft, workspace=ws)
+                p, a = bd.compress(base, ft, workspace=ws) if k == 1 else bd.compress_iterated(base, ft, k, workspace=ws)
                 if li == 0:
                     e1.record()
                     e1.synchronize()
                     compress_ms += e0.elapsed_time(e1)
-                    compress_bytes += out * inn * 4.125
+                    compress_bytes += out * inn * 4.125 * k
                 packed.append(p)
                 alphas.append(a)
                 del ft
-            table = bd.TenantTable(packed, alphas)
+            table = bd.TenantTable(packed, alphas) if k == 1 else None
             wt = ttable = None
-            if args.path != "rowmajor":
+            if k != 1:
+                wt = bd.tile_base(base)
+                ttable = bd.TiledPlaneTable([[bd.tile_signs(p[j], out, inn) for j in range(k)] for p in packed],
+                                            torch.stack(alphas))
+                base = None
+            elif args.path != "rowmajor":
                 wt = bd.tile_base(base)
                 ttable = bd.TiledTenantTable([bd.tile_signs(p, out, inn) for p in packed], table.alpha)
                 if li > 0:          # layer 0 keeps its row-major tensors for the naive baseline below
@@ -207,12 +218,19 @@ def main():
         else:
             def grouped(names):
                 ms = [by[n] for n in names]
-                g = bd.TiledGroup([m[5] for m in ms], [m[1] for m in ms], [m[6] for m in ms])
                 yl = [ys[(m[0], m[1])] for m in ms]
+                if k != 1:
+                    g = bd.TiledPlaneGroup([m[5] for m in ms], [m[1] for m in ms], [m[6] for m in ms])
+                    return lambda g=g, yl=yl, inn=ms[0][2]: bd.linear_multitenant_tiled_group_kbit(
+                        xs[inn], g, tok, ys=yl, tok_array=tok_arr)
+                g = bd.TiledGroup([m[5] for m in ms], [m[1] for m in ms], [m[6] for m in ms])
                 return lambda g=g, yl=yl, inn=ms[0][2]: bd.linear_multitenant_tiled_group(xs[inn], g, tok, ys=yl,
                                                                                            tok_array=tok_arr)
             def single(n):
                 m = by[n]
+                if k != 1:
+                    return lambda m=m: bd.linear_multitenant_tiled_kbit(xs[m[2]], m[5], m[1], m[6], tok,
+                                                                        y=ys[(m[0], m[1])], tok_array=tok_arr)
                 return lambda m=m: bd.linear_multitenant_tiled(xs[m[2]], m[5], m[1], m[6], tok, y=ys[(m[0], m[1])],
                                                                tok_array=tok_arr)
             plan = [grouped(["q", "k", "v"]), single("o"), grouped(["gate", "up"]), single("down")]
@@ -226,7 +244,7 @@ def main():
     launches_per_step = sum(len(p) for p in plans)
     P = sum(o * i for _, o, i in shapes)
     xy_bytes = sum(T * (i + o) * 2 for _, o, i in shapes)
-    bytes_per_step = n_layers * (2.0 * P + n_active * P / 8.0 + xy_bytes)   # algorithmic: W once, each active delta once, x, y
+    bytes_per_step = n_layers * (2.0 * P + n_active * k * P / 8.0 + xy_bytes)   # W once, each active delta (k planes) once, x, y
 
     run_stack()                                   # first call sets kernel attributes; keep it out of any capture
     torch.cuda.synchronize()
@@ -280,8 +298,8 @@ def main():
             "workload": f"llama-2-{args.model} linear stack: {n_layers} layers x (q,k,v,o,gate,up,down), "
                         f"B={B} tenants, " + (f"mixed decode batch of {T} tokens ({args.mix} per active tenant), "
                                                if args.mix else "one decode token per tenant, ")
-                        + "distinct 1-bit delta per (tenant, matrix)",
-            "tenants": B, "tokens": T, "active_tenants": n_active, "layers": n_layers, "launches_per_step": launches_per_step,
+                        + (f"distinct {k}-plane delta per (tenant, matrix)" if k != 1 else "distinct 1-bit delta per (tenant, matrix)"),
+            "tenants": B, "tokens": T, "active_tenants": n_active, "planes": k, "layers": n_layers, "launches_per_step": launches_per_step,
             "launch": "hip graph replay" if graph is not None else "eager",
             "path": args.path, "kernel_variant": args.variant,
         },
@@ -292,7 +310,7 @@ def main():
             "unit": "GB/s",
             "frac": round(achieved_gbs / HBM_PEAK_GBS, 4),
             "traffic": MEASURED_TRAFFIC_BYTES_PER_LAUNCH.get((args.model, B, args.path))
-                       if n_layers == 32 and not args.mix else None,
+                       if n_layers == 32 and not args.mix and k == 1 else None,
             "kernel": "linear_decode_mfma_kernel" if args.path == "rowmajor" else "linear_decode_tiled_kernel",
             "bytes_per_launch": round(bytes_per_step / launches_per_step, 1),
             "avg_launch_us": round(ms_per_step * 1e3 / launches_per_step, 3),
