@@ -135,6 +135,37 @@ def test_tiled_sizes_and_argument_errors(bd):
     assert g(0, *args) == 2 and g(4, *args) == 2                 # 1..3 matrices per launch
 
 
+def test_kbit_argument_errors(bd):
+    L = bd.lib()
+    vp = ctypes.c_void_p
+    need = bd.workspace_bytes(bd.OP_COMPRESS, 0, 16, 128, 1)
+    c = L.bd_compress_iterated
+    assert c(A, 2 * A, 16, 128, 0, 3 * A, 4 * A, 5 * A, need, 0) == 2            # k outside 1..BD_MAX_PLANES
+    assert c(A, 2 * A, 16, 128, 9, 3 * A, 4 * A, 5 * A, need, 0) == 2
+    assert c(A, 2 * A, 16, 100, 2, 3 * A, 4 * A, 5 * A, need, 0) == 2
+    assert c(0, 2 * A, 16, 128, 2, 3 * A, 4 * A, 5 * A, need, 0) == 1
+    assert c(A, 2 * A, 16, 128, 2, 3 * A, 0, 5 * A, need, 0) == 1
+    assert c(A, 2 * A, 16, 128, 2, 3 * A + 8, 4 * A, 5 * A, need, 0) == 3
+    assert c(A, 2 * A, 16, 128, 2, 3 * A, 4 * A, 5 * A, need - 1, 0) == 5
+    assert c(A, 2 * A, 16, 128, 2, A + 4096 - 256, 4 * A, 5 * A, need, 0) == 0x8     # the second plane would overwrite w_base
+    f = L.bd_linear_multitenant_tiled_kbit
+    ok = dict(x=A, w=2 * A, pk=(vp * 2)(3 * A, 3 * A + 4096), al=4 * A, tok=_tok(0), y=5 * A, T=1, out=16, inn=128, nt=1, k=2)
+
+    def call(**kw):
+        a = dict(ok, **kw)
+        return f(a["x"], a["w"], a["pk"], a["al"], a["tok"], a["y"], a["T"], a["out"], a["inn"], a["nt"], a["k"], 0)
+
+    assert call(k=0) == 2 and call(k=9) == 2 and call(inn=48) == 2
+    assert call(pk=(vp * 2)(3 * A, None)) == 1                   # every plane of an active tenant is needed
+    assert call(pk=(vp * 2)(3 * A, 3 * A + 4)) == 3
+    assert call(tok=_tok(1)) == 4 and call(x=0) == 1 and call(y=A) == 8
+    assert call(T=0, x=0, y=0) == 0
+    g = L.bd_linear_multitenant_tiled_group_kbit
+    i64 = ctypes.c_int64
+    args = [A, (vp * 1)(2 * A), (vp * 2)(3 * A, 3 * A + 4096), (vp * 1)(4 * A), _tok(0), (vp * 1)(5 * A), 1, (i64 * 1)(16), 128, 1]
+    assert g(0, *args, 2, 0) == 2 and g(1, *args, 0, 0) == 2
+
+
 def test_group_tokens_sorts_stably_and_cuts_jobs_at_the_tile_boundary(bd):
     import random
     rng = random.Random(5)
