@@ -9,12 +9,16 @@
 //   x tile   128 tokens x 64 k   fp16, gathered through the token permutation
 //   W tile   128 rows   x 64 k   fp16
 //   s tile   128 rows   x 64 k   two packed words per row, expanded to +-1.0 fp16 on the way into
-//                                LDS (four 16-byte entries of a 256-entry byte table per word)
+//                                LDS: a nibble of signs -> 4 fp16 through a 16-entry table kept in 32
+//                                copies (4 KB), lane l reading copy l % 32, so that the look-ups of
+//                                the lanes served together never share a bank
 // and every wavefront accumulates its 64 x 64 corner twice with v_mfma_f32_16x16x32_f16: x.W^T
 // and x.s^T in separate binary32 accumulators, combined as acc_b + alpha * acc_d at the end (alpha
 // multiplies the finished +-1 sum, as in the decode kernels).  Global loads of step k+1 are in
-// registers while step k is multiplied; LDS rows are padded to 144 bytes so that the 16-byte
-// operand reads of 16 lanes fall into 16 different bank groups.
+// registers while step k is multiplied.  An LDS row holds the 8 16-byte chunks of its 64 k in the order
+// chunk ^ ((row / 2) % 8): the 16 lanes that LDS serves together then touch all 64 banks once, both when
+// they write one chunk of 16 consecutive rows or 8 chunks of 2 rows (staging) and when they read one chunk
+// of 16 consecutive rows (operands).
 #include "bd_device.h"
 #include "bd_launch.h"
 
@@ -22,11 +26,19 @@ namespace bd {
 
 namespace {
 
-constexpr int kPfRowBytes = kPrefillK * 2 + 16;            // 144
-constexpr int kPfTileBytes = kPrefillTile * kPfRowBytes;   // 18432
+constexpr int kPfRowBytes = kPrefillK * 2;                 // 128
+constexpr int kPfTileBytes = kPrefillTile * kPfRowBytes;   // 16384
+static_assert(kPrefillK == 64, "the chunk swizzle assumes 8 chunks per row");
+
+__device__ __forceinline__ int pf_off(const int row, const int chunk) {
+    return row * kPfRowBytes + ((chunk ^ ((row >> 1) & 7)) << 4);
+}
 constexpr int kPfChunks = kPrefillK / 8;                   // 16-byte chunks per tile row
 constexpr int kPfPerThread = kPrefillTile * kPfChunks / 256;
-constexpr int kPfLutBytes = 256 * 16;
+constexpr int kPfLutBytes = 16 * 32 * 8;                   // [nibble][copy] of 4 fp16
+constexpr int kPfPanel = 8;                                // N tiles per column panel of the launch order
+constexpr int kPfChunk = 64;                               // consecutive tiles one XCD works on together (32 CUs x 2 workgroups)
+constexpr int kPfXcds = 8;
 
 }  // namespace
 
@@ -39,7 +51,7 @@ __global__ __launch_bounds__(256) void prefill_meta_kernel(const PrefillMetaChun
 __global__ __launch_bounds__(256, 2) void linear_prefill_kernel(
     const uint16_t* __restrict__ x, const uint16_t* __restrict__ w, const uint32_t* const* __restrict__ packed_by_tenant,
     const float* __restrict__ alpha_by_tenant, const int32_t* __restrict__ row_token, const int32_t* __restrict__ tile_tenant,
-    uint16_t* __restrict__ y, const int64_t out, const int64_t in) {
+    uint16_t* __restrict__ y, const int64_t out, const int64_t in, const int n_mtiles, const int n_ntiles) {
     __shared__ __align__(16) unsigned char lds[3 * kPfTileBytes + kPfLutBytes];
     unsigned char* const xs = lds;
     unsigned char* const ws = lds + kPfTileBytes;
@@ -49,22 +61,38 @@ __global__ __launch_bounds__(256, 2) void linear_prefill_kernel(
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
     const int r = lane & 15, g = lane >> 4;
-    const int64_t n0 = (int64_t)blockIdx.x * kPrefillTile;
-    const int mt = blockIdx.y;
+    // Launch order -> tile.  Workgroup ids go round-robin over the 8 XCDs, each with an L2 of its own; the
+    // workgroups an XCD runs together (ids L, L+8, ...) should form a compact block of tiles so that every x
+    // and W slice it fetches serves 8 of them.  Tiles are numbered panel by panel (8 N tiles wide, row-major
+    // inside), cut into chunks of 64 = 8 x 8 tiles, and chunk c goes to XCD c % 8.
+    int mt, nt;
+    {
+        const int L = blockIdx.x, xcd = L % kPfXcds, slot = L / kPfXcds;
+        const int chunk = (slot / kPfChunk) * kPfXcds + xcd;
+        const int t = chunk * kPfChunk + slot % kPfChunk;
+        if (t >= n_mtiles * n_ntiles) return;   // the grid is padded to whole rounds of chunks
+        const int per_panel = n_mtiles * kPfPanel;
+        const int panel = t / per_panel, tp = t - panel * per_panel;
+        const int width = n_ntiles - panel * kPfPanel < kPfPanel ? n_ntiles - panel * kPfPanel : kPfPanel;
+        mt = tp / width;
+        nt = panel * kPfPanel + tp % width;
+    }
+    const int64_t n0 = (int64_t)nt * kPrefillTile;
     const int tenant = tile_tenant[mt];
     const uint32_t* __restrict__ packed = packed_by_tenant[tenant];
     const float alpha = alpha_by_tenant[tenant];
     const int64_t words_per_row = in >> 5;
 
-    // byte -> 8 fp16 (+1.0 where the bit is set, else -1.0), element e = bit e
+    // nibble -> 4 fp16 (+1.0 where the bit is set, else -1.0), element e = bit e; entry [nibble][copy]
     {
-        const uint32_t b = (uint32_t)tid;
-        u32x4 e;
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-            e[i] = 0xBC00BC00u ^ (((b >> (2 * i)) & 1u) << 15) ^ (((b >> (2 * i + 1)) & 1u) << 31);
-        *(u32x4*)(lut + tid * 16) = e;
+        const uint32_t b = (uint32_t)tid >> 4;
+        uint2 e;
+        e.x = 0xBC00BC00u ^ ((b & 1u) << 15) ^ (((b >> 1) & 1u) << 31);
+        e.y = 0xBC00BC00u ^ (((b >> 2) & 1u) << 15) ^ (((b >> 3) & 1u) << 31);
+        *(uint2*)(lut + b * 256 + (tid & 15) * 8) = e;
+        *(uint2*)(lut + b * 256 + 128 + (tid & 15) * 8) = e;
     }
+    const uint32_t lut_lane = (uint32_t)(tid & 31) * 8u;
 
     // what this thread fetches per step: four 16-byte chunks of x, four of W, (threads < 128) the sign words of one row
     const unsigned char* xsrc[kPfPerThread];
@@ -79,7 +107,7 @@ __global__ __launch_bounds__(256, 2) void linear_prefill_kernel(
         xsrc[i] = (const unsigned char*)(x + (int64_t)(tok >= 0 ? tok : 0) * in) + c8 * 16;
         const int64_t wrow = n0 + row < out ? n0 + row : out - 1;   // rows beyond out repeat the last row; never stored
         wsrc[i] = (const unsigned char*)(w + wrow * in) + c8 * 16;
-        soff_lds[i] = row * kPfRowBytes + c8 * 16;
+        soff_lds[i] = pf_off(row, c8);
         kofs[i] = c8 * 8;
     }
     const int64_t srow = n0 + (tid & 127) < out ? n0 + (tid & 127) : out - 1;
@@ -112,7 +140,12 @@ __global__ __launch_bounds__(256, 2) void linear_prefill_kernel(
             for (int h = 0; h < kPrefillK / 32; ++h)
 #pragma unroll
                 for (int q = 0; q < 4; ++q)
-                    *(u32x4*)(ss + tid * kPfRowBytes + h * 64 + q * 16) = *(const u32x4*)(lut + ((sw[h] >> (8 * q)) & 0xFFu) * 16);
+                {
+                    const uint32_t byte = (sw[h] >> (8 * q)) & 0xFFu;
+                    const uint2 lo = *(const uint2*)(lut + (byte & 15u) * 256u + lut_lane);
+                    const uint2 hi = *(const uint2*)(lut + (byte >> 4) * 256u + lut_lane);
+                    *(u32x4*)(ss + pf_off(tid, 4 * h + q)) = u32x4{lo.x, lo.y, hi.x, hi.y};
+                }
         }
     };
 
@@ -133,9 +166,9 @@ __global__ __launch_bounds__(256, 2) void linear_prefill_kernel(
             half8 a[4], bw[4], bs[4];
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                a[i] = *(const half8*)(xs + (wm * 64 + i * 16 + r) * kPfRowBytes + h * 64 + g * 16);
-                bw[i] = *(const half8*)(ws + (wn * 64 + i * 16 + r) * kPfRowBytes + h * 64 + g * 16);
-                bs[i] = *(const half8*)(ss + (wn * 64 + i * 16 + r) * kPfRowBytes + h * 64 + g * 16);
+                a[i] = *(const half8*)(xs + pf_off(wm * 64 + i * 16 + r, 4 * h + g));
+                bw[i] = *(const half8*)(ws + pf_off(wn * 64 + i * 16 + r, 4 * h + g));
+                bs[i] = *(const half8*)(ss + pf_off(wn * 64 + i * 16 + r, 4 * h + g));
             }
 #pragma unroll
             for (int i = 0; i < 4; ++i)
@@ -172,9 +205,13 @@ hipError_t launch_prefill_meta(const PrefillMetaChunk& chunk, int32_t* dst, int 
 hipError_t launch_linear_prefill(const uint16_t* x, const uint16_t* w, const uint32_t* const* packed_by_tenant,
                                  const float* alpha_by_tenant, const int32_t* row_token, const int32_t* tile_tenant,
                                  int n_mtiles, uint16_t* y, int64_t out, int64_t in, hipStream_t st) {
-    const unsigned gx = (unsigned)((out + kPrefillTile - 1) / kPrefillTile);
-    hipLaunchKernelGGL(linear_prefill_kernel, dim3(gx, (unsigned)n_mtiles), dim3(256), 0, st, x, w, packed_by_tenant,
-                       alpha_by_tenant, row_token, tile_tenant, y, out, in);
+    const int n_ntiles = (int)((out + kPrefillTile - 1) / kPrefillTile);
+    const int64_t tiles = (int64_t)n_mtiles * n_ntiles;
+    if (tiles < 1 || tiles > (int64_t)1 << 30) return hipErrorInvalidValue;
+    const int64_t round = (int64_t)kPfChunk * kPfXcds;                      // one chunk for every XCD
+    const unsigned grid = (unsigned)((tiles + round - 1) / round * round);   // surplus workgroups return at once
+    hipLaunchKernelGGL(linear_prefill_kernel, dim3(grid), dim3(256), 0, st, x, w, packed_by_tenant, alpha_by_tenant,
+                       row_token, tile_tenant, y, out, in, n_mtiles, n_ntiles);
     return hipGetLastError();
 }
 
