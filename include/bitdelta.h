@@ -46,7 +46,9 @@ typedef enum bd_status {
     BD_ERR_WORKSPACE = 5,   /* workspace missing, too small or misaligned */
     BD_ERR_DEVICE = 6,      /* the HIP runtime reported an error when enqueuing */
     BD_ERR_UNSUPPORTED = 7, /* unknown kernel variant, or one that cannot run these sizes */
-    BD_ERR_ALIAS = 8        /* an output range overlaps an input range */
+    BD_ERR_ALIAS = 8,       /* an output range overlaps an input range */
+    BD_ERR_FORMAT = 9,      /* a delta image is malformed (magic, sizes, offsets, checksum) */
+    BD_ERR_IO = 10          /* a file could not be opened, read or written */
 } bd_status;
 
 typedef enum bd_op {
@@ -222,6 +224,57 @@ bd_status bd_linear_multitenant_tiled_group_kbit(int32_t n_mats, const uint16_t*
                                                  uint16_t* const* y_f16,
                                                  int64_t T, const int64_t* out, int64_t in, int32_t n_tenants,
                                                  int32_t k, void* stream);
+
+/* ---- delta images: storing a tenant's delta and swapping it in while serving ----------------
+ * Sec. 3.3 of the paper: a 1-bit delta is small enough to be kept per tenant on disk or in host
+ * memory and loaded on demand.  A delta IMAGE holds one tenant's whole compressed model (every
+ * matrix's k sign planes, row-major packed as bd_compress(_iterated) writes them, and scales) as one
+ * relocatable block of bytes: the file format and, unchanged, the pinned staging buffer of a swap.
+ * Layout (little-endian):
+ *   0  char[8] "BDLTv001" | 8 u32 n_mats | 12 u32 planes k | 16 u64 total bytes
+ *   24 u64 sum of the payload's 64-bit words | 32 entry[n_mats] { i64 out, in; u64 packed_offset,
+ *   packed_bytes, alpha_offset } | f32 alpha[n_mats][k] | pad to 256 | per matrix, 256-byte aligned:
+ *   u32 packed[k][out][in/32].
+ * All image and file calls run on the HOST and take host pointers.  A swap is then
+ *   bd_delta_file_read (or any other way of getting the bytes into pinned host memory)
+ *   bd_delta_upload     one asynchronous host-to-device copy of the whole image into an arena
+ *   bd_delta_install    re-tiles every plane from the arena into the serving layout and writes the
+ *                       tenant's scales into the per-matrix scale arrays, on the same stream;
+ * the linears may use the new pointers once that stream has reached this point (an event of the
+ * caller's).  Decode keeps running on another stream meanwhile; nothing here synchronises. */
+#define BD_DELTA_MAX_MATS 4096
+
+/* Bytes of the image for these matrices (0 for invalid arguments). out, in: HOST [n_mats]. */
+size_t bd_delta_image_bytes(int32_t n_mats, const int64_t* out, const int64_t* in, int32_t k);
+
+/* Writes the image into `image` (exactly bd_delta_image_bytes long, else BD_ERR_WORKSPACE).
+ * packed: HOST [n_mats] of HOST pointers to [k][out][in/32] words; alpha: HOST [n_mats] of HOST [k]. */
+bd_status bd_delta_image_build(void* image, size_t image_bytes, int32_t n_mats, const int64_t* out,
+                               const int64_t* in, int32_t k, const uint32_t* const* packed,
+                               const float* const* alpha);
+
+/* Validates header and entry table against `bytes` (and the checksum if asked); returns n_mats, k. */
+bd_status bd_delta_image_check(const void* image, size_t bytes, int32_t verify_checksum, int32_t* n_mats, int32_t* k);
+
+/* Shape and offsets (from the start of the image) of matrix m; any output pointer may be NULL. */
+bd_status bd_delta_image_entry(const void* image, size_t bytes, int32_t m, int64_t* out, int64_t* in,
+                               size_t* packed_offset, size_t* alpha_offset);
+
+/* File I/O: the file is the image, byte for byte.  bd_delta_file_bytes reads the size from the header. */
+bd_status bd_delta_file_write(const char* path, const void* image, size_t bytes);
+bd_status bd_delta_file_bytes(const char* path, size_t* bytes);
+bd_status bd_delta_file_read(const char* path, void* image, size_t bytes);
+
+/* image: HOST (pinned memory makes the copy truly asynchronous); arena: DEVICE, `bytes` long, 256-byte
+ * aligned.  Enqueues one copy on `stream`. */
+bd_status bd_delta_upload(const void* image, size_t bytes, void* arena, void* stream);
+
+/* After bd_delta_upload on the same stream.  tiled_dst: HOST [n_mats * k] of DEVICE buffers of
+ * bd_tiled_signs_bytes(out_m, in_m) bytes (entry m*k + j = plane j of matrix m); alpha_by_tenant:
+ * HOST [n_mats] of DEVICE arrays [n_tenants * k], of which entries tenant*k .. tenant*k + k-1 are
+ * written.  `image` must stay valid until the stream has passed this point. */
+bd_status bd_delta_install(const void* image, size_t bytes, const void* arena, int32_t tenant, int32_t n_tenants,
+                           uint32_t* const* tiled_dst, float* const* alpha_by_tenant, void* stream);
 
 /* The grouping step of the linear, exposed so that a scheduler (or a test) can see it: the
  * tokens of one decode launch (T <= 32, all HOST arrays) sorted by tenant, stable, and cut

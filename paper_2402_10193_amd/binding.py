@@ -17,7 +17,8 @@ LIB_PATH = os.environ.get("BITDELTA_LIB") or os.path.join(_PKG, "libbitdelta.so"
 
 BD_OK = 0
 STATUS_NAMES = {0: "BD_OK", 1: "BD_ERR_NULL", 2: "BD_ERR_SHAPE", 3: "BD_ERR_ALIGN", 4: "BD_ERR_TENANT",
-                5: "BD_ERR_WORKSPACE", 6: "BD_ERR_DEVICE", 7: "BD_ERR_UNSUPPORTED", 8: "BD_ERR_ALIAS"}
+                5: "BD_ERR_WORKSPACE", 6: "BD_ERR_DEVICE", 7: "BD_ERR_UNSUPPORTED", 8: "BD_ERR_ALIAS",
+                9: "BD_ERR_FORMAT", 10: "BD_ERR_IO"}
 OP_PACK_SIGNS, OP_COMPRESS, OP_LINEAR_MULTITENANT = 0, 1, 2
 
 # every symbol include/bitdelta.h declares
@@ -25,7 +26,9 @@ EXPORTS = ["bd_status_string", "bd_version", "bd_workspace_bytes", "bd_pack_sign
            "bd_linear_multitenant", "bd_linear_multitenant_variant", "bd_materialize", "bd_linear_naive",
            "bd_probe_read", "bd_probe_copy", "bd_tiled_base_bytes", "bd_tiled_signs_bytes", "bd_tile_base",
            "bd_tile_signs", "bd_linear_multitenant_tiled", "bd_linear_multitenant_tiled_group", "bd_compress_iterated",
-           "bd_linear_multitenant_tiled_kbit", "bd_linear_multitenant_tiled_group_kbit"]
+           "bd_linear_multitenant_tiled_kbit", "bd_linear_multitenant_tiled_group_kbit", "bd_delta_image_bytes",
+           "bd_delta_image_build", "bd_delta_image_check", "bd_delta_image_entry", "bd_delta_file_write",
+           "bd_delta_file_bytes", "bd_delta_file_read", "bd_delta_upload", "bd_delta_install"]
 
 
 class BitDeltaError(RuntimeError):
@@ -73,6 +76,17 @@ def lib() -> ctypes.CDLL:
         pvp, pi64 = ctypes.POINTER(vp), ctypes.POINTER(i64)
         L.bd_linear_multitenant_tiled.argtypes = [vp, vp, pvp, vp, pi, vp, i64, i64, i64, i32, vp]
         L.bd_linear_multitenant_tiled_group.argtypes = [i32, vp, pvp, pvp, pvp, pi, pvp, i64, pi64, i64, i32, vp]
+        psz = ctypes.POINTER(sz)
+        L.bd_delta_image_bytes.restype = sz
+        L.bd_delta_image_bytes.argtypes = [i32, pi64, pi64, i32]
+        L.bd_delta_image_build.argtypes = [vp, sz, i32, pi64, pi64, i32, pvp, pvp]
+        L.bd_delta_image_check.argtypes = [vp, sz, i32, pi, pi]
+        L.bd_delta_image_entry.argtypes = [vp, sz, i32, pi64, pi64, psz, psz]
+        L.bd_delta_file_write.argtypes = [ctypes.c_char_p, vp, sz]
+        L.bd_delta_file_bytes.argtypes = [ctypes.c_char_p, psz]
+        L.bd_delta_file_read.argtypes = [ctypes.c_char_p, vp, sz]
+        L.bd_delta_upload.argtypes = [vp, sz, vp, vp]
+        L.bd_delta_install.argtypes = [vp, sz, vp, i32, i32, pvp, pvp, vp]
         L.bd_compress_iterated.argtypes = [vp, vp, i64, i64, i32, vp, vp, vp, sz, vp]
         L.bd_linear_multitenant_tiled_kbit.argtypes = [vp, vp, pvp, vp, pi, vp, i64, i64, i64, i32, i32, vp]
         L.bd_linear_multitenant_tiled_group_kbit.argtypes = [i32, vp, pvp, pvp, pvp, pi, pvp, i64, pi64, i64, i32, i32, vp]
@@ -477,3 +491,84 @@ def linear_multitenant_tiled_group(x: torch.Tensor, group: TiledGroup, tenant_of
                                                    group.out_arr, inn, group.n_tenants, _stream(stream)),
            "bd_linear_multitenant_tiled_group")
     return list(ys)
+
+
+# ---- delta images and hot swap (host-side calls take CPU tensors) --------------------------------------
+
+def _host_u8(n: int, pinned: bool) -> torch.Tensor:
+    return torch.empty(n, dtype=torch.uint8, pin_memory=bool(pinned and torch.cuda.is_available()))
+
+
+def delta_image_bytes(outs: Sequence[int], ins: Sequence[int], k: int) -> int:
+    n = len(outs)
+    return int(lib().bd_delta_image_bytes(n, (ctypes.c_int64 * n)(*outs), (ctypes.c_int64 * n)(*ins), k))
+
+
+def delta_image_build(packed: Sequence[torch.Tensor], alpha: Sequence[torch.Tensor], outs: Sequence[int],
+                      ins: Sequence[int], k: int, pinned: bool = True) -> torch.Tensor:
+    """bd_delta_image_build from CPU tensors: packed[m] int32 [k, out_m, in_m/32], alpha[m] float32 [k].
+    Returns the image as a uint8 CPU tensor (pinned if asked and a GPU is present)."""
+    n = len(outs)
+    nbytes = delta_image_bytes(outs, ins, k)
+    if nbytes == 0:
+        raise BitDeltaError(2, "bd_delta_image_bytes")
+    pk = [p.contiguous() for p in packed]
+    al = [a.to(torch.float32).contiguous() for a in alpha]
+    for m in range(n):
+        if pk[m].device.type != "cpu" or pk[m].dtype != torch.int32 or pk[m].numel() != k * outs[m] * (ins[m] // 32):
+            raise ValueError("packed[m]: int32 CPU tensor [k, out, in/32]")
+        if al[m].device.type != "cpu" or al[m].numel() != k:
+            raise ValueError("alpha[m]: float32 CPU tensor [k]")
+    image = _host_u8(nbytes, pinned)
+    _check(lib().bd_delta_image_build(_ptr(image), nbytes, n, (ctypes.c_int64 * n)(*outs), (ctypes.c_int64 * n)(*ins), k,
+                                      (ctypes.c_void_p * n)(*[_ptr(p) or None for p in pk]),
+                                      (ctypes.c_void_p * n)(*[_ptr(a) for a in al])), "bd_delta_image_build")
+    return image
+
+
+def delta_image_check(image: torch.Tensor, verify_checksum: bool = True):
+    """Returns (n_mats, k) of a valid image, raises BitDeltaError otherwise."""
+    n, k = ctypes.c_int32(0), ctypes.c_int32(0)
+    _check(lib().bd_delta_image_check(_ptr(image), image.numel(), int(verify_checksum), ctypes.byref(n), ctypes.byref(k)),
+           "bd_delta_image_check")
+    return n.value, k.value
+
+
+def delta_image_entry(image: torch.Tensor, m: int):
+    """(out, in, packed_offset, alpha_offset) of matrix m."""
+    o, i = ctypes.c_int64(0), ctypes.c_int64(0)
+    po, ao = ctypes.c_size_t(0), ctypes.c_size_t(0)
+    _check(lib().bd_delta_image_entry(_ptr(image), image.numel(), m, ctypes.byref(o), ctypes.byref(i), ctypes.byref(po),
+                                      ctypes.byref(ao)), "bd_delta_image_entry")
+    return o.value, i.value, po.value, ao.value
+
+
+def delta_file_write(path: str, image: torch.Tensor) -> None:
+    _check(lib().bd_delta_file_write(os.fsencode(path), _ptr(image), image.numel()), "bd_delta_file_write")
+
+
+def delta_file_read(path: str, pinned: bool = True) -> torch.Tensor:
+    n = ctypes.c_size_t(0)
+    _check(lib().bd_delta_file_bytes(os.fsencode(path), ctypes.byref(n)), "bd_delta_file_bytes")
+    image = _host_u8(n.value, pinned)
+    _check(lib().bd_delta_file_read(os.fsencode(path), _ptr(image), n.value), "bd_delta_file_read")
+    return image
+
+
+def delta_upload(image: torch.Tensor, arena: Optional[torch.Tensor] = None, device="cuda", stream=None) -> torch.Tensor:
+    """bd_delta_upload: one asynchronous copy of the image into a device arena (allocated here if not given)."""
+    if arena is None:
+        arena = torch.empty(image.numel(), dtype=torch.uint8, device=device)
+    _check(lib().bd_delta_upload(_ptr(image), image.numel(), _ptr(arena), _stream(stream)), "bd_delta_upload")
+    return arena
+
+
+def delta_install(image: torch.Tensor, arena: torch.Tensor, tenant: int, n_tenants: int,
+                  tiled_dst: Sequence[Sequence[torch.Tensor]], alpha_by_tenant: Sequence[torch.Tensor], stream=None) -> None:
+    """bd_delta_install: tiled_dst[m][j] int32 device buffers in the serving layout, alpha_by_tenant[m] float32 device
+    arrays [n_tenants * k]."""
+    flat = [t for planes in tiled_dst for t in planes]
+    _check(lib().bd_delta_install(_ptr(image), image.numel(), _ptr(arena), tenant, n_tenants,
+                                  (ctypes.c_void_p * max(len(flat), 1))(*[_ptr(t) for t in flat]),
+                                  (ctypes.c_void_p * max(len(alpha_by_tenant), 1))(*[_ptr(a) for a in alpha_by_tenant]),
+                                  _stream(stream)), "bd_delta_install")

@@ -148,6 +148,8 @@ const char* bd_status_string(bd_status s) {
         case BD_ERR_DEVICE: return "the HIP runtime reported an error";
         case BD_ERR_UNSUPPORTED: return "unsupported op or kernel variant for these sizes";
         case BD_ERR_ALIAS: return "the output overlaps an input";
+        case BD_ERR_FORMAT: return "malformed delta image";
+        case BD_ERR_IO: return "file could not be opened, read or written";
     }
     return "unknown status";
 }
