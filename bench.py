@@ -45,7 +45,7 @@ def parse():
     ap.add_argument("--no-extras", action="store_true", help="skip naive baseline, read probe, compress rate")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
     ap.add_argument("--per-linear", action="store_true", help="also time each linear shape on its own")
-    ap.add_argument("--workload", choices=["decode", "prefill"], default="decode",
+    ap.add_argument("--workload", choices=["decode", "prefill", "hotswap"], default="decode",
                     help="prefill: 8 tenants x 512 tokens on the 4096x11008 and 11008x4096 linears (matrix-core GEMM)")
     ap.add_argument("--mix", type=str, default="",
                     help="mixed decode batch: tokens per active tenant, e.g. 6,4,3,1,1,1 (tenants 0.. of the B resident "
@@ -112,6 +112,74 @@ def run_prefill(args, torch, bd, synth, dev):
     }))
 
 
+def run_hotswap(args, torch, bd, dev, incoming, k, B, step, ms_decode_alone):
+    """One tenant's delta set (every matrix of the stack) from pinned host memory into the serving layout, alone and
+    while the decode stack keeps running on the main stream."""
+    outs, ins = [m[0] for m in incoming], [m[1] for m in incoming]
+    image = bd.delta_image_build([m[2] for m in incoming], [m[3] for m in incoming], outs, ins, k, pinned=True)
+    nbytes = image.numel()
+    arena = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+    tiled = [[torch.empty(bd.tiled_signs_bytes(o, i) // 4, dtype=torch.int32, device=dev) for _ in range(k)]
+             for o, i in zip(outs, ins)]
+    alphas = [torch.zeros(B * k, dtype=torch.float32, device=dev) for _ in outs]
+    side = torch.cuda.Stream()
+
+    def swap():
+        bd.delta_upload(image, arena, stream=side)
+        bd.delta_install(image, arena, 0, B, tiled, alphas, stream=side)
+
+    def timed(fn, reps):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        with torch.cuda.stream(side):
+            fn()
+            side.synchronize()
+            e0.record(side)
+            for _ in range(reps):
+                fn()
+            e1.record(side)
+        side.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+    ms_upload = timed(lambda: bd.delta_upload(image, arena, stream=side), 3)
+    ms_install = timed(lambda: bd.delta_install(image, arena, 0, B, tiled, alphas, stream=side), 3)
+    ms_swap_alone = timed(swap, 3)
+    # the same swap with decode steps running back to back on the main stream
+    torch.cuda.synchronize()
+    d0, d1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    s0, s1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    n_swaps, n_steps = 3, 0
+    d0.record()
+    with torch.cuda.stream(side):
+        s0.record(side)
+        for _ in range(n_swaps):
+            swap()
+        s1.record(side)
+    main_stream = torch.cuda.current_stream()
+    while not s1.query():
+        step()
+        main_stream.synchronize()      # no backlog: every counted step overlaps the swaps
+        n_steps += 1
+    d1.record()
+    torch.cuda.synchronize()
+    ms_swap_busy = s0.elapsed_time(s1) / n_swaps
+    ms_decode_busy = d0.elapsed_time(d1) / max(n_steps, 1)
+    print(json.dumps({
+        "metric": "delta hot swap: one tenant's delta set from pinned host memory into the serving layout, decode running",
+        "value": round(ms_swap_busy, 3), "unit": "ms per swap", "n_gpus": 1, "steps": n_swaps, "warmup": 1,
+        "ms_per_step": round(ms_swap_busy, 3), "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
+        "dtype": "u32 sign words", "data": "synthetic",
+        "config": {"workload": f"llama-2-{args.model} stack, {len(outs)} matrices, {k} plane(s), image of {nbytes / 1e6:.1f} MB; "
+                               f"B={B} tenants decoding meanwhile"},
+        "swap": {"image_MB": round(nbytes / 1e6, 1), "upload_ms_alone": round(ms_upload, 3),
+                 "upload_GBps_alone": round(nbytes / ms_upload / 1e6, 2), "install_ms_alone": round(ms_install, 3),
+                 "swap_ms_alone": round(ms_swap_alone, 3), "swap_ms_while_decoding": round(ms_swap_busy, 3),
+                 "host_to_device_GBps_while_decoding": round(nbytes / ms_swap_busy / 1e6, 2)},
+        "decode": {"ms_per_step_alone": round(ms_decode_alone, 4), "ms_per_step_during_swaps": round(ms_decode_busy, 4),
+                   "steps_during_swaps": n_steps,
+                   "slowdown": round(ms_decode_busy / ms_decode_alone, 4)},
+    }))
+
+
 def main():
     args = parse()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -163,6 +231,7 @@ def main():
     # ---- build the stack: base weights + B compressed deltas per matrix, all resident in HBM
     t_setup = time.time()
     layers = []
+    incoming = []
     ws = bd.new_workspace(bd.workspace_bytes(bd.OP_COMPRESS, 0, 1, 32, 1), dev)
     compress_bytes, compress_ms = 0.0, 0.0
     for li in range(n_layers):
@@ -184,6 +253,11 @@ def main():
                 packed.append(p)
                 alphas.append(a)
                 del ft
+            if args.workload == "hotswap":       # one more fine-tune per matrix: the tenant that will be swapped in
+                ft = synth.finetuned_weight(base, sigma=sigma, tag=("L", li, name, "incoming"))
+                p, a = bd.compress_iterated(base, ft, k, workspace=ws)
+                incoming.append((out, inn, p.cpu(), a.cpu()))
+                del ft, p
             table = bd.TenantTable(packed, alphas) if k == 1 else None
             wt = ttable = None
             if k != 1:
@@ -280,6 +354,10 @@ def main():
     ms_per_step = ms_total / args.steps
     tokens_per_s = T / (ms_per_step * 1e-3)
     achieved_gbs = bytes_per_step / (ms_per_step * 1e-3) / 1e9
+
+    if args.workload == "hotswap":
+        run_hotswap(args, torch, bd, dev, incoming, k, B, step, ms_per_step)
+        return
 
     result = {
         "metric": "decode tokens/s, fused fp16 base + 1-bit delta linear stack, B tenants",
