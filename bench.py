@@ -355,6 +355,15 @@ def main():
     tokens_per_s = T / (ms_per_step * 1e-3)
     achieved_gbs = bytes_per_step / (ms_per_step * 1e-3) / 1e9
 
+    # distribution over single steps (a pass of its own, after the timed region: one event pair per step)
+    pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    for a, b in pairs:
+        a.record()
+        step()
+        b.record()
+    torch.cuda.synchronize()
+    per_step = sorted(a.elapsed_time(b) for a, b in pairs)
+
     if args.workload == "hotswap":
         run_hotswap(args, torch, bd, dev, incoming, k, B, step, ms_per_step)
         return
@@ -393,6 +402,8 @@ def main():
             "bytes_per_launch": round(bytes_per_step / launches_per_step, 1),
             "avg_launch_us": round(ms_per_step * 1e3 / launches_per_step, 3),
         },
+        "step_ms_single": {"median": round(per_step[len(per_step) // 2], 4), "min": round(per_step[0], 4),
+                           "max": round(per_step[-1], 4)},
         "wall_s_timed_region": round(wall, 4),
         "setup_s": round(t_setup, 1),
     }

@@ -2,6 +2,8 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+
+#include <atomic>
 #include <stdint.h>
 
 #include "bd_device.h"
@@ -43,5 +45,22 @@ hipError_t launch_linear_naive(const uint16_t* x, const uint16_t* const* w_by_te
                                uint16_t* y, int64_t out, int64_t in, hipStream_t st);
 hipError_t launch_probe_read(const void* src, size_t bytes, uint32_t* sink, hipStream_t st);
 hipError_t launch_probe_copy(void* dst, const void* src, size_t bytes, hipStream_t st);
+
+// Per-device, once: a kernel attribute is a property of (kernel, device), and several host threads may
+// launch at the same time.  `done` is one flag word per kernel instantiation (bit d = device d).
+struct PerDeviceOnce {
+    std::atomic<uint64_t> done{0};
+    template <typename F>
+    hipError_t run(F&& f) {
+        int dev = 0;
+        hipError_t e = hipGetDevice(&dev);
+        if (e != hipSuccess) return e;
+        const uint64_t bit = (uint64_t)1 << (dev & 63);
+        if (done.load(std::memory_order_acquire) & bit) return hipSuccess;
+        e = f();   // idempotent: two threads racing here both set the same value
+        if (e == hipSuccess) done.fetch_or(bit, std::memory_order_release);
+        return e;
+    }
+};
 
 }  // namespace bd

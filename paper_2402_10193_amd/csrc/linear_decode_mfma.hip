@@ -379,13 +379,11 @@ static hipError_t launch_one(const uint16_t* x, const uint16_t* w, const uint32_
     const int n_waves = n_steps < kMaxWaves ? n_steps : kMaxWaves;
     const size_t lds = (size_t)n_waves * kXsWaveBytes;
     auto kernel = linear_decode_mfma_kernel<MODE, TILES, NG, JG>;
-    static bool attr_set = false;   // raising the dynamic LDS limit is idempotent; a race only repeats it
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                           kMaxWaves * kXsWaveBytes);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    static PerDeviceOnce lds_limit;   // one per instantiation
+    const hipError_t ea = lds_limit.run([&] {
+        return hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxWaves * kXsWaveBytes);
+    });
+    if (ea != hipSuccess) return ea;
     hipLaunchKernelGGL(kernel, dim3((unsigned)((out + 15) / 16)), dim3(n_waves * kWave), lds, st, x, w,
                        packed_by_tenant, alpha_by_tenant, meta, y, out, in);
     return hipGetLastError();

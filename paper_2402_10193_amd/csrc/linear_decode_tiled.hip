@@ -31,6 +31,7 @@
 #include <type_traits>
 
 #include "bd_device.h"
+#include "bd_launch.h"
 #include "bd_tiled.h"
 
 namespace bd {
@@ -427,16 +428,15 @@ template <int NJ, int XSTEPS, int NCT = 1>
 static hipError_t launch_inst(const TiledArgs& args, int n_waves, unsigned grid, hipStream_t st) {
     auto kernel = linear_decode_tiled_kernel<NJ, XSTEPS, NCT>;
     const size_t lds = (size_t)LdsPlan<XSTEPS>::kTotal;
-    static bool attr_set = false;   // raising the dynamic LDS limit is idempotent; a race only repeats it
-    if (!attr_set) {
+    static PerDeviceOnce lds_limit;   // one per instantiation
+    const hipError_t ea = lds_limit.run([&] {
         hipFuncAttributes fa;
-        hipError_t e = hipFuncGetAttributes(&fa, (const void*)kernel);
+        const hipError_t e = hipFuncGetAttributes(&fa, (const void*)kernel);
         if (e != hipSuccess) return e;
         if (fa.sharedSizeBytes != 0) return hipErrorInvalidValue;   // the table must start at LDS address 0
-        e = hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+        return hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    });
+    if (ea != hipSuccess) return ea;
     hipLaunchKernelGGL(kernel, dim3(grid), dim3(n_waves * kWave), lds, st, args);
     return hipGetLastError();
 }
@@ -454,14 +454,15 @@ hipError_t launch_linear_decode_tiled(const TiledArgs& args, int n_jobs, hipStre
         return hipErrorInvalidValue;
     const int rb_total = args.rb_end[args.n_mats - 1];
     if (rb_total < 1 || args.KT < 0) return hipErrorInvalidValue;
-    static int cus = 0;   // compute units of the current device, asked once
+    // compute units of the current device, asked once per device (0 = not asked yet; 64 devices at most are remembered)
+    static std::atomic<int> cus_of[64];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return hipErrorInvalidDevice;
+    int cus = cus_of[dev & 63].load(std::memory_order_relaxed);
     if (cus == 0) {
-        int dev = 0, v = 0;
-        if (hipGetDevice(&dev) == hipSuccess &&
-            hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
-            cus = v;
-        else
-            cus = 256;
+        int v = 0;
+        cus = (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0) ? v : 256;
+        cus_of[dev & 63].store(cus, std::memory_order_relaxed);
     }
     // persistent grid: one workgroup per compute unit, never more workgroups than row blocks;
     // 8 wavefronts, never more than k tiles (KT == 0: one idle-looping wavefront writes y = 0)
