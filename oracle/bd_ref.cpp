@@ -16,6 +16,8 @@
 //   * iterated compression   the compressor applied again with the compressed
 //                             model as the base: k sign planes, k scales
 //                                        (Sec. 4.2, ablation over the fidelity of Delta)
+//   * quantised base         8-bit round-to-nearest base weights under the same deltas
+//                                        (Sec. 4.2, "Quantized base models", Table 5)
 // Readings where the paper is silent (all listed in the design notes):
 //   * weights are [out, in] row-major, the reduction runs along `in`;
 //   * 32 signs per uint32 along `in`, least significant bit first,
@@ -33,6 +35,10 @@
 //     never re-rounded to binary16; every alpha_j is rounded to binary16 like
 //     the first; the k-plane linear accumulates each plane's +-1 sum separately
 //     in binary32 and adds alpha_j * sum_j to the base product in ascending j.
+//   * 8-bit RTN base: one scale per output row, s_n = max_k |W[n,k]| / 127 in binary32 (1 for an
+//     all-zero row), q = clamp(round-to-nearest-even(W / s_n), -127, 127); the base the deltas
+//     are taken against and the linear multiplies is s_n * q in binary32 (never re-rounded to
+//     binary16); activations, fine-tuned weights and alpha stay as they are.
 //
 // Parity pins live in tests/test_oracle_*.py (closed forms, brute force,
 // library special cases, hand-written words).  No function here is unpinned.
@@ -366,6 +372,108 @@ int bd_ref_linear_multitenant_kbit_f64(const uint16_t* x_f16, const uint16_t* w_
                 y += (double)alpha[e * k + j] * acc;
             }
             y_f64[t * out + n] = y;
+        }
+    }
+    return 0;
+}
+
+// ---- Sec. 4.2 (quantized base models): 8-bit round-to-nearest base ----------
+// q [out, in] int8, scale [out] binary32.
+int bd_ref_quantize_rtn8(const uint16_t* w_f16, int64_t out, int64_t in, int8_t* q, float* scale) {
+    for (int64_t n = 0; n < out; ++n) {
+        float amax = 0.0f;
+        for (int64_t c = 0; c < in; ++c) {
+            const float a = std::fabs(half_bits_to_float(w_f16[n * in + c]));
+            if (a > amax) amax = a;          // NaN never compares greater: it does not enter the scale
+        }
+        const float s = amax > 0.0f ? amax / 127.0f : 1.0f;
+        scale[n] = s;
+        for (int64_t c = 0; c < in; ++c) {
+            float v = std::nearbyintf(half_bits_to_float(w_f16[n * in + c]) / s);   // default rounding mode: to nearest even
+            if (!(v >= -127.0f)) v = -127.0f;   // also catches NaN
+            if (v > 127.0f) v = 127.0f;
+            q[n * in + c] = (int8_t)v;
+        }
+    }
+    return 0;
+}
+
+// The compressor of Sec. 3.1 against a quantised base: Delta = f32(W_fine) - scale[n] * q[n,k]  (binary32)
+int bd_ref_compress_q8(const int8_t* q, const float* scale, const uint16_t* w_ft_f16, int64_t out, int64_t in,
+                       uint32_t* packed, float* alpha_f16_as_float, double* alpha_unrounded) {
+    if (in % 32 != 0) return -1;
+    const int64_t words = in / 32;
+    std::vector<double> row_sum((size_t)out, 0.0);
+#pragma omp parallel for schedule(static)
+    for (int64_t n = 0; n < out; ++n) {
+        double s = 0.0;
+        for (int64_t w = 0; w < words; ++w) {
+            uint32_t word = 0;
+            for (int j = 0; j < 32; ++j) {
+                const int64_t idx = n * in + w * 32 + j;
+                const float base = scale[n] * (float)q[idx];
+                const float d = half_bits_to_float(w_ft_f16[idx]) - base;
+                if (d > 0.0f) word |= (1u << j);
+                s += (double)std::fabs(d);
+            }
+            packed[n * words + w] = word;
+        }
+        row_sum[(size_t)n] = s;
+    }
+    double total = 0.0;
+    for (int64_t n = 0; n < out; ++n) total += row_sum[(size_t)n];
+    const double mean = (out > 0 && in > 0) ? total / ((double)out * (double)in) : 0.0;
+    if (alpha_unrounded) *alpha_unrounded = mean;
+    if (alpha_f16_as_float) *alpha_f16_as_float = half_bits_to_float(float_to_half_bits((float)mean));
+    return 0;
+}
+
+// Eq. 6 with the quantised base: y = sum_k x * (scale[n] * q[n,k]) + alpha * sum_k x * s, binary32, ascending k.
+int bd_ref_linear_multitenant_q8(const uint16_t* x_f16, const int8_t* q, const float* scale,
+                                 const uint32_t* const* packed_by_tenant, const float* alpha_by_tenant,
+                                 const int32_t* tenant_of_token, uint16_t* y_f16, float* y_f32,
+                                 int64_t T, int64_t out, int64_t in, int32_t n_tenants) {
+    if (in % 32 != 0) return -1;
+    for (int64_t t = 0; t < T; ++t)
+        if (tenant_of_token[t] < 0 || tenant_of_token[t] >= n_tenants) return -2;
+    const int64_t words = in / 32;
+#pragma omp parallel for schedule(static)
+    for (int64_t n = 0; n < out; ++n) {
+        for (int64_t t = 0; t < T; ++t) {
+            const uint32_t* srow = packed_by_tenant[tenant_of_token[t]] + n * words;
+            float acc_base = 0.0f, acc_delta = 0.0f;
+            for (int64_t c = 0; c < in; ++c) {
+                const float xv = half_bits_to_float(x_f16[t * in + c]);
+                acc_base += xv * (scale[n] * (float)q[n * in + c]);
+                acc_delta += sign_of_bit(srow, c) > 0 ? xv : -xv;
+            }
+            const float y = acc_base + alpha_by_tenant[tenant_of_token[t]] * acc_delta;
+            if (y_f32) y_f32[t * out + n] = y;
+            if (y_f16) y_f16[t * out + n] = float_to_half_bits(y);
+        }
+    }
+    return 0;
+}
+
+int bd_ref_linear_multitenant_q8_f64(const uint16_t* x_f16, const int8_t* q, const float* scale,
+                                     const uint32_t* const* packed_by_tenant, const float* alpha_by_tenant,
+                                     const int32_t* tenant_of_token, double* y_f64,
+                                     int64_t T, int64_t out, int64_t in, int32_t n_tenants) {
+    if (in % 32 != 0) return -1;
+    for (int64_t t = 0; t < T; ++t)
+        if (tenant_of_token[t] < 0 || tenant_of_token[t] >= n_tenants) return -2;
+    const int64_t words = in / 32;
+#pragma omp parallel for schedule(static)
+    for (int64_t n = 0; n < out; ++n) {
+        for (int64_t t = 0; t < T; ++t) {
+            const uint32_t* srow = packed_by_tenant[tenant_of_token[t]] + n * words;
+            double acc_base = 0.0, acc_delta = 0.0;
+            for (int64_t c = 0; c < in; ++c) {
+                const double xv = (double)half_bits_to_float(x_f16[t * in + c]);
+                acc_base += xv * ((double)scale[n] * (double)q[n * in + c]);
+                acc_delta += (double)sign_of_bit(srow, c) * xv;
+            }
+            y_f64[t * out + n] = acc_base + (double)alpha_by_tenant[tenant_of_token[t]] * acc_delta;
         }
     }
     return 0;

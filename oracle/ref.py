@@ -62,6 +62,12 @@ def lib() -> ctypes.CDLL:
                                                      c_u16p, c_f32p, i64, i64, i64, ctypes.c_int32, ctypes.c_int32]
         L.bd_ref_linear_multitenant_kbit_f64.argtypes = [c_u16p, c_u16p, ctypes.POINTER(c_u32p), c_f32p, c_i32p,
                                                          c_f64p, i64, i64, i64, ctypes.c_int32, ctypes.c_int32]
+        L.bd_ref_quantize_rtn8.argtypes = [c_u16p, i64, i64, c_i8p, c_f32p]
+        L.bd_ref_compress_q8.argtypes = [c_i8p, c_f32p, c_u16p, i64, i64, c_u32p, c_f32p, c_f64p]
+        L.bd_ref_linear_multitenant_q8.argtypes = [c_u16p, c_i8p, c_f32p, ctypes.POINTER(c_u32p), c_f32p, c_i32p,
+                                                   c_u16p, c_f32p, i64, i64, i64, ctypes.c_int32]
+        L.bd_ref_linear_multitenant_q8_f64.argtypes = [c_u16p, c_i8p, c_f32p, ctypes.POINTER(c_u32p), c_f32p, c_i32p,
+                                                       c_f64p, i64, i64, i64, ctypes.c_int32]
         L.bd_ref_linear_materialised.argtypes = [c_u16p, c_u16p, c_u32p, ctypes.c_float, c_f32p, c_f32p,
                                                  i64, i64, i64]
         L.bd_ref_linear_naive.argtypes = [c_u16p, ctypes.POINTER(c_u16p), c_i32p, c_u16p, c_f32p,
@@ -197,6 +203,80 @@ def linear_multitenant_kbit_f64(x, w_base, planes_by_tenant, alpha_by_tenant, te
     rc = lib().bd_ref_linear_multitenant_kbit_f64(_p(xb, ctypes.c_uint16), _p(wb, ctypes.c_uint16), ptrs,
                                                   _p(alpha, ctypes.c_float), _p(tok, ctypes.c_int32),
                                                   _p(y, ctypes.c_double), T, out, inn, len(planes_by_tenant), k)
+    if rc == -1:
+        raise ValueError("in must be a multiple of 32")
+    if rc == -2:
+        raise IndexError("tenant id out of range")
+    del keep
+    return y
+
+
+def quantize_rtn8(w: np.ndarray):
+    """8-bit round-to-nearest base (Sec. 4.2, quantized base models): returns (q int8 [out,in], scale float32 [out])."""
+    wb = _u16(w)
+    out, inn = wb.shape
+    q = np.empty((out, inn), dtype=np.int8)
+    scale = np.empty(out, dtype=np.float32)
+    assert lib().bd_ref_quantize_rtn8(_p(wb, ctypes.c_uint16), out, inn, _p(q, ctypes.c_int8), _p(scale, ctypes.c_float)) == 0
+    return q, scale
+
+
+def compress_q8(q: np.ndarray, scale: np.ndarray, w_ft: np.ndarray):
+    """The 1-bit compressor against the quantised base scale[n] * q[n,k]: (packed, alpha, mean before rounding)."""
+    q = np.ascontiguousarray(q, dtype=np.int8)
+    scale = np.ascontiguousarray(scale, dtype=np.float32)
+    f = _u16(w_ft)
+    out, inn = f.shape
+    assert q.shape == (out, inn) and scale.shape == (out,)
+    if inn % 32 != 0:
+        raise ValueError("in must be a multiple of 32")
+    packed = np.empty((out, inn // 32), dtype=np.uint32)
+    alpha, mean = ctypes.c_float(0.0), ctypes.c_double(0.0)
+    rc = lib().bd_ref_compress_q8(_p(q, ctypes.c_int8), _p(scale, ctypes.c_float), _p(f, ctypes.c_uint16), out, inn,
+                                  _p(packed, ctypes.c_uint32), ctypes.byref(alpha), ctypes.byref(mean))
+    assert rc == 0
+    return packed, float(alpha.value), float(mean.value)
+
+
+def _q8_args(x, q, scale, packed_by_tenant, alpha_by_tenant, tenant_of_token):
+    xb = _u16(x)
+    q = np.ascontiguousarray(q, dtype=np.int8)
+    scale = np.ascontiguousarray(scale, dtype=np.float32)
+    T, inn = xb.shape
+    out = q.shape[0]
+    assert q.shape == (out, inn) and scale.shape == (out,)
+    packed = [np.ascontiguousarray(p, dtype=np.uint32) for p in packed_by_tenant]
+    for p in packed:
+        assert p.shape == (out, inn // 32)
+    ptrs, keep = _tenant_ptrs(packed, ctypes.c_uint32)
+    alpha = np.ascontiguousarray(alpha_by_tenant, dtype=np.float32)
+    tok = np.ascontiguousarray(tenant_of_token, dtype=np.int32)
+    assert tok.shape == (T,)
+    return xb, q, scale, T, out, inn, ptrs, keep, alpha, tok, len(packed)
+
+
+def linear_multitenant_q8(x, q, scale, packed_by_tenant, alpha_by_tenant, tenant_of_token):
+    """Eq. 6 over the quantised base.  Returns (y float16 [T,out], y float32 before rounding)."""
+    xb, q, scale, T, out, inn, ptrs, keep, alpha, tok, nt = _q8_args(x, q, scale, packed_by_tenant, alpha_by_tenant, tenant_of_token)
+    y16 = np.empty((T, out), dtype=np.uint16)
+    y32 = np.empty((T, out), dtype=np.float32)
+    rc = lib().bd_ref_linear_multitenant_q8(_p(xb, ctypes.c_uint16), _p(q, ctypes.c_int8), _p(scale, ctypes.c_float), ptrs,
+                                            _p(alpha, ctypes.c_float), _p(tok, ctypes.c_int32), _p(y16, ctypes.c_uint16),
+                                            _p(y32, ctypes.c_float), T, out, inn, nt)
+    if rc == -1:
+        raise ValueError("in must be a multiple of 32")
+    if rc == -2:
+        raise IndexError("tenant id out of range")
+    del keep
+    return y16.view(np.float16), y32
+
+
+def linear_multitenant_q8_f64(x, q, scale, packed_by_tenant, alpha_by_tenant, tenant_of_token):
+    xb, q, scale, T, out, inn, ptrs, keep, alpha, tok, nt = _q8_args(x, q, scale, packed_by_tenant, alpha_by_tenant, tenant_of_token)
+    y = np.empty((T, out), dtype=np.float64)
+    rc = lib().bd_ref_linear_multitenant_q8_f64(_p(xb, ctypes.c_uint16), _p(q, ctypes.c_int8), _p(scale, ctypes.c_float), ptrs,
+                                                _p(alpha, ctypes.c_float), _p(tok, ctypes.c_int32), _p(y, ctypes.c_double),
+                                                T, out, inn, nt)
     if rc == -1:
         raise ValueError("in must be a multiple of 32")
     if rc == -2:
