@@ -225,6 +225,47 @@ bd_status bd_linear_multitenant_tiled_group_kbit(int32_t n_mats, const uint16_t*
                                                  int64_t T, const int64_t* out, int64_t in, int32_t n_tenants,
                                                  int32_t k, void* stream);
 
+/* ---- 8-bit base (Sec. 4.2 of the paper, "Quantized base models") ---------------------------------
+ * Only the base weights are quantised: activations, fine-tuned weights, deltas and scales stay as they
+ * are.  The quantiser is 8-bit round-to-nearest with one scale per output row:
+ *   scale[n] = max_k |W[n,k]| / 127 (binary32; 1 for an all-zero row)
+ *   q[n,k]   = clamp(round_to_nearest_even(W[n,k] / scale[n]), -127, 127)
+ * and the base that deltas are taken against and that Eq. 6 multiplies is scale[n] * q[n,k] in
+ * binary32.  The base stream of the decode kernel halves, so at 16 tenants the deltas are two thirds
+ * of the bytes.
+ *   q [out, in] int8 row-major, scale [out] float, both on the device. */
+bd_status bd_quantize_base_q8(const uint16_t* w_f16, int64_t out, int64_t in, int8_t* q, float* scale, void* stream);
+
+/* The compressor of Sec. 3.1 against the quantised base: Delta = f32(w_ft) - scale[n] * q[n,k].
+ * Arguments, workspace and errors as bd_compress (q must be 8-byte aligned). */
+bd_status bd_compress_q8(const int8_t* q, const float* scale, const uint16_t* w_ft_f16, int64_t out, int64_t in,
+                         uint32_t* packed, float* alpha, void* workspace, size_t workspace_bytes, void* stream);
+
+/* Serving layout of the 8-bit base: tiles of 16 rows x 256 k, one byte u = q + 128 per weight,
+ *   Wq[rb][kt][i][l][h][e] = 128 + q[16 rb + l%16][256 kt + 32 (2 i + h) + 8 (l/16) + e]   i<4, l<64, h<2, e<8
+ * followed by the scales, 16 floats per row block (zeros beyond out).  bd_tiled_base_q8_bytes gives the
+ * size of the whole tensor (0 for shapes the tiled path rejects). */
+size_t bd_tiled_base_q8_bytes(int64_t out, int64_t in);
+bd_status bd_tile_base_q8(const int8_t* q, const float* scale, int64_t out, int64_t in, void* wq_tiled, void* stream);
+
+/* bd_linear_multitenant_tiled / _group over an 8-bit base (wq_tiled from bd_tile_base_q8; the deltas must
+ * have been compressed against the same quantised base, bd_compress_q8).  Same arguments otherwise. */
+bd_status bd_linear_multitenant_tiled_q8(const uint16_t* x_f16, const void* wq_tiled,
+                                         const uint32_t* const* tiled_by_tenant,
+                                         const float* alpha_by_tenant,
+                                         const int32_t* tenant_of_token,
+                                         uint16_t* y_f16,
+                                         int64_t T, int64_t out, int64_t in, int32_t n_tenants,
+                                         void* stream);
+bd_status bd_linear_multitenant_tiled_group_q8(int32_t n_mats, const uint16_t* x_f16,
+                                               const void* const* wq_tiled,
+                                               const uint32_t* const* tiled_by_mat_tenant,
+                                               const float* const* alpha_by_mat,
+                                               const int32_t* tenant_of_token,
+                                               uint16_t* const* y_f16,
+                                               int64_t T, const int64_t* out, int64_t in, int32_t n_tenants,
+                                               void* stream);
+
 /* ---- delta images: storing a tenant's delta and swapping it in while serving ----------------
  * Sec. 3.3 of the paper: a 1-bit delta is small enough to be kept per tenant on disk or in host
  * memory and loaded on demand.  A delta IMAGE holds one tenant's whole compressed model (every

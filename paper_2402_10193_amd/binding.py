@@ -28,7 +28,9 @@ EXPORTS = ["bd_status_string", "bd_version", "bd_workspace_bytes", "bd_pack_sign
            "bd_tile_signs", "bd_linear_multitenant_tiled", "bd_linear_multitenant_tiled_group", "bd_compress_iterated",
            "bd_linear_multitenant_tiled_kbit", "bd_linear_multitenant_tiled_group_kbit", "bd_delta_image_bytes",
            "bd_delta_image_build", "bd_delta_image_check", "bd_delta_image_entry", "bd_delta_file_write",
-           "bd_delta_file_bytes", "bd_delta_file_read", "bd_delta_upload", "bd_delta_install"]
+           "bd_delta_file_bytes", "bd_delta_file_read", "bd_delta_upload", "bd_delta_install", "bd_quantize_base_q8",
+           "bd_compress_q8", "bd_tiled_base_q8_bytes", "bd_tile_base_q8", "bd_linear_multitenant_tiled_q8",
+           "bd_linear_multitenant_tiled_group_q8"]
 
 
 class BitDeltaError(RuntimeError):
@@ -87,6 +89,13 @@ def lib() -> ctypes.CDLL:
         L.bd_delta_file_read.argtypes = [ctypes.c_char_p, vp, sz]
         L.bd_delta_upload.argtypes = [vp, sz, vp, vp]
         L.bd_delta_install.argtypes = [vp, sz, vp, i32, i32, pvp, pvp, vp]
+        L.bd_quantize_base_q8.argtypes = [vp, i64, i64, vp, vp, vp]
+        L.bd_compress_q8.argtypes = [vp, vp, vp, i64, i64, vp, vp, vp, sz, vp]
+        L.bd_tiled_base_q8_bytes.restype = sz
+        L.bd_tiled_base_q8_bytes.argtypes = [i64, i64]
+        L.bd_tile_base_q8.argtypes = [vp, vp, i64, i64, vp, vp]
+        L.bd_linear_multitenant_tiled_q8.argtypes = [vp, vp, pvp, vp, pi, vp, i64, i64, i64, i32, vp]
+        L.bd_linear_multitenant_tiled_group_q8.argtypes = [i32, vp, pvp, pvp, pvp, pi, pvp, i64, pi64, i64, i32, vp]
         L.bd_compress_iterated.argtypes = [vp, vp, i64, i64, i32, vp, vp, vp, sz, vp]
         L.bd_linear_multitenant_tiled_kbit.argtypes = [vp, vp, pvp, vp, pi, vp, i64, i64, i64, i32, i32, vp]
         L.bd_linear_multitenant_tiled_group_kbit.argtypes = [i32, vp, pvp, pvp, pvp, pi, pvp, i64, pi64, i64, i32, i32, vp]
@@ -572,3 +581,83 @@ def delta_install(image: torch.Tensor, arena: torch.Tensor, tenant: int, n_tenan
                                   (ctypes.c_void_p * max(len(flat), 1))(*[_ptr(t) for t in flat]),
                                   (ctypes.c_void_p * max(len(alpha_by_tenant), 1))(*[_ptr(a) for a in alpha_by_tenant]),
                                   _stream(stream)), "bd_delta_install")
+
+
+# ---- 8-bit round-to-nearest base -----------------------------------------------------------------------
+
+def quantize_base_q8(w: torch.Tensor, stream=None):
+    """bd_quantize_base_q8: returns (q int8 [out, in], scale float32 [out]) on the device."""
+    _dev(w, torch.float16, "w")
+    out, inn = w.shape
+    q = torch.empty((out, inn), dtype=torch.int8, device=w.device)
+    scale = torch.empty((out,), dtype=torch.float32, device=w.device)
+    _check(lib().bd_quantize_base_q8(_ptr(w), out, inn, _ptr(q), _ptr(scale), _stream(stream)), "bd_quantize_base_q8")
+    return q, scale
+
+
+def compress_q8(q: torch.Tensor, scale: torch.Tensor, w_ft: torch.Tensor, workspace: Optional[torch.Tensor] = None,
+                stream=None):
+    """bd_compress_q8: returns (packed int32 [out, in/32], alpha float32 [1]) on the device."""
+    _dev(q, torch.int8, "q")
+    _dev(scale, torch.float32, "scale")
+    _dev(w_ft, torch.float16, "w_ft")
+    out, inn = w_ft.shape
+    if q.shape != w_ft.shape or scale.numel() != out:
+        raise ValueError("q, scale and w_ft disagree in shape")
+    dev = w_ft.device
+    packed = torch.empty((out, max(inn // 32, 0)), dtype=torch.int32, device=dev)
+    alpha = torch.empty((1,), dtype=torch.float32, device=dev)
+    if workspace is None:
+        workspace = new_workspace(workspace_bytes(OP_COMPRESS, 0, out, inn, 1), dev)
+    _check(lib().bd_compress_q8(_ptr(q), _ptr(scale), _ptr(w_ft), out, inn, _ptr(packed), _ptr(alpha), _ptr(workspace),
+                                workspace.numel(), _stream(stream)), "bd_compress_q8")
+    return packed, alpha
+
+
+def tiled_base_q8_bytes(out: int, inn: int) -> int:
+    return int(lib().bd_tiled_base_q8_bytes(out, inn))
+
+
+def tile_base_q8(q: torch.Tensor, scale: torch.Tensor, stream=None) -> torch.Tensor:
+    """bd_tile_base_q8: the 8-bit base in the serving layout (uint8 tensor: tiles, then the padded scales)."""
+    _dev(q, torch.int8, "q")
+    _dev(scale, torch.float32, "scale")
+    out, inn = q.shape
+    n = tiled_base_q8_bytes(out, inn)
+    if n == 0 and out * inn > 0:
+        raise BitDeltaError(2, "bd_tiled_base_q8_bytes")
+    wq = torch.empty(n, dtype=torch.uint8, device=q.device)
+    _check(lib().bd_tile_base_q8(_ptr(q), _ptr(scale), out, inn, _ptr(wq), _stream(stream)), "bd_tile_base_q8")
+    return wq
+
+
+def linear_multitenant_tiled_q8(x: torch.Tensor, wq_tiled: torch.Tensor, out: int, tenants: TiledTenantTable,
+                                tenant_of_token: Sequence[int], y: Optional[torch.Tensor] = None, stream=None,
+                                tok_array=None) -> torch.Tensor:
+    """bd_linear_multitenant_tiled_q8: y fp16 [T, out]."""
+    _dev(x, torch.float16, "x")
+    _dev(wq_tiled, torch.uint8, "wq_tiled")
+    T, inn = x.shape
+    if y is None:
+        y = torch.empty((T, out), dtype=torch.float16, device=x.device)
+    _dev(y, torch.float16, "y")
+    tok = tok_array if tok_array is not None else _tok_array(tenant_of_token)
+    _check(lib().bd_linear_multitenant_tiled_q8(_ptr(x), _ptr(wq_tiled), tenants.host_ptrs, _ptr(tenants.alpha), tok,
+                                                _ptr(y), T, out, inn, tenants.n_tenants, _stream(stream)),
+           "bd_linear_multitenant_tiled_q8")
+    return y
+
+
+def linear_multitenant_tiled_group_q8(x: torch.Tensor, group: TiledGroup, tenant_of_token: Sequence[int],
+                                      ys: Optional[Sequence[torch.Tensor]] = None, stream=None, tok_array=None):
+    """bd_linear_multitenant_tiled_group_q8: `group` built from 8-bit tiled bases (TiledGroup takes any tensors)."""
+    _dev(x, torch.float16, "x")
+    T, inn = x.shape
+    if ys is None:
+        ys = [torch.empty((T, o), dtype=torch.float16, device=x.device) for o in group.outs]
+    yarr = (ctypes.c_void_p * group.n)(*[_ptr(_dev(y, torch.float16, "y")) for y in ys])
+    tok = tok_array if tok_array is not None else _tok_array(tenant_of_token)
+    _check(lib().bd_linear_multitenant_tiled_group_q8(group.n, _ptr(x), group.w, group.signs, group.alpha, tok, yarr, T,
+                                                      group.out_arr, inn, group.n_tenants, _stream(stream)),
+           "bd_linear_multitenant_tiled_group_q8")
+    return list(ys)

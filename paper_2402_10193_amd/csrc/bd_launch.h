@@ -39,6 +39,10 @@ hipError_t launch_linear_prefill(const uint16_t* x, const uint16_t* w, const uin
                                  const float* alpha_by_tenant, const int32_t* row_token, const int32_t* tile_tenant,
                                  int n_mtiles, uint16_t* y, int64_t out, int64_t in, hipStream_t st);
 
+// 8-bit round-to-nearest base: q [out, in] int8 and one binary32 scale per row; the compressor against scale * q
+hipError_t launch_quantize_rtn8(const uint16_t* w, int64_t out, int64_t in, int8_t* q, float* scale, hipStream_t st);
+hipError_t launch_compress_q8(const int8_t* q, const float* scale, const uint16_t* ft, int64_t out, int64_t in,
+                              uint32_t* packed, float* alpha, double* partial, hipStream_t st);
 hipError_t launch_materialize(const uint16_t* w_base, const uint32_t* packed, const float* alpha, uint16_t* w_out,
                               int64_t out, int64_t in, hipStream_t st);
 hipError_t launch_linear_naive(const uint16_t* x, const uint16_t* const* w_by_tenant, const DecodeMeta& meta,

@@ -12,6 +12,12 @@
 // so one 128-bit load per lane fetches a whole slice of the base (1 KiB contiguous per wavefront)
 // and one 64-bit load per lane fetches a tenant's signs of the whole tile (512 B contiguous).
 // Rows beyond `out` and elements beyond `in` are stored as zeros.  Tiles are ordered [rb][kt], kt fastest.
+//
+// 8-bit base (quantised, one binary32 scale per output row): one byte per weight, u = q + 128, and a
+// lane's 16 bytes of a load are two consecutive slices,
+//   base8  Wq[rb][kt][i][l][h][e]  byte = 128 + q[16 rb + r][256 kt + 32 (2 i + h) + 8 g + e]   i<4, h<2   (4 KiB per tile)
+// (padding: u = 128, i.e. q = 0).  The scales follow the tiles in the same tensor, one float per row of
+// every row block (padded with zeros to 16 per block).
 #pragma once
 
 #include <hip/hip_runtime.h>
@@ -22,6 +28,7 @@ namespace bd {
 constexpr int kTileRows = 16;
 constexpr int kTileK = 256;
 constexpr int kTileBaseBytes = kTileRows * kTileK * 2;   // 8192
+constexpr int kTileBaseQ8Bytes = kTileRows * kTileK;     // 4096
 constexpr int kTileSignBytes = kTileRows * kTileK / 8;   // 512
 constexpr int kTiledMaxMats = 3;                         // matrices one launch can cover (q,k,v or gate,up)
 constexpr int kTiledMaxJobs = 16;                        // delta jobs (distinct tenants) per launch
@@ -39,6 +46,7 @@ struct TiledArgs {
     const uint16_t* wt[kTiledMaxMats];                        // tiled base of each matrix
     uint16_t* y[kTiledMaxMats];                               // [T, out_m] fp16
     const float* alpha[kTiledMaxMats];                        // device array indexed by tenant id
+    const float* wscale[kTiledMaxMats];                       // 8-bit base only: per-row scales, 16 per row block
     int32_t out[kTiledMaxMats];
     int32_t rb_end[kTiledMaxMats];                            // cumulative row blocks: matrix m owns blocks [rb_end[m-1], rb_end[m])
     int32_t in, KT, n_mats, n_ct;                             // n_ct column tiles of up to 16 tokens each
@@ -59,5 +67,9 @@ hipError_t launch_tile_base(const uint16_t* w, int64_t out, int64_t in, uint16_t
 hipError_t launch_tile_signs(const uint32_t* packed, int64_t out, int64_t in, uint32_t* st_out, hipStream_t st);
 // n_jobs real job slots per column tile (1..16, the larger of the two); unused slots must repeat slot 0's pointers.
 hipError_t launch_linear_decode_tiled(const TiledArgs& args, int n_jobs, hipStream_t st);
+// the same over an 8-bit base: args.wt point at base8 tiles, args.wscale at their scales
+hipError_t launch_linear_decode_tiled_q8(const TiledArgs& args, int n_jobs, hipStream_t st);
+// q [out, in] int8, scale [out] -> base8 tiles followed by the padded scales
+hipError_t launch_tile_base_q8(const int8_t* q, const float* scale, int64_t out, int64_t in, unsigned char* wq, hipStream_t st);
 
 }  // namespace bd

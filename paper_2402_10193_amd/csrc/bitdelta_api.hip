@@ -318,10 +318,11 @@ namespace {
 
 // The tiled linear over n_mats matrices that share x, with k sign planes per tenant (k = 1: plain 1-bit
 // deltas).  Pointer table index: (m * n_tenants + tenant) * k + plane; scale index: tenant * k + plane.
+// q8: w_tiled point at 8-bit base tiles followed by their per-row scales (bd_tile_base_q8).
 bd_status tiled_linear_impl(int32_t n_mats, const uint16_t* x_f16, const uint16_t* const* w_tiled,
                             const uint32_t* const* tiled_by_mat_tenant, const float* const* alpha_by_mat,
                             const int32_t* tenant_of_token, uint16_t* const* y_f16, int64_t T, const int64_t* out,
-                            int64_t in, int32_t n_tenants, int32_t k, void* stream) {
+                            int64_t in, int32_t n_tenants, int32_t k, void* stream, bool q8 = false) {
     if (n_mats < 1 || n_mats > bd::kTiledMaxMats) return BD_ERR_SHAPE;
     if (k < 1 || k > bd::kTiledMaxPlanes) return BD_ERR_SHAPE;
     if (!out) return BD_ERR_NULL;
@@ -344,7 +345,7 @@ bd_status tiled_linear_impl(int32_t n_mats, const uint16_t* x_f16, const uint16_
         if (misaligned(w_tiled[m], 16) || misaligned(y_f16[m], 2) || misaligned(alpha_by_mat[m], 4)) return BD_ERR_ALIGN;
         const size_t ybytes = (size_t)T * out[m] * 2;
         if (overlaps(y_f16[m], ybytes, x_f16, (size_t)T * in * 2) ||
-            overlaps(y_f16[m], ybytes, w_tiled[m], bd_tiled_base_bytes(out[m], in)))
+            overlaps(y_f16[m], ybytes, w_tiled[m], q8 ? bd_tiled_base_q8_bytes(out[m], in) : bd_tiled_base_bytes(out[m], in)))
             return BD_ERR_ALIAS;
         for (int64_t t = 0; t < T; ++t)
             for (int j = 0; j < k; ++j) {
@@ -378,6 +379,9 @@ bd_status tiled_linear_impl(int32_t n_mats, const uint16_t* x_f16, const uint16_
             a.wt[mats] = w_tiled[m];
             a.y[mats] = y_f16[m] + t0 * out[m];
             a.alpha[mats] = alpha_by_mat[m];
+            if (q8)   // the scales follow the tiles
+                a.wscale[mats] = (const float*)((const unsigned char*)w_tiled[m] +
+                                                (size_t)(bd::tiled_row_blocks(out[m]) * bd::tiled_k_tiles(in)) * bd::kTileBaseQ8Bytes);
             a.out[mats] = (int32_t)out[m];
             rb += (int32_t)bd::tiled_row_blocks(out[m]);
             a.rb_end[mats] = rb;
@@ -413,12 +417,80 @@ bd_status tiled_linear_impl(int32_t n_mats, const uint16_t* x_f16, const uint16_
                     a.signs[ct][mi][sl] = tiled_by_mat_tenant[((size_t)mat_of[mi] * n_tenants + run_tenant[s / k]) * k + s % k];
                 }
         }
-        if (bd::launch_linear_decode_tiled(a, max_jobs, (hipStream_t)stream) != hipSuccess) return BD_ERR_DEVICE;
+        const hipError_t e = q8 ? bd::launch_linear_decode_tiled_q8(a, max_jobs, (hipStream_t)stream)
+                                : bd::launch_linear_decode_tiled(a, max_jobs, (hipStream_t)stream);
+        if (e != hipSuccess) return BD_ERR_DEVICE;
     }
     return BD_OK;
 }
 
 }  // namespace
+
+// ---- 8-bit round-to-nearest base ----
+
+size_t bd_tiled_base_q8_bytes(int64_t out, int64_t in) {
+    if (!tiled_shape_ok(out, in)) return 0;
+    const size_t RB = (size_t)bd::tiled_row_blocks(out), KT = (size_t)bd::tiled_k_tiles(in);
+    return RB * KT * bd::kTileBaseQ8Bytes + RB * bd::kTileRows * sizeof(float);
+}
+
+bd_status bd_quantize_base_q8(const uint16_t* w_f16, int64_t out, int64_t in, int8_t* q, float* scale, void* stream) {
+    if (out < 0 || in < 0 || out > ((int64_t)1 << 31) - 1) return BD_ERR_SHAPE;
+    if (out == 0) return BD_OK;
+    if (!scale || (in > 0 && (!w_f16 || !q))) return BD_ERR_NULL;
+    if (misaligned(w_f16, 2) || misaligned(scale, 4)) return BD_ERR_ALIGN;
+    if (in > 0 && overlaps(q, (size_t)out * in, w_f16, (size_t)out * in * 2)) return BD_ERR_ALIAS;
+    return bd::launch_quantize_rtn8(w_f16, out, in, q, scale, (hipStream_t)stream) == hipSuccess ? BD_OK : BD_ERR_DEVICE;
+}
+
+bd_status bd_tile_base_q8(const int8_t* q, const float* scale, int64_t out, int64_t in, void* wq_tiled, void* stream) {
+    if (!tiled_shape_ok(out, in)) return BD_ERR_SHAPE;
+    if (out == 0) return BD_OK;
+    if (!scale || !wq_tiled || (in > 0 && !q)) return BD_ERR_NULL;
+    if (misaligned(wq_tiled, 16) || misaligned(scale, 4)) return BD_ERR_ALIGN;
+    const size_t bytes = bd_tiled_base_q8_bytes(out, in);
+    if (overlaps(wq_tiled, bytes, q, (size_t)out * in) || overlaps(wq_tiled, bytes, scale, (size_t)out * 4)) return BD_ERR_ALIAS;
+    return bd::launch_tile_base_q8(q, scale, out, in, (unsigned char*)wq_tiled, (hipStream_t)stream) == hipSuccess ? BD_OK
+                                                                                                                  : BD_ERR_DEVICE;
+}
+
+bd_status bd_compress_q8(const int8_t* q, const float* scale, const uint16_t* w_ft_f16, int64_t out, int64_t in,
+                         uint32_t* packed, float* alpha, void* workspace, size_t workspace_bytes, void* stream) {
+    if (out < 0 || in < 0 || in % 32 != 0) return BD_ERR_SHAPE;
+    if (!alpha) return BD_ERR_NULL;
+    if (misaligned(alpha, 4)) return BD_ERR_ALIGN;
+    if (out > 0 && in > 0) {
+        if (!q || !scale || !w_ft_f16 || !packed) return BD_ERR_NULL;
+        if (misaligned(q, 8) || misaligned(scale, 4) || misaligned(w_ft_f16, 16) || misaligned(packed, 16)) return BD_ERR_ALIGN;
+        const size_t pbytes = (size_t)out * in / 8;
+        if (overlaps(packed, pbytes, q, (size_t)out * in) || overlaps(packed, pbytes, w_ft_f16, (size_t)out * in * 2) ||
+            overlaps(packed, pbytes, scale, (size_t)out * 4))
+            return BD_ERR_ALIAS;
+    }
+    const size_t need = bd_workspace_bytes(BD_OP_COMPRESS, 0, out, in, 1);
+    if (!workspace || workspace_bytes < need || misaligned(workspace, 256)) return BD_ERR_WORKSPACE;
+    return bd::launch_compress_q8(q, scale, w_ft_f16, out, in, packed, alpha, (double*)workspace, (hipStream_t)stream) ==
+                   hipSuccess
+               ? BD_OK
+               : BD_ERR_DEVICE;
+}
+
+bd_status bd_linear_multitenant_tiled_group_q8(int32_t n_mats, const uint16_t* x_f16, const void* const* wq_tiled,
+                                               const uint32_t* const* tiled_by_mat_tenant,
+                                               const float* const* alpha_by_mat, const int32_t* tenant_of_token,
+                                               uint16_t* const* y_f16, int64_t T, const int64_t* out, int64_t in,
+                                               int32_t n_tenants, void* stream) {
+    return tiled_linear_impl(n_mats, x_f16, (const uint16_t* const*)wq_tiled, tiled_by_mat_tenant, alpha_by_mat, tenant_of_token,
+                             y_f16, T, out, in, n_tenants, 1, stream, true);
+}
+
+bd_status bd_linear_multitenant_tiled_q8(const uint16_t* x_f16, const void* wq_tiled, const uint32_t* const* tiled_by_tenant,
+                                         const float* alpha_by_tenant, const int32_t* tenant_of_token, uint16_t* y_f16,
+                                         int64_t T, int64_t out, int64_t in, int32_t n_tenants, void* stream) {
+    const uint16_t* w = (const uint16_t*)wq_tiled;
+    return tiled_linear_impl(1, x_f16, &w, tiled_by_tenant, &alpha_by_tenant, tenant_of_token, &y_f16, T, &out, in, n_tenants, 1,
+                             stream, true);
+}
 
 bd_status bd_linear_multitenant_tiled_group(int32_t n_mats, const uint16_t* x_f16, const uint16_t* const* w_tiled,
                                             const uint32_t* const* tiled_by_mat_tenant,

@@ -82,6 +82,78 @@ __global__ __launch_bounds__(kCompressThreads) void compress_kernel(
     }
 }
 
+// ---- 8-bit round-to-nearest base (Sec. 4.2 of the paper, quantized base models) ----
+// One workgroup per output row: scale = max |w| / 127 in binary32 (1 for an all-zero row; NaN never enters
+// the maximum), q = clamp(round-to-nearest-even(w / scale), -127, 127) with an IEEE division.
+__global__ __launch_bounds__(kCompressThreads) void quantize_rtn8_kernel(const uint16_t* __restrict__ w, int8_t* __restrict__ q,
+                                                                          float* __restrict__ scale, const int64_t in) {
+    __shared__ float wave_max[kCompressThreads / kWave];
+    const uint16_t* row = w + (int64_t)blockIdx.x * in;
+    int8_t* qrow = q + (int64_t)blockIdx.x * in;
+    float amax = 0.0f;
+    for (int64_t c = threadIdx.x; c < in; c += kCompressThreads) {
+        const float a = __builtin_fabsf(h2f(row[c]));
+        if (a > amax) amax = a;
+    }
+#pragma unroll
+    for (int off = kWave / 2; off >= 1; off >>= 1) {
+        const float o = __shfl_xor(amax, off, kWave);
+        if (o > amax) amax = o;
+    }
+    if ((threadIdx.x & (kWave - 1)) == 0) wave_max[threadIdx.x / kWave] = amax;
+    __syncthreads();
+    amax = wave_max[0];
+#pragma unroll
+    for (int i = 1; i < kCompressThreads / kWave; ++i)
+        if (wave_max[i] > amax) amax = wave_max[i];
+    const float s = amax > 0.0f ? amax / 127.0f : 1.0f;
+    if (threadIdx.x == 0) scale[blockIdx.x] = s;
+    for (int64_t c = threadIdx.x; c < in; c += kCompressThreads) {
+        float v = __builtin_rintf(h2f(row[c]) / s);
+        if (!(v >= -127.0f)) v = -127.0f;   // also catches NaN
+        if (v > 127.0f) v = 127.0f;
+        qrow[c] = (int8_t)v;
+    }
+}
+
+// The compressor against the quantised base: delta = f32(w_ft) - scale[n] * q[n,k].  Every lane takes 8
+// consecutive elements of one row (in % 32 == 0), four lanes merge their bytes into one word.
+__global__ __launch_bounds__(kCompressThreads) void compress_q8_kernel(
+    const u32x2* __restrict__ q, const float* __restrict__ scale, const u32x4* __restrict__ ft,
+    uint32_t* __restrict__ packed, double* __restrict__ partial, const int64_t n_vec, const int64_t vec_per_row) {
+    __shared__ double wave_part[kCompressThreads / kWave];
+    const int lane = threadIdx.x & (kWave - 1);
+    const int64_t stride = (int64_t)gridDim.x * kCompressThreads;
+    double s = 0.0;
+    for (int64_t i = (int64_t)blockIdx.x * kCompressThreads + threadIdx.x; i < n_vec; i += stride) {
+        const u32x2 qv = __builtin_nontemporal_load(q + i);
+        const u32x4 f = __builtin_nontemporal_load(ft + i);
+        const float sc = scale[i / vec_per_row];
+        const uint32_t qw[2] = {qv[0], qv[1]};
+        const uint32_t fw[4] = {f[0], f[1], f[2], f[3]};
+        uint32_t byte = 0;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const float vb = sc * (float)(int8_t)(qw[e >> 2] >> (8 * (e & 3)));
+            const float vf = h2f((uint16_t)(fw[e >> 1] >> (16 * (e & 1))));
+            const float d = vf - vb;
+            byte |= (d > 0.0f ? 1u : 0u) << e;
+            s += (double)__builtin_fabsf(d);
+        }
+        const uint32_t word = merge_quad_bytes(byte, lane);
+        if ((lane & 3) == 0) packed[i >> 2] = word;
+    }
+    s = wave_sum(s);
+    if (lane == 0) wave_part[threadIdx.x / kWave] = s;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        double t = 0.0;
+#pragma unroll
+        for (int w = 0; w < kCompressThreads / kWave; ++w) t += wave_part[w];
+        partial[blockIdx.x] = t;
+    }
+}
+
 // alpha = fp16_rne( sum(partial) / count ), one block, fixed summation order.
 __global__ __launch_bounds__(256) void alpha_finalize_kernel(const double* __restrict__ partial, int n_partial,
                                                              double count, float* __restrict__ alpha) {
@@ -123,6 +195,27 @@ hipError_t launch_compress(const uint16_t* base, const uint16_t* ft, int64_t out
         blocks = compress_grid_blocks(n_vec);
         hipLaunchKernelGGL(compress_kernel, dim3(blocks), dim3(kCompressThreads), 0, st, (const u32x4*)base,
                            (const u32x4*)ft, packed, partial, n_vec, alpha_prev, n_prev);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL(alpha_finalize_kernel, dim3(1), dim3(256), 0, st, (const double*)partial, blocks,
+                       (double)out * (double)in, alpha);
+    return hipGetLastError();
+}
+
+hipError_t launch_quantize_rtn8(const uint16_t* w, int64_t out, int64_t in, int8_t* q, float* scale, hipStream_t st) {
+    if (out > 0) hipLaunchKernelGGL(quantize_rtn8_kernel, dim3((unsigned)out), dim3(kCompressThreads), 0, st, w, q, scale, in);
+    return hipGetLastError();
+}
+
+hipError_t launch_compress_q8(const int8_t* q, const float* scale, const uint16_t* ft, int64_t out, int64_t in,
+                              uint32_t* packed, float* alpha, double* partial, hipStream_t st) {
+    const int64_t n_vec = out * in / 8;
+    int blocks = 0;
+    if (n_vec > 0) {
+        blocks = compress_grid_blocks(n_vec);
+        hipLaunchKernelGGL(compress_q8_kernel, dim3(blocks), dim3(kCompressThreads), 0, st, (const u32x2*)q, scale,
+                           (const u32x4*)ft, packed, partial, n_vec, in / 8);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }

@@ -1,484 +1,10 @@
-// Decode kernel of the multi-tenant linear (Eq. 6 of the paper) over the tiled serving layout:
-//     y[t, n] = sum_k x[t,k] W_base[n,k]  +  alpha_e * sum_k x[t,k] s_e[n,k],   e = tenant(t).
-//
-// At decode every token has its own tenant, so a packed sign word is used exactly once and
-// the kernel is a pure stream: per byte of base weight it must turn B/16 sign bits into
-// multiply-add operands.  Both products run on v_mfma_f32_16x16x32_f16 (A = 16 output rows x
-// 32 k, B = 32 k x 16 token columns, tokens sorted by tenant); a delta "job" is one tenant's
-// signs against all 16 columns, of which only that tenant's columns are kept.
-//
-// Sign expansion.  A byte of 8 signs becomes the 8 fp16 values +-1.0 (one 128-bit MFMA operand
-// register group) by ONE look-up in LDS: the table has 256 entries x 16 B, replicated 16 times
-// so that lane l reads copy l % 16 and a group of 16 lanes never shares a bank.  The address
-// is built by one v_perm_b32 (sign byte -> address bits 8..15, lane copy -> bits 4..7), so the
-// vector ALU spends one instruction per 8 signs; the LDS read port does the rest, next to the
-// matrix pipe.  (Expanding with and-or instructions costs >= 8 per 8 signs and, at one token per
-// tenant, makes the vector ALU the bottleneck long before HBM.)
-//
-// Decomposition.  The grid is persistent: one workgroup per compute unit, each owning a
-// contiguous range of the launch's 16-row blocks (all matrices of a grouped launch laid end to
-// end); its wavefronts split the k tiles into contiguous ranges.  A task = one (row block, k tile):
-// 8 KiB of base (8 loads of 1 KiB), 512 B of signs per job (one 64-bit load per lane) and the
-// 16 x 256 block of x, which each lane loads straight from global memory (L2 hits) in B-operand
-// order: no staging, no barrier in the loop.  When a wavefront has at most two k tiles its x
-// stays in registers for all of its row blocks (x is then fetched once per workgroup instead
-// of once per task; the L1 is an in-order queue, so every x request it does not carry leaves
-// room for a weight request).  Otherwise x is double-buffered per task.
-// Everything of task t+1 is requested while task t is being multiplied: W[v] right after its
-// MFMA, the signs of job j right after their addresses are formed.  Per row block the
-// wavefronts' partial tiles go to LDS slots and are added in a fixed order when the slots are
-// full or the work is done; y is written once.
-#include <type_traits>
-
-#include "bd_device.h"
-#include "bd_launch.h"
-#include "bd_tiled.h"
+// The tiled decode kernel instantiated for the fp16 base (see linear_decode_tiled_kernel.h).
+#include "linear_decode_tiled_kernel.h"
 
 namespace bd {
 
-namespace {
-
-constexpr int kLutBytes = 256 * 16 * 16;          // 256 entries x 16 copies x 16 B
-constexpr int kRedBytesPerWave = 16 * 16 * 4;     // one 16 x 16 fp32 tile
-constexpr int kMaxWavesTiled = 8;
-// x staging of one wavefront: 16 token rows x (512 B + 16 B pad), the pad spreads the 16 rows over all banks
-constexpr int kStageRowBytes = kTileK * 2 + 16;
-constexpr int kStageBytes = 16 * kStageRowBytes;
-// LDS after the table: one region per wavefront = slots for the partial tiles of finished row blocks.
-// Resident x is staged there before the first task (the slots overlay the staging rows).
-template <int XSTEPS> struct LdsPlan {
-    static constexpr int kRedSlots = 8;   // 16 x 16 tiles; a row block takes one per column tile
-    static constexpr int kRegion = (XSTEPS > 0 && kStageBytes > kRedSlots * kRedBytesPerWave) ? kStageBytes : kRedSlots * kRedBytesPerWave;
-    static constexpr int kTotal = kLutBytes + kMaxWavesTiled * kRegion;
-};
-static_assert(LdsPlan<0>::kTotal <= 160 * 1024 && LdsPlan<2>::kTotal <= 160 * 1024, "LDS budget");
-
-__device__ __forceinline__ void lds_wave_sync() {   // order this wavefront's LDS writes before its later reads
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-}
-
-typedef const void __attribute__((address_space(1)))* gptr_t;
-typedef const u32x4 __attribute__((address_space(3)))* lds_u32x4_ptr;
-
-__device__ __forceinline__ u32x4 ldg16_stream(const unsigned char* base, uint32_t off) {
-    return __builtin_nontemporal_load((const u32x4*)(base + off));
-}
-__device__ __forceinline__ u32x2 ldg8_stream(const unsigned char* base, uint32_t off) {
-    return __builtin_nontemporal_load((const u32x2*)(base + off));
-}
-__device__ __forceinline__ u32x4 ldg16(const unsigned char* base, uint32_t off) {
-    return *(const u32x4*)(base + off);
-}
-
-// The MFMA operand of slice v of a job's tile: byte v of the lane's sign words -> table entry.
-// `lanebits` = 16 * (lane % 16) in byte 0; the selector puts sign byte (v % 4) of word v / 4
-// into byte 1 and zeros above: address = 256 * byte + 16 * copy (the table starts at LDS address 0).
-__device__ __forceinline__ u32x4 lut_read(const u32x2 s, const int v, const uint32_t lanebits) {
-    const uint32_t addr = __builtin_amdgcn_perm(s[v >> 2], lanebits, 0x0C0C0000u | ((4u + (v & 3)) << 8));
-    return *(lds_u32x4_ptr)(uintptr_t)addr;
-}
-
-}  // namespace
-
-// XSTEPS = 1 or 2: every wavefront has exactly that many k tiles and keeps their x in registers.
-// XSTEPS = 0: any number of k tiles per wavefront, x double-buffered per task.
-// NCT = 2 (streamed x only): 17..32 tokens as two column tiles; the tasks of one (row block, k tile)
-// then come in pairs that share the base registers, so the base is still read once.
-template <int NJ, int XSTEPS, int NCT>
-__global__ __launch_bounds__(kMaxWavesTiled * kWave) void linear_decode_tiled_kernel(const TiledArgs a) {
-    extern __shared__ __align__(16) unsigned char smem[];   // [0, 64 KiB): table; then one region per wavefront
-    const int lane = threadIdx.x & (kWave - 1);
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int nw = blockDim.x >> 6;
-    const int c = lane & 15;   // A row (output row) for loads, B/D column (token) for MFMA operands and results
-    const int g = lane >> 4;
-    using Plan = LdsPlan<XSTEPS>;
-    static_assert(NCT == 1 || XSTEPS == 0, "two column tiles only with streamed x");
-    // Touch every 64-byte line of the kernel arguments at once: the first read of a line is a trip
-    // to memory, and taken one after the other (pointer tables are indexed by values read before)
-    // those trips would delay the first weight request by microseconds.
-    {
-        const unsigned char __attribute__((address_space(4)))* ka =
-            (const unsigned char __attribute__((address_space(4)))*)__builtin_amdgcn_kernarg_segment_ptr();
-        constexpr int kLines = (int)((sizeof(TiledArgs) + 63) / 64);
-        uint32_t touched[kLines];
-#pragma unroll
-        for (int i = 0; i < kLines; ++i) {
-            const uint32_t off = (uint32_t)i * 64u;
-            asm volatile("s_load_dword %0, %1, %2" : "=s"(touched[i]) : "s"(ka), "s"(off));
-        }
-        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-#pragma unroll
-        for (int i = 0; i < kLines; ++i) asm volatile("" ::"s"(touched[i]));
-    }
-    const int KT = a.KT;
-    const int rb_total = a.rb_end[a.n_mats - 1];
-    // this workgroup's row blocks [r0, r1) of the concatenated matrices (the host keeps grid <= rb_total)
-    const int r0 = (int)((int64_t)blockIdx.x * rb_total / gridDim.x);
-    const int r1 = (int)((int64_t)(blockIdx.x + 1) * rb_total / gridDim.x);
-    const int n_rb = r1 - r0;
-    const int kb = wave * KT / nw, ke = (wave + 1) * KT / nw;   // this wavefront's k tiles
-    const int steps = XSTEPS > 0 ? XSTEPS : ke - kb;
-    const bool have_work = n_rb > 0 && steps > 0;
-
-    auto mat_of = [&](const int rbg, int& m, int& rb) {
-        m = 0;
-        if (a.n_mats > 1 && rbg >= a.rb_end[0]) m = 1;
-        if (a.n_mats > 2 && rbg >= a.rb_end[1]) m = 2;
-        rb = rbg - (m > 0 ? a.rb_end[m - 1] : 0);
-    };
-
-    // ---- pointers of the matrix whose tiles are being REQUESTED (the task being multiplied only
-    // needs registers); reloaded from the kernel arguments when the requests cross into the next matrix
-    int m_req, rb_req;
-    mat_of(r0, m_req, rb_req);
-    const unsigned char* wt = (const unsigned char*)a.wt[m_req];
-    const unsigned char* sp[NCT][NJ];
-#pragma unroll
-    for (int ct = 0; ct < NCT; ++ct)
-#pragma unroll
-        for (int j = 0; j < NJ; ++j) sp[ct][j] = (const unsigned char*)a.signs[ct][m_req][j];
-    const uint32_t lane16 = (uint32_t)lane * 16u, lane8 = (uint32_t)lane * 8u;
-
-    // ---- requests of the first task: base first, (table,) then x, then the signs
-    u32x4 wr[8];
-    u32x2 sr[NJ];
-    const uint32_t tile0 = (uint32_t)(rb_req * KT + kb);
-    if (have_work) {
-#pragma unroll
-        for (int v = 0; v < 8; ++v) wr[v] = ldg16_stream(wt, tile0 * (uint32_t)kTileBaseBytes + lane16 + v * 1024);
-    }
-
-    // ---- the table: entry b, copy cp at 256 b + 16 cp; element e = bit e of b ? +1.0 : -1.0.
-    // Built (and the workgroup synchronised) while only the first base requests are in flight: the
-    // later requests queue up behind the memory system, and a barrier behind them would hold the
-    // first multiplications back by microseconds.
-    for (int idx = threadIdx.x; idx < 256 * 2; idx += blockDim.x) {   // one entry, eight of its copies per pass
-        const uint32_t b = (uint32_t)idx >> 1;
-        u32x4 e;
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-            e[i] = 0xBC00BC00u ^ (((b >> (2 * i)) & 1u) << 15) ^ (((b >> (2 * i + 1)) & 1u) << 31);
-        unsigned char* dst = smem + b * 256 + (idx & 1) * 128;
-#pragma unroll
-        for (int cp = 0; cp < 8; ++cp) *(u32x4*)(dst + cp * 16) = e;
-    }
-    __syncthreads();
-
-
-    // x of one k tile is a [16 tokens][256] fp16 block.  It is fetched with loads whose lanes are
-    // contiguous in memory (load i: token rows 2i and 2i+1, 512 B each) and brought into B-operand
-    // order (lane (c, g): row c, elements 32 v + 8 g ..) through this wavefront's LDS staging rows:
-    // fetching it in operand order directly would make every lane its own 16-byte access.
-    // Rows of columns beyond T read token col_token[0] (valid memory); their results are never stored.
-    const unsigned char* xg = (const unsigned char*)a.x;
-    const int xh = lane >> 5;                                   // which of the two rows of a load
-    const uint32_t xcol = (uint32_t)(lane & 31) * 16u;          // byte inside the tile row
-    const int k_ragged = (a.in % kTileK != 0) ? KT - 1 : -1;    // the tile that reaches beyond `in`, if any
-    const uint32_t row_bytes = (uint32_t)a.in * 2u;
-    auto x_fetch = [&](u32x4 (&xraw)[8], const int kt) {
-        uint32_t xc = xcol;
-        asm volatile("" : "+v"(xc));   // keep "base + lane offset" a 32-bit offset (see task())
-        const uint32_t off = xc + (uint32_t)kt * (uint32_t)(kTileK * 2);
-        const bool inside = (kt != k_ragged) || (kt * kTileK + (lane & 31) * 8 < a.in);
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const int ra = 2 * i < a.T[0] ? a.col_token[0][2 * i] : a.col_token[0][0];
-            const int rbw = 2 * i + 1 < a.T[0] ? a.col_token[0][2 * i + 1] : a.col_token[0][0];
-            const uint32_t tokoff = (uint32_t)(xh ? rbw : ra) * row_bytes;
-            xraw[i] = u32x4{0u, 0u, 0u, 0u};
-            if (inside) xraw[i] = ldg16(xg, tokoff + off);
-        }
-    };
-    // Streamed x (a fresh tile per task) is fetched in operand order directly: lane (c, g), slice v reads
-    // x[token of column c][256 kt + 32 v + 8 g ..]; a trip through LDS per task would sit on the critical path.
-    uint32_t xlane[NCT];
-#pragma unroll
-    for (int ct = 0; ct < NCT; ++ct) {
-        int tok_c = a.col_token[ct][0];
-#pragma unroll
-        for (int i = 0; i < kTiledMaxTokens; ++i) tok_c = (c == i && i < a.T[ct]) ? a.col_token[ct][i] : tok_c;
-        xlane[ct] = (uint32_t)tok_c * row_bytes + (uint32_t)g * 16u;
-    }
-    auto x_fetch_operands = [&](u32x4 (&xop)[8], const int kt, const int ct) {
-        uint32_t xl = ct == 0 ? xlane[0] : xlane[NCT - 1];
-        asm volatile("" : "+v"(xl));
-        const uint32_t off = xl + (uint32_t)kt * (uint32_t)(kTileK * 2);
-        if (kt != k_ragged) {
-#pragma unroll
-            for (int v = 0; v < 8; ++v) xop[v] = ldg16(xg, off + v * 64);
-        } else {
-#pragma unroll
-            for (int v = 0; v < 8; ++v) {
-                xop[v] = u32x4{0u, 0u, 0u, 0u};
-                if (kt * kTileK + 32 * v + 8 * g < a.in) xop[v] = ldg16(xg, off + v * 64);
-            }
-        }
-    };
-    unsigned char* const region = smem + kLutBytes + wave * Plan::kRegion;
-    auto x_to_operands = [&](const u32x4 (&xraw)[8], u32x4 (&xop)[8]) {
-        lds_wave_sync();   // earlier reads of the staging rows are done
-#pragma unroll
-        for (int i = 0; i < 8; ++i) *(u32x4*)(region + (2 * i + xh) * kStageRowBytes + xcol) = xraw[i];
-        lds_wave_sync();
-#pragma unroll
-        for (int v = 0; v < 8; ++v) xop[v] = *(const u32x4*)(region + c * kStageRowBytes + 64 * v + 16 * g);
-    };
-
-    constexpr int XR = XSTEPS > 0 ? XSTEPS : 1;   // x register sets in operand order
-    u32x4 xs[XR][8];
-    u32x4 xraw[XR][8];                            // resident x as fetched; streamed x: the next task's operands
-    if (have_work) {
-        if constexpr (XSTEPS > 0) x_fetch(xraw[0], kb);
-        else x_fetch_operands(xs[0], kb, 0);
-        const uint32_t soff0 = tile0 * (uint32_t)kTileSignBytes + lane8;
-#pragma unroll
-        for (int j = 0; j < NJ; ++j) sr[j] = ldg8_stream(sp[0][j], soff0);
-        if constexpr (XSTEPS == 2) x_fetch(xraw[1], kb + 1);
-    }
-
-    // this lane's column: owning job, tenant (for the scale)
-    int myjob[NCT];
-    float alpha_m[NCT][kTiledMaxMats];
-#pragma unroll
-    for (int ct = 0; ct < NCT; ++ct) {
-        int tenant = 0;
-        myjob[ct] = -1;
-#pragma unroll
-        for (int i = 0; i < kTiledMaxTokens; ++i) {
-            myjob[ct] = (c == i && i < a.T[ct]) ? a.col_job[ct][i] : myjob[ct];
-            tenant = (c == i && i < a.T[ct]) ? a.col_tenant[ct][i] : tenant;
-        }
-#pragma unroll
-        for (int m = 0; m < kTiledMaxMats; ++m) alpha_m[ct][m] = m < a.n_mats ? a.alpha[m][tenant] : 0.f;
-    }
-
-    if (!have_work) return;   // uniform per workgroup (n_rb) / never true for steps (host: waves <= k tiles)
-#pragma unroll
-    for (int i = 0; i < (XSTEPS > 0 ? XR : 0); ++i) x_to_operands(xraw[i], xs[i]);
-    const uint32_t lanebits = (uint32_t)c << 4;
-
-    float4v accb[NCT], dsel[NCT];
-#pragma unroll
-    for (int ct = 0; ct < NCT; ++ct) accb[ct] = dsel[ct] = float4v{0.f, 0.f, 0.f, 0.f};
-
-    // One task = (row block, k tile, column tile CT).  MORE: there is a next task; its tile index is
-    // tile_next and its pointers are current (wt, sp).  The base registers are re-requested by the
-    // last column tile of a (row block, k tile) only.  xr: this task's x in operand order; with
-    // streamed x the next task's (kt_next, next column tile) is fetched into xnext during the task
-    // and replaces xr at its end.
-    auto task = [&](auto more_tag, auto ct_tag, u32x4 (&xr)[8], const uint32_t tile_next, u32x4 (&xnext)[8],
-                    const int kt_next) {
-        constexpr bool MORE = decltype(more_tag)::value;
-        constexpr int CT = decltype(ct_tag)::value;
-        constexpr int CT_NEXT = (CT + 1) % NCT;
-        constexpr bool NEW_BASE = CT == NCT - 1;   // the next task is on another tile of W
-        // The lane offsets pass through an empty asm in every task: otherwise the compiler hoists
-        // "uniform base + lane offset" of every load out of the loop as a 64-bit register pair per load.
-        uint32_t l16 = lane16, l8 = lane8;
-        asm volatile("" : "+v"(l16), "+v"(l8));
-        const uint32_t woff = tile_next * (uint32_t)kTileBaseBytes + l16, soff = tile_next * (uint32_t)kTileSignBytes + l8;
-        // ---- base product; W[v] of the next task goes into the register group just read
-#pragma unroll
-        for (int v = 0; v < 8; ++v) {
-            accb[CT] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8, wr[v]),
-                                                              __builtin_bit_cast(half8, xr[v]), accb[CT], 0, 0, 0);
-            if constexpr (MORE && NEW_BASE) wr[v] = ldg16_stream(wt, woff + v * 1024);
-            __builtin_amdgcn_sched_barrier(0);   // keep each request behind the MFMA that frees its registers
-        }
-        if constexpr (MORE && XSTEPS == 0) x_fetch_operands(xnext, kt_next, CT_NEXT);
-        __builtin_amdgcn_sched_barrier(0);
-        // ---- delta jobs.  The 8 NJ (job, slice) pairs of the task form one sequence; the table
-        // look-up of pair i + kLookAhead is issued before the MFMA of pair i, through a ring of
-        // operand registers, and a job's sign words are re-requested as soon as its last address exists.
-        constexpr int kLookAhead = NCT == 2 ? 4 : 6, kRing = kLookAhead + 2, kPairs = 8 * NJ;
-        u32x4 ring[kRing];
-        float4v sel = {0.f, 0.f, 0.f, 0.f};   // the job owning this lane's column, this tile
-        auto look_up = [&](const int i) {      // i = 8 * job + slice
-            const int j = i >> 3, v = i & 7;
-            ring[i % kRing] = lut_read(sr[j], v, lanebits);
-            if constexpr (MORE) {
-                if (v == 7) sr[j] = ldg8_stream(sp[CT_NEXT][j], soff);
-            }
-        };
-#pragma unroll
-        for (int i = 0; i < kLookAhead; ++i) look_up(i);
-        float4v acc = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int i = 0; i < kPairs; ++i) {
-            if (i + kLookAhead < kPairs) look_up(i + kLookAhead);
-            acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8, ring[i % kRing]),
-                                                         __builtin_bit_cast(half8, xr[i & 7]), acc, 0, 0, 0);
-            if ((i & 7) == 7) {
-                const bool mine = (myjob[CT] == (i >> 3));
-#pragma unroll
-                for (int q = 0; q < 4; ++q) sel[q] = mine ? acc[q] : sel[q];
-                // pin the selection here: left alone, the compiler sinks all of them below the last job
-                // and keeps one live accumulator per job
-                asm volatile("" : "+v"(sel[0]), "+v"(sel[1]), "+v"(sel[2]), "+v"(sel[3]));
-                acc = float4v{0.f, 0.f, 0.f, 0.f};
-                __builtin_amdgcn_sched_barrier(0);
-            }
-        }
-        dsel[CT] += sel;
-        if constexpr (MORE && XSTEPS == 0) {   // this task's x is spent: move the next one in
-#pragma unroll
-            for (int v = 0; v < 8; ++v) xr[v] = xnext[v];
-        }
-    };
-
-    // The partial tiles of `n` finished row blocks, first one rbg0: add the wavefronts in a fixed order, write y.
-    auto flush = [&](const int rbg0, const int n, const bool more_follow) {
-        __syncthreads();
-        for (int idx = threadIdx.x; idx < n * 256; idx += blockDim.x) {   // n slots = n / NCT row blocks
-            const int slot = idx >> 8, e = idx & 255, col = e >> 4, row = e & 15;
-            const int ct = slot % NCT;
-            int m, rb;
-            mat_of(rbg0 + slot / NCT, m, rb);
-            const int out = a.out[m], n_row = rb * kTileRows + row;
-            const int span = a.col_span[ct][col];   // columns of this token (its planes); 0: not a token's first column
-            if (col < a.T[ct] && n_row < out && span > 0) {
-                float s = 0.f;
-                for (int p = 0; p < span; ++p)
-                    for (int wv = 0; wv < nw; ++wv)
-                        s += *(const float*)(smem + kLutBytes + wv * Plan::kRegion + (slot * 256 + e + p * 16) * 4);
-                a.y[m][(int64_t)a.col_token[ct][col] * out + n_row] = f2h_rne(s);
-            }
-        }
-        if (more_follow) __syncthreads();
-    };
-
-    int slot = 0, flush_base = r0;
-    int m_cur = m_req;
-    for (int rbi = 0; rbi < n_rb; ++rbi) {
-        const bool last_rb = rbi + 1 == n_rb;
-        // where the requests go after this row block's last task
-        int m_nx = m_req, rb_nx = 0;
-        if (!last_rb) mat_of(r0 + rbi + 1, m_nx, rb_nx);
-        const uint32_t tile_rb = (uint32_t)(rb_req * KT + kb);            // first tile of this wavefront in this row block
-        const uint32_t tile_nx = (uint32_t)(rb_nx * KT + kb);             // ... and in the next one
-        auto cross = [&]() {   // requests move on to the next row block: switch the pointers if it is in another matrix
-            if (m_nx != m_req) {
-                wt = (const unsigned char*)a.wt[m_nx];
-#pragma unroll
-                for (int ct = 0; ct < NCT; ++ct)
-#pragma unroll
-                    for (int j = 0; j < NJ; ++j) sp[ct][j] = (const unsigned char*)a.signs[ct][m_nx][j];
-            }
-        };
-        using Ct0 = std::integral_constant<int, 0>;
-        using CtL = std::integral_constant<int, NCT - 1>;
-        if constexpr (XSTEPS > 0) {
-#pragma unroll
-            for (int ki = 0; ki < XSTEPS; ++ki) {
-                if (ki + 1 < XSTEPS) {
-                    task(std::true_type{}, Ct0{}, xs[ki], tile_rb + ki + 1, xraw[0], 0);
-                } else if (!last_rb) {
-                    cross();
-                    task(std::true_type{}, Ct0{}, xs[ki], tile_nx, xraw[0], 0);
-                } else {
-                    task(std::false_type{}, Ct0{}, xs[ki], 0u, xraw[0], 0);
-                }
-            }
-        } else {
-            for (int ki = 0; ki < steps; ++ki) {
-                const bool inner = ki + 1 < steps;
-                // all but the last column tile: the next task stays on this tile (same k tile, next columns)
-                if constexpr (NCT == 2) task(std::true_type{}, Ct0{}, xs[0], tile_rb + ki, xraw[0], kb + ki);
-                if (!inner && !last_rb) cross();
-                if (inner || !last_rb)
-                    task(std::true_type{}, CtL{}, xs[0], inner ? tile_rb + ki + 1 : tile_nx, xraw[0], inner ? kb + ki + 1 : kb);
-                else
-                    task(std::false_type{}, CtL{}, xs[0], 0u, xraw[0], 0);
-            }
-        }
-        // ---- row block done: this wavefront's partial tiles -> slots
-#pragma unroll
-        for (int ct = 0; ct < NCT; ++ct) {
-            const float al = m_cur == 0 ? alpha_m[ct][0] : (m_cur == 1 ? alpha_m[ct][1] : alpha_m[ct][2]);
-            if (a.planes > 1) {   // several planes per token: only a token's first column carries the base product
-                int cc = c;
-                asm volatile("" : "+v"(cc));   // derived here, once per row block, instead of living in a register
-                bool first = false;
-#pragma unroll
-                for (int i = 0; i < kTiledMaxTokens; ++i) first = (cc == i && a.col_span[ct][i] > 0) ? true : first;
-                if (!first) accb[ct] = float4v{0.f, 0.f, 0.f, 0.f};
-            }
-            float4v r;
-#pragma unroll
-            for (int i = 0; i < 4; ++i) r[i] = accb[ct][i] + al * dsel[ct][i];
-            *(float4v*)(region + ((slot + ct) * 256 + c * 16 + 4 * g) * 4) = r;   // [column][row]
-            accb[ct] = dsel[ct] = float4v{0.f, 0.f, 0.f, 0.f};
-        }
-        slot += NCT;
-        if (slot == Plan::kRedSlots || last_rb) {
-            flush(flush_base, slot, !last_rb);
-            flush_base += slot / NCT;
-            slot = 0;
-        }
-        m_cur = m_nx;
-        m_req = m_nx;
-        rb_req = rb_nx;
-    }
-}
-
-template <int NJ, int XSTEPS, int NCT = 1>
-static hipError_t launch_inst(const TiledArgs& args, int n_waves, unsigned grid, hipStream_t st) {
-    auto kernel = linear_decode_tiled_kernel<NJ, XSTEPS, NCT>;
-    const size_t lds = (size_t)LdsPlan<XSTEPS>::kTotal;
-    static PerDeviceOnce lds_limit;   // one per instantiation
-    const hipError_t ea = lds_limit.run([&] {
-        hipFuncAttributes fa;
-        const hipError_t e = hipFuncGetAttributes(&fa, (const void*)kernel);
-        if (e != hipSuccess) return e;
-        if (fa.sharedSizeBytes != 0) return hipErrorInvalidValue;   // the table must start at LDS address 0
-        return hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    });
-    if (ea != hipSuccess) return ea;
-    hipLaunchKernelGGL(kernel, dim3(grid), dim3(n_waves * kWave), lds, st, args);
-    return hipGetLastError();
-}
-
-template <int NJ>
-static hipError_t launch_nj(const TiledArgs& args, int n_waves, int xsteps, unsigned grid, hipStream_t st) {
-    if (xsteps == 1) return launch_inst<NJ, 1>(args, n_waves, grid, st);
-    if (xsteps == 2) return launch_inst<NJ, 2>(args, n_waves, grid, st);
-    return launch_inst<NJ, 0>(args, n_waves, grid, st);
-}
-
 hipError_t launch_linear_decode_tiled(const TiledArgs& args, int n_jobs, hipStream_t st) {
-    if (n_jobs < 1 || n_jobs > kTiledMaxJobs || args.n_mats < 1 || args.n_mats > kTiledMaxMats || args.n_ct < 1 ||
-        args.n_ct > kTiledMaxCt)
-        return hipErrorInvalidValue;
-    const int rb_total = args.rb_end[args.n_mats - 1];
-    if (rb_total < 1 || args.KT < 0) return hipErrorInvalidValue;
-    // compute units of the current device, asked once per device (0 = not asked yet; 64 devices at most are remembered)
-    static std::atomic<int> cus_of[64];
-    int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess) return hipErrorInvalidDevice;
-    int cus = cus_of[dev & 63].load(std::memory_order_relaxed);
-    if (cus == 0) {
-        int v = 0;
-        cus = (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0) ? v : 256;
-        cus_of[dev & 63].store(cus, std::memory_order_relaxed);
-    }
-    // persistent grid: one workgroup per compute unit, never more workgroups than row blocks;
-    // 8 wavefronts, never more than k tiles (KT == 0: one idle-looping wavefront writes y = 0)
-    const unsigned grid = (unsigned)(rb_total < cus ? rb_total : cus);
-    int n_waves = kMaxWavesTiled;
-    while (n_waves > 1 && n_waves > args.KT) n_waves >>= 1;
-    if (args.n_ct == 2) {   // 17..32 tokens: two column tiles, streamed x
-        if (n_jobs <= 4) return launch_inst<4, 0, 2>(args, n_waves, grid, st);
-        if (n_jobs <= 8) return launch_inst<8, 0, 2>(args, n_waves, grid, st);
-        return launch_inst<16, 0, 2>(args, n_waves, grid, st);
-    }
-    int xsteps = 0;
-    if (args.KT > 0 && args.KT % n_waves == 0 && args.KT / n_waves <= 2) xsteps = args.KT / n_waves;
-    if (n_jobs <= 4) return launch_nj<4>(args, n_waves, xsteps, grid, st);
-    if (n_jobs <= 8) return launch_nj<8>(args, n_waves, xsteps, grid, st);
-    return launch_nj<16>(args, n_waves, xsteps, grid, st);
+    return launch_tiled_t<false>(args, n_jobs, st);
 }
 
 }  // namespace bd

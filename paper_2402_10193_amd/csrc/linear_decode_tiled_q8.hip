@@ -1,0 +1,10 @@
+// The tiled decode kernel instantiated for the 8-bit round-to-nearest base (see linear_decode_tiled_kernel.h).
+#include "linear_decode_tiled_kernel.h"
+
+namespace bd {
+
+hipError_t launch_linear_decode_tiled_q8(const TiledArgs& args, int n_jobs, hipStream_t st) {
+    return launch_tiled_t<true>(args, n_jobs, st);
+}
+
+}  // namespace bd

@@ -44,6 +44,39 @@ __global__ __launch_bounds__(256) void tile_signs_kernel(const uint32_t* __restr
     }
 }
 
+// One 16-byte unit of the 8-bit base layout per thread: unit u = ((tile * 4 + i) * 64 + l), bytes [h][e] =
+// 128 + q[16 rb + l % 16][256 kt + 32 (2 i + h) + 8 (l / 16) + e]; 128 (q = 0) outside the matrix.
+__global__ __launch_bounds__(256) void tile_base_q8_kernel(const int8_t* __restrict__ q, u32x4* __restrict__ wq,
+                                                            const int64_t out, const int64_t in, const int64_t KT,
+                                                            const int64_t n_units) {
+    for (int64_t u = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; u < n_units; u += (int64_t)gridDim.x * blockDim.x) {
+        const int l = (int)(u & 63), i = (int)((u >> 6) & 3);
+        const int64_t tile = u >> 8, kt = tile % KT, rb = tile / KT;
+        const int64_t row = rb * kTileRows + (l & 15);
+        u32x4 val = {0x80808080u, 0x80808080u, 0x80808080u, 0x80808080u};
+        if (row < out) {
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const int64_t k0 = kt * kTileK + 32 * (2 * i + h) + 8 * (l >> 4);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const uint32_t byte = k0 + e < in ? (uint32_t)(uint8_t)(q[row * in + k0 + e] + 128) : 128u;
+                    const int pos = 8 * h + e;
+                    val[pos >> 2] = (val[pos >> 2] & ~(0xFFu << (8 * (pos & 3)))) | (byte << (8 * (pos & 3)));
+                }
+            }
+        }
+        wq[u] = val;
+    }
+}
+
+// scales of the rows of every row block, zero beyond `out`
+__global__ __launch_bounds__(256) void tile_scales_kernel(const float* __restrict__ scale, float* __restrict__ dst,
+                                                           const int64_t out, const int64_t n_padded) {
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n_padded; i += (int64_t)gridDim.x * blockDim.x)
+        dst[i] = i < out ? scale[i] : 0.0f;
+}
+
 static unsigned grid_for(int64_t n, int block) {
     int64_t g = (n + block - 1) / block;
     return (unsigned)(g < 1 ? 1 : (g > 65536 ? 65536 : g));
@@ -59,6 +92,17 @@ hipError_t launch_tile_signs(const uint32_t* packed, int64_t out, int64_t in, ui
     const int64_t KT = tiled_k_tiles(in), n_slots = tiled_row_blocks(out) * KT * 64;
     hipLaunchKernelGGL(tile_signs_kernel, dim3(grid_for(n_slots, 256)), dim3(256), 0, st, packed, (u32x2*)st_out, out, in, KT,
                        n_slots);
+    return hipGetLastError();
+}
+
+hipError_t launch_tile_base_q8(const int8_t* q, const float* scale, int64_t out, int64_t in, unsigned char* wq, hipStream_t st) {
+    const int64_t KT = tiled_k_tiles(in), RB = tiled_row_blocks(out), n_units = RB * KT * (kTileBaseQ8Bytes / 16);
+    if (n_units > 0)
+        hipLaunchKernelGGL(tile_base_q8_kernel, dim3(grid_for(n_units, 256)), dim3(256), 0, st, q, (u32x4*)wq, out, in, KT, n_units);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(tile_scales_kernel, dim3(grid_for(RB * kTileRows, 256)), dim3(256), 0, st, scale,
+                       (float*)(wq + RB * KT * kTileBaseQ8Bytes), out, RB * kTileRows);
     return hipGetLastError();
 }
 
