@@ -50,6 +50,8 @@ def parse():
     ap.add_argument("--mix", type=str, default="",
                     help="mixed decode batch: tokens per active tenant, e.g. 6,4,3,1,1,1 (tenants 0.. of the B resident "
                          "ones; the others stay idle); default: one token per tenant")
+    ap.add_argument("--base", choices=["fp16", "int8"], default="fp16",
+                    help="int8: 8-bit round-to-nearest base weights (one scale per output row), deltas taken against them")
     ap.add_argument("--planes", type=int, default=1,
                     help="sign planes per tenant (iterated compression); a token then takes that many of a launch's columns")
     ap.add_argument("--calibrate", action="store_true",
@@ -223,6 +225,10 @@ def main():
         args.no_extras = args.no_cpu = True      # the baselines below are defined for one token per tenant
     T, n_active = len(tok), len(set(tok))
     k = args.planes
+    q8 = args.base == "int8"
+    if q8:
+        assert args.path == "tiled-fused" and k == 1 and args.workload == "decode", "--base int8: tiled-fused decode, one plane"
+        args.no_extras = args.no_cpu = True
     if k != 1:
         assert args.path == "tiled-fused", "--planes needs the tiled-fused path"
         args.no_extras = args.no_cpu = True
@@ -238,13 +244,18 @@ def main():
         mats = []
         for name, out, inn in shapes:
             base = synth.base_weight(out, inn, device=dev, tag=("L", li, name))
+            if q8:
+                qb, qscale = bd.quantize_base_q8(base)
             packed, alphas = [], []
             for t in range(B):
                 ft = synth.finetuned_weight(base, sigma=sigma, tag=("L", li, name, t))
                 if li == 0:
                     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
                     e0.record()
-                p, a = bd.compress(base, ft, workspace=ws) if k == 1 else bd.compress_iterated(base, ft, k, workspace=ws)
+                if q8:
+                    p, a = bd.compress_q8(qb, qscale, ft, workspace=ws)
+                else:
+                    p, a = bd.compress(base, ft, workspace=ws) if k == 1 else bd.compress_iterated(base, ft, k, workspace=ws)
                 if li == 0:
                     e1.record()
                     e1.synchronize()
@@ -266,7 +277,7 @@ def main():
                                             torch.stack(alphas))
                 base = None
             elif args.path != "rowmajor":
-                wt = bd.tile_base(base)
+                wt = bd.tile_base_q8(qb, qscale) if q8 else bd.tile_base(base)
                 ttable = bd.TiledTenantTable([bd.tile_signs(p, out, inn) for p in packed], table.alpha)
                 if li > 0:          # layer 0 keeps its row-major tensors for the naive baseline below
                     base = table = None
@@ -298,6 +309,9 @@ def main():
                     return lambda g=g, yl=yl, inn=ms[0][2]: bd.linear_multitenant_tiled_group_kbit(
                         xs[inn], g, tok, ys=yl, tok_array=tok_arr)
                 g = bd.TiledGroup([m[5] for m in ms], [m[1] for m in ms], [m[6] for m in ms])
+                if q8:
+                    return lambda g=g, yl=yl, inn=ms[0][2]: bd.linear_multitenant_tiled_group_q8(xs[inn], g, tok, ys=yl,
+                                                                                                  tok_array=tok_arr)
                 return lambda g=g, yl=yl, inn=ms[0][2]: bd.linear_multitenant_tiled_group(xs[inn], g, tok, ys=yl,
                                                                                            tok_array=tok_arr)
             def single(n):
@@ -305,6 +319,9 @@ def main():
                 if k != 1:
                     return lambda m=m: bd.linear_multitenant_tiled_kbit(xs[m[2]], m[5], m[1], m[6], tok,
                                                                         y=ys[(m[0], m[1])], tok_array=tok_arr)
+                if q8:
+                    return lambda m=m: bd.linear_multitenant_tiled_q8(xs[m[2]], m[5], m[1], m[6], tok, y=ys[(m[0], m[1])],
+                                                                      tok_array=tok_arr)
                 return lambda m=m: bd.linear_multitenant_tiled(xs[m[2]], m[5], m[1], m[6], tok, y=ys[(m[0], m[1])],
                                                                tok_array=tok_arr)
             plan = [grouped(["q", "k", "v"]), single("o"), grouped(["gate", "up"]), single("down")]
@@ -318,7 +335,8 @@ def main():
     launches_per_step = sum(len(p) for p in plans)
     P = sum(o * i for _, o, i in shapes)
     xy_bytes = sum(T * (i + o) * 2 for _, o, i in shapes)
-    bytes_per_step = n_layers * (2.0 * P + n_active * k * P / 8.0 + xy_bytes)   # W once, each active delta (k planes) once, x, y
+    base_bytes = (1.0 * P + 4.0 * sum(o for _, o, _ in shapes)) if q8 else 2.0 * P   # int8: one byte per weight + a scale per row
+    bytes_per_step = n_layers * (base_bytes + n_active * k * P / 8.0 + xy_bytes)   # W once, each active delta (k planes) once, x, y
 
     run_stack()                                   # first call sets kernel attributes; keep it out of any capture
     torch.cuda.synchronize()
@@ -386,7 +404,7 @@ def main():
                         f"B={B} tenants, " + (f"mixed decode batch of {T} tokens ({args.mix} per active tenant), "
                                                if args.mix else "one decode token per tenant, ")
                         + (f"distinct {k}-plane delta per (tenant, matrix)" if k != 1 else "distinct 1-bit delta per (tenant, matrix)"),
-            "tenants": B, "tokens": T, "active_tenants": n_active, "planes": k, "layers": n_layers, "launches_per_step": launches_per_step,
+            "tenants": B, "tokens": T, "active_tenants": n_active, "planes": k, "base": args.base, "layers": n_layers, "launches_per_step": launches_per_step,
             "launch": "hip graph replay" if graph is not None else "eager",
             "path": args.path, "kernel_variant": args.variant,
         },
@@ -397,7 +415,7 @@ def main():
             "unit": "GB/s",
             "frac": round(achieved_gbs / HBM_PEAK_GBS, 4),
             "traffic": MEASURED_TRAFFIC_BYTES_PER_LAUNCH.get((args.model, B, args.path))
-                       if n_layers == 32 and not args.mix and k == 1 else None,
+                       if n_layers == 32 and not args.mix and k == 1 and not q8 else None,
             "kernel": "linear_decode_mfma_kernel" if args.path == "rowmajor" else "linear_decode_tiled_kernel",
             "bytes_per_launch": round(bytes_per_step / launches_per_step, 1),
             "avg_launch_us": round(ms_per_step * 1e3 / launches_per_step, 3),
