@@ -166,6 +166,36 @@ def test_kbit_argument_errors(bd):
     assert g(0, *args, 2, 0) == 2 and g(1, *args, 0, 0) == 2
 
 
+def test_q8_argument_errors(bd):
+    L = bd.lib()
+    vp = ctypes.c_void_p
+    assert bd.tiled_base_q8_bytes(4096, 4096) == 4096 * 4096 + 4096 * 4
+    assert bd.tiled_base_q8_bytes(50, 640) == 4 * 3 * 4096 + 64 * 4 and bd.tiled_base_q8_bytes(16, 40) == 0
+    qz = L.bd_quantize_base_q8
+    assert qz(A, -1, 64, 2 * A, 3 * A, 0) == 2 and qz(0, 4, 64, 2 * A, 3 * A, 0) == 1 and qz(A, 4, 64, 2 * A, 0, 0) == 1
+    assert qz(A, 4, 64, A + 64, 3 * A, 0) == 8 and qz(0, 0, 64, 0, 0, 0) == 0
+    need = bd.workspace_bytes(bd.OP_COMPRESS, 0, 16, 128, 1)
+    c = L.bd_compress_q8
+    assert c(A, 2 * A, 3 * A, 16, 100, 4 * A, 5 * A, 6 * A, need, 0) == 2
+    assert c(0, 2 * A, 3 * A, 16, 128, 4 * A, 5 * A, 6 * A, need, 0) == 1
+    assert c(A + 4, 2 * A, 3 * A, 16, 128, 4 * A, 5 * A, 6 * A, need, 0) == 3
+    assert c(A, 2 * A, 3 * A, 16, 128, 4 * A, 5 * A, 6 * A, need - 1, 0) == 5
+    assert c(A, 2 * A, 3 * A, 16, 128, A + 256, 5 * A, 6 * A, need, 0) == 8
+    t = L.bd_tile_base_q8
+    assert t(A, 2 * A, 16, 40, 3 * A, 0) == 2 and t(A, 0, 16, 64, 3 * A, 0) == 1 and t(A, 2 * A, 16, 64, 3 * A + 4, 0) == 3
+    assert t(A, 2 * A, 16, 256, A + 1024, 0) == 8
+    f = L.bd_linear_multitenant_tiled_q8
+    ok = dict(x=A, w=2 * A, pk=(vp * 1)(3 * A), al=4 * A, tok=_tok(0), y=5 * A, T=1, out=16, inn=128, nt=1)
+
+    def call(**kw):
+        a = dict(ok, **kw)
+        return f(a["x"], a["w"], a["pk"], a["al"], a["tok"], a["y"], a["T"], a["out"], a["inn"], a["nt"], 0)
+
+    assert call(inn=48) == 2 and call(w=0) == 1 and call(w=2 * A + 8) == 3 and call(tok=_tok(1)) == 4
+    assert call(y=2 * A + 4096) == 8          # y inside the scales that follow the tiles
+    assert call(T=0, x=0, y=0) == 0
+
+
 def test_group_tokens_sorts_stably_and_cuts_jobs_at_the_tile_boundary(bd):
     import random
     rng = random.Random(5)
