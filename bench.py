@@ -87,7 +87,7 @@ def run_prefill(args, torch, bd, synth, dev):
 
     def step():
         for x, base, table, y, ws, _, _ in mats:
-            bd.linear_multitenant(x, base, table, tok, y=y, tok_array=tok_arr, workspace=ws)
+            bd.linear_multitenant(x, base, table, tok, y=y, tok_array=tok_arr, workspace=ws, variant=args.variant)
     for _ in range(max(args.warmup, 1)):
         step()
     torch.cuda.synchronize()

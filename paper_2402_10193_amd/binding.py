@@ -257,7 +257,7 @@ def linear_multitenant(x: torch.Tensor, w_base: torch.Tensor, tenants: TenantTab
                                      T, out, inn, tenants.n_tenants, ws_ptr, ws_bytes, _stream(stream))
     else:
         st = L.bd_linear_multitenant_variant(_ptr(x), _ptr(w_base), _ptr(tenants.ptrs), _ptr(tenants.alpha), tok,
-                                             _ptr(y), T, out, inn, tenants.n_tenants, 0, 0, _stream(stream),
+                                             _ptr(y), T, out, inn, tenants.n_tenants, ws_ptr, ws_bytes, _stream(stream),
                                              int(variant))
     _check(st, "bd_linear_multitenant")
     return y

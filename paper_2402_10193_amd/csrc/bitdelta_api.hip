@@ -17,6 +17,8 @@ using bd::kMaxDecodeTokens;
 constexpr int kVersion = 200;   // 0.2.0
 constexpr int kVariantRowWave = 1;
 constexpr int kVariantDefaultMfma = 3;
+constexpr int kVariantPrefillSmall = 4;   // T > 32 with a workspace: the 128 x 128 tile GEMM
+constexpr int kVariantPrefillBig = 5;     // ... the 128 x 256 tile GEMM (in % 64 == 0)
 
 inline bool misaligned(const void* p, size_t a) { return ((uintptr_t)p & (a - 1)) != 0; }
 
@@ -101,7 +103,7 @@ size_t prefill_workspace_bytes(int64_t T, int32_t n_tenants) {
 // the two tables into the workspace (through kernel arguments: no host-to-device copy call) and runs the GEMM.
 hipError_t run_prefill(const uint16_t* x, const uint16_t* w, const uint32_t* const* packed_by_tenant,
                        const float* alpha_by_tenant, const int32_t* tenant_of_token, uint16_t* y, int64_t T, int64_t out,
-                       int64_t in, void* workspace, hipStream_t st) {
+                       int64_t in, void* workspace, hipStream_t st, bool big) {
     std::vector<int32_t> order((size_t)T);
     for (int64_t i = 0; i < T; ++i) order[(size_t)i] = (int32_t)i;
     std::stable_sort(order.begin(), order.end(),
@@ -129,6 +131,9 @@ hipError_t run_prefill(const uint16_t* x, const uint16_t* w, const uint32_t* con
         const hipError_t e = bd::launch_prefill_meta(c, dst + off, n, st);
         if (e != hipSuccess) return e;
     }
+    if (big)
+        return bd::launch_linear_prefill_big(x, w, packed_by_tenant, alpha_by_tenant, dst, dst + row_token.size(), n_mtiles, y,
+                                             T, out, in, st);
     return bd::launch_linear_prefill(x, w, packed_by_tenant, alpha_by_tenant, dst, dst + row_token.size(), n_mtiles, y, out,
                                      in, st);
 }
@@ -226,12 +231,14 @@ bd_status bd_linear_multitenant_variant(const uint16_t* x_f16, const uint16_t* w
     const bd_status st = check_linear_args(x_f16, w_base_f16, packed_by_tenant, alpha_by_tenant, tenant_of_token, y_f16,
                                            T, out, in, n_tenants);
     if (st != BD_OK) return st;
-    if (variant != 0 && variant != kVariantRowWave && !bd::decode_mfma_variant_known(variant)) return BD_ERR_UNSUPPORTED;
+    const bool prefill_variant = variant == kVariantPrefillSmall || variant == kVariantPrefillBig;
+    if (variant != 0 && variant != kVariantRowWave && !bd::decode_mfma_variant_known(variant) && !prefill_variant)
+        return BD_ERR_UNSUPPORTED;
     if (T == 0 || out == 0) return BD_OK;
     // 128-bit sign loads need whole, aligned 4-word groups; 32-bit lane offsets need tensors below 4 GiB
     const bool mfma_ok = (in % 128 == 0) && in > 0 && (uint64_t)out * (uint64_t)in * 2 < ((uint64_t)1 << 32) &&
                          (uint64_t)T * (uint64_t)in * 2 < ((uint64_t)1 << 32);
-    if (variant >= 2 && !mfma_ok) return BD_ERR_UNSUPPORTED;
+    if (variant >= 2 && !prefill_variant && !mfma_ok) return BD_ERR_UNSUPPORTED;
     int use = variant;
     if (use == 0) use = mfma_ok ? kVariantDefaultMfma : kVariantRowWave;
 
@@ -239,11 +246,19 @@ bd_status bd_linear_multitenant_variant(const uint16_t* x_f16, const uint16_t* w
     // More than one decode launch worth of tokens: the prefill GEMM, if the caller brought its workspace
     // (without one the call still works, as a sequence of decode launches that re-read the base).
     const size_t need = prefill_workspace_bytes(T, n_tenants);
-    if (variant == 0 && need > 0 && in > 0 && workspace && workspace_bytes >= need && !misaligned(workspace, 256))
+    const bool can_prefill = need > 0 && in > 0 && workspace && workspace_bytes >= need && !misaligned(workspace, 256);
+    if (prefill_variant && !can_prefill) return need > 0 && in > 0 ? BD_ERR_WORKSPACE : BD_ERR_UNSUPPORTED;
+    if (variant == kVariantPrefillBig && !bd::prefill_big_fits(T, out, in)) return BD_ERR_UNSUPPORTED;
+    if ((variant == 0 || prefill_variant) && can_prefill) {
+        // the large tile (one workgroup per CU, 256 output features wide) pays off when there are at least that many
+        const bool big = variant == kVariantPrefillBig ||
+                         (variant == 0 && out >= 256 && bd::prefill_big_fits(T, out, in));
         return run_prefill(x_f16, w_base_f16, packed_by_tenant, alpha_by_tenant, tenant_of_token, y_f16, T, out, in,
-                           workspace, hs) == hipSuccess
+                           workspace, hs, big) == hipSuccess
                    ? BD_OK
                    : BD_ERR_DEVICE;
+    }
+    if (prefill_variant) use = mfma_ok ? kVariantDefaultMfma : kVariantRowWave;   // not reached: can_prefill held above
     for (int64_t t0 = 0; t0 < T; t0 += kMaxDecodeTokens) {
         const int n = (int)std::min<int64_t>(kMaxDecodeTokens, T - t0);
         DecodeMeta meta;

@@ -1,0 +1,274 @@
+// Large-tile form of the prefill GEMM (Eq. 6 of the paper with many tokens per tenant; see
+// linear_prefill.hip for the formulation).  One workgroup of 4 wavefronts per compute unit, each
+// wavefront alone on its SIMD with the whole register file: it owns 128 tokens x 64 output features
+// of a 128 x 256 tile and multiplies with v_mfma_f32_32x32x16_f16 (A = 32 tokens x 16 k, B = 16 k x
+// 32 features, 32 cycles): a lone wavefront issues an instruction only every 8 cycles or so, and the
+// larger MFMA leaves room for the three other instructions (LDS reads, address arithmetic, loads)
+// that each one needs.  The 16 accumulator tiles (base and delta separately, alpha applied at the
+// end) fill the 256 accumulation registers.
+//   x tile   128 tokens x 64 k  fp16  -> LDS, rows of 8 chunks in the order chunk ^ ((row / 2) % 8)
+//   W tile   256 rows   x 64 k  fp16  -> LDS, same order
+//   signs    256 rows   x 2 words     -> LDS as they are; a lane's byte of 8 signs becomes the
+//            operand through two reads of a nibble table (16 entries x 32 copies x 8 B)
+// LDS is double-buffered (one barrier per step of 64 k); the global loads of step s + 3 are issued
+// into the registers that have just been written out for step s + 1, so two steps of loads are in
+// flight while a step is multiplied.  Inside a step the operands of the next 16-wide k slice (16 MFMAs)
+// are read while the current slice is multiplied.
+// Used when in % 64 == 0; other shapes take the 128 x 128 kernel.
+#include "bd_device.h"
+#include "bd_launch.h"
+
+namespace bd {
+
+namespace {
+
+constexpr int kBgM = 128, kBgN = 256, kBgK = 64;
+constexpr int kBgRowBytes = kBgK * 2;                    // 128
+constexpr int kBgXBytes = kBgM * kBgRowBytes;            // 16384
+constexpr int kBgWBytes = kBgN * kBgRowBytes;            // 32768
+constexpr int kBgSBytes = kBgN * 8;                      // 2048
+constexpr int kBgBufBytes = kBgXBytes + kBgWBytes + kBgSBytes;
+constexpr int kBgLutBytes = 16 * 32 * 8;
+constexpr int kBgLdsBytes = 2 * kBgBufBytes + kBgLutBytes;   // 106496
+constexpr int kBgXPer = kBgM * 8 / 256, kBgWPer = kBgN * 8 / 256;   // 16-byte chunks per thread and step: 4 and 8
+constexpr int kBgPanel = 8, kBgChunk = 32, kBgXcds = 8;  // launch order: 4 x 8 tiles per XCD at a time
+
+__device__ __forceinline__ int bg_off(const int row, const int chunk) {
+    return row * kBgRowBytes + ((chunk ^ ((row >> 1) & 7)) << 4);
+}
+
+// Workgroup barrier that orders LDS traffic only (__syncthreads also drains the global loads in flight).
+__device__ __forceinline__ void bg_barrier() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
+typedef const uint32_t __attribute__((address_space(1)))* bg_global_words;
+
+// acc += A . B with the accumulator held in place in the accumulation registers.  (Left to itself the
+// compiler gives every MFMA a fresh destination and copies it back, four moves per MFMA, once all
+// 256 accumulation registers are taken.)  Written as an asm statement the instruction is opaque to the
+// compiler's hazard bookkeeping, so the callers keep to what needs none: A and B come straight from
+// LDS reads, no accumulator is touched again within the next 15 MFMAs, and the epilogue waits
+// explicitly before it reads the accumulators.
+typedef float float16v __attribute__((ext_vector_type(16)));
+__device__ __forceinline__ void mfma_in_place(float16v& acc, const half8 a, const half8 b) {
+    asm volatile("v_mfma_f32_32x32x16_f16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
+}
+
+}  // namespace
+
+__global__ __launch_bounds__(256, 1) void linear_prefill_big_kernel(
+    const uint16_t* __restrict__ x, const uint16_t* __restrict__ w, const uint32_t* const* __restrict__ packed_by_tenant,
+    const float* __restrict__ alpha_by_tenant, const int32_t* __restrict__ row_token, const int32_t* __restrict__ tile_tenant,
+    uint16_t* __restrict__ y, const int64_t out, const int64_t in, const int n_mtiles, const int n_ntiles) {
+    extern __shared__ __align__(16) unsigned char lds[];   // [2 buffers: x, W, sign words][table]
+    unsigned char* const lut = lds + 2 * kBgBufBytes;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    int mt, nt;
+    {   // launch order -> tile: panels of 8 N tiles, row-major inside, chunks of 32 tiles per XCD
+        const int L = blockIdx.x, xcd = L % kBgXcds, slot = L / kBgXcds;
+        const int chunk = (slot / kBgChunk) * kBgXcds + xcd;
+        const int t = chunk * kBgChunk + slot % kBgChunk;
+        if (t >= n_mtiles * n_ntiles) return;
+        const int per_panel = n_mtiles * kBgPanel;
+        const int panel = t / per_panel, tp = t - panel * per_panel;
+        const int width = n_ntiles - panel * kBgPanel < kBgPanel ? n_ntiles - panel * kBgPanel : kBgPanel;
+        mt = tp / width;
+        nt = panel * kBgPanel + tp % width;
+    }
+    const int64_t n0 = (int64_t)nt * kBgN;
+    const int tenant = tile_tenant[mt];
+    const float alpha = alpha_by_tenant[tenant];
+    const int64_t words_per_row = in >> 5;
+    const int n_steps = (int)(in / kBgK), last = n_steps - 1;
+
+    {   // nibble -> 4 fp16 (+1.0 where the bit is set, else -1.0); entry [nibble][copy], lane l reads copy l % 32
+        const uint32_t b = (uint32_t)tid >> 4;
+        uint2 e;
+        e.x = 0xBC00BC00u ^ ((b & 1u) << 15) ^ (((b >> 1) & 1u) << 31);
+        e.y = 0xBC00BC00u ^ (((b >> 2) & 1u) << 15) ^ (((b >> 3) & 1u) << 31);
+        *(uint2*)(lut + b * 256 + (tid & 15) * 8) = e;
+        *(uint2*)(lut + b * 256 + 128 + (tid & 15) * 8) = e;
+    }
+    const uint32_t lut_lane = (uint32_t)(lane & 31) * 8u;
+
+    // What this thread fetches per step.  Empty token rows read token 0 and output rows beyond `out` the last
+    // row: their products are never stored, so nothing has to be zeroed and no load is conditional.
+    // Global addresses are a uniform base plus a 32-bit byte offset per thread (the host checks the ranges).
+    const unsigned char* const xbase = (const unsigned char*)x;
+    const unsigned char* const wbase = (const unsigned char*)(w + n0 * in);
+    uint32_t xsrc[kBgXPer], wsrc[kBgWPer];
+    int xoff[kBgXPer], woff[kBgWPer];
+#pragma unroll
+    for (int i = 0; i < kBgWPer; ++i) {
+        const int q = tid + 256 * i, row = q >> 3, c8 = q & 7;
+        const int64_t wrow = n0 + row < out ? row : out - 1 - n0;
+        wsrc[i] = (uint32_t)(wrow * in * 2) + c8 * 16;
+        woff[i] = kBgXBytes + bg_off(row, c8);
+        if (i < kBgXPer) {
+            const int tok = row_token[mt * kBgM + row];
+            xsrc[i] = (uint32_t)((int64_t)(tok >= 0 ? tok : 0) * in * 2) + c8 * 16;
+            xoff[i] = bg_off(row, c8);
+        }
+    }
+    const int64_t srow = n0 + tid < out ? n0 + tid : out - 1;
+    const bg_global_words ssrc = (bg_global_words)(packed_by_tenant[tenant] + srow * words_per_row);
+
+    struct Staged {
+        u32x4 xg[kBgXPer], wg[kBgWPer];
+        uint32_t s0, s1;
+    };
+    Staged set0, set1;
+    // item 0..3: x chunk, 4..11: W chunk, 12: the two sign words
+    constexpr int kItems = kBgXPer + kBgWPer + 1;
+    auto fetch_item = [&](Staged& st, const int step, const int item) {
+        if (item < kBgXPer) st.xg[item] = *(const u32x4*)(xbase + (int64_t)step * kBgRowBytes + xsrc[item]);
+        else if (item < kBgXPer + kBgWPer) st.wg[item - kBgXPer] = *(const u32x4*)(wbase + (int64_t)step * kBgRowBytes + wsrc[item - kBgXPer]);
+        else {
+            st.s0 = ssrc[2 * step];
+            st.s1 = ssrc[2 * step + 1];
+        }
+    };
+    auto stage_item = [&](const Staged& st, const int buf, const int item) {
+        unsigned char* const b = lds + buf * kBgBufBytes;
+        if (item < kBgXPer) *(u32x4*)(b + xoff[item]) = st.xg[item];
+        else if (item < kBgXPer + kBgWPer) *(u32x4*)(b + woff[item - kBgXPer]) = st.wg[item - kBgXPer];
+        else *(uint2*)(b + kBgXBytes + kBgWBytes + tid * 8) = uint2{st.s0, st.s1};
+    };
+    auto fetch = [&](Staged& st, const int step) {
+#pragma unroll
+        for (int it = 0; it < kItems; ++it) fetch_item(st, step, it);
+    };
+    auto stage = [&](const Staged& st, const int buf) {
+#pragma unroll
+        for (int it = 0; it < kItems; ++it) stage_item(st, buf, it);
+    };
+
+    float16v accb[4][2], accd[4][2];   // [token block of 32][feature block of 32]
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) accb[i][j][e] = accd[i][j][e] = 0.f;
+
+    // Operand of k slice s (16 k): lane (l % 32, l / 32) reads row base + l % 32, chunk 2 s + l / 32; the swizzle
+    // mask (row / 2) % 8 depends on the lane only.
+    const int r32 = lane & 31, hi = lane >> 5;
+    const int mask = (r32 >> 1) & 7;
+    int cho[4];
+#pragma unroll
+    for (int sl = 0; sl < 4; ++sl) cho[sl] = ((2 * sl + hi) ^ mask) << 4;
+    const int xrow = r32 * kBgRowBytes, wrow_off = kBgXBytes + (wave * 64 + r32) * kBgRowBytes;
+    const int srow_off = kBgXBytes + kBgWBytes + (wave * 64 + r32) * 8;
+    auto expand = [&](const uint32_t byte) {
+        const uint2 lo = *(const uint2*)(lut + (byte & 15u) * 256u + lut_lane);
+        const uint2 hh = *(const uint2*)(lut + (byte >> 4) * 256u + lut_lane);
+        return __builtin_bit_cast(half8, u32x4{lo.x, lo.y, hh.x, hh.y});
+    };
+
+    // While step `step` is multiplied, the tiles of step + 1 (in `next`) go into the other buffer and `next` is
+    // refilled with step + 3 -- one LDS write or one global load behind every other MFMA, so that the four
+    // wavefronts do not queue up at the LDS and at the address unit while their matrix pipes idle.
+    auto do_step = [&](const int step, const int buf, Staged& next) {
+        const int step3 = step + 3 < last ? step + 3 : last;
+        const unsigned char* const b = lds + buf * kBgBufBytes;
+        uint2 sw[2];                                            // this lane's row of the 2 feature blocks: 8 sign bytes each
+#pragma unroll
+        for (int j = 0; j < 2; ++j) sw[j] = *(const uint2*)(b + srow_off + j * 32 * 8);
+        auto sign_byte = [&](const int j, const int sl) {       // byte 2 sl + hi of the row's 8
+            const uint32_t word = sl < 2 ? sw[j].x : sw[j].y;
+            return (word >> (16 * (sl & 1) + 8 * hi)) & 0xFFu;
+        };
+        half8 a[2][4], bw[2][2], bs[2][2];
+        auto read_slice = [&](const int sl, const int set) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) a[set][i] = *(const half8*)(b + xrow + i * 32 * kBgRowBytes + cho[sl]);
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                bw[set][j] = *(const half8*)(b + wrow_off + j * 32 * kBgRowBytes + cho[sl]);
+                bs[set][j] = expand(sign_byte(j, sl));
+            }
+        };
+        read_slice(0, 0);
+#pragma unroll
+        for (int sl = 0; sl < 4; ++sl) {                        // k slice: 16 MFMAs
+            const int cur = sl & 1;
+            if (sl + 1 < 4) read_slice(sl + 1, cur ^ 1);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 2; ++j) {
+                    mfma_in_place(accb[i][j], a[cur][i], bw[cur][j]);
+                    mfma_in_place(accd[i][j], a[cur][i], bs[cur][j]);
+                    // pair p of the step's 32: item p leaves for LDS after pair p, and is fetched again after pair p + 6
+                    const int p = sl * 8 + i * 2 + j;
+                    if (p < kItems) stage_item(next, buf ^ 1, p);
+                    if (p >= 6 && p - 6 < kItems) fetch_item(next, step3, p - 6);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        bg_barrier();   // step + 1 is complete in the other buffer, and this one may be overwritten
+    };
+
+    fetch(set0, 0);
+    fetch(set1, 1 < last ? 1 : last);
+    stage(set0, 0);
+    fetch(set0, 2 < last ? 2 : last);
+    bg_barrier();       // the table and the tiles of step 0 are complete
+    int step = 0;
+    for (; step + 1 < n_steps; step += 2) {
+        do_step(step, 0, set1);
+        do_step(step + 1, 1, set0);
+    }
+    if (step < n_steps) do_step(step, 0, set1);
+
+    asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");   // the last MFMAs have left the pipe before their results are read
+    // 32 x 32 result tile (i, j), element e of a lane: token row 32 i + 8 (e / 4) + 4 (l / 32) + e % 4, feature
+    // n0 + 64 wave + 32 j + l % 32
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+            const int tok = row_token[mt * kBgM + 32 * i + 8 * (e >> 2) + 4 * hi + (e & 3)];
+            if (tok < 0) continue;
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const int64_t n = n0 + wave * 64 + 32 * j + r32;
+                if (n < out) y[(int64_t)tok * out + n] = f2h_rne(accb[i][j][e] + alpha * accd[i][j][e]);
+            }
+        }
+    }
+}
+
+// T: rows of x (its byte offsets and those inside one 256-row band of W must fit 32 bits)
+bool prefill_big_fits(int64_t T, int64_t out, int64_t in) {
+    return in >= kBgK && in % kBgK == 0 && out >= 1 && (uint64_t)T * (uint64_t)in * 2 < ((uint64_t)1 << 32) &&
+           (uint64_t)kBgN * (uint64_t)in * 2 < ((uint64_t)1 << 32);
+}
+
+hipError_t launch_linear_prefill_big(const uint16_t* x, const uint16_t* w, const uint32_t* const* packed_by_tenant,
+                                     const float* alpha_by_tenant, const int32_t* row_token, const int32_t* tile_tenant,
+                                     int n_mtiles, uint16_t* y, int64_t T, int64_t out, int64_t in, hipStream_t st) {
+    if (!prefill_big_fits(T, out, in)) return hipErrorInvalidValue;
+    const int n_ntiles = (int)((out + kBgN - 1) / kBgN);
+    const int64_t tiles = (int64_t)n_mtiles * n_ntiles;
+    if (tiles < 1 || tiles > (int64_t)1 << 30) return hipErrorInvalidValue;
+    static PerDeviceOnce lds_limit;
+    const hipError_t ea = lds_limit.run([&] {
+        return hipFuncSetAttribute((const void*)linear_prefill_big_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kBgLdsBytes);
+    });
+    if (ea != hipSuccess) return ea;
+    const int64_t round = (int64_t)kBgChunk * kBgXcds;
+    const unsigned grid = (unsigned)((tiles + round - 1) / round * round);
+    hipLaunchKernelGGL(linear_prefill_big_kernel, dim3(grid), dim3(256), kBgLdsBytes, st, x, w, packed_by_tenant, alpha_by_tenant,
+                       row_token, tile_tenant, y, out, in, n_mtiles, n_ntiles);
+    return hipGetLastError();
+}
+
+}  // namespace bd

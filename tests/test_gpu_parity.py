@@ -114,6 +114,8 @@ PREFILL_CASES = [
     (128, 1024, 2, [128, 256]),                  # exact tiles
     (1024, 2048, 8, [160] * 8),                  # 1280 tokens
     (64, 32, 4, [9, 9, 9, 9]),                   # a single k step
+    (520, 192, 3, [40, 3, 90]),                  # three 64-wide steps (odd), three 256-wide N tiles with a ragged one
+    (256, 64, 2, [33, 1]),                       # one 64-wide step
 ]
 
 
@@ -134,6 +136,17 @@ def test_prefill_gemm_matches_oracle(ref, case):
     check_close(y, y32, f"prefill case {case}")
     check_close(y_dec, y32, f"prefill case {case}, decode launches")
     assert torch.equal(bd.linear_multitenant(x, prob.w_base, prob.table, tok), y)    # bitwise reproducible
+    # both GEMM kernels by name: 4 = 128 x 128 tiles, 5 = 128 x 256 tiles (in % 64 == 0 only)
+    y4 = bd.linear_multitenant(x, prob.w_base, prob.table, tok, variant=4)
+    check_close(y4, y32, f"prefill case {case}, 128 x 128 tiles")
+    if inn % 64 == 0:
+        y5 = bd.linear_multitenant(x, prob.w_base, prob.table, tok, variant=5)
+        check_close(y5, y32, f"prefill case {case}, 128 x 256 tiles")
+        assert torch.equal(bd.linear_multitenant(x, prob.w_base, prob.table, tok, variant=5), y5)
+    else:
+        with pytest.raises(bd.BitDeltaError) as e:
+            bd.linear_multitenant(x, prob.w_base, prob.table, tok, variant=5)
+        assert e.value.status == 7
 
 
 @pytest.mark.parametrize("variant", VARIANTS)
