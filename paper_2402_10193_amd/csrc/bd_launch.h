@@ -42,7 +42,7 @@ hipError_t launch_linear_prefill(const uint16_t* x, const uint16_t* w, const uin
 bool prefill_big_fits(int64_t T, int64_t out, int64_t in);
 hipError_t launch_linear_prefill_big(const uint16_t* x, const uint16_t* w, const uint32_t* const* packed_by_tenant,
                                      const float* alpha_by_tenant, const int32_t* row_token, const int32_t* tile_tenant,
-                                     int n_mtiles, uint16_t* y, int64_t T, int64_t out, int64_t in, hipStream_t st);
+                                     int n_mtiles, uint16_t* y, int64_t T, int64_t out, int64_t in, int waves, hipStream_t st);
 
 // 8-bit round-to-nearest base: q [out, in] int8 and one binary32 scale per row; the compressor against scale * q
 hipError_t launch_quantize_rtn8(const uint16_t* w, int64_t out, int64_t in, int8_t* q, float* scale, hipStream_t st);

@@ -9,11 +9,13 @@
 //   x tile   128 tokens x 64 k  fp16  -> LDS, rows of 8 chunks in the order chunk ^ ((row / 2) % 8)
 //   W tile   256 rows   x 64 k  fp16  -> LDS, same order
 //   signs    256 rows   x 2 words     -> LDS as they are; a lane's byte of 8 signs becomes the
-//            operand through two reads of a nibble table (16 entries x 32 copies x 8 B)
+//            operand (8 fp16 of +-1.0) by one read of a byte table (256 entries x 8 copies x 16 B,
+//            lane l reading copy l % 8)
 // LDS is double-buffered (one barrier per step of 64 k); the global loads of step s + 3 are issued
 // into the registers that have just been written out for step s + 1, so two steps of loads are in
 // flight while a step is multiplied.  Inside a step the operands of the next 16-wide k slice (16 MFMAs)
-// are read while the current slice is multiplied.
+// are read while the current slice is multiplied; the step's barrier sits before its last slice, whose
+// operands are in registers by then, so that the first reads of the next step overlap those MFMAs.
 // Used when in % 64 == 0; other shapes take the 128 x 128 kernel.
 #include "bd_device.h"
 #include "bd_launch.h"
@@ -28,9 +30,8 @@ constexpr int kBgXBytes = kBgM * kBgRowBytes;            // 16384
 constexpr int kBgWBytes = kBgN * kBgRowBytes;            // 32768
 constexpr int kBgSBytes = kBgN * 8;                      // 2048
 constexpr int kBgBufBytes = kBgXBytes + kBgWBytes + kBgSBytes;
-constexpr int kBgLutBytes = 16 * 32 * 8;
+constexpr int kBgLutBytes = 256 * 8 * 16;
 constexpr int kBgLdsBytes = 2 * kBgBufBytes + kBgLutBytes;   // 106496
-constexpr int kBgXPer = kBgM * 8 / 256, kBgWPer = kBgN * 8 / 256;   // 16-byte chunks per thread and step: 4 and 8
 constexpr int kBgPanel = 8, kBgChunk = 32, kBgXcds = 8;  // launch order: 4 x 8 tiles per XCD at a time
 
 __device__ __forceinline__ int bg_off(const int row, const int chunk) {
@@ -59,14 +60,21 @@ __device__ __forceinline__ void mfma_in_place(float16v& acc, const half8 a, cons
 
 }  // namespace
 
-__global__ __launch_bounds__(256, 1) void linear_prefill_big_kernel(
+// WM = 1: 4 wavefronts (1 x 4), each 128 tokens x 64 features, alone on its SIMD; two sets of staging registers
+// (loads two steps ahead).  WM = 2: 8 wavefronts (2 x 4), each 64 x 64, two per SIMD; one set (one step ahead).
+template <int WM>
+__global__ __launch_bounds__(256 * WM, 1) void linear_prefill_big_kernel(
     const uint16_t* __restrict__ x, const uint16_t* __restrict__ w, const uint32_t* const* __restrict__ packed_by_tenant,
     const float* __restrict__ alpha_by_tenant, const int32_t* __restrict__ row_token, const int32_t* __restrict__ tile_tenant,
     uint16_t* __restrict__ y, const int64_t out, const int64_t in, const int n_mtiles, const int n_ntiles) {
     extern __shared__ __align__(16) unsigned char lds[];   // [2 buffers: x, W, sign words][table]
     unsigned char* const lut = lds + 2 * kBgBufBytes;
 
+    constexpr int kThreads = 256 * WM, kWaveM = kBgM / WM, MI = kWaveM / 32;
+    constexpr int kBgXPer = kBgM * 8 / kThreads, kBgWPer = kBgN * 8 / kThreads;   // 16-byte chunks per thread and step
+    constexpr int kSets = WM == 1 ? 2 : 1;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 2, wn = wave & 3;
     int mt, nt;
     {   // launch order -> tile: panels of 8 N tiles, row-major inside, chunks of 32 tiles per XCD
         const int L = blockIdx.x, xcd = L % kBgXcds, slot = L / kBgXcds;
@@ -85,15 +93,16 @@ __global__ __launch_bounds__(256, 1) void linear_prefill_big_kernel(
     const int64_t words_per_row = in >> 5;
     const int n_steps = (int)(in / kBgK), last = n_steps - 1;
 
-    {   // nibble -> 4 fp16 (+1.0 where the bit is set, else -1.0); entry [nibble][copy], lane l reads copy l % 32
-        const uint32_t b = (uint32_t)tid >> 4;
-        uint2 e;
-        e.x = 0xBC00BC00u ^ ((b & 1u) << 15) ^ (((b >> 1) & 1u) << 31);
-        e.y = 0xBC00BC00u ^ (((b >> 2) & 1u) << 15) ^ (((b >> 3) & 1u) << 31);
-        *(uint2*)(lut + b * 256 + (tid & 15) * 8) = e;
-        *(uint2*)(lut + b * 256 + 128 + (tid & 15) * 8) = e;
+    if (tid < 256) {   // byte -> 8 fp16 (+1.0 where the bit is set, else -1.0), element e = bit e; entry [byte][copy]
+        const uint32_t bb = (uint32_t)tid;
+        u32x4 e;
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            e[i] = 0xBC00BC00u ^ (((bb >> (2 * i)) & 1u) << 15) ^ (((bb >> (2 * i + 1)) & 1u) << 31);
+#pragma unroll
+        for (int cp = 0; cp < 8; ++cp) *(u32x4*)(lut + bb * 128 + cp * 16) = e;
     }
-    const uint32_t lut_lane = (uint32_t)(lane & 31) * 8u;
+    const unsigned char* const lut_lane = lut + (lane & 7) * 16;
 
     // What this thread fetches per step.  Empty token rows read token 0 and output rows beyond `out` the last
     // row: their products are never stored, so nothing has to be zeroed and no load is conditional.
@@ -104,7 +113,7 @@ __global__ __launch_bounds__(256, 1) void linear_prefill_big_kernel(
     int xoff[kBgXPer], woff[kBgWPer];
 #pragma unroll
     for (int i = 0; i < kBgWPer; ++i) {
-        const int q = tid + 256 * i, row = q >> 3, c8 = q & 7;
+        const int q = tid + kThreads * i, row = q >> 3, c8 = q & 7;
         const int64_t wrow = n0 + row < out ? row : out - 1 - n0;
         wsrc[i] = (uint32_t)(wrow * in * 2) + c8 * 16;
         woff[i] = kBgXBytes + bg_off(row, c8);
@@ -114,29 +123,32 @@ __global__ __launch_bounds__(256, 1) void linear_prefill_big_kernel(
             xoff[i] = bg_off(row, c8);
         }
     }
-    const int64_t srow = n0 + tid < out ? n0 + tid : out - 1;
-    const bg_global_words ssrc = (bg_global_words)(packed_by_tenant[tenant] + srow * words_per_row);
+    // sign words: 256 threads take a row's two words each, 512 threads one word each
+    const int s_row = WM == 1 ? tid : tid >> 1, s_word = WM == 1 ? 0 : tid & 1;
+    const int64_t srow = n0 + s_row < out ? n0 + s_row : out - 1;
+    const bg_global_words ssrc = (bg_global_words)(packed_by_tenant[tenant] + srow * words_per_row) + s_word;
 
     struct Staged {
         u32x4 xg[kBgXPer], wg[kBgWPer];
         uint32_t s0, s1;
     };
     Staged set0, set1;
-    // item 0..3: x chunk, 4..11: W chunk, 12: the two sign words
+    // items: the x chunks, the W chunks, the sign word(s)
     constexpr int kItems = kBgXPer + kBgWPer + 1;
     auto fetch_item = [&](Staged& st, const int step, const int item) {
         if (item < kBgXPer) st.xg[item] = *(const u32x4*)(xbase + (int64_t)step * kBgRowBytes + xsrc[item]);
         else if (item < kBgXPer + kBgWPer) st.wg[item - kBgXPer] = *(const u32x4*)(wbase + (int64_t)step * kBgRowBytes + wsrc[item - kBgXPer]);
         else {
             st.s0 = ssrc[2 * step];
-            st.s1 = ssrc[2 * step + 1];
+            if (WM == 1) st.s1 = ssrc[2 * step + 1];
         }
     };
     auto stage_item = [&](const Staged& st, const int buf, const int item) {
         unsigned char* const b = lds + buf * kBgBufBytes;
         if (item < kBgXPer) *(u32x4*)(b + xoff[item]) = st.xg[item];
         else if (item < kBgXPer + kBgWPer) *(u32x4*)(b + woff[item - kBgXPer]) = st.wg[item - kBgXPer];
-        else *(uint2*)(b + kBgXBytes + kBgWBytes + tid * 8) = uint2{st.s0, st.s1};
+        else if (WM == 1) *(uint2*)(b + kBgXBytes + kBgWBytes + tid * 8) = uint2{st.s0, st.s1};
+        else *(uint32_t*)(b + kBgXBytes + kBgWBytes + tid * 4) = st.s0;
     };
     auto fetch = [&](Staged& st, const int step) {
 #pragma unroll
@@ -147,9 +159,9 @@ __global__ __launch_bounds__(256, 1) void linear_prefill_big_kernel(
         for (int it = 0; it < kItems; ++it) stage_item(st, buf, it);
     };
 
-    float16v accb[4][2], accd[4][2];   // [token block of 32][feature block of 32]
+    float16v accb[MI][2], accd[MI][2];   // [token block of 32][feature block of 32]
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < MI; ++i)
 #pragma unroll
         for (int j = 0; j < 2; ++j)
 #pragma unroll
@@ -162,84 +174,90 @@ __global__ __launch_bounds__(256, 1) void linear_prefill_big_kernel(
     int cho[4];
 #pragma unroll
     for (int sl = 0; sl < 4; ++sl) cho[sl] = ((2 * sl + hi) ^ mask) << 4;
-    const int xrow = r32 * kBgRowBytes, wrow_off = kBgXBytes + (wave * 64 + r32) * kBgRowBytes;
-    const int srow_off = kBgXBytes + kBgWBytes + (wave * 64 + r32) * 8;
-    auto expand = [&](const uint32_t byte) {
-        const uint2 lo = *(const uint2*)(lut + (byte & 15u) * 256u + lut_lane);
-        const uint2 hh = *(const uint2*)(lut + (byte >> 4) * 256u + lut_lane);
-        return __builtin_bit_cast(half8, u32x4{lo.x, lo.y, hh.x, hh.y});
+    const int xrow = (wm * kWaveM + r32) * kBgRowBytes, wrow_off = kBgXBytes + (wn * 64 + r32) * kBgRowBytes;
+    const int srow_off = kBgXBytes + kBgWBytes + (wn * 64 + r32) * 8;
+    half8 a[2][MI], bw[2][2], bs[2][2];   // operands of two k slices: one being multiplied, one being read
+    uint2 sw[2];                         // this lane's row of the 2 feature blocks: the step's 8 sign bytes each
+    auto read_signs = [&](const int buf) {
+#pragma unroll
+        for (int j = 0; j < 2; ++j) sw[j] = *(const uint2*)(lds + buf * kBgBufBytes + srow_off + j * 32 * 8);
+    };
+    auto read_slice = [&](const int buf, const int sl, const int set) {
+        const unsigned char* const b = lds + buf * kBgBufBytes;
+#pragma unroll
+        for (int i = 0; i < MI; ++i) a[set][i] = *(const half8*)(b + xrow + i * 32 * kBgRowBytes + cho[sl]);
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            bw[set][j] = *(const half8*)(b + wrow_off + j * 32 * kBgRowBytes + cho[sl]);
+            const uint32_t word = sl < 2 ? sw[j].x : sw[j].y;                           // byte 2 sl + hi of the row's 8
+            const uint32_t byte = (word >> (16 * (sl & 1) + 8 * hi)) & 0xFFu;
+            bs[set][j] = *(const half8*)(lut_lane + byte * 128u);
+        }
     };
 
     // While step `step` is multiplied, the tiles of step + 1 (in `next`) go into the other buffer and `next` is
-    // refilled with step + 3 -- one LDS write or one global load behind every other MFMA, so that the four
-    // wavefronts do not queue up at the LDS and at the address unit while their matrix pipes idle.
+    // refilled with step + 1 + kSets -- one LDS write or one global load behind every other MFMA, so that the
+    // wavefronts do not queue up at the LDS and at the address unit while their matrix pipes idle.  On entry the
+    // operands of slice 0 are in operand set 0 (read behind the previous step's barrier).
+    constexpr int kLag = WM == 1 ? 6 : 3;   // pairs of MFMAs between an item's LDS write and its next load
+    static_assert(kItems - 1 + kLag < 3 * MI * 2, "all items are staged and fetched before the barrier slice");
     auto do_step = [&](const int step, const int buf, Staged& next) {
-        const int step3 = step + 3 < last ? step + 3 : last;
-        const unsigned char* const b = lds + buf * kBgBufBytes;
-        uint2 sw[2];                                            // this lane's row of the 2 feature blocks: 8 sign bytes each
-#pragma unroll
-        for (int j = 0; j < 2; ++j) sw[j] = *(const uint2*)(b + srow_off + j * 32 * 8);
-        auto sign_byte = [&](const int j, const int sl) {       // byte 2 sl + hi of the row's 8
-            const uint32_t word = sl < 2 ? sw[j].x : sw[j].y;
-            return (word >> (16 * (sl & 1) + 8 * hi)) & 0xFFu;
-        };
-        half8 a[2][4], bw[2][2], bs[2][2];
-        auto read_slice = [&](const int sl, const int set) {
-#pragma unroll
-            for (int i = 0; i < 4; ++i) a[set][i] = *(const half8*)(b + xrow + i * 32 * kBgRowBytes + cho[sl]);
-#pragma unroll
-            for (int j = 0; j < 2; ++j) {
-                bw[set][j] = *(const half8*)(b + wrow_off + j * 32 * kBgRowBytes + cho[sl]);
-                bs[set][j] = expand(sign_byte(j, sl));
-            }
-        };
-        read_slice(0, 0);
+        const int step3 = step + 1 + kSets < last ? step + 1 + kSets : last;
 #pragma unroll
         for (int sl = 0; sl < 4; ++sl) {                        // k slice: 16 MFMAs
             const int cur = sl & 1;
-            if (sl + 1 < 4) read_slice(sl + 1, cur ^ 1);
+            if (sl < 3) {
+                read_slice(buf, sl + 1, cur ^ 1);
+            } else {
+                // every read of this buffer has been issued (its last slice sits in operand set 1) and every item of
+                // step + 1 has been written: the other buffer is complete once all wavefronts are here
+                bg_barrier();
+                read_signs(buf ^ 1);
+                read_slice(buf ^ 1, 0, 0);
+            }
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int i = 0; i < 4; ++i)
+            for (int i = 0; i < MI; ++i)
 #pragma unroll
                 for (int j = 0; j < 2; ++j) {
                     mfma_in_place(accb[i][j], a[cur][i], bw[cur][j]);
                     mfma_in_place(accd[i][j], a[cur][i], bs[cur][j]);
-                    // pair p of the step's 32: item p leaves for LDS after pair p, and is fetched again after pair p + 6
-                    const int p = sl * 8 + i * 2 + j;
+                    // pair p of the step: item p leaves for LDS after pair p, and is fetched again after pair p + kLag
+                    const int p = sl * MI * 2 + i * 2 + j;
                     if (p < kItems) stage_item(next, buf ^ 1, p);
-                    if (p >= 6 && p - 6 < kItems) fetch_item(next, step3, p - 6);
+                    if (p >= kLag && p - kLag < kItems) fetch_item(next, step3, p - kLag);
                     __builtin_amdgcn_sched_barrier(0);
                 }
             __builtin_amdgcn_sched_barrier(0);
         }
-        bg_barrier();   // step + 1 is complete in the other buffer, and this one may be overwritten
     };
 
     fetch(set0, 0);
-    fetch(set1, 1 < last ? 1 : last);
+    if (kSets == 2) fetch(set1, 1 < last ? 1 : last);
     stage(set0, 0);
-    fetch(set0, 2 < last ? 2 : last);
+    fetch(set0, kSets < last ? kSets : last);
     bg_barrier();       // the table and the tiles of step 0 are complete
+    read_signs(0);
+    read_slice(0, 0, 0);
     int step = 0;
     for (; step + 1 < n_steps; step += 2) {
-        do_step(step, 0, set1);
+        do_step(step, 0, kSets == 2 ? set1 : set0);
         do_step(step + 1, 1, set0);
     }
-    if (step < n_steps) do_step(step, 0, set1);
+    if (step < n_steps) do_step(step, 0, kSets == 2 ? set1 : set0);
 
     asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");   // the last MFMAs have left the pipe before their results are read
     // 32 x 32 result tile (i, j), element e of a lane: token row 32 i + 8 (e / 4) + 4 (l / 32) + e % 4, feature
-    // n0 + 64 wave + 32 j + l % 32
+    // n0 + 64 wn + 32 j + l % 32
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < MI; ++i) {
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
-            const int tok = row_token[mt * kBgM + 32 * i + 8 * (e >> 2) + 4 * hi + (e & 3)];
+            const int tok = row_token[mt * kBgM + wm * kWaveM + 32 * i + 8 * (e >> 2) + 4 * hi + (e & 3)];
             if (tok < 0) continue;
 #pragma unroll
             for (int j = 0; j < 2; ++j) {
-                const int64_t n = n0 + wave * 64 + 32 * j + r32;
+                const int64_t n = n0 + wn * 64 + 32 * j + r32;
                 if (n < out) y[(int64_t)tok * out + n] = f2h_rne(accb[i][j][e] + alpha * accd[i][j][e]);
             }
         }
@@ -252,23 +270,33 @@ bool prefill_big_fits(int64_t T, int64_t out, int64_t in) {
            (uint64_t)kBgN * (uint64_t)in * 2 < ((uint64_t)1 << 32);
 }
 
+template <int WM>
+static hipError_t launch_big_t(const uint16_t* x, const uint16_t* w, const uint32_t* const* packed_by_tenant,
+                               const float* alpha_by_tenant, const int32_t* row_token, const int32_t* tile_tenant,
+                               int n_mtiles, int n_ntiles, uint16_t* y, int64_t out, int64_t in, hipStream_t st) {
+    auto kernel = linear_prefill_big_kernel<WM>;
+    static PerDeviceOnce lds_limit;
+    const hipError_t ea = lds_limit.run(
+        [&] { return hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kBgLdsBytes); });
+    if (ea != hipSuccess) return ea;
+    const int64_t tiles = (int64_t)n_mtiles * n_ntiles, round = (int64_t)kBgChunk * kBgXcds;
+    const unsigned grid = (unsigned)((tiles + round - 1) / round * round);   // surplus workgroups return at once
+    hipLaunchKernelGGL(kernel, dim3(grid), dim3(256 * WM), kBgLdsBytes, st, x, w, packed_by_tenant, alpha_by_tenant, row_token,
+                       tile_tenant, y, out, in, n_mtiles, n_ntiles);
+    return hipGetLastError();
+}
+
+// waves: 4 (one wavefront per SIMD) or 8 (two)
 hipError_t launch_linear_prefill_big(const uint16_t* x, const uint16_t* w, const uint32_t* const* packed_by_tenant,
                                      const float* alpha_by_tenant, const int32_t* row_token, const int32_t* tile_tenant,
-                                     int n_mtiles, uint16_t* y, int64_t T, int64_t out, int64_t in, hipStream_t st) {
-    if (!prefill_big_fits(T, out, in)) return hipErrorInvalidValue;
+                                     int n_mtiles, uint16_t* y, int64_t T, int64_t out, int64_t in, int waves, hipStream_t st) {
+    if (!prefill_big_fits(T, out, in) || (waves != 4 && waves != 8)) return hipErrorInvalidValue;
     const int n_ntiles = (int)((out + kBgN - 1) / kBgN);
     const int64_t tiles = (int64_t)n_mtiles * n_ntiles;
     if (tiles < 1 || tiles > (int64_t)1 << 30) return hipErrorInvalidValue;
-    static PerDeviceOnce lds_limit;
-    const hipError_t ea = lds_limit.run([&] {
-        return hipFuncSetAttribute((const void*)linear_prefill_big_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kBgLdsBytes);
-    });
-    if (ea != hipSuccess) return ea;
-    const int64_t round = (int64_t)kBgChunk * kBgXcds;
-    const unsigned grid = (unsigned)((tiles + round - 1) / round * round);
-    hipLaunchKernelGGL(linear_prefill_big_kernel, dim3(grid), dim3(256), kBgLdsBytes, st, x, w, packed_by_tenant, alpha_by_tenant,
-                       row_token, tile_tenant, y, out, in, n_mtiles, n_ntiles);
-    return hipGetLastError();
+    if (waves == 4)
+        return launch_big_t<1>(x, w, packed_by_tenant, alpha_by_tenant, row_token, tile_tenant, n_mtiles, n_ntiles, y, out, in, st);
+    return launch_big_t<2>(x, w, packed_by_tenant, alpha_by_tenant, row_token, tile_tenant, n_mtiles, n_ntiles, y, out, in, st);
 }
 
 }  // namespace bd
