@@ -63,6 +63,7 @@ struct TiledArgs {
     int32_t planes;                                           // k: 1 = plain 1-bit deltas
 };
 
+hipError_t launch_fill_zero_u16(uint16_t* p, int64_t n, hipStream_t st);
 hipError_t launch_tile_base(const uint16_t* w, int64_t out, int64_t in, uint16_t* wt, hipStream_t st);
 hipError_t launch_tile_signs(const uint32_t* packed, int64_t out, int64_t in, uint32_t* st_out, hipStream_t st);
 // n_jobs real job slots per column tile (1..16, the larger of the two); unused slots must repeat slot 0's pointers.

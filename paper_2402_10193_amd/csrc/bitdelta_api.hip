@@ -352,6 +352,14 @@ bd_status tiled_linear_impl(int32_t n_mats, const uint16_t* x_f16, const uint16_
     if (row_blocks > 0x7fffffff) return BD_ERR_SHAPE;
     if ((uint64_t)T * (uint64_t)in * 2 >= ((uint64_t)1 << 32)) return BD_ERR_SHAPE;   // 32-bit byte offsets into x
     if (T == 0 || row_blocks == 0) return BD_OK;
+    if (in == 0) {   // empty reduction: y = 0, nothing else is read
+        if (!y_f16) return BD_ERR_NULL;
+        for (int m = 0; m < n_mats; ++m)
+            if (out[m] > 0 && !y_f16[m]) return BD_ERR_NULL;
+        for (int m = 0; m < n_mats; ++m)
+            if (out[m] > 0 && bd::launch_fill_zero_u16(y_f16[m], T * out[m], (hipStream_t)stream) != hipSuccess) return BD_ERR_DEVICE;
+        return BD_OK;
+    }
     if (!x_f16 || !w_tiled || !tiled_by_mat_tenant || !alpha_by_mat || !tenant_of_token || !y_f16) return BD_ERR_NULL;
     if (misaligned(x_f16, 16)) return BD_ERR_ALIGN;
     for (int64_t t = 0; t < T; ++t)
@@ -371,8 +379,6 @@ bd_status tiled_linear_impl(int32_t n_mats, const uint16_t* x_f16, const uint16_
                 if (misaligned(p, 16)) return BD_ERR_ALIGN;
             }
     }
-    // in == 0 (empty reduction) needs no special case: the kernel runs zero steps and writes y = 0
-
     // A token takes k columns (one per plane) of a 16-column tile; a launch covers two tiles.
     const int per_tile = bd::kTiledMaxTokens / k;
     const int per_launch = per_tile * bd::kTiledMaxCt;

@@ -496,7 +496,7 @@ static hipError_t launch_tiled_t(const TiledArgs& args, int n_jobs, hipStream_t 
         args.n_ct > kTiledMaxCt)
         return hipErrorInvalidValue;
     const int rb_total = args.rb_end[args.n_mats - 1];
-    if (rb_total < 1 || args.KT < 0) return hipErrorInvalidValue;
+    if (rb_total < 1 || args.KT < 1) return hipErrorInvalidValue;
     // compute units of the current device, asked once per device (0 = not asked yet; 64 devices at most are remembered)
     static std::atomic<int> cus_of[64];
     int dev = 0;
@@ -508,7 +508,7 @@ static hipError_t launch_tiled_t(const TiledArgs& args, int n_jobs, hipStream_t 
         cus_of[dev & 63].store(cus, std::memory_order_relaxed);
     }
     // persistent grid: one workgroup per compute unit, never more workgroups than row blocks;
-    // 8 wavefronts, never more than k tiles (KT == 0: one idle-looping wavefront writes y = 0)
+    // 8 wavefronts, never more than k tiles (an empty reduction, KT == 0, never gets here: the host writes y = 0)
     const unsigned grid = (unsigned)(rb_total < cus ? rb_total : cus);
     int n_waves = kMaxWavesTiled;
     while (n_waves > 1 && n_waves > args.KT) n_waves >>= 1;

@@ -77,6 +77,10 @@ __global__ __launch_bounds__(256) void tile_scales_kernel(const float* __restric
         dst[i] = i < out ? scale[i] : 0.0f;
 }
 
+__global__ __launch_bounds__(256) void fill_zero_u16_kernel(uint16_t* __restrict__ p, const int64_t n) {
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) p[i] = 0;
+}
+
 static unsigned grid_for(int64_t n, int block) {
     int64_t g = (n + block - 1) / block;
     return (unsigned)(g < 1 ? 1 : (g > 65536 ? 65536 : g));
@@ -92,6 +96,12 @@ hipError_t launch_tile_signs(const uint32_t* packed, int64_t out, int64_t in, ui
     const int64_t KT = tiled_k_tiles(in), n_slots = tiled_row_blocks(out) * KT * 64;
     hipLaunchKernelGGL(tile_signs_kernel, dim3(grid_for(n_slots, 256)), dim3(256), 0, st, packed, (u32x2*)st_out, out, in, KT,
                        n_slots);
+    return hipGetLastError();
+}
+
+// p[0 .. n) = 0 (a kernel rather than a memset node: safe to capture into a HIP graph)
+hipError_t launch_fill_zero_u16(uint16_t* p, int64_t n, hipStream_t st) {
+    if (n > 0) hipLaunchKernelGGL(fill_zero_u16_kernel, dim3(grid_for(n, 256)), dim3(256), 0, st, p, n);
     return hipGetLastError();
 }
 

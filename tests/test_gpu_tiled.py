@@ -146,6 +146,12 @@ def test_tiled_matches_row_major_entry_point_and_errors(ref):
         bd.linear_multitenant_tiled(x[:1].contiguous(), prob.w_tiled, 48, prob.ttable, [4])
     assert e.value.status == 4
     assert bd.linear_multitenant_tiled(x[:0], prob.w_tiled, 48, prob.ttable, []).shape == (0, 48)
+    # an empty reduction (in = 0) is a sum of nothing: y = 0, and nothing else is read
+    y0 = torch.full((3, 48), 7.0, dtype=torch.float16, device=DEV)
+    x0 = torch.empty((3, 0), dtype=torch.float16, device=DEV)
+    empty = bd.TiledTenantTable([torch.empty(0, dtype=torch.int32, device=DEV)] * 4, prob.table.alpha)
+    bd.linear_multitenant_tiled(x0, torch.empty(0, dtype=torch.float16, device=DEV), 48, empty, [1, 0, 3], y=y0)
+    assert float(y0.abs().max().item()) == 0.0
 
 
 def test_tiled_group_equals_separate_calls(ref):
