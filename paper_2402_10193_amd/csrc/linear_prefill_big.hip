@@ -13,9 +13,12 @@
 //            lane l reading copy l % 8)
 // LDS is double-buffered (one barrier per step of 64 k); the global loads of step s + 3 are issued
 // into the registers that have just been written out for step s + 1, so two steps of loads are in
-// flight while a step is multiplied.  Inside a step the operands of the next 16-wide k slice (16 MFMAs)
-// are read while the current slice is multiplied; the step's barrier sits before its last slice, whose
-// operands are in registers by then, so that the first reads of the next step overlap those MFMAs.
+// flight while a step is multiplied.  A wavefront alone on its SIMD issues in order, so everything
+// else is dealt out between the MFMAs in portions that fit into the 32 cycles of one: behind the first
+// MFMA of a pair one operand read of the next 16-wide k slice, behind the second one LDS write and one
+// global load.  The step's barrier sits before its last slice, whose operands are in registers by
+// then, so that the first reads of the next step overlap those MFMAs.  The finished tile leaves
+// through LDS as fp16 rows, in 16-byte stores.
 // Used when in % 64 == 0; other shapes take the 128 x 128 kernel.
 #include "bd_device.h"
 #include "bd_launch.h"
@@ -31,7 +34,12 @@ constexpr int kBgWBytes = kBgN * kBgRowBytes;            // 32768
 constexpr int kBgSBytes = kBgN * 8;                      // 2048
 constexpr int kBgBufBytes = kBgXBytes + kBgWBytes + kBgSBytes;
 constexpr int kBgLutBytes = 256 * 8 * 16;
-constexpr int kBgLdsBytes = 2 * kBgBufBytes + kBgLutBytes;   // 106496
+constexpr int kBgTokBytes = kBgM * 4;                    // the tile's token of every row
+constexpr int kBgLdsBytes = 2 * kBgBufBytes + kBgLutBytes + kBgTokBytes;   // 135680
+// Epilogue: a wavefront's rows of y as fp16, 64 features + 16 B of padding each (rows 4 apart, which one LDS
+// instruction writes together, then fall into different banks), in the tile buffers, which are free by then.
+constexpr int kBgOutRowBytes = 64 * 2 + 16;
+static_assert(kBgM * kBgOutRowBytes * 4 <= 2 * kBgBufBytes, "the result rows of all wavefronts fit the tile buffers");
 constexpr int kBgPanel = 8, kBgChunk = 32, kBgXcds = 8;  // launch order: 4 x 8 tiles per XCD at a time
 
 __device__ __forceinline__ int bg_off(const int row, const int chunk) {
@@ -46,6 +54,20 @@ __device__ __forceinline__ void bg_barrier() {
 }
 
 typedef const uint32_t __attribute__((address_space(1)))* bg_global_words;
+
+// LDS through pointers in the LDS address space, made from byte offsets.  The kernel has no static LDS, so its
+// dynamic LDS starts at address 0 (the host checks that): no instruction is spent on adding the (relocated, zero)
+// base of the array, and a constant added to such a pointer travels in the offset field of the LDS instruction.
+typedef unsigned char __attribute__((address_space(3)))* lds_bytes;
+__device__ __forceinline__ lds_bytes lds_at(const uint32_t off) { return (lds_bytes)(uintptr_t)off; }
+template <typename T>
+__device__ __forceinline__ T lds_get(const lds_bytes p) {
+    return *(const T __attribute__((address_space(3)))*)p;
+}
+template <typename T>
+__device__ __forceinline__ void lds_put(const lds_bytes p, const T v) {
+    *(T __attribute__((address_space(3)))*)p = v;
+}
 
 // acc += A . B with the accumulator held in place in the accumulation registers.  (Left to itself the
 // compiler gives every MFMA a fresh destination and copies it back, four moves per MFMA, once all
@@ -102,7 +124,7 @@ __global__ __launch_bounds__(256 * WM, 1) void linear_prefill_big_kernel(
 #pragma unroll
         for (int cp = 0; cp < 8; ++cp) *(u32x4*)(lut + bb * 128 + cp * 16) = e;
     }
-    const unsigned char* const lut_lane = lut + (lane & 7) * 16;
+    const lds_bytes lut_lane = lds_at(2 * kBgBufBytes + (lane & 7) * 16);
 
     // What this thread fetches per step.  Empty token rows read token 0 and output rows beyond `out` the last
     // row: their products are never stored, so nothing has to be zeroed and no load is conditional.
@@ -110,17 +132,19 @@ __global__ __launch_bounds__(256 * WM, 1) void linear_prefill_big_kernel(
     const unsigned char* const xbase = (const unsigned char*)x;
     const unsigned char* const wbase = (const unsigned char*)(w + n0 * in);
     uint32_t xsrc[kBgXPer], wsrc[kBgWPer];
-    int xoff[kBgXPer], woff[kBgWPer];
+    lds_bytes xdst[kBgXPer], wdst[kBgWPer];   // in buffer 0
 #pragma unroll
     for (int i = 0; i < kBgWPer; ++i) {
         const int q = tid + kThreads * i, row = q >> 3, c8 = q & 7;
         const int64_t wrow = n0 + row < out ? row : out - 1 - n0;
         wsrc[i] = (uint32_t)(wrow * in * 2) + c8 * 16;
-        woff[i] = kBgXBytes + bg_off(row, c8);
+        wdst[i] = lds_at(kBgXBytes + bg_off(row, c8));
+        asm volatile("" : "+v"(wdst[i]));   // a register of its own: derived from xdst[i], it would cost an addition per use
         if (i < kBgXPer) {
             const int tok = row_token[mt * kBgM + row];
             xsrc[i] = (uint32_t)((int64_t)(tok >= 0 ? tok : 0) * in * 2) + c8 * 16;
-            xoff[i] = bg_off(row, c8);
+            if (c8 == 0) lds_put<int>(lds_at(2 * kBgBufBytes + kBgLutBytes + row * 4), tok);   // for the epilogue
+            xdst[i] = lds_at(bg_off(row, c8));
         }
     }
     // sign words: 256 threads take a row's two words each, 512 threads one word each
@@ -128,6 +152,7 @@ __global__ __launch_bounds__(256 * WM, 1) void linear_prefill_big_kernel(
     const int64_t srow = n0 + s_row < out ? n0 + s_row : out - 1;
     const bg_global_words ssrc = (bg_global_words)(packed_by_tenant[tenant] + srow * words_per_row) + s_word;
 
+    const lds_bytes sdst = lds_at(kBgXBytes + kBgWBytes + tid * (WM == 1 ? 8 : 4));
     struct Staged {
         u32x4 xg[kBgXPer], wg[kBgWPer];
         uint32_t s0, s1;
@@ -136,19 +161,25 @@ __global__ __launch_bounds__(256 * WM, 1) void linear_prefill_big_kernel(
     // items: the x chunks, the W chunks, the sign word(s)
     constexpr int kItems = kBgXPer + kBgWPer + 1;
     auto fetch_item = [&](Staged& st, const int step, const int item) {
-        if (item < kBgXPer) st.xg[item] = *(const u32x4*)(xbase + (int64_t)step * kBgRowBytes + xsrc[item]);
-        else if (item < kBgXPer + kBgWPer) st.wg[item - kBgXPer] = *(const u32x4*)(wbase + (int64_t)step * kBgRowBytes + wsrc[item - kBgXPer]);
-        else {
+        // uniform address of the step plus the lane's 32-bit offset (passed through an empty asm statement: otherwise
+        // "base + lane offset" is hoisted out of the loop as a 64-bit register pair per load, and added to per step)
+        if (item < kBgXPer) {
+            asm volatile("" : "+v"(xsrc[item]));
+            st.xg[item] = *(const u32x4*)(xbase + (int64_t)step * kBgRowBytes + xsrc[item]);
+        } else if (item < kBgXPer + kBgWPer) {
+            asm volatile("" : "+v"(wsrc[item - kBgXPer]));
+            st.wg[item - kBgXPer] = *(const u32x4*)(wbase + (int64_t)step * kBgRowBytes + wsrc[item - kBgXPer]);
+        } else {
             st.s0 = ssrc[2 * step];
             if (WM == 1) st.s1 = ssrc[2 * step + 1];
         }
     };
     auto stage_item = [&](const Staged& st, const int buf, const int item) {
-        unsigned char* const b = lds + buf * kBgBufBytes;
-        if (item < kBgXPer) *(u32x4*)(b + xoff[item]) = st.xg[item];
-        else if (item < kBgXPer + kBgWPer) *(u32x4*)(b + woff[item - kBgXPer]) = st.wg[item - kBgXPer];
-        else if (WM == 1) *(uint2*)(b + kBgXBytes + kBgWBytes + tid * 8) = uint2{st.s0, st.s1};
-        else *(uint32_t*)(b + kBgXBytes + kBgWBytes + tid * 4) = st.s0;
+        const int b = buf * kBgBufBytes;
+        if (item < kBgXPer) lds_put<u32x4>(xdst[item] + b, st.xg[item]);
+        else if (item < kBgXPer + kBgWPer) lds_put<u32x4>(wdst[item - kBgXPer] + b, st.wg[item - kBgXPer]);
+        else if (WM == 1) lds_put<u32x2>(sdst + b, u32x2{st.s0, st.s1});
+        else lds_put<uint32_t>(sdst + b, st.s0);
     };
     auto fetch = [&](Staged& st, const int step) {
 #pragma unroll
@@ -171,28 +202,42 @@ __global__ __launch_bounds__(256 * WM, 1) void linear_prefill_big_kernel(
     // mask (row / 2) % 8 depends on the lane only.
     const int r32 = lane & 31, hi = lane >> 5;
     const int mask = (r32 >> 1) & 7;
-    int cho[4];
+    lds_bytes xrd[4], wrd[4];   // this lane's x and W operand of k slice sl in buffer 0
 #pragma unroll
-    for (int sl = 0; sl < 4; ++sl) cho[sl] = ((2 * sl + hi) ^ mask) << 4;
-    const int xrow = (wm * kWaveM + r32) * kBgRowBytes, wrow_off = kBgXBytes + (wn * 64 + r32) * kBgRowBytes;
-    const int srow_off = kBgXBytes + kBgWBytes + (wn * 64 + r32) * 8;
+    for (int sl = 0; sl < 4; ++sl) {
+        const int cho = ((2 * sl + hi) ^ mask) << 4;
+        xrd[sl] = lds_at((wm * kWaveM + r32) * kBgRowBytes + cho);
+        wrd[sl] = lds_at(kBgXBytes + (wn * 64 + r32) * kBgRowBytes + cho);
+        asm volatile("" : "+v"(xrd[sl]), "+v"(wrd[sl]));
+    }
+    const lds_bytes srd = lds_at(kBgXBytes + kBgWBytes + (wn * 64 + r32) * 8);
     half8 a[2][MI], bw[2][2], bs[2][2];   // operands of two k slices: one being multiplied, one being read
-    uint2 sw[2];                         // this lane's row of the 2 feature blocks: the step's 8 sign bytes each
+    u32x2 sw[2];                         // this lane's row of the 2 feature blocks: the step's 8 sign bytes each
     auto read_signs = [&](const int buf) {
 #pragma unroll
-        for (int j = 0; j < 2; ++j) sw[j] = *(const uint2*)(lds + buf * kBgBufBytes + srow_off + j * 32 * 8);
+        for (int j = 0; j < 2; ++j) sw[j] = lds_get<u32x2>(srd + buf * kBgBufBytes + j * 32 * 8);
+    };
+    // The MI + 4 operand reads of a k slice, in the order the MFMAs of the slice need them.
+    constexpr int kReads = MI + 4;
+    const uint32_t sh[2] = {8u * hi, 16u + 8u * hi};   // bit position of the lane's sign byte in the word: slice 2 w + (0 | 1)
+    auto read_item = [&](const int buf, const int sl, const int set, const int r) {
+        const int b = buf * kBgBufBytes;
+        // r: 0 W(0), 1 signs(0), 2 x(0), 3 W(1), 4 signs(1), 5.. x(1..)
+        if (r == 0 || r == 3) {
+            const int j = r / 3;
+            bw[set][j] = lds_get<half8>(wrd[sl] + (b + j * 32 * kBgRowBytes));
+        } else if (r == 1 || r == 4) {
+            const int j = r / 3;
+            const uint32_t byte = __builtin_amdgcn_ubfe(sl < 2 ? sw[j][0] : sw[j][1], sh[sl & 1], 8u);   // byte 2 sl + hi of the row's 8
+            bs[set][j] = lds_get<half8>(lut_lane + (byte << 7));
+        } else {
+            const int i = r == 2 ? 0 : r - 4;
+            a[set][i] = lds_get<half8>(xrd[sl] + (b + i * 32 * kBgRowBytes));
+        }
     };
     auto read_slice = [&](const int buf, const int sl, const int set) {
-        const unsigned char* const b = lds + buf * kBgBufBytes;
 #pragma unroll
-        for (int i = 0; i < MI; ++i) a[set][i] = *(const half8*)(b + xrow + i * 32 * kBgRowBytes + cho[sl]);
-#pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            bw[set][j] = *(const half8*)(b + wrow_off + j * 32 * kBgRowBytes + cho[sl]);
-            const uint32_t word = sl < 2 ? sw[j].x : sw[j].y;                           // byte 2 sl + hi of the row's 8
-            const uint32_t byte = (word >> (16 * (sl & 1) + 8 * hi)) & 0xFFu;
-            bs[set][j] = *(const half8*)(lut_lane + byte * 128u);
-        }
+        for (int r = 0; r < kReads; ++r) read_item(buf, sl, set, r);
     };
 
     // While step `step` is multiplied, the tiles of step + 1 (in `next`) go into the other buffer and `next` is
@@ -206,24 +251,31 @@ __global__ __launch_bounds__(256 * WM, 1) void linear_prefill_big_kernel(
 #pragma unroll
         for (int sl = 0; sl < 4; ++sl) {                        // k slice: 16 MFMAs
             const int cur = sl & 1;
-            if (sl < 3) {
-                read_slice(buf, sl + 1, cur ^ 1);
-            } else {
+            if (sl == 3) {
                 // every read of this buffer has been issued (its last slice sits in operand set 1) and every item of
                 // step + 1 has been written: the other buffer is complete once all wavefronts are here
                 bg_barrier();
                 read_signs(buf ^ 1);
-                read_slice(buf ^ 1, 0, 0);
             }
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int i = 0; i < MI; ++i)
 #pragma unroll
                 for (int j = 0; j < 2; ++j) {
+                    // A wavefront alone on its SIMD issues in order, an instruction every 8 cycles or so: what follows an
+                    // MFMA must fit into its 32 cycles, or the next MFMA starts late.  Behind the first MFMA of pair q of
+                    // the slice: its share of the next slice's operand reads; behind the second: one LDS write, one load.
                     mfma_in_place(accb[i][j], a[cur][i], bw[cur][j]);
+                    const int q = i * 2 + j;
+#pragma unroll
+                    for (int r = q * kReads / (MI * 2); r < (q + 1) * kReads / (MI * 2); ++r) {
+                        if (sl < 3) read_item(buf, sl + 1, cur ^ 1, r);
+                        else read_item(buf ^ 1, 0, 0, r);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
                     mfma_in_place(accd[i][j], a[cur][i], bs[cur][j]);
                     // pair p of the step: item p leaves for LDS after pair p, and is fetched again after pair p + kLag
-                    const int p = sl * MI * 2 + i * 2 + j;
+                    const int p = sl * MI * 2 + q;
                     if (p < kItems) stage_item(next, buf ^ 1, p);
                     if (p >= kLag && p - kLag < kItems) fetch_item(next, step3, p - kLag);
                     __builtin_amdgcn_sched_barrier(0);
@@ -247,19 +299,39 @@ __global__ __launch_bounds__(256 * WM, 1) void linear_prefill_big_kernel(
     if (step < n_steps) do_step(step, 0, kSets == 2 ? set1 : set0);
 
     asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");   // the last MFMAs have left the pipe before their results are read
+    // Every wavefront has passed the last step's barrier, so nobody reads the tiles or the table any more (the
+    // operand reads issued behind that barrier fetch a step that does not exist; their results are never used).
     // 32 x 32 result tile (i, j), element e of a lane: token row 32 i + 8 (e / 4) + 4 (l / 32) + e % 4, feature
-    // n0 + 64 wn + 32 j + l % 32
+    // 32 j + l % 32 of the wavefront's 64.  The rows go to LDS as fp16 and leave as whole 16-byte pieces: written
+    // from the accumulator layout y would take 256 two-byte stores per lane.
+    const lds_bytes orow = lds_at(wave * (kWaveM * kBgOutRowBytes));
 #pragma unroll
-    for (int i = 0; i < MI; ++i) {
+    for (int i = 0; i < MI; ++i)
 #pragma unroll
-        for (int e = 0; e < 16; ++e) {
-            const int tok = row_token[mt * kBgM + wm * kWaveM + 32 * i + 8 * (e >> 2) + 4 * hi + (e & 3)];
-            if (tok < 0) continue;
+        for (int j = 0; j < 2; ++j)
 #pragma unroll
-            for (int j = 0; j < 2; ++j) {
-                const int64_t n = n0 + wn * 64 + 32 * j + r32;
-                if (n < out) y[(int64_t)tok * out + n] = f2h_rne(accb[i][j][e] + alpha * accd[i][j][e]);
+            for (int e = 0; e < 16; ++e) {
+                const int row = 32 * i + 8 * (e >> 2) + 4 * hi + (e & 3);
+                lds_put<uint16_t>(orow + row * kBgOutRowBytes + (32 * j + r32) * 2, f2h_rne(accb[i][j][e] + alpha * accd[i][j][e]));
             }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    const bool whole = (out & 7) == 0;   // rows of y start on 16-byte boundaries
+#pragma unroll 4
+    for (int it = 0; it < kWaveM * 8 / 64; ++it) {
+        const int q = it * 64 + lane, row = q >> 3, piece = q & 7;
+        const int tok = lds_get<int>(lds_at(2 * kBgBufBytes + kBgLutBytes + (wm * kWaveM + row) * 4));
+        const u32x4 v = lds_get<u32x4>(orow + row * kBgOutRowBytes + piece * 16);
+        const int64_t n = n0 + wn * 64 + piece * 8;
+        if (tok < 0 || n >= out) continue;
+        uint16_t* const dst = y + (int64_t)tok * out + n;
+        if (whole) {
+            *(u32x4*)dst = v;
+        } else {
+#pragma unroll
+            for (int k = 0; k < 8; ++k)
+                if (n + k < out) dst[k] = (uint16_t)(v[k >> 1] >> (16 * (k & 1)));
         }
     }
 }
@@ -276,8 +348,13 @@ static hipError_t launch_big_t(const uint16_t* x, const uint16_t* w, const uint3
                                int n_mtiles, int n_ntiles, uint16_t* y, int64_t out, int64_t in, hipStream_t st) {
     auto kernel = linear_prefill_big_kernel<WM>;
     static PerDeviceOnce lds_limit;
-    const hipError_t ea = lds_limit.run(
-        [&] { return hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kBgLdsBytes); });
+    const hipError_t ea = lds_limit.run([&] {
+        hipFuncAttributes fa;
+        const hipError_t e = hipFuncGetAttributes(&fa, (const void*)kernel);
+        if (e != hipSuccess) return e;
+        if (fa.sharedSizeBytes != 0) return hipErrorInvalidValue;   // the kernel addresses its dynamic LDS from 0
+        return hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kBgLdsBytes);
+    });
     if (ea != hipSuccess) return ea;
     const int64_t tiles = (int64_t)n_mtiles * n_ntiles, round = (int64_t)kBgChunk * kBgXcds;
     const unsigned grid = (unsigned)((tiles + round - 1) / round * round);   // surplus workgroups return at once
