@@ -119,7 +119,8 @@ bd_status bd_linear_multitenant(const uint16_t* x_f16, const uint16_t* w_base_f1
  *              variant cannot run these sizes
  *   variant 4, 5, 6  the prefill GEMM with 128 x 128 tiles / 128 x 256 tiles and 4 wavefronts / 128 x 256
  *              tiles and 8 wavefronts (T > 32 and a workspace as for variant 0, else BD_ERR_UNSUPPORTED /
- *              BD_ERR_WORKSPACE; 5 and 6 need in % 64 == 0). */
+ *              BD_ERR_WORKSPACE; 5, 6 and 7 need in % 64 == 0)
+ *   variant 7  as 5, but every tile whole (5 runs the tiles of a last, sparsely filled round as halves) */
 bd_status bd_linear_multitenant_variant(const uint16_t* x_f16, const uint16_t* w_base_f16,
                                         const uint32_t* const* packed_by_tenant,
                                         const float* alpha_by_tenant,

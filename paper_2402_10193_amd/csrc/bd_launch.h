@@ -38,11 +38,13 @@ hipError_t launch_prefill_meta(const PrefillMetaChunk& chunk, int32_t* dst, int 
 hipError_t launch_linear_prefill(const uint16_t* x, const uint16_t* w, const uint32_t* const* packed_by_tenant,
                                  const float* alpha_by_tenant, const int32_t* row_token, const int32_t* tile_tenant,
                                  int n_mtiles, uint16_t* y, int64_t out, int64_t in, hipStream_t st);
-// the 128 x 256 tile GEMM of linear_prefill_big.hip; T = rows of x
+// the 128 x 256 tile GEMM of linear_prefill_big.hip; T = rows of x; halve_last_round (4 wavefronts only): the tiles of a
+// last round that would occupy at most half of the compute units run as two workgroups of 64 token rows each
 bool prefill_big_fits(int64_t T, int64_t out, int64_t in);
 hipError_t launch_linear_prefill_big(const uint16_t* x, const uint16_t* w, const uint32_t* const* packed_by_tenant,
                                      const float* alpha_by_tenant, const int32_t* row_token, const int32_t* tile_tenant,
-                                     int n_mtiles, uint16_t* y, int64_t T, int64_t out, int64_t in, int waves, hipStream_t st);
+                                     int n_mtiles, uint16_t* y, int64_t T, int64_t out, int64_t in, int waves, bool halve_last_round,
+                                     hipStream_t st);
 
 // 8-bit round-to-nearest base: q [out, in] int8 and one binary32 scale per row; the compressor against scale * q
 hipError_t launch_quantize_rtn8(const uint16_t* w, int64_t out, int64_t in, int8_t* q, float* scale, hipStream_t st);
@@ -71,5 +73,22 @@ struct PerDeviceOnce {
         return e;
     }
 };
+
+// Compute units of the current device, asked once per device (64 devices at most are remembered).
+inline hipError_t device_cu_count(int* cus) {
+    static std::atomic<int> cus_of[64];
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    int c = cus_of[dev & 63].load(std::memory_order_relaxed);
+    if (c == 0) {
+        e = hipDeviceGetAttribute(&c, hipDeviceAttributeMultiprocessorCount, dev);
+        if (e != hipSuccess) return e;
+        if (c < 1) return hipErrorInvalidDevice;
+        cus_of[dev & 63].store(c, std::memory_order_relaxed);
+    }
+    *cus = c;
+    return hipSuccess;
+}
 
 }  // namespace bd

@@ -20,6 +20,7 @@ constexpr int kVariantDefaultMfma = 3;
 constexpr int kVariantPrefillSmall = 4;   // T > 32 with a workspace: the 128 x 128 tile GEMM
 constexpr int kVariantPrefillBig = 5;     // ... the 128 x 256 tile GEMM (in % 64 == 0), one wavefront per SIMD
 constexpr int kVariantPrefillBig8 = 6;    // ... the same tile with two wavefronts per SIMD
+constexpr int kVariantPrefillBigWhole = 7;   // ... as 5, but never cutting the tiles of the last round in two
 
 inline bool misaligned(const void* p, size_t a) { return ((uintptr_t)p & (a - 1)) != 0; }
 
@@ -104,7 +105,7 @@ size_t prefill_workspace_bytes(int64_t T, int32_t n_tenants) {
 // the two tables into the workspace (through kernel arguments: no host-to-device copy call) and runs the GEMM.
 hipError_t run_prefill(const uint16_t* x, const uint16_t* w, const uint32_t* const* packed_by_tenant,
                        const float* alpha_by_tenant, const int32_t* tenant_of_token, uint16_t* y, int64_t T, int64_t out,
-                       int64_t in, void* workspace, hipStream_t st, int big_waves) {
+                       int64_t in, void* workspace, hipStream_t st, int big_waves, bool halve_last_round) {
     std::vector<int32_t> order((size_t)T);
     for (int64_t i = 0; i < T; ++i) order[(size_t)i] = (int32_t)i;
     std::stable_sort(order.begin(), order.end(),
@@ -134,7 +135,7 @@ hipError_t run_prefill(const uint16_t* x, const uint16_t* w, const uint32_t* con
     }
     if (big_waves)
         return bd::launch_linear_prefill_big(x, w, packed_by_tenant, alpha_by_tenant, dst, dst + row_token.size(), n_mtiles, y,
-                                             T, out, in, big_waves, st);
+                                             T, out, in, big_waves, halve_last_round, st);
     return bd::launch_linear_prefill(x, w, packed_by_tenant, alpha_by_tenant, dst, dst + row_token.size(), n_mtiles, y, out,
                                      in, st);
 }
@@ -232,7 +233,8 @@ bd_status bd_linear_multitenant_variant(const uint16_t* x_f16, const uint16_t* w
     const bd_status st = check_linear_args(x_f16, w_base_f16, packed_by_tenant, alpha_by_tenant, tenant_of_token, y_f16,
                                            T, out, in, n_tenants);
     if (st != BD_OK) return st;
-    const bool prefill_variant = variant == kVariantPrefillSmall || variant == kVariantPrefillBig || variant == kVariantPrefillBig8;
+    const bool big_variant = variant == kVariantPrefillBig || variant == kVariantPrefillBig8 || variant == kVariantPrefillBigWhole;
+    const bool prefill_variant = variant == kVariantPrefillSmall || big_variant;
     if (variant != 0 && variant != kVariantRowWave && !bd::decode_mfma_variant_known(variant) && !prefill_variant)
         return BD_ERR_UNSUPPORTED;
     if (T == 0 || out == 0) return BD_OK;
@@ -249,14 +251,16 @@ bd_status bd_linear_multitenant_variant(const uint16_t* x_f16, const uint16_t* w
     const size_t need = prefill_workspace_bytes(T, n_tenants);
     const bool can_prefill = need > 0 && in > 0 && workspace && workspace_bytes >= need && !misaligned(workspace, 256);
     if (prefill_variant && !can_prefill) return need > 0 && in > 0 ? BD_ERR_WORKSPACE : BD_ERR_UNSUPPORTED;
-    if ((variant == kVariantPrefillBig || variant == kVariantPrefillBig8) && !bd::prefill_big_fits(T, out, in)) return BD_ERR_UNSUPPORTED;
+    if (big_variant && !bd::prefill_big_fits(T, out, in)) return BD_ERR_UNSUPPORTED;
     if ((variant == 0 || prefill_variant) && can_prefill) {
         // the large tile (one workgroup per CU, 256 output features wide) pays off when there are at least that many
         int big_waves = 0;
         if (variant == kVariantPrefillBig8) big_waves = 8;
-        if (variant == kVariantPrefillBig || (variant == 0 && out >= 256 && bd::prefill_big_fits(T, out, in))) big_waves = 4;
+        if (variant == kVariantPrefillBig || variant == kVariantPrefillBigWhole ||
+            (variant == 0 && out >= 256 && bd::prefill_big_fits(T, out, in)))
+            big_waves = 4;
         return run_prefill(x_f16, w_base_f16, packed_by_tenant, alpha_by_tenant, tenant_of_token, y_f16, T, out, in,
-                           workspace, hs, big_waves) == hipSuccess
+                           workspace, hs, big_waves, variant != kVariantPrefillBigWhole) == hipSuccess
                    ? BD_OK
                    : BD_ERR_DEVICE;
     }

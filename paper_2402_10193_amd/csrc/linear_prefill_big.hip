@@ -40,7 +40,7 @@ constexpr int kBgLdsBytes = 2 * kBgBufBytes + kBgLutBytes + kBgTokBytes;   // 13
 // instruction writes together, then fall into different banks), in the tile buffers, which are free by then.
 constexpr int kBgOutRowBytes = 64 * 2 + 16;
 static_assert(kBgM * kBgOutRowBytes * 4 <= 2 * kBgBufBytes, "the result rows of all wavefronts fit the tile buffers");
-constexpr int kBgPanel = 8, kBgChunk = 32, kBgXcds = 8;  // launch order: 4 x 8 tiles per XCD at a time
+constexpr int kBgPanel = 4, kBgChunk = 32, kBgXcds = 8;  // launch order: 8 x 4 tiles (1024 tokens x 1024 features) per XCD at a time
 
 __device__ __forceinline__ int bg_off(const int row, const int chunk) {
     return row * kBgRowBytes + ((chunk ^ ((row >> 1) & 7)) << 4);
@@ -82,33 +82,23 @@ __device__ __forceinline__ void mfma_in_place(float16v& acc, const half8 a, cons
 
 }  // namespace
 
-// WM = 1: 4 wavefronts (1 x 4), each 128 tokens x 64 features, alone on its SIMD; two sets of staging registers
-// (loads two steps ahead).  WM = 2: 8 wavefronts (2 x 4), each 64 x 64, two per SIMD; one set (one step ahead).
-template <int WM>
-__global__ __launch_bounds__(256 * WM, 1) void linear_prefill_big_kernel(
+// One tile: TM token rows r0 .. r0 + TM of the 128-row token tile mt, output features 256 nt .. + 256.
+// WM = 1: 4 wavefronts (1 x 4), each TM tokens x 64 features, alone on its SIMD; two sets of staging registers
+// (loads two steps ahead).  WM = 2: 8 wavefronts (2 x 4), each TM / 2 x 64, two per SIMD; one set (one step ahead).
+// TM = 128, or 64 (WM = 1 only): half a tile, for the tiles of a last round that would leave most units idle.
+template <int WM, int TM>
+__device__ __forceinline__ void prefill_big_tile(
     const uint16_t* __restrict__ x, const uint16_t* __restrict__ w, const uint32_t* const* __restrict__ packed_by_tenant,
     const float* __restrict__ alpha_by_tenant, const int32_t* __restrict__ row_token, const int32_t* __restrict__ tile_tenant,
-    uint16_t* __restrict__ y, const int64_t out, const int64_t in, const int n_mtiles, const int n_ntiles) {
-    extern __shared__ __align__(16) unsigned char lds[];   // [2 buffers: x, W, sign words][table]
+    uint16_t* __restrict__ y, const int64_t out, const int64_t in, const int mt, const int nt, const int r0) {
+    extern __shared__ __align__(16) unsigned char lds[];   // [2 buffers: x, W, sign words][table][tokens]
     unsigned char* const lut = lds + 2 * kBgBufBytes;
 
-    constexpr int kThreads = 256 * WM, kWaveM = kBgM / WM, MI = kWaveM / 32;
-    constexpr int kBgXPer = kBgM * 8 / kThreads, kBgWPer = kBgN * 8 / kThreads;   // 16-byte chunks per thread and step
+    constexpr int kThreads = 256 * WM, kWaveM = TM / WM, MI = kWaveM / 32;
+    constexpr int kBgXPer = TM * 8 / kThreads, kBgWPer = kBgN * 8 / kThreads;   // 16-byte chunks per thread and step
     constexpr int kSets = WM == 1 ? 2 : 1;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 2, wn = wave & 3;
-    int mt, nt;
-    {   // launch order -> tile: panels of 8 N tiles, row-major inside, chunks of 32 tiles per XCD
-        const int L = blockIdx.x, xcd = L % kBgXcds, slot = L / kBgXcds;
-        const int chunk = (slot / kBgChunk) * kBgXcds + xcd;
-        const int t = chunk * kBgChunk + slot % kBgChunk;
-        if (t >= n_mtiles * n_ntiles) return;
-        const int per_panel = n_mtiles * kBgPanel;
-        const int panel = t / per_panel, tp = t - panel * per_panel;
-        const int width = n_ntiles - panel * kBgPanel < kBgPanel ? n_ntiles - panel * kBgPanel : kBgPanel;
-        mt = tp / width;
-        nt = panel * kBgPanel + tp % width;
-    }
     const int64_t n0 = (int64_t)nt * kBgN;
     const int tenant = tile_tenant[mt];
     const float alpha = alpha_by_tenant[tenant];
@@ -141,7 +131,7 @@ __global__ __launch_bounds__(256 * WM, 1) void linear_prefill_big_kernel(
         wdst[i] = lds_at(kBgXBytes + bg_off(row, c8));
         asm volatile("" : "+v"(wdst[i]));   // a register of its own: derived from xdst[i], it would cost an addition per use
         if (i < kBgXPer) {
-            const int tok = row_token[mt * kBgM + row];
+            const int tok = row_token[mt * kBgM + r0 + row];
             xsrc[i] = (uint32_t)((int64_t)(tok >= 0 ? tok : 0) * in * 2) + c8 * 16;
             if (c8 == 0) lds_put<int>(lds_at(2 * kBgBufBytes + kBgLutBytes + row * 4), tok);   // for the epilogue
             xdst[i] = lds_at(bg_off(row, c8));
@@ -244,7 +234,9 @@ __global__ __launch_bounds__(256 * WM, 1) void linear_prefill_big_kernel(
     // refilled with step + 1 + kSets -- one LDS write or one global load behind every other MFMA, so that the
     // wavefronts do not queue up at the LDS and at the address unit while their matrix pipes idle.  On entry the
     // operands of slice 0 are in operand set 0 (read behind the previous step's barrier).
-    constexpr int kLag = WM == 1 ? 6 : 3;   // pairs of MFMAs between an item's LDS write and its next load
+    // pairs of MFMAs between an item's LDS write and its next load
+    constexpr int kLagMax = 3 * MI * 2 - kItems, kLag = kLagMax < (WM == 1 ? 6 : 3) ? kLagMax : (WM == 1 ? 6 : 3);
+    static_assert(kLag >= 1, "an item is written out before it is fetched again");
     static_assert(kItems - 1 + kLag < 3 * MI * 2, "all items are staged and fetched before the barrier slice");
     auto do_step = [&](const int step, const int buf, Staged& next) {
         const int step3 = step + 1 + kSets < last ? step + 1 + kSets : last;
@@ -336,6 +328,34 @@ __global__ __launch_bounds__(256 * WM, 1) void linear_prefill_big_kernel(
     }
 }
 
+// Launch order -> tile.  Tiles are numbered in panels of 8 N tiles, row-major inside, and an XCD takes chunks of 32
+// consecutive numbers, so that the workgroups it runs together form a compact block of tiles.  The tiles from n_full
+// on are run as two workgroups of half a tile each (n_full = all of them: none).
+template <int WM>
+__global__ __launch_bounds__(256 * WM, 1) void linear_prefill_big_kernel(
+    const uint16_t* __restrict__ x, const uint16_t* __restrict__ w, const uint32_t* const* __restrict__ packed_by_tenant,
+    const float* __restrict__ alpha_by_tenant, const int32_t* __restrict__ row_token, const int32_t* __restrict__ tile_tenant,
+    uint16_t* __restrict__ y, const int64_t out, const int64_t in, const int n_mtiles, const int n_ntiles, const int n_full) {
+    const int L = blockIdx.x, xcd = L % kBgXcds, slot = L / kBgXcds;
+    const int chunk = (slot / kBgChunk) * kBgXcds + xcd;
+    const int v = chunk * kBgChunk + slot % kBgChunk;
+    const int n_tiles = n_mtiles * n_ntiles;
+    if (v >= n_full + 2 * (n_tiles - n_full)) return;
+    const int t = v < n_full ? v : n_full + ((v - n_full) >> 1);
+    const int per_panel = n_mtiles * kBgPanel;
+    const int panel = t / per_panel, tp = t - panel * per_panel;
+    const int width = n_ntiles - panel * kBgPanel < kBgPanel ? n_ntiles - panel * kBgPanel : kBgPanel;
+    const int mt = tp / width, nt = panel * kBgPanel + tp % width;
+    if constexpr (WM == 1) {
+        if (v >= n_full) {
+            prefill_big_tile<1, kBgM / 2>(x, w, packed_by_tenant, alpha_by_tenant, row_token, tile_tenant, y, out, in, mt, nt,
+                                          ((v - n_full) & 1) * (kBgM / 2));
+            return;
+        }
+    }
+    prefill_big_tile<WM, kBgM>(x, w, packed_by_tenant, alpha_by_tenant, row_token, tile_tenant, y, out, in, mt, nt, 0);
+}
+
 // T: rows of x (its byte offsets and those inside one 256-row band of W must fit 32 bits)
 bool prefill_big_fits(int64_t T, int64_t out, int64_t in) {
     return in >= kBgK && in % kBgK == 0 && out >= 1 && (uint64_t)T * (uint64_t)in * 2 < ((uint64_t)1 << 32) &&
@@ -345,7 +365,8 @@ bool prefill_big_fits(int64_t T, int64_t out, int64_t in) {
 template <int WM>
 static hipError_t launch_big_t(const uint16_t* x, const uint16_t* w, const uint32_t* const* packed_by_tenant,
                                const float* alpha_by_tenant, const int32_t* row_token, const int32_t* tile_tenant,
-                               int n_mtiles, int n_ntiles, uint16_t* y, int64_t out, int64_t in, hipStream_t st) {
+                               int n_mtiles, int n_ntiles, uint16_t* y, int64_t out, int64_t in, bool halve_last_round,
+                               hipStream_t st) {
     auto kernel = linear_prefill_big_kernel<WM>;
     static PerDeviceOnce lds_limit;
     const hipError_t ea = lds_limit.run([&] {
@@ -357,23 +378,36 @@ static hipError_t launch_big_t(const uint16_t* x, const uint16_t* w, const uint3
     });
     if (ea != hipSuccess) return ea;
     const int64_t tiles = (int64_t)n_mtiles * n_ntiles, round = (int64_t)kBgChunk * kBgXcds;
-    const unsigned grid = (unsigned)((tiles + round - 1) / round * round);   // surplus workgroups return at once
+    // One workgroup per compute unit at a time: when the last round of tiles would keep at most half of the units
+    // busy, its tiles are cut in two (64 token rows each), which takes little more than half the time of a round.
+    int64_t n_full = tiles;
+    if (WM == 1 && halve_last_round) {
+        int cus = 0;
+        const hipError_t ec = device_cu_count(&cus);
+        if (ec != hipSuccess) return ec;
+        const int64_t r = tiles % cus;
+        if (r != 0 && 2 * r <= cus) n_full = tiles - r;
+    }
+    const int64_t n_virtual = n_full + 2 * (tiles - n_full);
+    const unsigned grid = (unsigned)((n_virtual + round - 1) / round * round);   // surplus workgroups return at once
     hipLaunchKernelGGL(kernel, dim3(grid), dim3(256 * WM), kBgLdsBytes, st, x, w, packed_by_tenant, alpha_by_tenant, row_token,
-                       tile_tenant, y, out, in, n_mtiles, n_ntiles);
+                       tile_tenant, y, out, in, n_mtiles, n_ntiles, (int)n_full);
     return hipGetLastError();
 }
 
 // waves: 4 (one wavefront per SIMD) or 8 (two)
 hipError_t launch_linear_prefill_big(const uint16_t* x, const uint16_t* w, const uint32_t* const* packed_by_tenant,
                                      const float* alpha_by_tenant, const int32_t* row_token, const int32_t* tile_tenant,
-                                     int n_mtiles, uint16_t* y, int64_t T, int64_t out, int64_t in, int waves, hipStream_t st) {
+                                     int n_mtiles, uint16_t* y, int64_t T, int64_t out, int64_t in, int waves, bool halve_last_round,
+                                     hipStream_t st) {
     if (!prefill_big_fits(T, out, in) || (waves != 4 && waves != 8)) return hipErrorInvalidValue;
     const int n_ntiles = (int)((out + kBgN - 1) / kBgN);
     const int64_t tiles = (int64_t)n_mtiles * n_ntiles;
     if (tiles < 1 || tiles > (int64_t)1 << 30) return hipErrorInvalidValue;
     if (waves == 4)
-        return launch_big_t<1>(x, w, packed_by_tenant, alpha_by_tenant, row_token, tile_tenant, n_mtiles, n_ntiles, y, out, in, st);
-    return launch_big_t<2>(x, w, packed_by_tenant, alpha_by_tenant, row_token, tile_tenant, n_mtiles, n_ntiles, y, out, in, st);
+        return launch_big_t<1>(x, w, packed_by_tenant, alpha_by_tenant, row_token, tile_tenant, n_mtiles, n_ntiles, y, out, in,
+                               halve_last_round, st);
+    return launch_big_t<2>(x, w, packed_by_tenant, alpha_by_tenant, row_token, tile_tenant, n_mtiles, n_ntiles, y, out, in, false, st);
 }
 
 }  // namespace bd

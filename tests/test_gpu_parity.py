@@ -136,14 +136,20 @@ def test_prefill_gemm_matches_oracle(ref, case):
     check_close(y, y32, f"prefill case {case}")
     check_close(y_dec, y32, f"prefill case {case}, decode launches")
     assert torch.equal(bd.linear_multitenant(x, prob.w_base, prob.table, tok), y)    # bitwise reproducible
-    # both GEMM kernels by name: 4 = 128 x 128 tiles, 5 = 128 x 256 tiles (in % 64 == 0 only)
+    # the GEMM kernels by name: 4 = 128 x 128 tiles; 128 x 256 tiles (in % 64 == 0 only): 5 = one wavefront per SIMD,
+    # the tiles of a sparsely filled last round (here: all of them) as halves of 64 token rows, 6 = two wavefronts
+    # per SIMD, 7 = as 5 with every tile whole
     y4 = bd.linear_multitenant(x, prob.w_base, prob.table, tok, variant=4)
     check_close(y4, y32, f"prefill case {case}, 128 x 128 tiles")
     if inn % 64 == 0:
-        for v in (5, 6):                                   # one / two wavefronts per SIMD
+        by_variant = {}
+        for v in (5, 6, 7):
             y5 = bd.linear_multitenant(x, prob.w_base, prob.table, tok, variant=v)
             check_close(y5, y32, f"prefill case {case}, 128 x 256 tiles, variant {v}")
             assert torch.equal(bd.linear_multitenant(x, prob.w_base, prob.table, tok, variant=v), y5)
+            by_variant[v] = y5
+        # half tiles add up every element in the same order as whole tiles
+        assert torch.equal(by_variant[5], by_variant[7])
     else:
         with pytest.raises(bd.BitDeltaError) as e:
             bd.linear_multitenant(x, prob.w_base, prob.table, tok, variant=5)
