@@ -41,13 +41,16 @@ __global__ __launch_bounds__(kCompressThreads) void pack_signs_kernel(
 // Iterated compression (Sec. 4.2, fidelity of Delta): with n_prev > 0 the element's delta is first
 // carried through the n_prev earlier iterations, r <- r - alpha_i * Sign(r) in binary32, so that
 // plane n_prev is the sign of the residual left by the planes before it.
+// NPREV is a template parameter and the update a select, not a branch: with the number of earlier planes a
+// run-time value the loop body was a hundred scalar branches per 8 elements, and the stream ran at half its rate.
+template <int NPREV>
 __global__ __launch_bounds__(kCompressThreads) void compress_kernel(
     const u32x4* __restrict__ base, const u32x4* __restrict__ ft, uint32_t* __restrict__ packed,
-    double* __restrict__ partial, int64_t n_vec, const float* __restrict__ alpha_prev, const int n_prev) {
+    double* __restrict__ partial, int64_t n_vec, const float* __restrict__ alpha_prev) {
     __shared__ double wave_part[kCompressThreads / kWave];
-    float ap[kCompressMaxPlanes - 1];
+    float ap[NPREV > 0 ? NPREV : 1];
 #pragma unroll
-    for (int i = 0; i < kCompressMaxPlanes - 1; ++i) ap[i] = i < n_prev ? alpha_prev[i] : 0.0f;
+    for (int i = 0; i < NPREV; ++i) ap[i] = alpha_prev[i];
     const int lane = threadIdx.x & (kWave - 1);
     const int64_t stride = (int64_t)gridDim.x * kCompressThreads;
     double s = 0.0;
@@ -63,8 +66,7 @@ __global__ __launch_bounds__(kCompressThreads) void compress_kernel(
             const float vf = h2f((uint16_t)(fw[e >> 1] >> (16 * (e & 1))));
             float d = vf - vb;                      // the delta of Sec. 3.1, IEEE binary32
 #pragma unroll
-            for (int i = 0; i < kCompressMaxPlanes - 1; ++i)
-                if (i < n_prev) d = d > 0.0f ? d - ap[i] : d + ap[i];
+            for (int i = 0; i < NPREV; ++i) d += d > 0.0f ? -ap[i] : ap[i];   // d - a and d + (-a) are the same binary32 number
             byte |= (d > 0.0f ? 1u : 0u) << e;      // Eq. 2: +1 only for d > 0
             s += (double)__builtin_fabsf(d);
         }
@@ -193,8 +195,19 @@ hipError_t launch_compress(const uint16_t* base, const uint16_t* ft, int64_t out
     int blocks = 0;
     if (n_vec > 0) {
         blocks = compress_grid_blocks(n_vec);
-        hipLaunchKernelGGL(compress_kernel, dim3(blocks), dim3(kCompressThreads), 0, st, (const u32x4*)base,
-                           (const u32x4*)ft, packed, partial, n_vec, alpha_prev, n_prev);
+        const dim3 g(blocks), b(kCompressThreads);
+        const u32x4 *pb = (const u32x4*)base, *pf = (const u32x4*)ft;
+        switch (n_prev) {
+            case 0: hipLaunchKernelGGL(compress_kernel<0>, g, b, 0, st, pb, pf, packed, partial, n_vec, alpha_prev); break;
+            case 1: hipLaunchKernelGGL(compress_kernel<1>, g, b, 0, st, pb, pf, packed, partial, n_vec, alpha_prev); break;
+            case 2: hipLaunchKernelGGL(compress_kernel<2>, g, b, 0, st, pb, pf, packed, partial, n_vec, alpha_prev); break;
+            case 3: hipLaunchKernelGGL(compress_kernel<3>, g, b, 0, st, pb, pf, packed, partial, n_vec, alpha_prev); break;
+            case 4: hipLaunchKernelGGL(compress_kernel<4>, g, b, 0, st, pb, pf, packed, partial, n_vec, alpha_prev); break;
+            case 5: hipLaunchKernelGGL(compress_kernel<5>, g, b, 0, st, pb, pf, packed, partial, n_vec, alpha_prev); break;
+            case 6: hipLaunchKernelGGL(compress_kernel<6>, g, b, 0, st, pb, pf, packed, partial, n_vec, alpha_prev); break;
+            default: hipLaunchKernelGGL(compress_kernel<7>, g, b, 0, st, pb, pf, packed, partial, n_vec, alpha_prev); break;
+        }
+        static_assert(kCompressMaxPlanes - 1 == 7, "one instantiation per number of earlier planes");
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
