@@ -100,10 +100,42 @@ __device__ __forceinline__ void prefill_big_tile(
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 2, wn = wave & 3;
     const int64_t n0 = (int64_t)nt * kBgN;
-    const int tenant = tile_tenant[mt];
-    const float alpha = alpha_by_tenant[tenant];
     const int64_t words_per_row = in >> 5;
     const int n_steps = (int)(in / kBgK), last = n_steps - 1;
+
+    // What this thread fetches per step.  Empty token rows read token 0 and output rows beyond `out` the last
+    // row: their products are never stored, so nothing has to be zeroed and no load is conditional.
+    // Global addresses are a uniform base plus a 32-bit byte offset per thread (the host checks the ranges).
+    // The prologue asks for things in the order in which their addresses become known, so that the trips to memory
+    // overlap: W (kernel arguments only), then the tile's tenant and tokens; behind those x, the sign pointer, the signs.
+    const unsigned char* const xbase = (const unsigned char*)x;
+    const unsigned char* const wbase = (const unsigned char*)(w + n0 * in);
+    uint32_t xsrc[kBgXPer], wsrc[kBgWPer];
+    lds_bytes xdst[kBgXPer], wdst[kBgWPer];   // in buffer 0
+    struct Staged {
+        u32x4 xg[kBgXPer], wg[kBgWPer];
+        uint32_t s0, s1;
+    };
+    Staged set0, set1;
+    const int step_b = 1 < last ? 1 : last;   // what the second set holds first
+#pragma unroll
+    for (int i = 0; i < kBgWPer; ++i) {
+        const int q = tid + kThreads * i, row = q >> 3, c8 = q & 7;
+        const int64_t wrow = n0 + row < out ? row : out - 1 - n0;
+        wsrc[i] = (uint32_t)(wrow * in * 2) + c8 * 16;
+        wdst[i] = lds_at(kBgXBytes + bg_off(row, c8));
+        asm volatile("" : "+v"(wdst[i]));   // a register of its own: derived from xdst[i], it would cost an addition per use
+        set0.wg[i] = *(const u32x4*)(wbase + wsrc[i]);
+    }
+    const int tenant = tile_tenant[mt];
+    int tokv[kBgXPer];
+#pragma unroll
+    for (int i = 0; i < kBgXPer; ++i) tokv[i] = row_token[mt * kBgM + r0 + ((tid + kThreads * i) >> 3)];
+    if (kSets == 2) {
+#pragma unroll
+        for (int i = 0; i < kBgWPer; ++i) set1.wg[i] = *(const u32x4*)(wbase + (int64_t)step_b * kBgRowBytes + wsrc[i]);
+    }
+    __builtin_amdgcn_sched_barrier(0);
 
     if (tid < 256) {   // byte -> 8 fp16 (+1.0 where the bit is set, else -1.0), element e = bit e; entry [byte][copy]
         const uint32_t bb = (uint32_t)tid;
@@ -115,39 +147,31 @@ __device__ __forceinline__ void prefill_big_tile(
         for (int cp = 0; cp < 8; ++cp) *(u32x4*)(lut + bb * 128 + cp * 16) = e;
     }
     const lds_bytes lut_lane = lds_at(2 * kBgBufBytes + (lane & 7) * 16);
+    __builtin_amdgcn_sched_barrier(0);
 
-    // What this thread fetches per step.  Empty token rows read token 0 and output rows beyond `out` the last
-    // row: their products are never stored, so nothing has to be zeroed and no load is conditional.
-    // Global addresses are a uniform base plus a 32-bit byte offset per thread (the host checks the ranges).
-    const unsigned char* const xbase = (const unsigned char*)x;
-    const unsigned char* const wbase = (const unsigned char*)(w + n0 * in);
-    uint32_t xsrc[kBgXPer], wsrc[kBgWPer];
-    lds_bytes xdst[kBgXPer], wdst[kBgWPer];   // in buffer 0
-#pragma unroll
-    for (int i = 0; i < kBgWPer; ++i) {
-        const int q = tid + kThreads * i, row = q >> 3, c8 = q & 7;
-        const int64_t wrow = n0 + row < out ? row : out - 1 - n0;
-        wsrc[i] = (uint32_t)(wrow * in * 2) + c8 * 16;
-        wdst[i] = lds_at(kBgXBytes + bg_off(row, c8));
-        asm volatile("" : "+v"(wdst[i]));   // a register of its own: derived from xdst[i], it would cost an addition per use
-        if (i < kBgXPer) {
-            const int tok = row_token[mt * kBgM + r0 + row];
-            xsrc[i] = (uint32_t)((int64_t)(tok >= 0 ? tok : 0) * in * 2) + c8 * 16;
-            if (c8 == 0) lds_put<int>(lds_at(2 * kBgBufBytes + kBgLutBytes + row * 4), tok);   // for the epilogue
-            xdst[i] = lds_at(bg_off(row, c8));
-        }
-    }
+    const float alpha = alpha_by_tenant[tenant];
     // sign words: 256 threads take a row's two words each, 512 threads one word each
     const int s_row = WM == 1 ? tid : tid >> 1, s_word = WM == 1 ? 0 : tid & 1;
     const int64_t srow = n0 + s_row < out ? n0 + s_row : out - 1;
     const bg_global_words ssrc = (bg_global_words)(packed_by_tenant[tenant] + srow * words_per_row) + s_word;
+#pragma unroll
+    for (int i = 0; i < kBgXPer; ++i) {
+        const int q = tid + kThreads * i, row = q >> 3, c8 = q & 7;
+        const int tok = tokv[i];
+        xsrc[i] = (uint32_t)((int64_t)(tok >= 0 ? tok : 0) * in * 2) + c8 * 16;
+        if (c8 == 0) lds_put<int>(lds_at(2 * kBgBufBytes + kBgLutBytes + row * 4), tok);   // for the epilogue
+        xdst[i] = lds_at(bg_off(row, c8));
+        set0.xg[i] = *(const u32x4*)(xbase + xsrc[i]);
+        if (kSets == 2) set1.xg[i] = *(const u32x4*)(xbase + (int64_t)step_b * kBgRowBytes + xsrc[i]);
+    }
+    set0.s0 = ssrc[0];
+    if (WM == 1) set0.s1 = ssrc[1];
+    if (kSets == 2) {
+        set1.s0 = ssrc[2 * step_b];
+        if (WM == 1) set1.s1 = ssrc[2 * step_b + 1];
+    }
 
     const lds_bytes sdst = lds_at(kBgXBytes + kBgWBytes + tid * (WM == 1 ? 8 : 4));
-    struct Staged {
-        u32x4 xg[kBgXPer], wg[kBgWPer];
-        uint32_t s0, s1;
-    };
-    Staged set0, set1;
     // items: the x chunks, the W chunks, the sign word(s)
     constexpr int kItems = kBgXPer + kBgWPer + 1;
     auto fetch_item = [&](Staged& st, const int step, const int item) {
@@ -276,9 +300,7 @@ __device__ __forceinline__ void prefill_big_tile(
         }
     };
 
-    fetch(set0, 0);
-    if (kSets == 2) fetch(set1, 1 < last ? 1 : last);
-    stage(set0, 0);
+    stage(set0, 0);   // both sets were requested at the top
     fetch(set0, kSets < last ? kSets : last);
     bg_barrier();       // the table and the tiles of step 0 are complete
     read_signs(0);
