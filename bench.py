@@ -193,7 +193,7 @@ def main():
     args = parse()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (the path has no collective); use --gpus 1. "
-              "How the path would shard over several GPUs is described in DESIGN.md.", file=sys.stderr)
+              "Over several GPUs the path would shard by output rows, with one all-gather of y per linear.", file=sys.stderr)
         sys.exit(2)
 
     import numpy as np
