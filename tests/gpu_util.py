@@ -41,6 +41,15 @@ class Problem:
         return synth.activations(T, self.inn, seed=seed, tag=(tag, T), device=self.w_base.device)
 
 
+class TiledProblem(Problem):
+    """The same problem with base and deltas also in the tiled serving layout."""
+
+    def __init__(self, ref, out, inn, n_tenants, **kw):
+        super().__init__(ref, out, inn, n_tenants, **kw)
+        self.w_tiled = bd.tile_base(self.w_base)
+        self.ttable = bd.TiledTenantTable([bd.tile_signs(p, out, inn) for p in self.table.packed], self.table.alpha)
+
+
 def check_close(y_gpu: torch.Tensor, y_ref32: np.ndarray, what=""):
     y = to_np(y_gpu).astype(np.float64)
     r = y_ref32.astype(np.float64)

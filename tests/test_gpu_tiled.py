@@ -9,7 +9,7 @@ pytestmark = pytest.mark.gpu
 
 from paper_2402_10193_amd import binding as bd   # noqa: E402
 from paper_2402_10193_amd import synth           # noqa: E402
-from gpu_util import Problem, check_close, packed_to_np, to_np   # noqa: E402
+from gpu_util import Problem, TiledProblem, check_close, packed_to_np, to_np   # noqa: E402
 
 DEV = "cuda"
 
@@ -57,13 +57,6 @@ def test_tile_layouts_bit_exact(ref, out, inn):
     assert st.numel() * 4 == bd.tiled_signs_bytes(out, inn)
     bits = ((ref.unpack_signs(packed_to_np(packed), inn) + 1) // 2).astype(np.uint8)    # +-1 -> 1/0
     assert np.array_equal(to_np(st).view(np.uint8), tiled_signs_np(bits))
-
-
-class TiledProblem(Problem):
-    def __init__(self, ref, out, inn, n_tenants, **kw):
-        super().__init__(ref, out, inn, n_tenants, **kw)
-        self.w_tiled = bd.tile_base(self.w_base)
-        self.ttable = bd.TiledTenantTable([bd.tile_signs(p, out, inn) for p in self.table.packed], self.table.alpha)
 
 
 CASES = [
