@@ -169,15 +169,15 @@ __global__ __launch_bounds__(kMaxWavesTiled * kWave) void linear_decode_tiled_ke
     // Built (and the workgroup synchronised) while only the first base requests are in flight: the
     // later requests queue up behind the memory system, and a barrier behind them would hold the
     // first multiplications back by microseconds.
-    for (int idx = threadIdx.x; idx < 256 * 2; idx += blockDim.x) {   // one entry, eight of its copies per pass
-        const uint32_t b = (uint32_t)idx >> 1;
+    // Consecutive lanes write consecutive 16-byte copies (16 per entry), a wavefront 1 KiB at a stretch: with a
+    // lane per entry the writes of a wavefront were 128 bytes apart, eight of them on every bank.
+    for (int q = threadIdx.x; q < 256 * 16; q += blockDim.x) {
+        const uint32_t b = (uint32_t)q >> 4;
         u32x4 e;
 #pragma unroll
         for (int i = 0; i < 4; ++i)
             e[i] = 0xBC00BC00u ^ (((b >> (2 * i)) & 1u) << 15) ^ (((b >> (2 * i + 1)) & 1u) << 31);
-        unsigned char* dst = smem + b * 256 + (idx & 1) * 128;
-#pragma unroll
-        for (int cp = 0; cp < 8; ++cp) *(u32x4*)(dst + cp * 16) = e;
+        *(u32x4*)(smem + q * 16) = e;
     }
     __syncthreads();
 
