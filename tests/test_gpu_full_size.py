@@ -29,6 +29,20 @@ def _gpu_layer(out, inn, B, sigma, tag):
     return base, fts, bd.TenantTable(packed, alphas)
 
 
+def _oracle_deltas(ref, base, fts, table):
+    """The oracle's own compression of the same (base, fine-tuned) pairs -- what the oracle's linear is fed -- and
+    the check that the library's compressor, whose output the library's linear is fed, agrees with it bit for bit."""
+    base_np = to_np(base)
+    packed, alphas = [], []
+    for t, ft in enumerate(fts):
+        p, a, _ = ref.compress(base_np, to_np(ft))
+        assert np.array_equal(packed_to_np(table.packed[t]), p)
+        assert float(table.alpha[t].item()) == a
+        packed.append(p)
+        alphas.append(a)
+    return packed, alphas
+
+
 @pytest.mark.timeout(600)
 @pytest.mark.parametrize("name,out,inn", [("q", 4096, 4096), ("gate", 11008, 4096), ("down", 4096, 11008)])
 def test_llama2_7b_layer_b16_full_output(ref, name, out, inn):
@@ -67,15 +81,14 @@ def test_llama2_7b_grouped_launch_b16_full_output(ref, names, outs, inn):
     wts, tables, keep = [], [], []
     for name, out in zip(names, outs):
         base, fts, table = _gpu_layer(out, inn, B, 0.002, ("7bg", name))
+        oracle_packed, oracle_alphas = _oracle_deltas(ref, base, fts, table)
         del fts
         wts.append(bd.tile_base(base))
         tables.append(bd.TiledTenantTable([bd.tile_signs(p, out, inn) for p in table.packed], table.alpha))
-        keep.append((base, table))
+        keep.append((base, oracle_packed, oracle_alphas))
     ys = bd.linear_multitenant_tiled_group(x, bd.TiledGroup(wts, list(outs), tables), tok)
     torch.cuda.synchronize()
-    for i, (base, table) in enumerate(keep):
-        packed = [packed_to_np(p) for p in table.packed]          # bit-exactness of these is covered above
-        alphas = [float(a) for a in to_np(table.alpha)]
+    for i, (base, packed, alphas) in enumerate(keep):
         _, y32 = ref.linear_multitenant(to_np(x), to_np(base), packed, alphas, tok)
         err = check_close(ys[i], y32, f"7B grouped {names[i]}")
         print(f"   {names[i]}: max rel err {err:.2e}", flush=True)
@@ -102,23 +115,26 @@ def test_llama2_7b_mixed_batch_gate_up_full_output(ref, case):
     wts, tables, keep = [], [], []
     for name in ("gate", "up"):
         base = synth.base_weight(out, inn, device=DEV, tag=("7bmix", case, name))
-        tiled, packed = [None] * n_res, [None] * n_res
+        tiled = [None] * n_res
         alpha = torch.zeros(n_res, dtype=torch.float32, device=DEV)
+        dummy = np.zeros((out, inn // 32), dtype=np.uint32)              # never selected: idle tenants have no token
+        oracle_packed, oracle_alphas = [dummy] * n_res, [0.0] * n_res
+        base_np = to_np(base)
         for t in active:
             ft = synth.finetuned_weight(base, sigma=0.002, tag=("7bmix", case, name, t))
             p, a = bd.compress(base, ft, workspace=ws)
+            oracle_packed[t], oracle_alphas[t], _ = ref.compress(base_np, to_np(ft))   # the oracle's own deltas
             del ft
-            packed[t], alpha[t] = p, a
+            assert np.array_equal(packed_to_np(p), oracle_packed[t]) and float(a.item()) == oracle_alphas[t]
+            alpha[t] = a
             tiled[t] = bd.tile_signs(p, out, inn)
         wts.append(bd.tile_base(base))
         tables.append(bd.TiledTenantTable(tiled, alpha))
-        keep.append((base, packed, alpha))
+        keep.append((base_np, oracle_packed, oracle_alphas))
     ys = bd.linear_multitenant_tiled_group(x, bd.TiledGroup(wts, [out, out], tables), tok)
     torch.cuda.synchronize()
-    for i, (base, packed, alpha) in enumerate(keep):
-        dummy = np.zeros((out, inn // 32), dtype=np.uint32)              # never selected: idle tenants have no token
-        packed_np = [packed_to_np(p) if p is not None else dummy for p in packed]   # bit-exactness is covered above
-        _, y32 = ref.linear_multitenant(to_np(x), to_np(base), packed_np, [float(a) for a in to_np(alpha)], tok)
+    for i, (base_np, packed_np, alphas) in enumerate(keep):
+        _, y32 = ref.linear_multitenant(to_np(x), base_np, packed_np, alphas, tok)
         err = check_close(ys[i], y32, f"7B mixed batch {i}")
         print(f"   matrix {i}: max rel err {err:.2e}", flush=True)
 
@@ -162,6 +178,7 @@ def test_prefill_8_tenants_x_512_tokens_sampled_rows(ref, name, out, inn):
     B, per, n_rows = 8, 512, 96
     print(f"prefill {name} {out}x{inn} T={B * per}", flush=True)
     base, fts, table = _gpu_layer(out, inn, B, 0.002, ("pf", name))
+    oracle_packed, alphas = _oracle_deltas(ref, base, fts, table)
     del fts
     tok = [t for t in range(B) for _ in range(per)]
     x = synth.activations(B * per, inn, device=DEV, tag=("pf", name))
@@ -170,8 +187,7 @@ def test_prefill_8_tenants_x_512_tokens_sampled_rows(ref, name, out, inn):
     g = torch.Generator().manual_seed(11)
     rows = torch.sort(torch.randperm(out, generator=g)[:n_rows]).values
     rows[0], rows[-1] = 0, out - 1
-    packed = [np.ascontiguousarray(packed_to_np(p)[rows.numpy()]) for p in table.packed]
-    alphas = [float(a) for a in to_np(table.alpha)]
+    packed = [np.ascontiguousarray(p[rows.numpy()]) for p in oracle_packed]
     base_np = np.ascontiguousarray(to_np(base)[rows.numpy()])
     _, y32 = ref.linear_multitenant(to_np(x), base_np, packed, alphas, tok)
     err = check_close(y[:, rows.to(DEV)], y32, f"prefill {name}")

@@ -26,10 +26,20 @@ def test_hot_swap_round_trip(ref, tmp_path, k):
     packed = [[None] * n_tenants for _ in shapes]
     alphas = [torch.zeros(n_tenants * k, dtype=torch.float32, device=DEV) for _ in shapes]
     tiled = [[None] * n_tenants for _ in shapes]
+    # the oracle compresses the same pairs itself: its linear is never fed anything the library produced
+    ref_planes = [[None] * n_tenants for _ in shapes]
+    ref_alphas = [np.zeros((n_tenants, k), dtype=np.float32) for _ in shapes]
+
+    def oracle_delta(m, ft, p, a):
+        p_ref, a_ref, _, _ = ref.compress_iterated(to_np(bases[m]), to_np(ft), k)
+        assert np.array_equal(packed_to_np(p), p_ref) and np.array_equal(to_np(a), np.asarray(a_ref, dtype=np.float32))
+        return [p_ref[j] for j in range(k)], np.asarray(a_ref, dtype=np.float32)
+
     for m, (o, i) in enumerate(shapes):
         for t in range(n_tenants):
             ft = synth.finetuned_weight(bases[m], sigma=0.002, tag=("hs", k, m, t))
             p, a = bd.compress_iterated(bases[m], ft, k)
+            ref_planes[m][t], ref_alphas[m][t] = oracle_delta(m, ft, p, a)
             packed[m][t] = p
             alphas[m][t * k:(t + 1) * k] = a
             tiled[m][t] = [bd.tile_signs(p[j].contiguous(), o, i) for j in range(k)]
@@ -38,6 +48,7 @@ def test_hot_swap_round_trip(ref, tmp_path, k):
     for m, (o, i) in enumerate(shapes):
         ft = synth.finetuned_weight(bases[m], sigma=0.002, tag=("hs", k, m, "new"))
         p, a = bd.compress_iterated(bases[m], ft, k)
+        ref_planes[m][new_tenant], ref_alphas[m][new_tenant] = oracle_delta(m, ft, p, a)   # tenant 1 after the swap
         new_packed.append(p)
         new_alpha.append(a)
     torch.cuda.synchronize()
@@ -82,7 +93,5 @@ def test_hot_swap_round_trip(ref, tmp_path, k):
         y_d = bd.linear_multitenant_tiled_kbit(x[i], wts[m], o, direct, tok)
         assert torch.equal(y_s, y_d)
         assert not torch.equal(y_s, y_before[m])
-        planes_np = [[packed_to_np(packed[m][0])[j] for j in range(k)], [packed_to_np(new_packed[m])[j] for j in range(k)],
-                     [packed_to_np(packed[m][2])[j] for j in range(k)]]
-        _, y32 = ref.linear_multitenant_kbit(to_np(x[i]), to_np(bases[m]), planes_np, to_np(direct_alpha).reshape(n_tenants, k), tok)
+        _, y32 = ref.linear_multitenant_kbit(to_np(x[i]), to_np(bases[m]), ref_planes[m], ref_alphas[m], tok)
         check_close(y_s, y32, f"hot swap matrix {m}")

@@ -137,7 +137,7 @@ def test_q8_llama2_7b_gate_b16_full_output(ref):
     q_np, s_np = ref.quantize_rtn8(to_np(w))
     assert np.array_equal(to_np(q), q_np) and np.array_equal(to_np(scale), s_np)
     ws = bd.new_workspace(bd.workspace_bytes(bd.OP_COMPRESS, 0, out, inn, 1), DEV)
-    tiled, alphas, packed_np = [], [], []
+    tiled, alphas, packed_np, alphas_ref = [], [], [], []
     for t in range(B):
         ft = synth.finetuned_weight(w, sigma=0.002, tag=("q87b", t))
         p, a = bd.compress_q8(q, scale, ft, workspace=ws)
@@ -147,11 +147,12 @@ def test_q8_llama2_7b_gate_b16_full_output(ref):
         tiled.append(bd.tile_signs(p, out, inn))
         alphas.append(a)
         packed_np.append(p_ref)
+        alphas_ref.append(a_ref)
     table = bd.TiledTenantTable(tiled, alphas)
     x = synth.activations(B, inn, device=DEV, tag=("q87b", "x"))
     tok = synth.one_token_per_tenant(B)
     y = bd.linear_multitenant_tiled_q8(x, bd.tile_base_q8(q, scale), out, table, tok)
     torch.cuda.synchronize()
-    _, y32 = ref.linear_multitenant_q8(to_np(x), q_np, s_np, packed_np, [float(a.item()) for a in alphas], tok)
+    _, y32 = ref.linear_multitenant_q8(to_np(x), q_np, s_np, packed_np, alphas_ref, tok)
     err = check_close(y, y32, "7B gate q8")
     _p(f"   max rel err {err:.2e}")
