@@ -15,7 +15,7 @@ Prints ONE JSON line: decode tokens/s, the HBM roofline of the decode kernel, an
 host cores on one layer of the same workload.
 
 Other workloads and options (each prints one JSON line of its own):
-  --workload prefill   8 tenants x 512 tokens through the matrix-core GEMM (--variant 4/5/6 picks the kernel)
+  --workload prefill   8 tenants x 512 tokens through the matrix-core GEMM (--variant 4/5/6/7 picks the kernel)
   --workload hotswap   one tenant's delta set from pinned host memory into the serving layout while B tenants decode
   --mix 6,4,3,1,1,1    a mixed decode batch (tokens per active tenant; the other resident tenants idle)
   --planes K           K sign planes per tenant (iterated compression)
