@@ -258,10 +258,11 @@ __device__ __forceinline__ void prefill_big_tile(
     // refilled with step + 1 + kSets -- one LDS write or one global load behind every other MFMA, so that the
     // wavefronts do not queue up at the LDS and at the address unit while their matrix pipes idle.  On entry the
     // operands of slice 0 are in operand set 0 (read behind the previous step's barrier).
-    // pairs of MFMAs between an item's LDS write and its next load
-    constexpr int kLagMax = 3 * MI * 2 - kItems, kLag = kLagMax < (WM == 1 ? 6 : 3) ? kLagMax : (WM == 1 ? 6 : 3);
+    // pairs of MFMAs between an item's LDS write and its next load: where the step is long enough, all the writes
+    // first and then all the loads, so that no pair carries both
+    constexpr int kLagMax = 4 * MI * 2 - kItems, kLag = kLagMax < kItems ? kLagMax : kItems;
     static_assert(kLag >= 1, "an item is written out before it is fetched again");
-    static_assert(kItems - 1 + kLag < 3 * MI * 2, "all items are staged and fetched before the barrier slice");
+    static_assert(kItems <= 3 * MI * 2 && kItems - 1 + kLag < 4 * MI * 2, "all items are staged before the barrier slice and fetched within the step");
     auto do_step = [&](const int step, const int buf, Staged& next) {
         const int step3 = step + 1 + kSets < last ? step + 1 + kSets : last;
 #pragma unroll
