@@ -140,6 +140,46 @@ hipError_t run_prefill(const uint16_t* x, const uint16_t* w, const uint32_t* con
                                      in, st);
 }
 
+// Which way is quicker for T > 32 tokens when both are possible: one GEMM launch, whose tiles of 128 token rows
+// never mix tenants (a tenant with 3 tokens still costs a whole tile), or decode launches of 32 tokens each, which
+// re-read the base per launch but spend nothing on empty rows.  Rough model from measured rates: a 128 x 256 tile
+// takes 1.45 us per 64-wide k step plus 10 us around the loop, one tile per compute unit at a time; a decode launch
+// of the row-major kernels streams its bytes at 2.6 TB/s (1.3 with the vector-ALU kernel) plus 8 us.  A wrong guess costs
+// time, never correctness.
+bool prefill_gemm_pays(const int32_t* tenant_of_token, int64_t T, int64_t out, int64_t in, int32_t n_tenants, bool big,
+                       bool decode_on_matrix_cores) {
+    std::vector<int32_t> count((size_t)n_tenants, 0);
+    for (int64_t i = 0; i < T; ++i) ++count[(size_t)tenant_of_token[i]];
+    int64_t n_mtiles = 0;
+    for (int32_t t = 0; t < n_tenants; ++t) n_mtiles += (count[(size_t)t] + bd::kPrefillTile - 1) / bd::kPrefillTile;
+    int cus = 256;
+    if (bd::device_cu_count(&cus) != hipSuccess || cus < 1) cus = 256;
+    const double steps = (double)in / 64.0;
+    double gemm_us;
+    if (big) {
+        const int64_t tiles = n_mtiles * ((out + 255) / 256);
+        gemm_us = (double)((tiles + cus - 1) / cus) * (steps * 1.45 + 10.0);
+    } else {   // 128 x 128 tiles, two workgroups per compute unit
+        const int64_t tiles = n_mtiles * ((out + 127) / 128);
+        gemm_us = (double)((tiles + 2 * cus - 1) / (2 * cus)) * (steps * 1.9 + 10.0);
+    }
+    double decode_us = 0.0;
+    std::vector<int32_t> seen((size_t)n_tenants, -1);
+    for (int64_t t0 = 0, chunk = 0; t0 < T; t0 += kMaxDecodeTokens, ++chunk) {
+        const int64_t n = std::min<int64_t>(kMaxDecodeTokens, T - t0);
+        int distinct = 0;
+        for (int64_t i = t0; i < t0 + n; ++i) {
+            int32_t& s = seen[(size_t)tenant_of_token[i]];
+            if (s != (int32_t)chunk) {
+                s = (int32_t)chunk;
+                ++distinct;
+            }
+        }
+        decode_us += (double)out * (double)in * (2.0 + (double)distinct / 8.0) / (decode_on_matrix_cores ? 2.6e6 : 1.3e6) + 8.0;
+    }
+    return gemm_us < decode_us;
+}
+
 }  // namespace
 
 extern "C" {
@@ -252,12 +292,14 @@ bd_status bd_linear_multitenant_variant(const uint16_t* x_f16, const uint16_t* w
     const bool can_prefill = need > 0 && in > 0 && workspace && workspace_bytes >= need && !misaligned(workspace, 256);
     if (prefill_variant && !can_prefill) return need > 0 && in > 0 ? BD_ERR_WORKSPACE : BD_ERR_UNSUPPORTED;
     if (big_variant && !bd::prefill_big_fits(T, out, in)) return BD_ERR_UNSUPPORTED;
-    if ((variant == 0 || prefill_variant) && can_prefill) {
+    const bool big_default = out >= 256 && bd::prefill_big_fits(T, out, in);
+    if (can_prefill &&
+        (prefill_variant || (variant == 0 && prefill_gemm_pays(tenant_of_token, T, out, in, n_tenants, big_default, mfma_ok)))) {
         // the large tile (one workgroup per CU, 256 output features wide) pays off when there are at least that many
         int big_waves = 0;
         if (variant == kVariantPrefillBig8) big_waves = 8;
         if (variant == kVariantPrefillBig || variant == kVariantPrefillBigWhole ||
-            (variant == 0 && out >= 256 && bd::prefill_big_fits(T, out, in)))
+            (variant == 0 && big_default))
             big_waves = 4;
         return run_prefill(x_f16, w_base_f16, packed_by_tenant, alpha_by_tenant, tenant_of_token, y_f16, T, out, in,
                            workspace, hs, big_waves, variant != kVariantPrefillBigWhole) == hipSuccess
