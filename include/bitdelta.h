@@ -99,10 +99,12 @@ bd_status bd_compress(const uint16_t* w_base_f16, const uint16_t* w_ft_f16,
  * the result is rounded once to fp16 (nearest even).
  * T == 0 or out == 0 is a no-op returning BD_OK.  T up to 65535.
  * Up to 32 tokens run as one decode launch and need no workspace.  More tokens (the prefill regime
- * of Sec. 4.3: many tokens per tenant) run as ONE matrix-core GEMM launch over all tokens if
+ * of Sec. 4.3: many tokens per tenant) can run as ONE matrix-core GEMM launch over all tokens if
  * `workspace` holds bd_workspace_bytes(BD_OP_LINEAR_MULTITENANT, T, out, in, n_tenants) bytes
- * (256-byte aligned; it receives the token permutation); with a NULL or smaller workspace the same
- * result is produced by ceil(T / 32) decode launches, each re-reading the base. */
+ * (256-byte aligned; it receives the token permutation).  With a NULL or smaller workspace the same
+ * result is produced by ceil(T / 32) decode launches, each re-reading the base; with a workspace the
+ * library takes whichever of the two a cost estimate on the host says is quicker (GEMM tiles hold one
+ * tenant's tokens only, so a batch with a few tokens per tenant is cheaper as decode launches). */
 bd_status bd_linear_multitenant(const uint16_t* x_f16, const uint16_t* w_base_f16,
                                 const uint32_t* const* packed_by_tenant,
                                 const float* alpha_by_tenant,
