@@ -425,17 +425,19 @@ bd_status tiled_linear_impl(int32_t n_mats, const uint16_t* x_f16, const uint16_
                 if (misaligned(p, 16)) return BD_ERR_ALIGN;
             }
     }
-    // A token takes k columns (one per plane) of a 16-column tile; a launch covers two tiles.
+    // A token takes k columns (one per plane) of a 16-column tile; a launch covers two tiles.  More tokens than one
+    // launch takes: all of them are sorted by tenant first (stable), so that a tenant's tokens share launches and
+    // its delta is streamed as few times as possible; the kernel finds the rows of x and y through the token ids.
     const int per_tile = bd::kTiledMaxTokens / k;
     const int per_launch = per_tile * bd::kTiledMaxCt;
+    std::vector<int32_t> order((size_t)T);
+    for (int64_t i = 0; i < T; ++i) order[(size_t)i] = (int32_t)i;
+    std::stable_sort(order.begin(), order.end(), [&](int32_t p, int32_t q) { return tenant_of_token[p] < tenant_of_token[q]; });
     for (int64_t t0 = 0; t0 < T; t0 += per_launch) {
         const int n = (int)std::min<int64_t>(per_launch, T - t0);
-        int order[bd::kTiledMaxTokens * bd::kTiledMaxCt];
-        for (int i = 0; i < n; ++i) order[i] = i;
-        std::stable_sort(order, order + n, [&](int p, int q) { return tenant_of_token[t0 + p] < tenant_of_token[t0 + q]; });
         bd::TiledArgs a;
         std::memset(&a, 0, sizeof(a));
-        a.x = x_f16 + t0 * in;
+        a.x = x_f16;
         a.in = (int32_t)in;
         a.KT = (int32_t)bd::tiled_k_tiles(in);
         a.n_ct = n > per_tile ? 2 : 1;
@@ -446,7 +448,7 @@ bd_status tiled_linear_impl(int32_t n_mats, const uint16_t* x_f16, const uint16_
         for (int m = 0; m < n_mats; ++m) {
             if (out[m] == 0) continue;
             a.wt[mats] = w_tiled[m];
-            a.y[mats] = y_f16[m] + t0 * out[m];
+            a.y[mats] = y_f16[m];
             a.alpha[mats] = alpha_by_mat[m];
             if (q8)   // the scales follow the tiles
                 a.wscale[mats] = (const float*)((const unsigned char*)w_tiled[m] +
@@ -466,8 +468,8 @@ bd_status tiled_linear_impl(int32_t n_mats, const uint16_t* x_f16, const uint16_
             int n_runs = 0, run_tenant[bd::kTiledMaxTokens];
             int col = 0;
             for (int i = tok_begin; i < tok_end; ++i) {
-                const int tok = order[i];
-                const int tenant = tenant_of_token[t0 + tok];
+                const int tok = order[(size_t)(t0 + i)];
+                const int tenant = tenant_of_token[tok];
                 if (n_runs == 0 || run_tenant[n_runs - 1] != tenant) run_tenant[n_runs++] = tenant;
                 for (int j = 0; j < k; ++j, ++col) {   // the token's columns: plane j is job slot (run, j)
                     a.col_token[ct][col] = tok;

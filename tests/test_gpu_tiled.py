@@ -73,6 +73,7 @@ CASES = [
     (40, 96, 2, [1, 0, 1]),                                          # K % 128 != 0
     (64, 11008, 16, list(range(15, -1, -1))),                        # the down-projection's K: 43 tiles
     (80, 2048, 6, [5] * 6 + [1] * 5 + [2] * 5 + [0] * 4 + [1] * 3),  # 23 tokens of 4 tenants: two column tiles, few jobs each
+    (48, 1024, 9, [(7 * i) % 9 for i in range(70)]),                 # 70 interleaved tokens: three launches, each tenant's tokens gathered from all over the batch
 ]
 
 
