@@ -160,9 +160,10 @@ bd_status bd_tile_signs(const uint32_t* packed, int64_t out, int64_t in, uint32_
  *                    Entries of tenants without a token in this call may be NULL.
  *   alpha_by_tenant  device array of n_tenants floats
  *   tenant_of_token  HOST [T]; x_f16 [T, in]; y_f16 [T, out], must not overlap x or w_tiled.
- * Tokens are grouped by tenant inside the call; up to 32 tokens are one launch (two 16-column tiles
- * that share the base registers), more run as several launches of 32 (the base is then streamed once
- * per launch).  Needs no workspace. */
+ * Tokens are grouped by tenant inside the call, over the whole batch; up to 32 tokens are one launch
+ * (two 16-column tiles that share the base registers), more run as several launches of 32 consecutive
+ * tokens of the grouped order (the base is then streamed once per launch, a delta once per launch that
+ * holds one of its tenant's tokens).  Needs no workspace. */
 bd_status bd_linear_multitenant_tiled(const uint16_t* x_f16, const uint16_t* w_tiled,
                                       const uint32_t* const* tiled_by_tenant,
                                       const float* alpha_by_tenant,
