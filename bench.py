@@ -502,6 +502,22 @@ def main():
         }
         del naive, naive2
         extras["compress_GBs"] = round(compress_bytes / (compress_ms * 1e-3) / 1e9, 1) if compress_ms > 0 else None
+        if not q8 and k == 1:
+            # the same compressor with the matrices of a layer in one call (bd_compress_batch): whole-call rate
+            cb_bases = [synth.base_weight(out, inn, device=dev, tag=("L", 0, name)) for name, out, inn in shapes]
+            cb_fts = [synth.finetuned_weight(b, sigma=sigma, tag=("L", 0, name, 0)) for b, (name, _, _) in zip(cb_bases, shapes)]
+            ws_b = bd.new_workspace(bd.COMPRESS_BATCH_MAX * bd.workspace_bytes(bd.OP_COMPRESS, 0, 1, 32, 1), dev)
+            best = None
+            for _ in range(4):
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                bd.compress_batch(cb_bases, cb_fts, workspace=ws_b)
+                e1.record()
+                e1.synchronize()
+                ms = e0.elapsed_time(e1)
+                best = ms if best is None or ms < best else best
+            extras["compress_batch_GBs"] = round(sum(o * i for _, o, i in shapes) * 4.125 / (best * 1e-3) / 1e9, 1)
+            del cb_bases, cb_fts
     result["extras"] = extras
 
     # ---- the oracle on the host cores, one layer of the same workload

@@ -85,6 +85,19 @@ bd_status bd_compress(const uint16_t* w_base_f16, const uint16_t* w_ft_f16,
                       uint32_t* packed, float* alpha,
                       void* workspace, size_t workspace_bytes, void* stream);
 
+/* bd_compress for n matrices (say, the linears of one layer of one fine-tune) in two launches instead of
+ * 2 n: same arithmetic, and matrix m is cut into blocks exactly as bd_compress would cut it, so packed[m] and
+ * alpha[m] are bit for bit what n separate calls give.
+ *   w_base_f16, w_ft_f16, packed, out, in   HOST arrays of n entries (the pointers in them: device memory)
+ *   alpha                                   device array of n floats
+ *   workspace                               BD_COMPRESS_BATCH_MAX * bd_workspace_bytes(BD_OP_COMPRESS, ...) bytes
+ * More than BD_COMPRESS_BATCH_MAX matrices run as several such pairs of launches.  Errors as bd_compress;
+ * no packed[m] may overlap any input matrix or another packed[o] (BD_ERR_ALIAS). */
+#define BD_COMPRESS_BATCH_MAX 8
+bd_status bd_compress_batch(int32_t n, const uint16_t* const* w_base_f16, const uint16_t* const* w_ft_f16,
+                            const int64_t* out, const int64_t* in, uint32_t* const* packed, float* alpha,
+                            void* workspace, size_t workspace_bytes, void* stream);
+
 /* The multi-tenant linear of Eq. 6.
  *   x_f16            [T, in]   fp16 activations, one row per token
  *   w_base_f16       [out, in] fp16 base weight shared by every token

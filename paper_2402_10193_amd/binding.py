@@ -22,7 +22,8 @@ STATUS_NAMES = {0: "BD_OK", 1: "BD_ERR_NULL", 2: "BD_ERR_SHAPE", 3: "BD_ERR_ALIG
 OP_PACK_SIGNS, OP_COMPRESS, OP_LINEAR_MULTITENANT = 0, 1, 2
 
 # every symbol include/bitdelta.h declares
-EXPORTS = ["bd_status_string", "bd_version", "bd_workspace_bytes", "bd_pack_signs", "bd_compress", "bd_group_tokens",
+EXPORTS = ["bd_status_string", "bd_version", "bd_workspace_bytes", "bd_pack_signs", "bd_compress", "bd_compress_batch",
+           "bd_group_tokens",
            "bd_linear_multitenant", "bd_linear_multitenant_variant", "bd_materialize", "bd_linear_naive",
            "bd_probe_read", "bd_probe_copy", "bd_tiled_base_bytes", "bd_tiled_signs_bytes", "bd_tile_base",
            "bd_tile_signs", "bd_linear_multitenant_tiled", "bd_linear_multitenant_tiled_group", "bd_compress_iterated",
@@ -97,6 +98,8 @@ def lib() -> ctypes.CDLL:
         L.bd_linear_multitenant_tiled_q8.argtypes = [vp, vp, pvp, vp, pi, vp, i64, i64, i64, i32, vp]
         L.bd_linear_multitenant_tiled_group_q8.argtypes = [i32, vp, pvp, pvp, pvp, pi, pvp, i64, pi64, i64, i32, vp]
         L.bd_compress_iterated.argtypes = [vp, vp, i64, i64, i32, vp, vp, vp, sz, vp]
+        L.bd_compress_batch.argtypes = [i32, pvp, pvp, pi64, pi64, pvp, vp, vp, sz, vp]
+        L.bd_compress_batch.restype = ctypes.c_int
         L.bd_linear_multitenant_tiled_kbit.argtypes = [vp, vp, pvp, vp, pi, vp, i64, i64, i64, i32, i32, vp]
         L.bd_linear_multitenant_tiled_group_kbit.argtypes = [i32, vp, pvp, pvp, pvp, pi, pvp, i64, pi64, i64, i32, i32, vp]
         for name in ("bd_pack_signs", "bd_compress", "bd_linear_multitenant", "bd_linear_multitenant_variant",
@@ -179,6 +182,37 @@ def compress(w_base: torch.Tensor, w_ft: torch.Tensor, packed: Optional[torch.Te
         workspace = new_workspace(workspace_bytes(OP_COMPRESS, 0, out, inn, 1), dev)
     _check(lib().bd_compress(_ptr(w_base), _ptr(w_ft), out, inn, _ptr(packed), _ptr(alpha), _ptr(workspace),
                              workspace.numel(), _stream(stream)), "bd_compress")
+    return packed, alpha
+
+
+COMPRESS_BATCH_MAX = 8
+
+
+def compress_batch(w_bases: Sequence[torch.Tensor], w_fts: Sequence[torch.Tensor],
+                   workspace: Optional[torch.Tensor] = None, stream=None):
+    """bd_compress_batch: several matrices of one fine-tune in one call.  Returns (list of packed int32 [out, in/32],
+    alpha float32 [n]) on the device."""
+    n = len(w_bases)
+    if len(w_fts) != n:
+        raise ValueError("one fine-tuned matrix per base matrix")
+    if n == 0:
+        return [], torch.empty((0,), dtype=torch.float32)
+    dev = w_bases[0].device
+    packed = []
+    for b, f in zip(w_bases, w_fts):
+        _dev(b, torch.float16, "w_base")
+        _dev(f, torch.float16, "w_ft")
+        if b.shape != f.shape:
+            raise ValueError("w_base and w_ft differ in shape")
+        packed.append(torch.empty((b.shape[0], max(b.shape[1] // 32, 0)), dtype=torch.int32, device=dev))
+    alpha = torch.empty((n,), dtype=torch.float32, device=dev)
+    if workspace is None:
+        workspace = new_workspace(COMPRESS_BATCH_MAX * workspace_bytes(OP_COMPRESS, 0, 1, 32, 1), dev)
+    ptrs = lambda ts: (ctypes.c_void_p * n)(*[_ptr(t) or None for t in ts])
+    outs = (ctypes.c_int64 * n)(*[int(b.shape[0]) for b in w_bases])
+    ins = (ctypes.c_int64 * n)(*[int(b.shape[1]) for b in w_bases])
+    _check(lib().bd_compress_batch(n, ptrs(w_bases), ptrs(w_fts), outs, ins, ptrs(packed), _ptr(alpha), _ptr(workspace),
+                                   workspace.numel(), _stream(stream)), "bd_compress_batch")
     return packed, alpha
 
 

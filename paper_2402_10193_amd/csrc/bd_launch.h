@@ -18,6 +18,19 @@ hipError_t launch_pack_signs(const uint16_t* delta, int64_t out, int64_t in, uin
 hipError_t launch_compress(const uint16_t* base, const uint16_t* ft, int64_t out, int64_t in, uint32_t* packed,
                            float* alpha, double* partial, hipStream_t st, const float* alpha_prev = nullptr, int n_prev = 0);
 
+// Several matrices of one fine-tune through the compressor in one launch (plus one to finish the scales).
+constexpr int kCompressBatchMax = 8;
+struct CompressBatch {
+    const uint16_t* base[kCompressBatchMax];
+    const uint16_t* ft[kCompressBatchMax];
+    uint32_t* packed[kCompressBatchMax];
+    int64_t n_vec[kCompressBatchMax];    // out * in / 8 of each matrix
+    int32_t blocks[kCompressBatchMax];   // filled in by the launcher
+    int32_t n;
+};
+// alpha: n floats; partial: n * kCompressMaxBlocks binary64 sums
+hipError_t launch_compress_batch(CompressBatch a, float* alpha, double* partial, hipStream_t st);
+
 // Plain vector-ALU linear: any T <= kMaxDecodeTokens per launch, tokens in caller order.
 hipError_t launch_linear_rowwave(const uint16_t* x, const uint16_t* w, const uint32_t* const* packed_by_tenant,
                                  const float* alpha_by_tenant, const DecodeMeta& meta, uint16_t* y, int64_t out,

@@ -242,6 +242,46 @@ bd_status bd_compress(const uint16_t* w_base_f16, const uint16_t* w_ft_f16, int6
                : BD_ERR_DEVICE;
 }
 
+bd_status bd_compress_batch(int32_t n, const uint16_t* const* w_base_f16, const uint16_t* const* w_ft_f16,
+                            const int64_t* out, const int64_t* in, uint32_t* const* packed, float* alpha, void* workspace,
+                            size_t workspace_bytes, void* stream) {
+    if (n < 0) return BD_ERR_SHAPE;
+    if (n == 0) return BD_OK;
+    if (!w_base_f16 || !w_ft_f16 || !out || !in || !packed || !alpha) return BD_ERR_NULL;
+    if (misaligned(alpha, 4)) return BD_ERR_ALIGN;
+    for (int32_t m = 0; m < n; ++m) {
+        if (out[m] < 0 || in[m] < 0 || in[m] % 32 != 0) return BD_ERR_SHAPE;
+        if (out[m] == 0 || in[m] == 0) continue;
+        if (!w_base_f16[m] || !w_ft_f16[m] || !packed[m]) return BD_ERR_NULL;
+        if (misaligned(w_base_f16[m], 16) || misaligned(w_ft_f16[m], 16) || misaligned(packed[m], 16)) return BD_ERR_ALIGN;
+        const size_t wbytes = (size_t)out[m] * in[m] * 2, pbytes = (size_t)out[m] * in[m] / 8;
+        for (int32_t o = 0; o < n; ++o) {   // no plane of signs may lie over any matrix that is still to be read
+            if (out[o] == 0 || in[o] == 0) continue;
+            const size_t obytes = (size_t)out[o] * in[o] * 2;
+            if (overlaps(packed[m], pbytes, w_base_f16[o], obytes) || overlaps(packed[m], pbytes, w_ft_f16[o], obytes))
+                return BD_ERR_ALIAS;
+            if (o != m && overlaps(packed[m], pbytes, packed[o], (size_t)out[o] * in[o] / 8)) return BD_ERR_ALIAS;
+        }
+        (void)wbytes;
+    }
+    const size_t need = (size_t)BD_COMPRESS_BATCH_MAX * bd_workspace_bytes(BD_OP_COMPRESS, 0, 1, 32, 1);
+    if (!workspace || workspace_bytes < need || misaligned(workspace, 256)) return BD_ERR_WORKSPACE;
+    for (int32_t m0 = 0; m0 < n; m0 += bd::kCompressBatchMax) {   // launches of up to 8 matrices, in stream order
+        bd::CompressBatch a;
+        std::memset(&a, 0, sizeof(a));
+        a.n = std::min<int32_t>(bd::kCompressBatchMax, n - m0);
+        for (int i = 0; i < a.n; ++i) {
+            const int32_t m = m0 + i;
+            a.base[i] = w_base_f16[m];
+            a.ft[i] = w_ft_f16[m];
+            a.packed[i] = packed[m];
+            a.n_vec[i] = out[m] * in[m] / 8;
+        }
+        if (bd::launch_compress_batch(a, alpha + m0, (double*)workspace, (hipStream_t)stream) != hipSuccess) return BD_ERR_DEVICE;
+    }
+    return BD_OK;
+}
+
 bd_status bd_compress_iterated(const uint16_t* w_base_f16, const uint16_t* w_ft_f16, int64_t out, int64_t in, int32_t k,
                                uint32_t* packed, float* alpha, void* workspace, size_t workspace_bytes, void* stream) {
     if (out < 0 || in < 0 || in % 32 != 0 || k < 1 || k > bd::kCompressMaxPlanes) return BD_ERR_SHAPE;

@@ -156,6 +156,50 @@ __global__ __launch_bounds__(kCompressThreads) void compress_q8_kernel(
     }
 }
 
+// The compressor (no earlier planes) over up to kCompressBatchMax matrices in one launch.  Matrix m is cut into
+// blocks[m] blocks exactly as a launch of compress_kernel for it alone would be, so its partial sums -- and with
+// them its scale -- are the same bit for bit.
+__global__ __launch_bounds__(kCompressThreads) void compress_batch_kernel(const CompressBatch a, double* __restrict__ partial) {
+    __shared__ double wave_part[kCompressThreads / kWave];
+    const int lane = threadIdx.x & (kWave - 1);
+    for (int m = 0; m < a.n; ++m) {
+        if ((int)blockIdx.x >= a.blocks[m]) continue;   // uniform per block
+        const u32x4* __restrict__ base = (const u32x4*)a.base[m];
+        const u32x4* __restrict__ ft = (const u32x4*)a.ft[m];
+        uint32_t* __restrict__ packed = a.packed[m];
+        const int64_t n_vec = a.n_vec[m];
+        const int64_t stride = (int64_t)a.blocks[m] * kCompressThreads;
+        double s = 0.0;
+        for (int64_t i = (int64_t)blockIdx.x * kCompressThreads + threadIdx.x; i < n_vec; i += stride) {
+            const u32x4 b = __builtin_nontemporal_load(base + i);
+            const u32x4 f = __builtin_nontemporal_load(ft + i);
+            const uint32_t bw[4] = {b[0], b[1], b[2], b[3]};
+            const uint32_t fw[4] = {f[0], f[1], f[2], f[3]};
+            uint32_t byte = 0;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const float vb = h2f((uint16_t)(bw[e >> 1] >> (16 * (e & 1))));
+                const float vf = h2f((uint16_t)(fw[e >> 1] >> (16 * (e & 1))));
+                const float d = vf - vb;
+                byte |= (d > 0.0f ? 1u : 0u) << e;
+                s += (double)__builtin_fabsf(d);
+            }
+            const uint32_t word = merge_quad_bytes(byte, lane);
+            if ((lane & 3) == 0) packed[i >> 2] = word;
+        }
+        s = wave_sum(s);
+        if (lane == 0) wave_part[threadIdx.x / kWave] = s;
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            double t = 0.0;
+#pragma unroll
+            for (int w = 0; w < kCompressThreads / kWave; ++w) t += wave_part[w];
+            partial[(size_t)m * kCompressMaxBlocks + blockIdx.x] = t;
+        }
+        __syncthreads();   // wave_part is free again
+    }
+}
+
 // alpha = fp16_rne( sum(partial) / count ), one block, fixed summation order.
 __global__ __launch_bounds__(256) void alpha_finalize_kernel(const double* __restrict__ partial, int n_partial,
                                                              double count, float* __restrict__ alpha) {
@@ -172,6 +216,28 @@ __global__ __launch_bounds__(256) void alpha_finalize_kernel(const double* __res
         const double mean = count > 0.0 ? sm[0] / count : 0.0;
         const float m32 = (float)mean;
         *alpha = (float)(_Float16)m32;   // one rounding to fp16, carried as a float
+    }
+}
+
+// the same per matrix of a batch: block m finishes matrix m
+__global__ __launch_bounds__(256) void alpha_finalize_batch_kernel(const double* __restrict__ partial, const CompressBatch a,
+                                                                   float* __restrict__ alpha) {
+    __shared__ double sm[256];
+    const int m = blockIdx.x;
+    const double* p = partial + (size_t)m * kCompressMaxBlocks;
+    double t = 0.0;
+    for (int i = threadIdx.x; i < a.blocks[m]; i += 256) t += p[i];
+    sm[threadIdx.x] = t;
+    __syncthreads();
+    for (int w = 128; w >= 1; w >>= 1) {
+        if ((int)threadIdx.x < w) sm[threadIdx.x] += sm[threadIdx.x + w];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) {
+        const double count = (double)a.n_vec[m] * 8.0;
+        const double mean = count > 0.0 ? sm[0] / count : 0.0;
+        const float m32 = (float)mean;
+        alpha[m] = (float)(_Float16)m32;
     }
 }
 
@@ -213,6 +279,22 @@ hipError_t launch_compress(const uint16_t* base, const uint16_t* ft, int64_t out
     }
     hipLaunchKernelGGL(alpha_finalize_kernel, dim3(1), dim3(256), 0, st, (const double*)partial, blocks,
                        (double)out * (double)in, alpha);
+    return hipGetLastError();
+}
+
+hipError_t launch_compress_batch(CompressBatch a, float* alpha, double* partial, hipStream_t st) {
+    if (a.n < 1 || a.n > kCompressBatchMax) return hipErrorInvalidValue;
+    int grid = 0;
+    for (int m = 0; m < a.n; ++m) {
+        a.blocks[m] = a.n_vec[m] > 0 ? compress_grid_blocks(a.n_vec[m]) : 0;
+        grid = a.blocks[m] > grid ? a.blocks[m] : grid;
+    }
+    if (grid > 0) {
+        hipLaunchKernelGGL(compress_batch_kernel, dim3(grid), dim3(kCompressThreads), 0, st, a, partial);
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL(alpha_finalize_batch_kernel, dim3(a.n), dim3(256), 0, st, (const double*)partial, a, alpha);
     return hipGetLastError();
 }
 

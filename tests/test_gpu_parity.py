@@ -82,6 +82,27 @@ CASES = [
 ]
 
 
+def test_compress_batch_equals_separate_calls_and_the_oracle(ref):
+    """Several matrices per call: the same bits and the same scales as one bd_compress per matrix, and as the oracle."""
+    shapes = [(48, 1024), (272, 2176), (0, 64), (1, 32), (300, 512), (64, 4096), (1024, 1024), (17, 96), (33, 64), (5, 0), (640, 256)]
+    _p(f"compress_batch {len(shapes)} matrices")
+    bases = [synth.base_weight(o, i, device=DEV, tag=("cb", n)) for n, (o, i) in enumerate(shapes)]
+    fts = [synth.finetuned_weight(b, sigma=0.002, tag=("cb", n, "ft")) for n, b in enumerate(bases)]
+    packed, alpha = bd.compress_batch(bases, fts)            # 11 matrices: two launches of the batch kernel
+    torch.cuda.synchronize()
+    assert alpha.shape == (len(shapes),)
+    for n, (o, i) in enumerate(shapes):
+        p1, a1 = bd.compress(bases[n], fts[n])
+        assert torch.equal(packed[n], p1), f"matrix {n}"
+        assert float(alpha[n].item()) == float(a1.item()), f"matrix {n}"
+        if o > 0 and i > 0:
+            p_ref, a_ref, _ = ref.compress(to_np(bases[n]), to_np(fts[n]))
+            assert np.array_equal(packed_to_np(packed[n]), p_ref), f"matrix {n} against the oracle"
+            assert float(alpha[n].item()) == a_ref
+        else:
+            assert float(alpha[n].item()) == 0.0
+
+
 @pytest.mark.parametrize("variant", VARIANTS)
 @pytest.mark.parametrize("case", range(len(CASES)))
 def test_linear_matches_oracle(ref, case, variant):

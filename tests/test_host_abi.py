@@ -103,6 +103,36 @@ def test_compress_and_pack_argument_errors(bd):
     assert L.bd_materialize(A, 2 * A, 0, 3 * A, 16, 64, 0) == 1
 
 
+def test_compress_batch_argument_errors(bd):
+    import ctypes
+    L = bd.lib()
+    need = bd.COMPRESS_BATCH_MAX * bd.workspace_bytes(bd.OP_COMPRESS, 0, 16, 128, 1)
+    c = L.bd_compress_batch
+
+    def ptrs(*v):
+        return (ctypes.c_void_p * len(v))(*[x or None for x in v])
+
+    def i64s(*v):
+        return (ctypes.c_int64 * len(v))(*v)
+
+    MB = 1 << 20   # far enough apart that the 16 x 128 matrices never overlap
+    bases, fts, pk = ptrs(A, A + MB), ptrs(A + 2 * MB, A + 3 * MB), ptrs(A + 4 * MB, A + 5 * MB)
+    outs, ins = i64s(16, 16), i64s(128, 128)
+    assert c(0, None, None, None, None, None, 0, 0, 0, 0) == 0                       # nothing to do
+    assert c(-1, bases, fts, outs, ins, pk, 6 * A, 7 * A, need, 0) == 2
+    assert c(2, bases, fts, outs, i64s(128, 100), pk, 6 * A, 7 * A, need, 0) == 2      # in % 32
+    assert c(2, None, fts, outs, ins, pk, 6 * A, 7 * A, need, 0) == 1
+    assert c(2, bases, fts, outs, ins, pk, 0, 7 * A, need, 0) == 1                     # alpha
+    assert c(2, ptrs(A, 0), fts, outs, ins, pk, 6 * A, 7 * A, need, 0) == 1            # one matrix missing
+    assert c(2, ptrs(A, A + MB + 4), fts, outs, ins, pk, 6 * A, 7 * A, need, 0) == 3
+    assert c(2, bases, fts, outs, ins, pk, 6 * A, 0, need, 0) == 5
+    assert c(2, bases, fts, outs, ins, pk, 6 * A, 7 * A, need - 1, 0) == 5
+    assert c(2, bases, fts, outs, ins, ptrs(A + 4 * MB, A + 1024), 6 * A, 7 * A, need, 0) == 8   # signs of 1 over base 0
+    assert c(2, bases, fts, outs, ins, ptrs(A + 4 * MB, A + 4 * MB + 128), 6 * A, 7 * A, need, 0) == 8   # signs over signs
+    # an empty matrix needs no pointers
+    assert c(1, ptrs(0), ptrs(0), i64s(0), i64s(128), ptrs(0), 6 * A, 0, 0, 0) == 5    # but the call still wants its workspace
+
+
 def test_tiled_sizes_and_argument_errors(bd):
     L = bd.lib()
     # sizes: tiles of 16 rows x 256 k, 8 KiB of base and 512 B of signs each; zero for rejected shapes
