@@ -137,14 +137,16 @@ __device__ __forceinline__ void prefill_big_tile(
     }
     __builtin_amdgcn_sched_barrier(0);
 
-    if (tid < 256) {   // byte -> 8 fp16 (+1.0 where the bit is set, else -1.0), element e = bit e; entry [byte][copy]
-        const uint32_t bb = (uint32_t)tid;
+    // byte -> 8 fp16 (+1.0 where the bit is set, else -1.0), element e = bit e; entry [byte][copy].  Consecutive lanes
+    // write consecutive 16-byte copies (a wavefront 1 KiB at a stretch; a lane per entry would put its writes 128
+    // bytes apart, several of them on every bank).
+    for (int q = tid; q < 256 * 8; q += kThreads) {
+        const uint32_t bb = (uint32_t)q >> 3;
         u32x4 e;
 #pragma unroll
         for (int i = 0; i < 4; ++i)
             e[i] = 0xBC00BC00u ^ (((bb >> (2 * i)) & 1u) << 15) ^ (((bb >> (2 * i + 1)) & 1u) << 31);
-#pragma unroll
-        for (int cp = 0; cp < 8; ++cp) *(u32x4*)(lut + bb * 128 + cp * 16) = e;
+        *(u32x4*)(lut + q * 16) = e;
     }
     const lds_bytes lut_lane = lds_at(2 * kBgBufBytes + (lane & 7) * 16);
     __builtin_amdgcn_sched_barrier(0);
