@@ -115,7 +115,7 @@ def run_prefill(args, torch, bd, synth, dev):
         "config": {"workload": "prefill: 8 tenants x 512 tokens, linears 4096->11008 and 11008->4096 (one step = both)",
                    "tenants": B, "tokens": T},
         "roofline": {"bound": "mfma", "achieved": round(tflops, 1), "peak": MFMA_F16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                     "frac": round(tflops / MFMA_F16_PEAK_TFLOPS, 4), "traffic": None, "kernel": "linear_prefill_kernel",
+                     "frac": round(tflops / MFMA_F16_PEAK_TFLOPS, 4), "traffic": None, "kernel": "linear_prefill_big_kernel" if args.variant != 4 else "linear_prefill_kernel",
                      "flops_per_launch": flops / 2, "avg_launch_us": round(ms * 1e3 / 2, 2),
                      "useful_fraction_note": "half of the flops are the base product, half the +-1 delta product"},
     }))
