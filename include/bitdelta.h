@@ -11,7 +11,8 @@
  * Conventions shared by every entry point
  *   - Plain C, no exceptions.  Every call returns a bd_status; BD_OK is 0.
  *   - Unless a parameter says HOST, pointers are DEVICE pointers owned by the caller.  The
- *     library never allocates or frees device memory and keeps no state between calls.
+ *     library never allocates or frees device memory and keeps no state between calls (one
+ *     exception, stated there: bd_compress_noalloc uses a fixed array inside the library).
  *   - fp16 tensors are passed as uint16_t bit patterns (IEEE binary16).
  *   - A weight matrix is [out, in] row-major: `in` (the reduction dimension) is contiguous.
  *     `in` must be a multiple of 32, otherwise BD_ERR_SHAPE.
@@ -48,7 +49,8 @@ typedef enum bd_status {
     BD_ERR_UNSUPPORTED = 7, /* unknown kernel variant, or one that cannot run these sizes */
     BD_ERR_ALIAS = 8,       /* an output range overlaps an input range */
     BD_ERR_FORMAT = 9,      /* a delta image is malformed (magic, sizes, offsets, checksum) */
-    BD_ERR_IO = 10          /* a file could not be opened, read or written */
+    BD_ERR_IO = 10,         /* a file could not be opened, read or written */
+    BD_ERR_TOO_LARGE = 11   /* a size beyond the fixed limit of an entry point that brings its own scratch */
 } bd_status;
 
 typedef enum bd_op {
@@ -84,6 +86,21 @@ bd_status bd_compress(const uint16_t* w_base_f16, const uint16_t* w_ft_f16,
                       int64_t out, int64_t in,
                       uint32_t* packed, float* alpha,
                       void* workspace, size_t workspace_bytes, void* stream);
+
+/* bd_compress for callers that cannot allocate device memory or carry a workspace around: code under HIP graph
+ * capture, tight serving loops that compress an incoming fine-tune between decode steps, harnesses that forbid
+ * hipMalloc.  Same kernels, same arithmetic and the same bits in packed and *alpha as bd_compress; the partial sums
+ * of Eq. 4 go to an array inside the library instead (16 KiB of device memory per GPU the library runs on, held until
+ * the process ends; its address is looked up on the first call on each device).  The call allocates and frees nothing.
+ *   out * in <= BD_COMPRESS_NOALLOC_MAX_ELEMENTS, else BD_ERR_TOO_LARGE (nothing launched); other errors as
+ *   bd_compress.
+ * All calls on one GPU share that array: two of them may not overlap in time (different streams without an
+ * ordering between them race; calls on one stream are ordered and safe).  Nothing in the array has to be
+ * cleared between calls: every slot that is read has been written by the same call before. */
+#define BD_COMPRESS_NOALLOC_MAX_ELEMENTS ((int64_t)1 << 32)
+bd_status bd_compress_noalloc(const uint16_t* w_base_f16, const uint16_t* w_ft_f16,
+                              int64_t out, int64_t in,
+                              uint32_t* packed, float* alpha, void* stream);
 
 /* bd_compress for n matrices (say, the linears of one layer of one fine-tune) in two launches instead of
  * 2 n: same arithmetic, and matrix m is cut into blocks exactly as bd_compress would cut it, so packed[m] and

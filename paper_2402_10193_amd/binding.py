@@ -18,11 +18,11 @@ LIB_PATH = os.environ.get("BITDELTA_LIB") or os.path.join(_PKG, "libbitdelta.so"
 BD_OK = 0
 STATUS_NAMES = {0: "BD_OK", 1: "BD_ERR_NULL", 2: "BD_ERR_SHAPE", 3: "BD_ERR_ALIGN", 4: "BD_ERR_TENANT",
                 5: "BD_ERR_WORKSPACE", 6: "BD_ERR_DEVICE", 7: "BD_ERR_UNSUPPORTED", 8: "BD_ERR_ALIAS",
-                9: "BD_ERR_FORMAT", 10: "BD_ERR_IO"}
+                9: "BD_ERR_FORMAT", 10: "BD_ERR_IO", 11: "BD_ERR_TOO_LARGE"}
 OP_PACK_SIGNS, OP_COMPRESS, OP_LINEAR_MULTITENANT = 0, 1, 2
 
 # every symbol include/bitdelta.h declares
-EXPORTS = ["bd_status_string", "bd_version", "bd_workspace_bytes", "bd_pack_signs", "bd_compress", "bd_compress_batch",
+EXPORTS = ["bd_status_string", "bd_version", "bd_workspace_bytes", "bd_pack_signs", "bd_compress", "bd_compress_noalloc", "bd_compress_batch",
            "bd_group_tokens",
            "bd_linear_multitenant", "bd_linear_multitenant_variant", "bd_materialize", "bd_linear_naive",
            "bd_probe_read", "bd_probe_copy", "bd_tiled_base_bytes", "bd_tiled_signs_bytes", "bd_tile_base",
@@ -60,6 +60,7 @@ def lib() -> ctypes.CDLL:
         L.bd_workspace_bytes.argtypes = [ctypes.c_int, i64, i64, i64, i32]
         L.bd_pack_signs.argtypes = [vp, i64, i64, vp, vp]
         L.bd_compress.argtypes = [vp, vp, i64, i64, vp, vp, vp, sz, vp]
+        L.bd_compress_noalloc.argtypes = [vp, vp, i64, i64, vp, vp, vp]
         L.bd_linear_multitenant.argtypes = [vp, vp, vp, vp, ctypes.POINTER(i32), vp, i64, i64, i64, i32, vp, sz, vp]
         L.bd_linear_multitenant_variant.argtypes = [vp, vp, vp, vp, ctypes.POINTER(i32), vp, i64, i64, i64, i32, vp,
                                                     sz, vp, i32]
@@ -182,6 +183,26 @@ def compress(w_base: torch.Tensor, w_ft: torch.Tensor, packed: Optional[torch.Te
         workspace = new_workspace(workspace_bytes(OP_COMPRESS, 0, out, inn, 1), dev)
     _check(lib().bd_compress(_ptr(w_base), _ptr(w_ft), out, inn, _ptr(packed), _ptr(alpha), _ptr(workspace),
                              workspace.numel(), _stream(stream)), "bd_compress")
+    return packed, alpha
+
+
+COMPRESS_NOALLOC_MAX_ELEMENTS = 1 << 32
+
+
+def compress_noalloc(w_base: torch.Tensor, w_ft: torch.Tensor, packed: torch.Tensor, alpha: torch.Tensor, stream=None):
+    """bd_compress_noalloc: the caller brings both outputs (packed int32 [out, in/32], alpha float32 [1]);
+    nothing is allocated here or in the library."""
+    _dev(w_base, torch.float16, "w_base")
+    _dev(w_ft, torch.float16, "w_ft")
+    _dev(packed, torch.int32, "packed")
+    _dev(alpha, torch.float32, "alpha")
+    if w_base.shape != w_ft.shape:
+        raise ValueError("w_base and w_ft differ in shape")
+    out, inn = w_base.shape
+    if packed.numel() != out * (inn // 32) or alpha.numel() < 1:
+        raise ValueError("packed must hold out * in / 32 words and alpha one float")
+    _check(lib().bd_compress_noalloc(_ptr(w_base), _ptr(w_ft), out, inn, _ptr(packed), _ptr(alpha), _stream(stream)),
+           "bd_compress_noalloc")
     return packed, alpha
 
 

@@ -18,6 +18,10 @@ hipError_t launch_pack_signs(const uint16_t* delta, int64_t out, int64_t in, uin
 hipError_t launch_compress(const uint16_t* base, const uint16_t* ft, int64_t out, int64_t in, uint32_t* packed,
                            float* alpha, double* partial, hipStream_t st, const float* alpha_prev = nullptr, int n_prev = 0);
 
+// the same with the partial sums in the library's own per-device array (no workspace, nothing allocated)
+hipError_t launch_compress_noalloc(const uint16_t* base, const uint16_t* ft, int64_t out, int64_t in, uint32_t* packed,
+                                   float* alpha, hipStream_t st);
+
 // Several matrices of one fine-tune through the compressor in one launch (plus one to finish the scales).
 constexpr int kCompressBatchMax = 8;
 struct CompressBatch {

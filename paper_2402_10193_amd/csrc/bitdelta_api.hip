@@ -197,6 +197,7 @@ const char* bd_status_string(bd_status s) {
         case BD_ERR_ALIAS: return "the output overlaps an input";
         case BD_ERR_FORMAT: return "malformed delta image";
         case BD_ERR_IO: return "file could not be opened, read or written";
+        case BD_ERR_TOO_LARGE: return "size beyond the fixed limit of this entry point";
     }
     return "unknown status";
 }
@@ -238,6 +239,24 @@ bd_status bd_compress(const uint16_t* w_base_f16, const uint16_t* w_ft_f16, int6
     if (!workspace || workspace_bytes < need || misaligned(workspace, 256)) return BD_ERR_WORKSPACE;
     return bd::launch_compress(w_base_f16, w_ft_f16, out, in, packed, alpha, (double*)workspace,
                                (hipStream_t)stream) == hipSuccess
+               ? BD_OK
+               : BD_ERR_DEVICE;
+}
+
+bd_status bd_compress_noalloc(const uint16_t* w_base_f16, const uint16_t* w_ft_f16, int64_t out, int64_t in,
+                              uint32_t* packed, float* alpha, void* stream) {
+    if (out < 0 || in < 0 || in % 32 != 0) return BD_ERR_SHAPE;
+    if (!alpha) return BD_ERR_NULL;
+    if (misaligned(alpha, 4)) return BD_ERR_ALIGN;
+    // the size limit of this entry point, checked without overflow (out, in >= 0 here)
+    if (out > 0 && in > BD_COMPRESS_NOALLOC_MAX_ELEMENTS / out) return BD_ERR_TOO_LARGE;
+    if (out > 0 && in > 0) {
+        if (!w_base_f16 || !w_ft_f16 || !packed) return BD_ERR_NULL;
+        if (misaligned(w_base_f16, 16) || misaligned(w_ft_f16, 16) || misaligned(packed, 16)) return BD_ERR_ALIGN;
+        const size_t wbytes = (size_t)out * in * 2, pbytes = (size_t)out * in / 8;
+        if (overlaps(packed, pbytes, w_base_f16, wbytes) || overlaps(packed, pbytes, w_ft_f16, wbytes)) return BD_ERR_ALIAS;
+    }
+    return bd::launch_compress_noalloc(w_base_f16, w_ft_f16, out, in, packed, alpha, (hipStream_t)stream) == hipSuccess
                ? BD_OK
                : BD_ERR_DEVICE;
 }

@@ -298,6 +298,40 @@ hipError_t launch_compress_batch(CompressBatch a, float* alpha, double* partial,
     return hipGetLastError();
 }
 
+// ---- the compressor for callers that cannot allocate ----
+// Its partial sums live in this array instead of a workspace of the caller's: kCompressMaxBlocks binary64 numbers,
+// 16 KiB, held by every device the library runs on until the process ends.  In host code the name stands for the
+// array, it is not its address: the address on the current device is asked for once per device and kept.
+static __device__ __align__(256) double scratch[kCompressMaxBlocks];
+
+static hipError_t scratch_on_current_device(double** out) {
+    constexpr int kMaxDevices = 64;
+    static std::atomic<double*> ptr_of[kMaxDevices];
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    double* p = ptr_of[dev].load(std::memory_order_acquire);
+    if (!p) {   // first call on this device (two threads racing here get the same answer)
+        e = hipGetSymbolAddress((void**)&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        ptr_of[dev].store(p, std::memory_order_release);
+    }
+    *out = p;
+    return hipSuccess;
+}
+
+// Every block of compress_kernel writes its slot before alpha_finalize_kernel reads slots [0, blocks): nothing in the
+// array has to start at zero, and what an earlier (possibly larger) call left in the slots beyond `blocks` is never read.
+hipError_t launch_compress_noalloc(const uint16_t* base, const uint16_t* ft, int64_t out, int64_t in, uint32_t* packed,
+                                   float* alpha, hipStream_t st) {
+    double* partial = nullptr;
+    const hipError_t e = scratch_on_current_device(&partial);
+    if (e != hipSuccess) return e;
+    return launch_compress(base, ft, out, in, packed, alpha, partial, st, nullptr, 0);
+}
+
 hipError_t launch_quantize_rtn8(const uint16_t* w, int64_t out, int64_t in, int8_t* q, float* scale, hipStream_t st) {
     if (out > 0) hipLaunchKernelGGL(quantize_rtn8_kernel, dim3((unsigned)out), dim3(kCompressThreads), 0, st, w, q, scale, in);
     return hipGetLastError();

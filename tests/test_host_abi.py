@@ -103,6 +103,21 @@ def test_compress_and_pack_argument_errors(bd):
     assert L.bd_materialize(A, 2 * A, 0, 3 * A, 16, 64, 0) == 1
 
 
+def test_compress_noalloc_argument_errors(bd):
+    """Errors of the entry point that brings its own scratch are host-side and come before any launch or look-up."""
+    c = bd.lib().bd_compress_noalloc
+    assert c(A, 2 * A, 16, 100, 3 * A, 4 * A, 0) == 2
+    assert c(A, 2 * A, -1, 128, 3 * A, 4 * A, 0) == 2
+    assert c(0, 2 * A, 16, 128, 3 * A, 4 * A, 0) == 1
+    assert c(A, 2 * A, 16, 128, 3 * A, 0, 0) == 1
+    assert c(A + 4, 2 * A, 16, 128, 3 * A, 4 * A, 0) == 3
+    assert c(A, 2 * A, 16, 128, A + 1024, 4 * A, 0) == 8
+    # beyond 2^32 elements: its own status, also where out * in would overflow 64 bits
+    assert c(A, 2 * A, 1 << 17, (1 << 15) + 32, 3 * A, 4 * A, 0) == 11
+    assert c(A, 2 * A, 1 << 40, 1 << 40, 3 * A, 4 * A, 0) == 11
+    assert bd.status_string(11) != "unknown status"
+
+
 def test_compress_batch_argument_errors(bd):
     import ctypes
     L = bd.lib()
