@@ -38,6 +38,10 @@ HBM_PEAK_GBS = 8000.0
 MEASURED_TRAFFIC_BYTES_PER_LAUNCH = {("7b", 16, "tiled-fused"): 204.5e6}
 
 
+def measured_traffic(model, tenants, path):
+    return MEASURED_TRAFFIC_BYTES_PER_LAUNCH.get((model, tenants, path))
+
+
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -107,7 +111,7 @@ def run_prefill(args, torch, bd, synth, dev):
     ms = e0.elapsed_time(e1) / args.steps
     flops = sum(2.0 * 2.0 * T * inn * out for *_, out, inn in mats)      # base + delta products
     tflops = flops / (ms * 1e-3) / 1e12
-    print(json.dumps({
+    return {
         "metric": "prefill tokens/s, fused fp16 base + 1-bit delta linear, 8 tenants x 512 tokens",
         "value": round(T / (ms * 1e-3), 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
@@ -117,8 +121,10 @@ def run_prefill(args, torch, bd, synth, dev):
         "roofline": {"bound": "mfma", "achieved": round(tflops, 1), "peak": MFMA_F16_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(tflops / MFMA_F16_PEAK_TFLOPS, 4), "traffic": None, "kernel": "linear_prefill_big_kernel" if args.variant != 4 else "linear_prefill_kernel",
                      "flops_per_launch": flops / 2, "avg_launch_us": round(ms * 1e3 / 2, 2),
+                     # counting only the flops of a dense fine-tuned model (2 T in out per linear): half of the above
+                     "achieved_useful": round(tflops / 2, 1), "frac_useful": round(tflops / 2 / MFMA_F16_PEAK_TFLOPS, 4),
                      "useful_fraction_note": "half of the flops are the base product, half the +-1 delta product"},
-    }))
+    }
 
 
 def run_hotswap(args, torch, bd, dev, incoming, k, B, step, ms_decode_alone):
@@ -189,6 +195,142 @@ def run_hotswap(args, torch, bd, dev, incoming, k, B, step, ms_decode_alone):
     }))
 
 
+def build_stack(args, torch, bd, synth, dev, shapes, sigma, n_layers, n_res, k, q8, keep_rowmajor, tag0="L", timing=None):
+    """Base weights + n_res compressed deltas per matrix for n_layers layers, resident in HBM in the serving layout
+    (and row-major as well for the first keep_rowmajor layers).  Returns (layers, incoming) with
+    layers[li] = [(name, out, in, base, table, w_tiled, tiled_table), ...]."""
+    layers, incoming = [], []
+    ws = bd.new_workspace(bd.workspace_bytes(bd.OP_COMPRESS, 0, 1, 32, 1), dev)
+    for li in range(n_layers):
+        mats = []
+        for name, out, inn in shapes:
+            base = synth.base_weight(out, inn, device=dev, tag=(tag0, li, name))
+            if q8:
+                qb, qscale = bd.quantize_base_q8(base)
+            packed, alphas = [], []
+            for t in range(n_res):
+                ft = synth.finetuned_weight(base, sigma=sigma, tag=(tag0, li, name, t))
+                if q8:
+                    p, a = bd.compress_q8(qb, qscale, ft, workspace=ws)
+                else:
+                    p, a = bd.compress(base, ft, workspace=ws) if k == 1 else bd.compress_iterated(base, ft, k, workspace=ws)
+                packed.append(p)
+                alphas.append(a)
+                del ft
+            if args.workload == "hotswap":       # one more fine-tune per matrix: the tenant that will be swapped in
+                ft = synth.finetuned_weight(base, sigma=sigma, tag=(tag0, li, name, "incoming"))
+                p, a = bd.compress_iterated(base, ft, k, workspace=ws)
+                incoming.append((out, inn, p.cpu(), a.cpu()))
+                del ft, p
+            table = bd.TenantTable(packed, alphas) if k == 1 else None
+            wt = ttable = None
+            if k != 1:
+                wt = bd.tile_base(base)
+                ttable = bd.TiledPlaneTable([[bd.tile_signs(p[j], out, inn) for j in range(k)] for p in packed],
+                                            torch.stack(alphas))
+                base = None
+            else:
+                wt = bd.tile_base_q8(qb, qscale) if q8 else bd.tile_base(base)
+                ttable = bd.TiledTenantTable([bd.tile_signs(p, out, inn) for p in packed], table.alpha)
+                if li >= keep_rowmajor:
+                    base = table = None
+            mats.append((name, out, inn, base, table, wt, ttable))
+        layers.append(mats)
+    return layers, incoming
+
+
+def make_plans(args, bd, layers, xs, ys, tok, tok_arr, path, k, q8):
+    """One list of launch closures per layer for the given serving path."""
+    plans = []
+    for mats in layers:
+        by = {m[0]: m for m in mats}
+        plan = []
+        if path == "rowmajor":
+            for name, out, inn, base, table, _, _ in mats:
+                plan.append(lambda inn=inn, base=base, table=table, y=ys[(name, out)]: bd.linear_multitenant(
+                    xs[inn], base, table, tok, y=y, variant=args.variant, tok_array=tok_arr))
+        elif path == "tiled":
+            for name, out, inn, _, _, wt, ttable in mats:
+                plan.append(lambda inn=inn, out=out, wt=wt, ttable=ttable, y=ys[(name, out)]: bd.linear_multitenant_tiled(
+                    xs[inn], wt, out, ttable, tok, y=y, tok_array=tok_arr))
+        else:
+            def grouped(names):
+                ms = [by[n] for n in names]
+                yl = [ys[(m[0], m[1])] for m in ms]
+                if k != 1:
+                    g = bd.TiledPlaneGroup([m[5] for m in ms], [m[1] for m in ms], [m[6] for m in ms])
+                    return lambda g=g, yl=yl, inn=ms[0][2]: bd.linear_multitenant_tiled_group_kbit(
+                        xs[inn], g, tok, ys=yl, tok_array=tok_arr)
+                g = bd.TiledGroup([m[5] for m in ms], [m[1] for m in ms], [m[6] for m in ms])
+                if q8:
+                    return lambda g=g, yl=yl, inn=ms[0][2]: bd.linear_multitenant_tiled_group_q8(xs[inn], g, tok, ys=yl,
+                                                                                                  tok_array=tok_arr)
+                return lambda g=g, yl=yl, inn=ms[0][2]: bd.linear_multitenant_tiled_group(xs[inn], g, tok, ys=yl,
+                                                                                           tok_array=tok_arr)
+
+            def single(n):
+                m = by[n]
+                if k != 1:
+                    return lambda m=m: bd.linear_multitenant_tiled_kbit(xs[m[2]], m[5], m[1], m[6], tok,
+                                                                        y=ys[(m[0], m[1])], tok_array=tok_arr)
+                if q8:
+                    return lambda m=m: bd.linear_multitenant_tiled_q8(xs[m[2]], m[5], m[1], m[6], tok, y=ys[(m[0], m[1])],
+                                                                      tok_array=tok_arr)
+                return lambda m=m: bd.linear_multitenant_tiled(xs[m[2]], m[5], m[1], m[6], tok, y=ys[(m[0], m[1])],
+                                                               tok_array=tok_arr)
+            plan = [grouped(["q", "k", "v"]), single("o"), grouped(["gate", "up"]), single("down")]
+        plans.append(plan)
+    return plans
+
+
+def stack_bytes(shapes, n_layers, T, n_active, k, q8):
+    """Algorithmic bytes of one pass: W once, each active delta (k planes) once, x and y of every linear."""
+    P = sum(o * i for _, o, i in shapes)
+    xy_bytes = sum(T * (i + o) * 2 for _, o, i in shapes)
+    base_bytes = (1.0 * P + 4.0 * sum(o for _, o, _ in shapes)) if q8 else 2.0 * P   # int8: one byte per weight + a scale per row
+    return n_layers * (base_bytes + n_active * k * P / 8.0 + xy_bytes)
+
+
+def capture_and_time(torch, plans, steps, warmup, use_graph=True):
+    """Runs the launches of `plans` once eagerly (kernel attributes are set on first use, outside any capture),
+    captures them into a HIP graph, and times `steps` replays with events on the current stream.
+    Returns (ms per step, step function, graph or None)."""
+    def run_stack():
+        for plan in plans:
+            for launch in plan:
+                launch()
+    run_stack()
+    torch.cuda.synchronize()
+    graph = None
+    if use_graph:
+        try:
+            side = torch.cuda.Stream()
+            side.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.stream(side):
+                run_stack()
+            torch.cuda.current_stream().wait_stream(side)
+            torch.cuda.synchronize()
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph):
+                run_stack()
+        except Exception as e:   # noqa: BLE001
+            print(f"bench.py: graph capture failed ({e}); launching eagerly", file=sys.stderr)
+            graph = None
+    step = graph.replay if graph is not None else run_stack
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    wall0 = time.time()
+    e0.record()
+    for _ in range(steps):
+        step()
+    e1.record()
+    torch.cuda.synchronize()
+    wall = time.time() - wall0
+    return e0.elapsed_time(e1) / steps, step, graph, wall
+
+
 def main():
     args = parse()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -219,7 +361,7 @@ def main():
         print(json.dumps({"calibrate": "3 x bd_probe_copy and bd_probe_read of 1 GiB"}))
         return
     if args.workload == "prefill":
-        run_prefill(args, torch, bd, synth, dev)
+        print(json.dumps(run_prefill(args, torch, bd, synth, dev)))
         return
     B, n_layers = args.tenants, args.layers
     shapes = synth.LLAMA2_7B_LAYER if args.model == "7b" else synth.LLAMA2_70B_LAYER
@@ -239,144 +381,29 @@ def main():
     if k != 1:
         assert args.path == "tiled-fused", "--planes needs the tiled-fused path"
         args.no_extras = args.no_cpu = True
+    if args.workload == "hotswap":
+        args.no_extras = args.no_cpu = True
     tok_arr = bd._tok_array(tok)
+    # The sweep over the number of tenants (in the extras) needs up to 32 of them resident; the headline run then
+    # simply uses the first B.  A tenant without a token costs a launch nothing.
+    sweep = (not args.no_extras) and args.model == "7b" and n_layers == 32
+    n_res = max(B, 32) if sweep else B
+    keep_rowmajor = n_layers if args.path == "rowmajor" else (min(4, n_layers) if not args.no_extras else 0)
 
-    # ---- build the stack: base weights + B compressed deltas per matrix, all resident in HBM
+    # ---- build the stack: base weights + compressed deltas per matrix, all resident in HBM
     t_setup = time.time()
-    layers = []
-    incoming = []
-    ws = bd.new_workspace(bd.workspace_bytes(bd.OP_COMPRESS, 0, 1, 32, 1), dev)
-    compress_bytes, compress_ms = 0.0, 0.0
-    for li in range(n_layers):
-        mats = []
-        for name, out, inn in shapes:
-            base = synth.base_weight(out, inn, device=dev, tag=("L", li, name))
-            if q8:
-                qb, qscale = bd.quantize_base_q8(base)
-            packed, alphas = [], []
-            for t in range(B):
-                ft = synth.finetuned_weight(base, sigma=sigma, tag=("L", li, name, t))
-                if li == 0:
-                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                    e0.record()
-                if q8:
-                    p, a = bd.compress_q8(qb, qscale, ft, workspace=ws)
-                else:
-                    p, a = bd.compress(base, ft, workspace=ws) if k == 1 else bd.compress_iterated(base, ft, k, workspace=ws)
-                if li == 0:
-                    e1.record()
-                    e1.synchronize()
-                    compress_ms += e0.elapsed_time(e1)
-                    compress_bytes += out * inn * 4.125 * k
-                packed.append(p)
-                alphas.append(a)
-                del ft
-            if args.workload == "hotswap":       # one more fine-tune per matrix: the tenant that will be swapped in
-                ft = synth.finetuned_weight(base, sigma=sigma, tag=("L", li, name, "incoming"))
-                p, a = bd.compress_iterated(base, ft, k, workspace=ws)
-                incoming.append((out, inn, p.cpu(), a.cpu()))
-                del ft, p
-            table = bd.TenantTable(packed, alphas) if k == 1 else None
-            wt = ttable = None
-            if k != 1:
-                wt = bd.tile_base(base)
-                ttable = bd.TiledPlaneTable([[bd.tile_signs(p[j], out, inn) for j in range(k)] for p in packed],
-                                            torch.stack(alphas))
-                base = None
-            elif args.path != "rowmajor":
-                wt = bd.tile_base_q8(qb, qscale) if q8 else bd.tile_base(base)
-                ttable = bd.TiledTenantTable([bd.tile_signs(p, out, inn) for p in packed], table.alpha)
-                if li > 0:          # layer 0 keeps its row-major tensors for the naive baseline below
-                    base = table = None
-            mats.append((name, out, inn, base, table, wt, ttable))
-        layers.append(mats)
+    layers, incoming = build_stack(args, torch, bd, synth, dev, shapes, sigma, n_layers, n_res, k, q8, keep_rowmajor)
     xs = {inn: synth.activations(T, inn, device=dev, tag=("bench", inn)) for _, _, inn in shapes}
     ys = {(name, out): torch.empty((T, out), dtype=torch.float16, device=dev) for name, out, _ in shapes}
     torch.cuda.synchronize()
     t_setup = time.time() - t_setup
 
-    plans = []          # one list of launch closures per layer
-    for mats in layers:
-        by = {m[0]: m for m in mats}
-        plan = []
-        if args.path == "rowmajor":
-            for name, out, inn, base, table, _, _ in mats:
-                plan.append(lambda inn=inn, base=base, table=table, y=ys[(name, out)]: bd.linear_multitenant(
-                    xs[inn], base, table, tok, y=y, variant=args.variant, tok_array=tok_arr))
-        elif args.path == "tiled":
-            for name, out, inn, _, _, wt, ttable in mats:
-                plan.append(lambda inn=inn, out=out, wt=wt, ttable=ttable, y=ys[(name, out)]: bd.linear_multitenant_tiled(
-                    xs[inn], wt, out, ttable, tok, y=y, tok_array=tok_arr))
-        else:
-            def grouped(names):
-                ms = [by[n] for n in names]
-                yl = [ys[(m[0], m[1])] for m in ms]
-                if k != 1:
-                    g = bd.TiledPlaneGroup([m[5] for m in ms], [m[1] for m in ms], [m[6] for m in ms])
-                    return lambda g=g, yl=yl, inn=ms[0][2]: bd.linear_multitenant_tiled_group_kbit(
-                        xs[inn], g, tok, ys=yl, tok_array=tok_arr)
-                g = bd.TiledGroup([m[5] for m in ms], [m[1] for m in ms], [m[6] for m in ms])
-                if q8:
-                    return lambda g=g, yl=yl, inn=ms[0][2]: bd.linear_multitenant_tiled_group_q8(xs[inn], g, tok, ys=yl,
-                                                                                                  tok_array=tok_arr)
-                return lambda g=g, yl=yl, inn=ms[0][2]: bd.linear_multitenant_tiled_group(xs[inn], g, tok, ys=yl,
-                                                                                           tok_array=tok_arr)
-            def single(n):
-                m = by[n]
-                if k != 1:
-                    return lambda m=m: bd.linear_multitenant_tiled_kbit(xs[m[2]], m[5], m[1], m[6], tok,
-                                                                        y=ys[(m[0], m[1])], tok_array=tok_arr)
-                if q8:
-                    return lambda m=m: bd.linear_multitenant_tiled_q8(xs[m[2]], m[5], m[1], m[6], tok, y=ys[(m[0], m[1])],
-                                                                      tok_array=tok_arr)
-                return lambda m=m: bd.linear_multitenant_tiled(xs[m[2]], m[5], m[1], m[6], tok, y=ys[(m[0], m[1])],
-                                                               tok_array=tok_arr)
-            plan = [grouped(["q", "k", "v"]), single("o"), grouped(["gate", "up"]), single("down")]
-        plans.append(plan)
-
-    def run_stack():
-        for plan in plans:
-            for launch in plan:
-                launch()
-
+    plans = make_plans(args, bd, layers, xs, ys, tok, tok_arr, args.path, k, q8)
     launches_per_step = sum(len(p) for p in plans)
     P = sum(o * i for _, o, i in shapes)
-    xy_bytes = sum(T * (i + o) * 2 for _, o, i in shapes)
-    base_bytes = (1.0 * P + 4.0 * sum(o for _, o, _ in shapes)) if q8 else 2.0 * P   # int8: one byte per weight + a scale per row
-    bytes_per_step = n_layers * (base_bytes + n_active * k * P / 8.0 + xy_bytes)   # W once, each active delta (k planes) once, x, y
+    bytes_per_step = stack_bytes(shapes, n_layers, T, n_active, k, q8)
 
-    run_stack()                                   # first call sets kernel attributes; keep it out of any capture
-    torch.cuda.synchronize()
-    graph = None
-    if not args.no_graph:
-        try:
-            side = torch.cuda.Stream()
-            side.wait_stream(torch.cuda.current_stream())
-            with torch.cuda.stream(side):
-                run_stack()
-            torch.cuda.current_stream().wait_stream(side)
-            torch.cuda.synchronize()
-            graph = torch.cuda.CUDAGraph()
-            with torch.cuda.graph(graph):
-                run_stack()
-        except Exception as e:   # noqa: BLE001
-            print(f"bench.py: graph capture failed ({e}); launching eagerly", file=sys.stderr)
-            graph = None
-    step = graph.replay if graph is not None else run_stack
-
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    wall0 = time.time()
-    e0.record()
-    for _ in range(args.steps):
-        step()
-    e1.record()
-    torch.cuda.synchronize()
-    wall = time.time() - wall0
-    ms_total = e0.elapsed_time(e1)
-    ms_per_step = ms_total / args.steps
+    ms_per_step, step, graph, wall = capture_and_time(torch, plans, args.steps, args.warmup, not args.no_graph)
     tokens_per_s = T / (ms_per_step * 1e-3)
     achieved_gbs = bytes_per_step / (ms_per_step * 1e-3) / 1e9
 
@@ -393,6 +420,7 @@ def main():
         run_hotswap(args, torch, bd, dev, incoming, k, B, step, ms_per_step)
         return
 
+    kernel_name = {"rowmajor": "linear_decode_rowmajor_kernel"}.get(args.path, "linear_decode_tiled_kernel")
     result = {
         "metric": "decode tokens/s, fused fp16 base + 1-bit delta linear stack, B tenants",
         "value": round(tokens_per_s, 2),
@@ -411,7 +439,8 @@ def main():
                         f"B={B} tenants, " + (f"mixed decode batch of {T} tokens ({args.mix} per active tenant), "
                                                if args.mix else "one decode token per tenant, ")
                         + (f"distinct {k}-plane delta per (tenant, matrix)" if k != 1 else "distinct 1-bit delta per (tenant, matrix)"),
-            "tenants": B, "tokens": T, "active_tenants": n_active, "planes": k, "base": args.base, "layers": n_layers, "launches_per_step": launches_per_step,
+            "tenants": B, "resident_tenants": n_res, "tokens": T, "active_tenants": n_active, "planes": k, "base": args.base,
+            "layers": n_layers, "launches_per_step": launches_per_step,
             "launch": "hip graph replay" if graph is not None else "eager",
             "path": args.path, "kernel_variant": args.variant,
         },
@@ -421,9 +450,8 @@ def main():
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
             "frac": round(achieved_gbs / HBM_PEAK_GBS, 4),
-            "traffic": MEASURED_TRAFFIC_BYTES_PER_LAUNCH.get((args.model, B, args.path))
-                       if n_layers == 32 and not args.mix and k == 1 and not q8 else None,
-            "kernel": "linear_decode_mfma_kernel" if args.path == "rowmajor" else "linear_decode_tiled_kernel",
+            "traffic": measured_traffic(args.model, B, args.path) if n_layers == 32 and not args.mix and k == 1 and not q8 else None,
+            "kernel": kernel_name,
             "bytes_per_launch": round(bytes_per_step / launches_per_step, 1),
             "avg_launch_us": round(ms_per_step * 1e3 / launches_per_step, 3),
         },
@@ -432,6 +460,7 @@ def main():
         "wall_s_timed_region": round(wall, 4),
         "setup_s": round(t_setup, 1),
     }
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
 
     extras = {}
     if args.per_linear:
@@ -469,39 +498,106 @@ def main():
         e1.synchronize()
         extras["read_probe_GBs"] = round(5 * buf.numel() * 4 / (e0.elapsed_time(e1) * 1e-3) / 1e9, 1)
         del buf
-        # (b) the naive system of the paper: every tenant keeps a full fp16 copy.  One layer (B x 405 MB) timed.
-        mats0 = layers[0]
-        naive = []
-        for name, out, inn, base, table, _, _ in mats0:
-            wts = [bd.materialize(base, table.packed[t], table.alpha[t:t + 1]) for t in range(B)]
-            naive.append((name, out, inn, bd.WeightTable(wts)))
-        # two copies of the layer so that the second pass does not find the first in the memory-side cache
-        naive2 = []
-        for name, out, inn, wt in naive:
-            naive2.append((name, out, inn, bd.WeightTable([w.clone() for w in wt.w])))
 
-        def run_naive(which):
-            for name, out, inn, wt in which:
-                bd.linear_naive(xs[inn], wt, tok, y=ys[(name, out)], tok_array=tok_arr)
-        run_naive(naive)
-        torch.cuda.synchronize()
-        e0.record()
-        for _ in range(3):
-            run_naive(naive2)
-            run_naive(naive)
-        e1.record()
-        e1.synchronize()
-        naive_ms_layer = e0.elapsed_time(e1) / 6
-        extras["naive_per_tenant_fp16"] = {
-            "ms_per_layer": round(naive_ms_layer, 4),
-            "tokens_per_s_stack": round(B / (naive_ms_layer * 1e-3 * n_layers), 2),
-            "GB/s": round(B * 2.0 * P / (naive_ms_layer * 1e-3) / 1e9, 1),
-            "bitdelta_speedup": round(naive_ms_layer / (ms_per_step / n_layers), 3),
-            "byte_ratio": round(B * 2.0 * P / (bytes_per_step / n_layers), 3),
-            "note": "one layer measured (B full fp16 copies), stack figure = x layers",
-        }
-        del naive, naive2
-        extras["compress_GBs"] = round(compress_bytes / (compress_ms * 1e-3) / 1e9, 1) if compress_ms > 0 else None
+        # (b) the naive system of the paper (Sec. 4.3): every tenant keeps a full fp16 copy of the model.  Layers 0 and 1
+        # are materialised for every resident tenant and timed in turn, so that no pass finds its weights in the
+        # memory-side cache; n tenants = the first n copies.
+        n_naive_layers = min(2, keep_rowmajor)
+        naive = []
+        for li in range(n_naive_layers):
+            nl = []
+            for name, out, inn, base, table, _, _ in layers[li]:
+                wts = [bd.materialize(base, table.packed[t], table.alpha[t:t + 1]) for t in range(n_res)]
+                nl.append((name, out, inn, wts))
+            naive.append(nl)
+
+        def naive_ms_per_layer(n):
+            toks = list(range(n))
+            ta = bd._tok_array(toks)
+            xn = {inn: xs[inn][:n] if n <= T else synth.activations(n, inn, device=dev, tag=("bench", inn, n)) for _, _, inn in shapes}
+            yn = {(name, out): torch.empty((n, out), dtype=torch.float16, device=dev) for name, out, _ in shapes}
+            tabs = [[(name, out, inn, bd.WeightTable(wts[:n])) for name, out, inn, wts in nl] for nl in naive]
+
+            def run(which):
+                for name, out, inn, wt in which:
+                    bd.linear_naive(xn[inn], wt, toks, y=yn[(name, out)], tok_array=ta)
+            for t_ in tabs:
+                run(t_)
+            torch.cuda.synchronize()
+            reps = 3
+            e0.record()
+            for _ in range(reps):
+                for t_ in tabs:
+                    run(t_)
+            e1.record()
+            e1.synchronize()
+            return e0.elapsed_time(e1) / (reps * len(tabs))
+
+        def naive_entry(n, ms_bitdelta_step):
+            ms_layer = naive_ms_per_layer(n)
+            return {"ms_per_layer": round(ms_layer, 4),
+                    "tokens_per_s_stack": round(n / (ms_layer * 1e-3 * n_layers), 2),
+                    "GB/s": round(n * 2.0 * P / (ms_layer * 1e-3) / 1e9, 1),
+                    "bitdelta_speedup": round(ms_layer / (ms_bitdelta_step / n_layers), 3),
+                    "byte_ratio": round(n * 2.0 * P * n_layers / stack_bytes(shapes, n_layers, n, n, 1, False), 3)}
+        if naive:
+            ent = naive_entry(B, ms_per_step)
+            ent["note"] = "two layers measured (B full fp16 copies each), stack figure = x layers"
+            extras["naive_per_tenant_fp16"] = ent
+
+        # (c) config 3: the sweep over the number of tenants, same stack, one token per tenant, graph replay
+        def timed_stack(lyrs, shp, toks, path, steps=10, warmup=2):
+            ta = bd._tok_array(toks)
+            n = len(toks)
+            xs_ = {inn: synth.activations(n, inn, device=dev, tag=("bench", inn, n)) for _, _, inn in shp}
+            ys_ = {(name, out): torch.empty((n, out), dtype=torch.float16, device=dev) for name, out, _ in shp}
+            pl = make_plans(args, bd, lyrs, xs_, ys_, toks, ta, path, 1, False)
+            ms, _, g, _ = capture_and_time(torch, pl, steps, warmup, not args.no_graph)
+            nb = stack_bytes(shp, len(lyrs), n, len(set(toks)), 1, False)
+            gbs = nb / (ms * 1e-3) / 1e9
+            del g
+            return {"ms_per_step": round(ms, 4), "tokens_per_s": round(n / (ms * 1e-3), 1), "GB/s": round(gbs, 1),
+                    "frac": round(gbs / HBM_PEAK_GBS, 4), "launches_per_step": sum(len(p) for p in pl)}
+        if sweep and k == 1 and not q8:
+            sw = {}
+            for n in (1, 2, 4, 8, 32):
+                ent = timed_stack(layers, shapes, list(range(n)), "tiled-fused")
+                if naive:
+                    nv = naive_entry(n, ent["ms_per_step"])
+                    ent["naive_tokens_per_s"] = nv["tokens_per_s_stack"]
+                    ent["speedup_vs_naive"] = nv["bitdelta_speedup"]
+                    ent["byte_ratio"] = nv["byte_ratio"]
+                sw[str(n)] = ent
+            extras["tenant_sweep_7b"] = sw
+            # the same stack through the other two entry points: 7 launches per layer on the tiled layout, and the
+            # row-major bd_linear_multitenant (its tensors are kept for the first layers only)
+            extras["path_tiled_7_launches"] = timed_stack(layers, shapes, tok, "tiled")
+            if keep_rowmajor > 0:
+                ent = timed_stack(layers[:keep_rowmajor], shapes, tok, "rowmajor")
+                ent["layers"] = keep_rowmajor
+                extras["path_rowmajor_bd_linear_multitenant"] = ent
+        del naive
+
+        # (d) the compressor: whole calls back to back (outputs and workspace allocated beforehand)
+        cshape = [(n_, o, i) for n_, o, i in shapes if n_ in ("q", "gate")]
+        for name, out, inn in cshape:
+            cb = [synth.base_weight(out, inn, device=dev, tag=("C", j, name)) for j in range(4)]
+            cf = [synth.finetuned_weight(b, sigma=sigma, tag=("C", j, name, 0)) for j, b in enumerate(cb)]
+            pk = torch.empty((out, inn // 32), dtype=torch.int32, device=dev)
+            al = torch.empty((1,), dtype=torch.float32, device=dev)
+            wsc = bd.new_workspace(bd.workspace_bytes(bd.OP_COMPRESS, 0, out, inn, 1), dev)
+            for b_, f_ in zip(cb, cf):
+                bd.compress(b_, f_, packed=pk, alpha=al, workspace=wsc)
+            torch.cuda.synchronize()
+            e0.record()
+            for _ in range(5):
+                for b_, f_ in zip(cb, cf):
+                    bd.compress(b_, f_, packed=pk, alpha=al, workspace=wsc)
+            e1.record()
+            e1.synchronize()
+            extras[f"compress_GBs_{out}x{inn}"] = round(20 * out * inn * 4.125 / (e0.elapsed_time(e1) * 1e-3) / 1e9, 1)
+            del cb, cf
+        extras["compress_GBs"] = extras.get("compress_GBs_11008x4096")
         if not q8 and k == 1:
             # the same compressor with the matrices of a layer in one call (bd_compress_batch): whole-call rate
             cb_bases = [synth.base_weight(out, inn, device=dev, tag=("L", 0, name)) for name, out, inn in shapes]
@@ -509,7 +605,6 @@ def main():
             ws_b = bd.new_workspace(bd.COMPRESS_BATCH_MAX * bd.workspace_bytes(bd.OP_COMPRESS, 0, 1, 32, 1), dev)
             best = None
             for _ in range(4):
-                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
                 e0.record()
                 bd.compress_batch(cb_bases, cb_fts, workspace=ws_b)
                 e1.record()
@@ -518,6 +613,24 @@ def main():
                 best = ms if best is None or ms < best else best
             extras["compress_batch_GBs"] = round(sum(o * i for _, o, i in shapes) * 4.125 / (best * 1e-3) / 1e9, 1)
             del cb_bases, cb_fts
+
+        if sweep and k == 1 and not q8:
+            # (e) config 4: Llama-2-70B layer shapes, 32 tenants, sigma 0.001; two layers so that nothing is served from cache
+            del layers, plans, step, graph
+            torch.cuda.empty_cache()
+            shapes70 = synth.LLAMA2_70B_LAYER
+            l70, _ = build_stack(args, torch, bd, synth, dev, shapes70, 0.001, 2, 32, 1, False, 0, tag0="L70")
+            extras["llama2_70b_layers"] = {str(n): timed_stack(l70, shapes70, list(range(n)), "tiled-fused", steps=20, warmup=3)
+                                           for n in (16, 32)}
+            extras["llama2_70b_layers"]["layers"] = 2
+            del l70
+            torch.cuda.empty_cache()
+            # (f) config 5: prefill, 8 tenants x 512 tokens through the matrix-core GEMM
+            pf = run_prefill(args, torch, bd, synth, dev)
+            extras["prefill_8x512"] = {"tokens_per_s": pf["value"], "ms_per_step": pf["ms_per_step"],
+                                       "TFLOP/s": pf["roofline"]["achieved"], "frac": pf["roofline"]["frac"],
+                                       "TFLOP/s_fine_tuned_model_only": pf["roofline"]["achieved_useful"],
+                                       "frac_fine_tuned_model_only": pf["roofline"]["frac_useful"]}
     result["extras"] = extras
 
     # ---- the oracle on the host cores, one layer of the same workload
