@@ -147,8 +147,8 @@ bd_status bd_linear_multitenant(const uint16_t* x_f16, const uint16_t* w_base_f1
  * benchmarking the kernel variants against each other.
  *   variant 0  library's choice (identical to bd_linear_multitenant)
  *   variant 1  plain vector-ALU kernel: one wavefront per output row, DPP reductions
- *   variant 2, 3  matrix-core decode kernels on the row-major tensors; BD_ERR_UNSUPPORTED if the
- *              variant cannot run these sizes
+ *   variant 2  the matrix-core decode kernel of the serving path reading the row-major tensors as they are
+ *              (in % 128 == 0 and a base below 4 GiB, else BD_ERR_UNSUPPORTED); the library's choice for such sizes
  *   variant 4, 5, 6  the prefill GEMM with 128 x 128 tiles / 128 x 256 tiles and 4 wavefronts / 128 x 256
  *              tiles and 8 wavefronts (T > 32 and a workspace as for variant 0, else BD_ERR_UNSUPPORTED /
  *              BD_ERR_WORKSPACE; 5, 6 and 7 need in % 64 == 0)

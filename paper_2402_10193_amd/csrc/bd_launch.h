@@ -40,12 +40,6 @@ hipError_t launch_linear_rowwave(const uint16_t* x, const uint16_t* w, const uin
                                  const float* alpha_by_tenant, const DecodeMeta& meta, uint16_t* y, int64_t out,
                                  int64_t in, hipStream_t st);
 
-// Matrix-core decode kernel.  Returns hipErrorInvalidValue if `variant` is unknown.
-hipError_t launch_linear_decode_mfma(const uint16_t* x, const uint16_t* w, const uint32_t* const* packed_by_tenant,
-                                     const float* alpha_by_tenant, const DecodeMeta& meta, uint16_t* y, int64_t out,
-                                     int64_t in, int variant, hipStream_t st);
-bool decode_mfma_variant_known(int variant);
-
 // Prefill GEMM (many tokens per tenant).  row_token: n_mtiles * kPrefillTile ints, the token of every
 // tile row or -1 for padding; tile_tenant: n_mtiles ints.  Both in device memory (the workspace).
 constexpr int kPrefillTile = 128;   // tile of y: 128 tokens x 128 output features

@@ -61,6 +61,10 @@ struct TiledArgs {
     // when y is written and only the first contributes the base product.  One plane: all 1.
     int32_t col_span[kTiledMaxCt][kTiledMaxTokens];
     int32_t planes;                                           // k: 1 = plain 1-bit deltas
+    // Row-major entry point only (wt[0] = W [out, in] row-major, signs[][][] unused): the caller's DEVICE table of
+    // tenants' packed deltas [out, in/32] and the tenant of every job slot (slots beyond the jobs repeat slot 0's).
+    const uint32_t* const* packed_by_tenant;
+    int32_t job_tenant[kTiledMaxCt][kTiledMaxJobs];
 };
 
 hipError_t launch_fill_zero_u16(uint16_t* p, int64_t n, hipStream_t st);
@@ -68,6 +72,8 @@ hipError_t launch_tile_base(const uint16_t* w, int64_t out, int64_t in, uint16_t
 hipError_t launch_tile_signs(const uint32_t* packed, int64_t out, int64_t in, uint32_t* st_out, hipStream_t st);
 // n_jobs real job slots per column tile (1..16, the larger of the two); unused slots must repeat slot 0's pointers.
 hipError_t launch_linear_decode_tiled(const TiledArgs& args, int n_jobs, hipStream_t st);
+// the same kernel over the row-major tensors of bd_linear_multitenant (one matrix, in % 128 == 0)
+hipError_t launch_linear_decode_rowmajor(const TiledArgs& args, int n_jobs, hipStream_t st);
 // the same over an 8-bit base: args.wt point at base8 tiles, args.wscale at their scales
 hipError_t launch_linear_decode_tiled_q8(const TiledArgs& args, int n_jobs, hipStream_t st);
 // q [out, in] int8, scale [out] -> base8 tiles followed by the padded scales

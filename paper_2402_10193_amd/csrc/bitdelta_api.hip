@@ -16,7 +16,7 @@ using bd::kMaxDecodeTokens;
 
 constexpr int kVersion = 200;   // 0.2.0
 constexpr int kVariantRowWave = 1;
-constexpr int kVariantDefaultMfma = 3;
+constexpr int kVariantRowMajorMfma = 2;   // the matrix-core decode kernel on the row-major tensors (in % 128 == 0)
 constexpr int kVariantPrefillSmall = 4;   // T > 32 with a workspace: the 128 x 128 tile GEMM
 constexpr int kVariantPrefillBig = 5;     // ... the 128 x 256 tile GEMM (in % 64 == 0), one wavefront per SIMD
 constexpr int kVariantPrefillBig8 = 6;    // ... the same tile with two wavefronts per SIMD
@@ -142,10 +142,11 @@ hipError_t run_prefill(const uint16_t* x, const uint16_t* w, const uint32_t* con
 
 // Which way is quicker for T > 32 tokens when both are possible: one GEMM launch, whose tiles of 128 token rows
 // never mix tenants (a tenant with 3 tokens still costs a whole tile), or decode launches of 32 tokens each, which
-// re-read the base per launch but spend nothing on empty rows.  Rough model from measured rates: a 128 x 256 tile
-// takes 1.45 us per 64-wide k step plus 10 us around the loop, one tile per compute unit at a time; a decode launch
-// of the row-major kernels streams its bytes at 2.6 TB/s (1.3 with the vector-ALU kernel) plus 8 us.  A wrong guess costs
-// time, never correctness.
+// re-read the base per launch but spend nothing on empty rows.  Rough model from measured rates (MI355X, graph
+// replay): a 128 x 256 tile takes 1.45 us per 64-wide k step plus 10 us around the loop, one tile per compute unit at
+// a time; a decode launch of the matrix-core kernel on the row-major tensors takes 6 us plus its base bytes at
+// 4.2 TB/s plus its sign bytes at 2.15 TB/s (7B shapes, 1 to 16 tenants: 21 to 46 us per launch); the vector-ALU
+// kernel streams everything at 1.3 TB/s plus 8 us.  A wrong guess costs time, never correctness.
 bool prefill_gemm_pays(const int32_t* tenant_of_token, int64_t T, int64_t out, int64_t in, int32_t n_tenants, bool big,
                        bool decode_on_matrix_cores) {
     std::vector<int32_t> count((size_t)n_tenants, 0);
@@ -175,7 +176,9 @@ bool prefill_gemm_pays(const int32_t* tenant_of_token, int64_t T, int64_t out, i
                 ++distinct;
             }
         }
-        decode_us += (double)out * (double)in * (2.0 + (double)distinct / 8.0) / (decode_on_matrix_cores ? 2.6e6 : 1.3e6) + 8.0;
+        const double elems = (double)out * (double)in;
+        decode_us += decode_on_matrix_cores ? 6.0 + 2.0 * elems / 4.2e6 + (double)distinct * elems / 8.0 / 2.15e6
+                                            : 8.0 + elems * (2.0 + (double)distinct / 8.0) / 1.3e6;
     }
     return gemm_us < decode_us;
 }
@@ -324,6 +327,14 @@ bd_status bd_compress_iterated(const uint16_t* w_base_f16, const uint16_t* w_ft_
     return BD_OK;
 }
 
+namespace {
+bd_status tiled_linear_impl(int32_t n_mats, const uint16_t* x_f16, const uint16_t* const* w_tiled,
+                            const uint32_t* const* tiled_by_mat_tenant, const float* const* alpha_by_mat,
+                            const int32_t* tenant_of_token, uint16_t* const* y_f16, int64_t T, const int64_t* out,
+                            int64_t in, int32_t n_tenants, int32_t k, void* stream, bool q8,
+                            const uint32_t* const* packed_rowmajor_dev);
+}
+
 bd_status bd_linear_multitenant_variant(const uint16_t* x_f16, const uint16_t* w_base_f16,
                                         const uint32_t* const* packed_by_tenant, const float* alpha_by_tenant,
                                         const int32_t* tenant_of_token, uint16_t* y_f16, int64_t T, int64_t out,
@@ -334,7 +345,7 @@ bd_status bd_linear_multitenant_variant(const uint16_t* x_f16, const uint16_t* w
     if (st != BD_OK) return st;
     const bool big_variant = variant == kVariantPrefillBig || variant == kVariantPrefillBig8 || variant == kVariantPrefillBigWhole;
     const bool prefill_variant = variant == kVariantPrefillSmall || big_variant;
-    if (variant != 0 && variant != kVariantRowWave && !bd::decode_mfma_variant_known(variant) && !prefill_variant)
+    if (variant != 0 && variant != kVariantRowWave && variant != kVariantRowMajorMfma && !prefill_variant)
         return BD_ERR_UNSUPPORTED;
     if (T == 0 || out == 0) return BD_OK;
     // 128-bit sign loads need whole, aligned 4-word groups; 32-bit lane offsets need tensors below 4 GiB
@@ -342,7 +353,7 @@ bd_status bd_linear_multitenant_variant(const uint16_t* x_f16, const uint16_t* w
                          (uint64_t)T * (uint64_t)in * 2 < ((uint64_t)1 << 32);
     if (variant >= 2 && !prefill_variant && !mfma_ok) return BD_ERR_UNSUPPORTED;
     int use = variant;
-    if (use == 0) use = mfma_ok ? kVariantDefaultMfma : kVariantRowWave;
+    if (use == 0) use = mfma_ok ? kVariantRowMajorMfma : kVariantRowWave;
 
     hipStream_t hs = (hipStream_t)stream;
     // More than one decode launch worth of tokens: the prefill GEMM, if the caller brought its workspace
@@ -365,7 +376,12 @@ bd_status bd_linear_multitenant_variant(const uint16_t* x_f16, const uint16_t* w
                    ? BD_OK
                    : BD_ERR_DEVICE;
     }
-    if (prefill_variant) use = mfma_ok ? kVariantDefaultMfma : kVariantRowWave;   // not reached: can_prefill held above
+    if (prefill_variant) use = mfma_ok ? kVariantRowMajorMfma : kVariantRowWave;   // not reached: can_prefill held above
+    if (use == kVariantRowMajorMfma && in > 0)
+        // the decode kernel of the serving path, reading the row-major tensors as they are; all tokens are grouped by
+        // tenant first, then cut into launches of 32
+        return tiled_linear_impl(1, x_f16, &w_base_f16, nullptr, &alpha_by_tenant, tenant_of_token, &y_f16, T, &out, in,
+                                 n_tenants, 1, stream, false, packed_by_tenant);
     for (int64_t t0 = 0; t0 < T; t0 += kMaxDecodeTokens) {
         const int n = (int)std::min<int64_t>(kMaxDecodeTokens, T - t0);
         DecodeMeta meta;
@@ -373,14 +389,8 @@ bd_status bd_linear_multitenant_variant(const uint16_t* x_f16, const uint16_t* w
         const uint16_t* xs = x_f16 + t0 * in;
         uint16_t* ys = y_f16 + t0 * out;
         hipError_t e;
-        if (in == 0) {
-            // empty reduction: y = 0.  The row-wave kernel handles it (its loop body never runs).
-            e = bd::launch_linear_rowwave(xs, w_base_f16, packed_by_tenant, alpha_by_tenant, meta, ys, out, in, hs);
-        } else if (use == kVariantRowWave) {
-            e = bd::launch_linear_rowwave(xs, w_base_f16, packed_by_tenant, alpha_by_tenant, meta, ys, out, in, hs);
-        } else {
-            e = bd::launch_linear_decode_mfma(xs, w_base_f16, packed_by_tenant, alpha_by_tenant, meta, ys, out, in, use, hs);
-        }
+        // the vector-ALU kernel; also the empty reduction, y = 0 (its loop body never runs)
+        e = bd::launch_linear_rowwave(xs, w_base_f16, packed_by_tenant, alpha_by_tenant, meta, ys, out, in, hs);
         if (e != hipSuccess) return BD_ERR_DEVICE;
     }
     return BD_OK;
@@ -441,10 +451,15 @@ namespace {
 // The tiled linear over n_mats matrices that share x, with k sign planes per tenant (k = 1: plain 1-bit
 // deltas).  Pointer table index: (m * n_tenants + tenant) * k + plane; scale index: tenant * k + plane.
 // q8: w_tiled point at 8-bit base tiles followed by their per-row scales (bd_tile_base_q8).
+// packed_rowmajor_dev != NULL: the row-major entry point.  w_tiled[0] is then W [out, in] row-major, the deltas are
+// reached through that DEVICE table of n_tenants pointers (tiled_by_mat_tenant is not used), n_mats = k = 1.
 bd_status tiled_linear_impl(int32_t n_mats, const uint16_t* x_f16, const uint16_t* const* w_tiled,
                             const uint32_t* const* tiled_by_mat_tenant, const float* const* alpha_by_mat,
                             const int32_t* tenant_of_token, uint16_t* const* y_f16, int64_t T, const int64_t* out,
-                            int64_t in, int32_t n_tenants, int32_t k, void* stream, bool q8 = false) {
+                            int64_t in, int32_t n_tenants, int32_t k, void* stream, bool q8,
+                            const uint32_t* const* packed_rowmajor_dev) {
+    const bool rm = packed_rowmajor_dev != nullptr;
+    if (rm && (n_mats != 1 || k != 1 || q8 || in % 128 != 0)) return BD_ERR_UNSUPPORTED;
     if (n_mats < 1 || n_mats > bd::kTiledMaxMats) return BD_ERR_SHAPE;
     if (k < 1 || k > bd::kTiledMaxPlanes) return BD_ERR_SHAPE;
     if (!out) return BD_ERR_NULL;
@@ -465,7 +480,7 @@ bd_status tiled_linear_impl(int32_t n_mats, const uint16_t* x_f16, const uint16_
             if (out[m] > 0 && bd::launch_fill_zero_u16(y_f16[m], T * out[m], (hipStream_t)stream) != hipSuccess) return BD_ERR_DEVICE;
         return BD_OK;
     }
-    if (!x_f16 || !w_tiled || !tiled_by_mat_tenant || !alpha_by_mat || !tenant_of_token || !y_f16) return BD_ERR_NULL;
+    if (!x_f16 || !w_tiled || (!rm && !tiled_by_mat_tenant) || !alpha_by_mat || !tenant_of_token || !y_f16) return BD_ERR_NULL;
     if (misaligned(x_f16, 16)) return BD_ERR_ALIGN;
     for (int64_t t = 0; t < T; ++t)
         if (tenant_of_token[t] < 0 || tenant_of_token[t] >= n_tenants) return BD_ERR_TENANT;
@@ -474,10 +489,10 @@ bd_status tiled_linear_impl(int32_t n_mats, const uint16_t* x_f16, const uint16_
         if (!w_tiled[m] || !alpha_by_mat[m] || !y_f16[m]) return BD_ERR_NULL;
         if (misaligned(w_tiled[m], 16) || misaligned(y_f16[m], 2) || misaligned(alpha_by_mat[m], 4)) return BD_ERR_ALIGN;
         const size_t ybytes = (size_t)T * out[m] * 2;
-        if (overlaps(y_f16[m], ybytes, x_f16, (size_t)T * in * 2) ||
-            overlaps(y_f16[m], ybytes, w_tiled[m], q8 ? bd_tiled_base_q8_bytes(out[m], in) : bd_tiled_base_bytes(out[m], in)))
+        const size_t wbytes = rm ? (size_t)out[m] * in * 2 : (q8 ? bd_tiled_base_q8_bytes(out[m], in) : bd_tiled_base_bytes(out[m], in));
+        if (overlaps(y_f16[m], ybytes, x_f16, (size_t)T * in * 2) || overlaps(y_f16[m], ybytes, w_tiled[m], wbytes))
             return BD_ERR_ALIAS;
-        for (int64_t t = 0; t < T; ++t)
+        for (int64_t t = 0; t < T && !rm; ++t)
             for (int j = 0; j < k; ++j) {
                 const uint32_t* p = tiled_by_mat_tenant[((size_t)m * n_tenants + tenant_of_token[t]) * k + j];
                 if (!p) return BD_ERR_NULL;
@@ -501,6 +516,7 @@ bd_status tiled_linear_impl(int32_t n_mats, const uint16_t* x_f16, const uint16_
         a.KT = (int32_t)bd::tiled_k_tiles(in);
         a.n_ct = n > per_tile ? 2 : 1;
         a.planes = k;
+        a.packed_by_tenant = packed_rowmajor_dev;
         int32_t rb = 0;
         int mats = 0;
         int mat_of[bd::kTiledMaxMats] = {0, 0, 0};
@@ -541,14 +557,16 @@ bd_status tiled_linear_impl(int32_t n_mats, const uint16_t* x_f16, const uint16_
             for (; col < bd::kTiledMaxTokens; ++col) a.col_job[ct][col] = -1;
             const int n_jobs = n_runs * k;
             max_jobs = std::max(max_jobs, n_jobs);
-            for (int mi = 0; mi < mats; ++mi)
-                for (int sl = 0; sl < bd::kTiledMaxJobs; ++sl) {   // slots beyond the jobs repeat slot 0 (never selected)
-                    const int s = sl < n_jobs ? sl : 0;
+            for (int sl = 0; sl < bd::kTiledMaxJobs; ++sl) {   // slots beyond the jobs repeat slot 0 (never selected)
+                const int s = sl < n_jobs ? sl : 0;
+                a.job_tenant[ct][sl] = run_tenant[s / k];
+                for (int mi = 0; mi < mats && !rm; ++mi)
                     a.signs[ct][mi][sl] = tiled_by_mat_tenant[((size_t)mat_of[mi] * n_tenants + run_tenant[s / k]) * k + s % k];
-                }
+            }
         }
-        const hipError_t e = q8 ? bd::launch_linear_decode_tiled_q8(a, max_jobs, (hipStream_t)stream)
-                                : bd::launch_linear_decode_tiled(a, max_jobs, (hipStream_t)stream);
+        const hipError_t e = rm   ? bd::launch_linear_decode_rowmajor(a, max_jobs, (hipStream_t)stream)
+                             : q8 ? bd::launch_linear_decode_tiled_q8(a, max_jobs, (hipStream_t)stream)
+                                  : bd::launch_linear_decode_tiled(a, max_jobs, (hipStream_t)stream);
         if (e != hipSuccess) return BD_ERR_DEVICE;
     }
     return BD_OK;
@@ -611,7 +629,7 @@ bd_status bd_linear_multitenant_tiled_group_q8(int32_t n_mats, const uint16_t* x
                                                uint16_t* const* y_f16, int64_t T, const int64_t* out, int64_t in,
                                                int32_t n_tenants, void* stream) {
     return tiled_linear_impl(n_mats, x_f16, (const uint16_t* const*)wq_tiled, tiled_by_mat_tenant, alpha_by_mat, tenant_of_token,
-                             y_f16, T, out, in, n_tenants, 1, stream, true);
+                             y_f16, T, out, in, n_tenants, 1, stream, true, nullptr);
 }
 
 bd_status bd_linear_multitenant_tiled_q8(const uint16_t* x_f16, const void* wq_tiled, const uint32_t* const* tiled_by_tenant,
@@ -619,7 +637,7 @@ bd_status bd_linear_multitenant_tiled_q8(const uint16_t* x_f16, const void* wq_t
                                          int64_t T, int64_t out, int64_t in, int32_t n_tenants, void* stream) {
     const uint16_t* w = (const uint16_t*)wq_tiled;
     return tiled_linear_impl(1, x_f16, &w, tiled_by_tenant, &alpha_by_tenant, tenant_of_token, &y_f16, T, &out, in, n_tenants, 1,
-                             stream, true);
+                             stream, true, nullptr);
 }
 
 bd_status bd_linear_multitenant_tiled_group(int32_t n_mats, const uint16_t* x_f16, const uint16_t* const* w_tiled,
@@ -628,7 +646,7 @@ bd_status bd_linear_multitenant_tiled_group(int32_t n_mats, const uint16_t* x_f1
                                             uint16_t* const* y_f16, int64_t T, const int64_t* out, int64_t in,
                                             int32_t n_tenants, void* stream) {
     return tiled_linear_impl(n_mats, x_f16, w_tiled, tiled_by_mat_tenant, alpha_by_mat, tenant_of_token, y_f16, T, out, in,
-                             n_tenants, 1, stream);
+                             n_tenants, 1, stream, false, nullptr);
 }
 
 bd_status bd_linear_multitenant_tiled(const uint16_t* x_f16, const uint16_t* w_tiled,
@@ -636,7 +654,7 @@ bd_status bd_linear_multitenant_tiled(const uint16_t* x_f16, const uint16_t* w_t
                                       const int32_t* tenant_of_token, uint16_t* y_f16, int64_t T, int64_t out, int64_t in,
                                       int32_t n_tenants, void* stream) {
     return tiled_linear_impl(1, x_f16, &w_tiled, tiled_by_tenant, &alpha_by_tenant, tenant_of_token, &y_f16, T, &out, in,
-                             n_tenants, 1, stream);
+                             n_tenants, 1, stream, false, nullptr);
 }
 
 bd_status bd_linear_multitenant_tiled_group_kbit(int32_t n_mats, const uint16_t* x_f16, const uint16_t* const* w_tiled,
@@ -645,7 +663,7 @@ bd_status bd_linear_multitenant_tiled_group_kbit(int32_t n_mats, const uint16_t*
                                                  uint16_t* const* y_f16, int64_t T, const int64_t* out, int64_t in,
                                                  int32_t n_tenants, int32_t k, void* stream) {
     return tiled_linear_impl(n_mats, x_f16, w_tiled, planes_by_mat_tenant, alpha_by_mat, tenant_of_token, y_f16, T, out, in,
-                             n_tenants, k, stream);
+                             n_tenants, k, stream, false, nullptr);
 }
 
 bd_status bd_linear_multitenant_tiled_kbit(const uint16_t* x_f16, const uint16_t* w_tiled,
@@ -653,7 +671,7 @@ bd_status bd_linear_multitenant_tiled_kbit(const uint16_t* x_f16, const uint16_t
                                            const int32_t* tenant_of_token, uint16_t* y_f16, int64_t T, int64_t out,
                                            int64_t in, int32_t n_tenants, int32_t k, void* stream) {
     return tiled_linear_impl(1, x_f16, &w_tiled, planes_by_tenant, &alpha_by_tenant, tenant_of_token, &y_f16, T, &out, in,
-                             n_tenants, k, stream);
+                             n_tenants, k, stream, false, nullptr);
 }
 
 bd_status bd_group_tokens(const int32_t* tenant_of_token, int32_t T, int32_t* token_of_col, int32_t* job_tenant,

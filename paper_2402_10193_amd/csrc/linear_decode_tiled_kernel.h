@@ -36,8 +36,18 @@
 // accumulates sum_k x, and the finished row block is scale[n] * (acc - 1152 * sum_k x): no
 // arithmetic per weight beyond the byte shuffle.
 //
-// This header is the kernel; linear_decode_tiled.hip and linear_decode_tiled_q8.hip instantiate it
-// for the fp16 and the 8-bit base (two translation units, so that they compile side by side).
+// Row-major tensors (RM; what bd_compress writes and bd_linear_multitenant takes).  The same kernel reads W
+// [out, in] fp16 and packed signs [out, in/32] as they are: slice v of a base tile is then 16 rows x 64 bytes
+// (lane (r, g) reads 16 bytes of row r), and a tenant's signs of a tile are 16 rows x 32 bytes, of which lane
+// (r, g) loads words 2 g and 2 g + 1.  Those hold sign BYTE i of slices 2 g and 2 g + 1 for every lane group i,
+// while the lane needs byte g of all eight slices: the four lanes of a row exchange them with two byte shuffles,
+// a swap between the wavefront's halves, two more shuffles and a swap between neighbouring rows of 16 lanes
+// (v_permlane32_swap / v_permlane16_swap), six vector instructions per job and task.  The tenants' pointers
+// come from the caller's device table (one scalar load each) instead of the kernel arguments.
+//
+// This header is the kernel; linear_decode_tiled.hip, linear_decode_tiled_q8.hip and linear_decode_rowmajor.hip
+// instantiate it for the fp16 base, the 8-bit base and the row-major tensors (three translation units, so that
+// they compile side by side).
 #pragma once
 
 #include <type_traits>
@@ -92,14 +102,37 @@ __device__ __forceinline__ u32x4 lut_read(const u32x2 s, const int v, const uint
     return *(lds_u32x4_ptr)(uintptr_t)addr;
 }
 
+// Row-major signs.  In: this lane's words 2 g and 2 g + 1 of its row (lane (r, g) = (lane % 16, lane / 16)); byte i of
+// word w is the sign byte of slice w for lane group i.  Out: s[0] = byte g of words 0, 1, 4, 5 and s[1] = byte g of
+// words 2, 3, 6, 7 (in that order), i.e. everything lane (r, g) needs.  All 64 lanes must be active.
+__device__ __forceinline__ u32x2 rm_gather_sign_bytes(const u32x2 w) {
+    // bytes for lane groups 0, 1 and for 2, 3, the two words interleaved
+    const uint32_t p = __builtin_amdgcn_perm(w[1], w[0], 0x05010400u);
+    const uint32_t q = __builtin_amdgcn_perm(w[1], w[0], 0x07030602u);
+    // lanes 32..63 of p against lanes 0..31 of q: groups 0, 1 now hold both halves' p, groups 2, 3 both halves' q
+    const auto h = __builtin_amdgcn_permlane32_swap(p, q, false, false);
+    // split by the parity of the byte index, then trade with the neighbouring group
+    const uint32_t u = __builtin_amdgcn_perm(h[1], h[0], 0x05040100u);
+    const uint32_t t = __builtin_amdgcn_perm(h[1], h[0], 0x07060302u);
+    const auto f = __builtin_amdgcn_permlane16_swap(u, t, false, false);
+    return u32x2{f[0], f[1]};
+}
+// slice v of the gathered bytes: word (v / 2) % 2, byte v % 2 + 2 * (v / 4)
+__device__ __forceinline__ u32x4 lut_read_rm(const u32x2 s, const int v, const uint32_t lanebits) {
+    const uint32_t addr = __builtin_amdgcn_perm(s[(v >> 1) & 1], lanebits, 0x0C0C0000u | ((4u + ((v & 1) | ((v & 4) >> 1))) << 8));
+    return *(lds_u32x4_ptr)(uintptr_t)addr;
+}
+
 }  // namespace
 
 // XSTEPS = 1 or 2: every wavefront has exactly that many k tiles and keeps their x in registers.
 // XSTEPS = 0: any number of k tiles per wavefront, x double-buffered per task.
 // NCT = 2 (streamed x only): 17..32 tokens as two column tiles; the tasks of one (row block, k tile)
 // then come in pairs that share the base registers, so the base is still read once.
-template <int NJ, int XSTEPS, int NCT, bool Q8>
+// RM: row-major W and packed signs (one matrix, fp16 base, in % 128 == 0) instead of the tiled tensors.
+template <int NJ, int XSTEPS, int NCT, bool Q8, bool RM = false>
 __global__ __launch_bounds__(kMaxWavesTiled * kWave) void linear_decode_tiled_kernel(const TiledArgs a) {
+    static_assert(!(RM && Q8), "the 8-bit base exists in the tiled layout only");
     constexpr uint32_t kWTile = Q8 ? kTileBaseQ8Bytes : kTileBaseBytes;   // bytes of one base tile
     constexpr int kWLoads = Q8 ? 4 : 8;                                   // 1 KiB loads per base tile
     extern __shared__ __align__(16) unsigned char smem[];   // [0, 64 KiB): table; then one region per wavefront
@@ -153,16 +186,71 @@ __global__ __launch_bounds__(kMaxWavesTiled * kWave) void linear_decode_tiled_ke
 #pragma unroll
     for (int ct = 0; ct < NCT; ++ct)
 #pragma unroll
-        for (int j = 0; j < NJ; ++j) sp[ct][j] = (const unsigned char*)a.signs[ct][m_req][j];
-    const uint32_t lane16 = (uint32_t)lane * 16u, lane8 = (uint32_t)lane * 8u;
+        for (int j = 0; j < NJ; ++j) sp[ct][j] = RM ? nullptr : (const unsigned char*)a.signs[ct][m_req][j];
+    // Row-major: the tenants' pointers come from the caller's table in device memory.  Sixteen pointers held as
+    // scalars cannot be dropped and fetched again like kernel arguments, and would push the kernel's vector
+    // registers into scratch; so lane j of one register pair holds the pointer of job slot j, and a sign load
+    // takes its base address from there with two v_readlane.
+    uint32_t ptr_lo[NCT], ptr_hi[NCT];
+#pragma unroll
+    for (int ct = 0; ct < NCT; ++ct) {
+        ptr_lo[ct] = ptr_hi[ct] = 0u;
+        if constexpr (RM) {
+            int tenant_l = a.job_tenant[ct][0];
+#pragma unroll
+            for (int i = 1; i < kTiledMaxJobs; ++i) tenant_l = (lane == i) ? a.job_tenant[ct][i] : tenant_l;
+            const uint64_t pv = (uint64_t)a.packed_by_tenant[tenant_l];
+            ptr_lo[ct] = (uint32_t)pv;
+            ptr_hi[ct] = (uint32_t)(pv >> 32);
+        }
+    }
+    auto sign_ptr = [&](const int ct, const int j) -> const unsigned char* {
+        if constexpr (RM) {
+            const uint32_t lo = __builtin_amdgcn_readlane(ptr_lo[ct], j), hi = __builtin_amdgcn_readlane(ptr_hi[ct], j);
+            return (const unsigned char*)(((uint64_t)hi << 32) | lo);
+        } else {
+            return sp[ct][j];
+        }
+    };
+    // Byte offsets of a task's loads = a uniform part (tile) + this lane's part.  Tiled: the lane's part is its place
+    // inside a tile.  Row-major: the uniform part is the k tile only and the lane's part carries the row, so it
+    // changes with the row block (rows beyond `out` read the last row again; their results are never stored).
+    uint32_t lane16 = (uint32_t)lane * 16u, lane8 = (uint32_t)lane * 8u;
+    auto rm_lane_offsets = [&](const int rb) {
+        const int row = min(rb * kTileRows + c, a.out[0] - 1);
+        lane16 = (uint32_t)row * ((uint32_t)a.in * 2u) + (uint32_t)g * 16u;
+        lane8 = (uint32_t)row * ((uint32_t)a.in >> 3) + (uint32_t)g * 8u;
+    };
+    if constexpr (RM) rm_lane_offsets(rb_req);
+    auto w_off = [&](const int rb, const int kt) {   // uniform byte offset of tile (rb, kt) of the base
+        return RM ? (uint32_t)kt * (uint32_t)(kTileK * 2) : (uint32_t)(rb * KT + kt) * kWTile;
+    };
+    auto s_off = [&](const int rb, const int kt) {   // ... of a tenant's signs
+        return RM ? (uint32_t)kt * (uint32_t)(kTileK / 8) : (uint32_t)(rb * KT + kt) * (uint32_t)kTileSignBytes;
+    };
+    constexpr uint32_t kSliceStride = RM ? 64u : 1024u;   // bytes between a lane's loads of consecutive slices
+    // Row-major, `in` = 128 mod 256: the last k tile of a row has 4 slices.  No load may reach beyond the row (the
+    // last row ends the tensor), so slices 4..7 of such a tile read slices 0..3 again and are replaced by zeros when
+    // they are multiplied; lane groups 2, 3 read the row's first sign words instead of theirs (any valid words do:
+    // their x is zero).  All of it is uniform arithmetic per task, no branch around a load.
+    const int kt_short = (RM && (a.in % kTileK) != 0) ? KT - 1 : -1;
+    auto w_base_hi = [&](const int kt) {   // the pointer slices 4..7 of tile kt are read through
+        return (RM && kt == kt_short) ? wt - 4 * kSliceStride : wt;
+    };
+    auto s_lane_off = [&](const uint32_t off_u, const uint32_t l8, const int kt) {
+        uint32_t off = off_u + l8;
+        if constexpr (RM) off = (kt == kt_short && g >= 2) ? l8 - (uint32_t)g * 8u : off;
+        return off;
+    };
 
     // ---- requests of the first task: base first, (table,) then x, then the signs
     u32x4 wr[kWLoads];   // fp16 base: slice v; 8-bit base: slices 2 i and 2 i + 1 (8 bytes each)
     u32x2 sr[NJ];
-    const uint32_t tile0 = (uint32_t)(rb_req * KT + kb);
     if (have_work) {
+        const uint32_t woff0 = w_off(rb_req, kb) + lane16;
+        const unsigned char* const wt_hi0 = w_base_hi(kb);
 #pragma unroll
-        for (int v = 0; v < kWLoads; ++v) wr[v] = ldg16_stream(wt, tile0 * kWTile + lane16 + v * 1024);
+        for (int v = 0; v < kWLoads; ++v) wr[v] = ldg16_stream(v >= 4 ? wt_hi0 : wt, woff0 + (uint32_t)v * kSliceStride);
     }
 
     // ---- the table: entry b, copy cp at 256 b + 16 cp; element e = bit e of b ? +1.0 : -1.0.
@@ -247,9 +335,9 @@ __global__ __launch_bounds__(kMaxWavesTiled * kWave) void linear_decode_tiled_ke
     if (have_work) {
         if constexpr (XSTEPS > 0) x_fetch(xraw[0], kb);
         else x_fetch_operands(xs[0], kb, 0);
-        const uint32_t soff0 = tile0 * (uint32_t)kTileSignBytes + lane8;
+        const uint32_t soff0 = s_lane_off(s_off(rb_req, kb), lane8, kb);
 #pragma unroll
-        for (int j = 0; j < NJ; ++j) sr[j] = ldg8_stream(sp[0][j], soff0);
+        for (int j = 0; j < NJ; ++j) sr[j] = ldg8_stream(sign_ptr(0, j), soff0);
         if constexpr (XSTEPS == 2) x_fetch(xraw[1], kb + 1);
     }
 
@@ -292,8 +380,8 @@ __global__ __launch_bounds__(kMaxWavesTiled * kWave) void linear_decode_tiled_ke
     // last column tile of a (row block, k tile) only.  xr: this task's x in operand order; with
     // streamed x the next task's (kt_next, next column tile) is fetched into xnext during the task
     // and replaces xr at its end.
-    auto task = [&](auto more_tag, auto ct_tag, u32x4 (&xr)[8], const uint32_t tile_next, u32x4 (&xnext)[8],
-                    const int kt_next) {
+    auto task = [&](auto more_tag, auto ct_tag, u32x4 (&xr)[8], const int kt_cur, const int rb_next, const int kt_next,
+                    u32x4 (&xnext)[8]) {
         constexpr bool MORE = decltype(more_tag)::value;
         constexpr int CT = decltype(ct_tag)::value;
         constexpr int CT_NEXT = (CT + 1) % NCT;
@@ -302,7 +390,9 @@ __global__ __launch_bounds__(kMaxWavesTiled * kWave) void linear_decode_tiled_ke
         // "uniform base + lane offset" of every load out of the loop as a 64-bit register pair per load.
         uint32_t l16 = lane16, l8 = lane8;
         asm volatile("" : "+v"(l16), "+v"(l8));
-        const uint32_t woff = tile_next * kWTile + l16, soff = tile_next * (uint32_t)kTileSignBytes + l8;
+        const uint32_t woff = w_off(rb_next, kt_next) + l16, soff = s_lane_off(s_off(rb_next, kt_next), l8, kt_next);
+        const unsigned char* const wt_hi = w_base_hi(kt_next);
+        const bool short_cur = RM && kt_cur == kt_short;
         // ---- base product; W[v] of the next task goes into the register group just read
 #pragma unroll
         for (int v = 0; v < 8; ++v) {
@@ -314,9 +404,11 @@ __global__ __launch_bounds__(kMaxWavesTiled * kWave) void linear_decode_tiled_ke
                     if (v & 1) wr[v >> 1] = ldg16_stream(wt, woff + (v >> 1) * 1024);
                 }
             } else {
-                accb[CT] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8, wr[v]),
+                u32x4 wv = wr[v];
+                if (RM && v >= 4) wv = short_cur ? u32x4{0u, 0u, 0u, 0u} : wv;
+                accb[CT] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8, wv),
                                                                   __builtin_bit_cast(half8, xr[v]), accb[CT], 0, 0, 0);
-                if constexpr (MORE && NEW_BASE) wr[v] = ldg16_stream(wt, woff + v * 1024);
+                if constexpr (MORE && NEW_BASE) wr[v] = ldg16_stream(v >= 4 ? wt_hi : wt, woff + (uint32_t)v * kSliceStride);
             }
             __builtin_amdgcn_sched_barrier(0);   // keep each request behind the MFMA that frees its registers
         }
@@ -325,14 +417,20 @@ __global__ __launch_bounds__(kMaxWavesTiled * kWave) void linear_decode_tiled_ke
         // ---- delta jobs.  The 8 NJ (job, slice) pairs of the task form one sequence; the table
         // look-up of pair i + kLookAhead is issued before the MFMA of pair i, through a ring of
         // operand registers, and a job's sign words are re-requested as soon as its last address exists.
-        constexpr int kLookAhead = NCT == 2 ? 4 : 6, kRing = kLookAhead + 2, kPairs = 8 * NJ;
+        // (row-major with 16 jobs: a shorter ring, so that the two registers the row offsets take do not end up in scratch)
+        constexpr int kLookAhead = (NCT == 2 || (RM && NJ == 16)) ? 4 : 6, kRing = kLookAhead + 2, kPairs = 8 * NJ;
         u32x4 ring[kRing];
         float4v sel = {0.f, 0.f, 0.f, 0.f};   // the job owning this lane's column, this tile
         auto look_up = [&](const int i) {      // i = 8 * job + slice
             const int j = i >> 3, v = i & 7;
-            ring[i % kRing] = lut_read(sr[j], v, lanebits);
+            if constexpr (RM) {
+                if (v == 0) sr[j] = rm_gather_sign_bytes(sr[j]);
+                ring[i % kRing] = lut_read_rm(sr[j], v, lanebits);
+            } else {
+                ring[i % kRing] = lut_read(sr[j], v, lanebits);
+            }
             if constexpr (MORE) {
-                if (v == 7) sr[j] = ldg8_stream(sp[CT_NEXT][j], soff);
+                if (v == 7) sr[j] = ldg8_stream(sign_ptr(CT_NEXT, j), soff);
             }
         };
 #pragma unroll
@@ -396,9 +494,8 @@ __global__ __launch_bounds__(kMaxWavesTiled * kWave) void linear_decode_tiled_ke
         // where the requests go after this row block's last task
         int m_nx = m_req, rb_nx = 0;
         if (!last_rb) mat_of(r0 + rbi + 1, m_nx, rb_nx);
-        const uint32_t tile_rb = (uint32_t)(rb_req * KT + kb);            // first tile of this wavefront in this row block
-        const uint32_t tile_nx = (uint32_t)(rb_nx * KT + kb);             // ... and in the next one
         auto cross = [&]() {   // requests move on to the next row block: switch the pointers if it is in another matrix
+            if constexpr (RM) rm_lane_offsets(rb_nx);
             if (m_nx != m_req) {
                 wt = (const unsigned char*)a.wt[m_nx];
 #pragma unroll
@@ -413,24 +510,24 @@ __global__ __launch_bounds__(kMaxWavesTiled * kWave) void linear_decode_tiled_ke
 #pragma unroll
             for (int ki = 0; ki < XSTEPS; ++ki) {
                 if (ki + 1 < XSTEPS) {
-                    task(std::true_type{}, Ct0{}, xs[ki], tile_rb + ki + 1, xraw[0], 0);
+                    task(std::true_type{}, Ct0{}, xs[ki], kb + ki, rb_req, kb + ki + 1, xraw[0]);
                 } else if (!last_rb) {
                     cross();
-                    task(std::true_type{}, Ct0{}, xs[ki], tile_nx, xraw[0], 0);
+                    task(std::true_type{}, Ct0{}, xs[ki], kb + ki, rb_nx, kb, xraw[0]);
                 } else {
-                    task(std::false_type{}, Ct0{}, xs[ki], 0u, xraw[0], 0);
+                    task(std::false_type{}, Ct0{}, xs[ki], kb + ki, 0, 0, xraw[0]);
                 }
             }
         } else {
             for (int ki = 0; ki < steps; ++ki) {
                 const bool inner = ki + 1 < steps;
                 // all but the last column tile: the next task stays on this tile (same k tile, next columns)
-                if constexpr (NCT == 2) task(std::true_type{}, Ct0{}, xs[0], tile_rb + ki, xraw[0], kb + ki);
+                if constexpr (NCT == 2) task(std::true_type{}, Ct0{}, xs[0], kb + ki, rb_req, kb + ki, xraw[0]);
                 if (!inner && !last_rb) cross();
                 if (inner || !last_rb)
-                    task(std::true_type{}, CtL{}, xs[0], inner ? tile_rb + ki + 1 : tile_nx, xraw[0], inner ? kb + ki + 1 : kb);
+                    task(std::true_type{}, CtL{}, xs[0], kb + ki, inner ? rb_req : rb_nx, inner ? kb + ki + 1 : kb, xraw[0]);
                 else
-                    task(std::false_type{}, CtL{}, xs[0], 0u, xraw[0], 0);
+                    task(std::false_type{}, CtL{}, xs[0], kb + ki, 0, 0, xraw[0]);
             }
         }
         // ---- row block done: this wavefront's partial tiles -> slots
@@ -466,9 +563,9 @@ __global__ __launch_bounds__(kMaxWavesTiled * kWave) void linear_decode_tiled_ke
     }
 }
 
-template <bool Q8, int NJ, int XSTEPS, int NCT = 1>
+template <bool Q8, bool RM, int NJ, int XSTEPS, int NCT = 1>
 static hipError_t launch_inst(const TiledArgs& args, int n_waves, unsigned grid, hipStream_t st) {
-    auto kernel = linear_decode_tiled_kernel<NJ, XSTEPS, NCT, Q8>;
+    auto kernel = linear_decode_tiled_kernel<NJ, XSTEPS, NCT, Q8, RM>;
     const size_t lds = (size_t)LdsPlan<XSTEPS>::kTotal;
     static PerDeviceOnce lds_limit;   // one per instantiation
     const hipError_t ea = lds_limit.run([&] {
@@ -483,15 +580,16 @@ static hipError_t launch_inst(const TiledArgs& args, int n_waves, unsigned grid,
     return hipGetLastError();
 }
 
-template <bool Q8, int NJ>
+template <bool Q8, bool RM, int NJ>
 static hipError_t launch_nj(const TiledArgs& args, int n_waves, int xsteps, unsigned grid, hipStream_t st) {
-    if (xsteps == 1) return launch_inst<Q8, NJ, 1>(args, n_waves, grid, st);
-    if (xsteps == 2) return launch_inst<Q8, NJ, 2>(args, n_waves, grid, st);
-    return launch_inst<Q8, NJ, 0>(args, n_waves, grid, st);
+    if (xsteps == 1) return launch_inst<Q8, RM, NJ, 1>(args, n_waves, grid, st);
+    if (xsteps == 2) return launch_inst<Q8, RM, NJ, 2>(args, n_waves, grid, st);
+    return launch_inst<Q8, RM, NJ, 0>(args, n_waves, grid, st);
 }
 
-template <bool Q8>
+template <bool Q8, bool RM = false>
 static hipError_t launch_tiled_t(const TiledArgs& args, int n_jobs, hipStream_t st) {
+    if (RM && (args.n_mats != 1 || args.in % 128 != 0 || args.in < 128 || !args.packed_by_tenant)) return hipErrorInvalidValue;
     if (n_jobs < 1 || n_jobs > kTiledMaxJobs || args.n_mats < 1 || args.n_mats > kTiledMaxMats || args.n_ct < 1 ||
         args.n_ct > kTiledMaxCt)
         return hipErrorInvalidValue;
@@ -513,15 +611,15 @@ static hipError_t launch_tiled_t(const TiledArgs& args, int n_jobs, hipStream_t 
     int n_waves = kMaxWavesTiled;
     while (n_waves > 1 && n_waves > args.KT) n_waves >>= 1;
     if (args.n_ct == 2) {   // 17..32 tokens: two column tiles, streamed x
-        if (n_jobs <= 4) return launch_inst<Q8, 4, 0, 2>(args, n_waves, grid, st);
-        if (n_jobs <= 8) return launch_inst<Q8, 8, 0, 2>(args, n_waves, grid, st);
-        return launch_inst<Q8, 16, 0, 2>(args, n_waves, grid, st);
+        if (n_jobs <= 4) return launch_inst<Q8, RM, 4, 0, 2>(args, n_waves, grid, st);
+        if (n_jobs <= 8) return launch_inst<Q8, RM, 8, 0, 2>(args, n_waves, grid, st);
+        return launch_inst<Q8, RM, 16, 0, 2>(args, n_waves, grid, st);
     }
     int xsteps = 0;
     if (args.KT > 0 && args.KT % n_waves == 0 && args.KT / n_waves <= 2) xsteps = args.KT / n_waves;
-    if (n_jobs <= 4) return launch_nj<Q8, 4>(args, n_waves, xsteps, grid, st);
-    if (n_jobs <= 8) return launch_nj<Q8, 8>(args, n_waves, xsteps, grid, st);
-    return launch_nj<Q8, 16>(args, n_waves, xsteps, grid, st);
+    if (n_jobs <= 4) return launch_nj<Q8, RM, 4>(args, n_waves, xsteps, grid, st);
+    if (n_jobs <= 8) return launch_nj<Q8, RM, 8>(args, n_waves, xsteps, grid, st);
+    return launch_nj<Q8, RM, 16>(args, n_waves, xsteps, grid, st);
 }
 
 }  // namespace bd

@@ -12,7 +12,7 @@ from paper_2402_10193_amd import synth           # noqa: E402
 from gpu_util import Problem, check_close, packed_to_np, to_np, packed_to_device   # noqa: E402
 
 DEV = "cuda"
-VARIANTS = [0, 1, 2, 3]
+VARIANTS = [0, 1, 2]   # library's choice, vector-ALU kernel, matrix-core kernel on the row-major tensors
 
 
 @pytest.fixture(scope="module", autouse=True)
