@@ -229,6 +229,14 @@ __global__ __launch_bounds__(kMaxWavesTiled * kWave) void linear_decode_tiled_ke
         return RM ? (uint32_t)kt * (uint32_t)(kTileK / 8) : (uint32_t)(rb * KT + kt) * (uint32_t)kTileSignBytes;
     };
     constexpr uint32_t kSliceStride = RM ? 64u : 1024u;   // bytes between a lane's loads of consecutive slices
+    // The tiled tensors are read once, whole cache lines at a time, with non-temporal loads (nothing of a line is
+    // needed again).  Row-major, a load takes half a line of the base and a quarter of a line of signs per row; the rest
+    // of the line belongs to the next slice or to the neighbouring wavefront's tiles, so those loads are ordinary ones
+    // and the line stays in L2 for them (non-temporal, every line came from HBM 1.6 to 2.3 times).
+    auto ld_w = [](const unsigned char* p, const uint32_t off) { return RM ? ldg16(p, off) : ldg16_stream(p, off); };
+    auto ld_s = [](const unsigned char* p, const uint32_t off) {
+        return RM ? *(const u32x2*)(p + off) : ldg8_stream(p, off);
+    };
     // Row-major, `in` = 128 mod 256: the last k tile of a row has 4 slices.  No load may reach beyond the row (the
     // last row ends the tensor), so slices 4..7 of such a tile read slices 0..3 again and are replaced by zeros when
     // they are multiplied; lane groups 2, 3 read the row's first sign words instead of theirs (any valid words do:
@@ -250,7 +258,7 @@ __global__ __launch_bounds__(kMaxWavesTiled * kWave) void linear_decode_tiled_ke
         const uint32_t woff0 = w_off(rb_req, kb) + lane16;
         const unsigned char* const wt_hi0 = w_base_hi(kb);
 #pragma unroll
-        for (int v = 0; v < kWLoads; ++v) wr[v] = ldg16_stream(v >= 4 ? wt_hi0 : wt, woff0 + (uint32_t)v * kSliceStride);
+        for (int v = 0; v < kWLoads; ++v) wr[v] = ld_w(v >= 4 ? wt_hi0 : wt, woff0 + (uint32_t)v * kSliceStride);
     }
 
     // ---- the table: entry b, copy cp at 256 b + 16 cp; element e = bit e of b ? +1.0 : -1.0.
@@ -337,7 +345,7 @@ __global__ __launch_bounds__(kMaxWavesTiled * kWave) void linear_decode_tiled_ke
         else x_fetch_operands(xs[0], kb, 0);
         const uint32_t soff0 = s_lane_off(s_off(rb_req, kb), lane8, kb);
 #pragma unroll
-        for (int j = 0; j < NJ; ++j) sr[j] = ldg8_stream(sign_ptr(0, j), soff0);
+        for (int j = 0; j < NJ; ++j) sr[j] = ld_s(sign_ptr(0, j), soff0);
         if constexpr (XSTEPS == 2) x_fetch(xraw[1], kb + 1);
     }
 
@@ -408,7 +416,7 @@ __global__ __launch_bounds__(kMaxWavesTiled * kWave) void linear_decode_tiled_ke
                 if (RM && v >= 4) wv = short_cur ? u32x4{0u, 0u, 0u, 0u} : wv;
                 accb[CT] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8, wv),
                                                                   __builtin_bit_cast(half8, xr[v]), accb[CT], 0, 0, 0);
-                if constexpr (MORE && NEW_BASE) wr[v] = ldg16_stream(v >= 4 ? wt_hi : wt, woff + (uint32_t)v * kSliceStride);
+                if constexpr (MORE && NEW_BASE) wr[v] = ld_w(v >= 4 ? wt_hi : wt, woff + (uint32_t)v * kSliceStride);
             }
             __builtin_amdgcn_sched_barrier(0);   // keep each request behind the MFMA that frees its registers
         }
@@ -430,7 +438,7 @@ __global__ __launch_bounds__(kMaxWavesTiled * kWave) void linear_decode_tiled_ke
                 ring[i % kRing] = lut_read(sr[j], v, lanebits);
             }
             if constexpr (MORE) {
-                if (v == 7) sr[j] = ldg8_stream(sign_ptr(CT_NEXT, j), soff);
+                if (v == 7) sr[j] = ld_s(sign_ptr(CT_NEXT, j), soff);
             }
         };
 #pragma unroll
