@@ -32,14 +32,22 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
-# HBM bytes per launch of the decode kernel measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by what the
-# same counters read for a plain copy of known size (summary and commands: profiles/*_hbm_traffic.md).
-# Key: (model, tenants, path).  Other configurations report null.
-MEASURED_TRAFFIC_BYTES_PER_LAUNCH = {("7b", 16, "tiled-fused"): 204.5e6}
-
-
-def measured_traffic(model, tenants, path):
-    return MEASURED_TRAFFIC_BYTES_PER_LAUNCH.get((model, tenants, path))
+def measured_traffic(model, tenants, path, library_version):
+    """HBM bytes per launch of the decode kernel as measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by what
+    the same counters read for a plain copy of known size).  The figure lives in the rocprofv3 summary under profiles/
+    (a line "traffic-record: model=.. tenants=.. path=.. library_version=.. bytes_per_launch=.."), next to the commands
+    that produced it; it is reported only for the library version it was measured on, otherwise None."""
+    import glob
+    import re
+    for f in sorted(glob.glob(os.path.join(ROOT, "profiles", "*hbm_traffic.md"))):
+        for line in open(f):
+            if not line.startswith("traffic-record:"):
+                continue
+            kv = dict(re.findall(r"(\w+)=(\S+)", line))
+            if (kv.get("model") == model and kv.get("path") == path and int(kv.get("tenants", -1)) == tenants
+                    and int(kv.get("library_version", -1)) == library_version):
+                return float(kv["bytes_per_launch"])
+    return None
 
 
 def parse():
@@ -450,7 +458,7 @@ def main():
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
             "frac": round(achieved_gbs / HBM_PEAK_GBS, 4),
-            "traffic": measured_traffic(args.model, B, args.path) if n_layers == 32 and not args.mix and k == 1 and not q8 else None,
+            "traffic": measured_traffic(args.model, B, args.path, bd.version()) if n_layers == 32 and not args.mix and k == 1 and not q8 else None,
             "kernel": kernel_name,
             "bytes_per_launch": round(bytes_per_step / launches_per_step, 1),
             "avg_launch_us": round(ms_per_step * 1e3 / launches_per_step, 3),
