@@ -23,8 +23,8 @@
 //   * 32 signs per uint32 along `in`, least significant bit first,
 //     bit = 1 means +1 (Eq. 2's "d > 0"), so zero and negative map to bit 0;
 //   * Delta is formed in IEEE binary32 from the binary16 inputs;
-//   * alpha is summed in binary64, divided by out*in, rounded once to binary16
-//     and carried as a float;
+//   * alpha is summed in binary64, divided by out*in, rounded ONCE (binary64 ->
+//     binary16, nearest even; not by way of binary32) and carried as a float;
 //   * the two products of Eq. 6 are accumulated separately in binary32 in
 //     ascending k, alpha is applied to the finished +-1 sum in binary32, and the
 //     result is rounded once (nearest even) to binary16.  A binary64 variant
@@ -116,6 +116,36 @@ inline uint16_t float_to_half_bits(float v) {
     return (uint16_t)(sign | half);
 }
 
+// binary64 -> binary16, ONE rounding to nearest even, written out from the IEEE layout (not by way of binary32:
+// a value a hair above the middle between two binary16 neighbours would first round onto that middle and then,
+// as a tie, to the even neighbour).
+inline uint16_t double_to_half_bits(double v) {
+    uint64_t bits;
+    std::memcpy(&bits, &v, sizeof(bits));
+    const uint16_t sign = (uint16_t)((bits >> 48) & 0x8000u);
+    const uint64_t absbits = bits & 0x7FFFFFFFFFFFFFFFull;
+    if (absbits >= 0x7FF0000000000000ull)   // Inf or NaN
+        return (uint16_t)(sign | 0x7C00u | ((absbits > 0x7FF0000000000000ull) ? 0x0200u : 0u));
+    const int e = (int)(absbits >> 52) - 1023;          // unbiased (binary64 subnormals: far below binary16's range)
+    const uint64_t frac = absbits & 0xFFFFFFFFFFFFFull;  // 52 bits
+    if (e >= 16) return (uint16_t)(sign | 0x7C00u);
+    if (e >= -14) {
+        uint32_t mant = (uint32_t)(frac >> 42);          // 10 bits kept
+        const uint64_t rest = frac & ((1ull << 42) - 1), halfway = 1ull << 41;
+        uint32_t half = ((uint32_t)(e + 15) << 10) | mant;
+        if (rest > halfway || (rest == halfway && (mant & 1u))) ++half;   // may carry into the exponent / to Inf
+        return (uint16_t)(sign | half);
+    }
+    if (e < -25) return sign;                            // below half of the smallest subnormal (2^-25 itself: see below)
+    // subnormal result, unit 2^-24: value = (2^52 + frac) * 2^(e-52)
+    const uint64_t full = frac | (1ull << 52);
+    const int drop = (-24) - (e - 52);                   // 42 + (-14 - e) : 43..53
+    const uint64_t mant = full >> drop, rest = full & ((1ull << drop) - 1), halfway = 1ull << (drop - 1);
+    uint32_t half = (uint32_t)mant;
+    if (rest > halfway || (rest == halfway && (mant & 1ull))) ++half;
+    return (uint16_t)(sign | half);
+}
+
 inline int sign_of_bit(const uint32_t* row_words, int64_t k) {
     return ((row_words[k >> 5] >> (k & 31)) & 1u) ? +1 : -1;
 }
@@ -127,6 +157,7 @@ extern "C" {
 // ---- conversions, exported so tests can pin them against a library -------
 float bd_ref_f16_to_f32(uint16_t h) { return half_bits_to_float(h); }
 uint16_t bd_ref_f32_to_f16(float v) { return float_to_half_bits(v); }
+uint16_t bd_ref_f64_to_f16(double v) { return double_to_half_bits(v); }
 
 int bd_ref_num_threads(void) {
 #ifdef _OPENMP
@@ -192,7 +223,7 @@ int bd_ref_compress(const uint16_t* w_base_f16, const uint16_t* w_ft_f16, int64_
     for (int64_t n = 0; n < out; ++n) total += row_sum[(size_t)n];
     const double mean = (out > 0 && in > 0) ? total / ((double)out * (double)in) : 0.0;
     if (alpha_unrounded) *alpha_unrounded = mean;
-    if (alpha_f16_as_float) *alpha_f16_as_float = half_bits_to_float(float_to_half_bits((float)mean));
+    if (alpha_f16_as_float) *alpha_f16_as_float = half_bits_to_float(double_to_half_bits(mean));
     return 0;
 }
 
@@ -292,7 +323,7 @@ int bd_ref_compress_iterated(const uint16_t* w_base_f16, const uint16_t* w_ft_f1
         if (residual_sq) residual_sq[j] = total_sq;
         if (j == k) break;
         const double mean = count > 0 ? total_abs / (double)count : 0.0;
-        const float a = half_bits_to_float(float_to_half_bits((float)mean));
+        const float a = half_bits_to_float(double_to_half_bits(mean));
         if (alpha_unrounded) alpha_unrounded[j] = mean;
         alpha_f16_as_float[j] = a;
         uint32_t* plane = packed + (int64_t)j * out * words;
@@ -424,7 +455,7 @@ int bd_ref_compress_q8(const int8_t* q, const float* scale, const uint16_t* w_ft
     for (int64_t n = 0; n < out; ++n) total += row_sum[(size_t)n];
     const double mean = (out > 0 && in > 0) ? total / ((double)out * (double)in) : 0.0;
     if (alpha_unrounded) *alpha_unrounded = mean;
-    if (alpha_f16_as_float) *alpha_f16_as_float = half_bits_to_float(float_to_half_bits((float)mean));
+    if (alpha_f16_as_float) *alpha_f16_as_float = half_bits_to_float(double_to_half_bits(mean));
     return 0;
 }
 

@@ -49,6 +49,8 @@ def lib() -> ctypes.CDLL:
         L.bd_ref_f16_to_f32.argtypes = [ctypes.c_uint16]
         L.bd_ref_f32_to_f16.restype = ctypes.c_uint16
         L.bd_ref_f32_to_f16.argtypes = [ctypes.c_float]
+        L.bd_ref_f64_to_f16.restype = ctypes.c_uint16
+        L.bd_ref_f64_to_f16.argtypes = [ctypes.c_double]
         L.bd_ref_num_threads.restype = ctypes.c_int
         L.bd_ref_pack_signs.argtypes = [c_u16p, i64, i64, c_u32p]
         L.bd_ref_unpack_signs.argtypes = [c_u32p, i64, i64, c_i8p]
@@ -100,6 +102,11 @@ def f16_to_f32(bits: int) -> float:
 
 def f32_to_f16(v: float) -> int:
     return int(lib().bd_ref_f32_to_f16(float(v)))
+
+
+def f64_to_f16(v: float) -> int:
+    """binary64 -> binary16 bits, one rounding to nearest even (what the scale of Eq. 4 goes through)."""
+    return int(lib().bd_ref_f64_to_f16(float(v)))
 
 
 def pack_signs(delta: np.ndarray) -> np.ndarray:

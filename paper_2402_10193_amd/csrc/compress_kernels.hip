@@ -200,6 +200,22 @@ __global__ __launch_bounds__(kCompressThreads) void compress_batch_kernel(const 
     }
 }
 
+// binary64 -> binary16 with ONE rounding to nearest even, returned as a float.  There is no such conversion in
+// hardware; going through binary32 would round twice (a mean a hair above the middle between two binary16 neighbours
+// lands on the middle first and then, as a tie, on the even neighbour).  So the binary32 step rounds to ODD instead:
+// truncate towards zero and set the last bit if anything was dropped; binary32 keeps 13 more bits than binary16, so
+// the final rounding then sees on which side of every binary16 middle the mean really lies.
+__device__ __forceinline__ float f64_to_f16_once(const double v) {
+    float f = (float)v;   // nearest even
+    if ((double)f != v && __builtin_isfinite(f)) {   // inexact (NaN stays as it is)
+        uint32_t bits = __builtin_bit_cast(uint32_t, f);
+        if (__builtin_fabs((double)f) > __builtin_fabs(v)) bits -= 1u;   // back to the truncated value
+        bits |= 1u;
+        f = __builtin_bit_cast(float, bits);
+    }
+    return (float)(_Float16)f;
+}
+
 // alpha = fp16_rne( sum(partial) / count ), one block, fixed summation order.
 __global__ __launch_bounds__(256) void alpha_finalize_kernel(const double* __restrict__ partial, int n_partial,
                                                              double count, float* __restrict__ alpha) {
@@ -214,8 +230,7 @@ __global__ __launch_bounds__(256) void alpha_finalize_kernel(const double* __res
     }
     if (threadIdx.x == 0) {
         const double mean = count > 0.0 ? sm[0] / count : 0.0;
-        const float m32 = (float)mean;
-        *alpha = (float)(_Float16)m32;   // one rounding to fp16, carried as a float
+        *alpha = f64_to_f16_once(mean);   // one rounding to fp16, carried as a float
     }
 }
 
@@ -236,8 +251,7 @@ __global__ __launch_bounds__(256) void alpha_finalize_batch_kernel(const double*
     if (threadIdx.x == 0) {
         const double count = (double)a.n_vec[m] * 8.0;
         const double mean = count > 0.0 ? sm[0] / count : 0.0;
-        const float m32 = (float)mean;
-        alpha[m] = (float)(_Float16)m32;
+        alpha[m] = f64_to_f16_once(mean);
     }
 }
 

@@ -1,8 +1,8 @@
 """GPU parity at the benchmark's full sizes (Llama-2-7B and 70B layer shapes), in the launch configuration
 bench.py times: the row-major entry point, the tiled entry point and the grouped (q,k,v / gate,up) tiled
-launches.  The 7B layer is compared in full; the 70B matrices on sampled output rows, which the oracle
-computes one by one (rows of a linear are independent, so a row slice of W and of the packed deltas is a
-complete problem)."""
+launches.  The 7B layer and the 70B matrices (32 tenants) are compared in full; the prefill GEMM (4096 tokens)
+on sampled output rows for every token and on every output row for sampled tokens (rows of a linear and tokens
+of a batch are independent, so a slice of either is a complete problem for the oracle)."""
 import numpy as np
 import pytest
 import torch
@@ -140,34 +140,30 @@ def test_llama2_7b_mixed_batch_gate_up_full_output(ref, case):
 
 
 @pytest.mark.timeout(900)
-@pytest.mark.parametrize("name,out,inn", [("kv", 1024, 8192), ("gate", 28672, 8192), ("down", 8192, 28672)])
-def test_llama2_70b_b32_sampled_rows(ref, name, out, inn):
-    B, n_rows = 32, 256
+@pytest.mark.parametrize("name,out,inn", [("kv", 1024, 8192), ("qo", 8192, 8192), ("gate", 28672, 8192), ("down", 8192, 28672)])
+def test_llama2_70b_b32_full_output(ref, name, out, inn):
+    B = 32
     print(f"70B {name} {out}x{inn} B={B}", flush=True)
     base, fts, table = _gpu_layer(out, inn, B, 0.001, ("70b", name))
     x = synth.activations(B, inn, device=DEV, tag=("70b", name))
     tok = synth.one_token_per_tenant(B)
     y = bd.linear_multitenant(x, base, table, tok)
     ttable = bd.TiledTenantTable([bd.tile_signs(p, out, inn) for p in table.packed], table.alpha)
-    y_tiled = bd.linear_multitenant_tiled(x, bd.tile_base(base), out, ttable, tok)   # 32 tokens: two launches of 16
+    y_tiled = bd.linear_multitenant_tiled(x, bd.tile_base(base), out, ttable, tok)   # 32 tokens: one launch, two column tiles
     torch.cuda.synchronize()
-    g = torch.Generator().manual_seed(7)
-    rows = torch.sort(torch.randperm(out, generator=g)[:n_rows]).values
-    rows[0], rows[-1] = 0, out - 1
-    rows_d = rows.to(DEV)
-    base_full = to_np(base)
+    base_np = to_np(base)
     refc, alphas = [], []
     for t in range(B):
-        p, a, _ = ref.compress(base_full, to_np(fts[t]))                   # oracle compression of the full matrix
+        p, a, _ = ref.compress(base_np, to_np(fts[t]))                     # oracle compression of the full matrix
         assert np.array_equal(packed_to_np(table.packed[t]), p)
         assert float(table.alpha[t].item()) == a
-        refc.append(np.ascontiguousarray(p[rows.numpy()]))
+        refc.append(p)
         alphas.append(a)
         fts[t] = None
-    base_np = np.ascontiguousarray(base_full[rows.numpy()])
+    print("   oracle linear ...", flush=True)
     _, y32 = ref.linear_multitenant(to_np(x), base_np, refc, alphas, tok)
-    err = check_close(y[:, rows_d], y32, f"70B {name}")
-    err_t = check_close(y_tiled[:, rows_d], y32, f"70B {name} tiled")
+    err = check_close(y, y32, f"70B {name}")
+    err_t = check_close(y_tiled, y32, f"70B {name} tiled")
     print(f"   max rel err {err:.2e} (row-major)  {err_t:.2e} (tiled)", flush=True)
 
 
@@ -191,4 +187,29 @@ def test_prefill_8_tenants_x_512_tokens_sampled_rows(ref, name, out, inn):
     base_np = np.ascontiguousarray(to_np(base)[rows.numpy()])
     _, y32 = ref.linear_multitenant(to_np(x), base_np, packed, alphas, tok)
     err = check_close(y[:, rows.to(DEV)], y32, f"prefill {name}")
+    print(f"   max rel err {err:.2e}", flush=True)
+
+
+@pytest.mark.timeout(900)
+def test_prefill_8_tenants_x_512_tokens_every_output_row_of_sampled_tokens(ref):
+    """The same launch (all 4096 tokens go through the GEMM) checked the other way round: every output row, i.e. every
+    tile of every workgroup, for 8 sampled tokens of each tenant."""
+    B, per, out, inn = 8, 512, 11008, 4096
+    print(f"prefill up {out}x{inn} T={B * per}, all rows of sampled tokens", flush=True)
+    base, fts, table = _gpu_layer(out, inn, B, 0.002, ("pf", "up"))
+    oracle_packed, alphas = _oracle_deltas(ref, base, fts, table)
+    del fts
+    tok = [t for t in range(B) for _ in range(per)]
+    x = synth.activations(B * per, inn, device=DEV, tag=("pf", "up"))
+    y = bd.linear_multitenant(x, base, table, tok)
+    torch.cuda.synchronize()
+    g = torch.Generator().manual_seed(13)
+    picks = []
+    for t in range(B):
+        p = torch.sort(torch.randperm(per, generator=g)[:8]).values + t * per
+        p[0], p[-1] = t * per, (t + 1) * per - 1          # first and last token of the tenant's tiles
+        picks.append(p)
+    picks = torch.cat(picks)
+    _, y32 = ref.linear_multitenant(to_np(x[picks.to(DEV)]), to_np(base), oracle_packed, alphas, [tok[i] for i in picks.tolist()])
+    err = check_close(y[picks.to(DEV)], y32, "prefill up, sampled tokens")
     print(f"   max rel err {err:.2e}", flush=True)

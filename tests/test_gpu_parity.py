@@ -56,6 +56,19 @@ def test_compress_bits_exact_alpha_within_one_fp16_ulp(ref, out, inn, sigma):
     assert a == a_ref, (a, a_ref)                    # the binary64 sums agree to ~1e-16, so in practice: equal
 
 
+def test_compress_scale_rounded_once_at_a_binary16_middle(ref):
+    """The mean |Delta| of this pair lies 2^-29 above the middle between two binary16 numbers: rounded once it goes up,
+    by way of binary32 it would land on the middle and go down.  Kernel and oracle must both go up."""
+    from test_oracle_pins import midpoint_scale_matrices
+    base_np, ft_np = midpoint_scale_matrices()
+    base, ft = torch.from_numpy(base_np).to(DEV), torch.from_numpy(ft_np).to(DEV)
+    _, alpha = bd.compress(base, ft)
+    _, a_ref, _ = ref.compress(base_np, ft_np)
+    assert float(alpha.item()) == a_ref == 1.0 + 2.0**-10
+    _, ab = bd.compress_batch([base, base], [ft, ft])
+    assert ab.tolist() == [a_ref, a_ref]
+
+
 def test_compress_propagates_inf_and_handles_empty(ref):
     base = synth.base_weight(8, 64, device=DEV)
     ft = base.clone()

@@ -42,6 +42,53 @@ def test_f32_to_f16_round_nearest_even_matches_numpy(ref):
     assert np.array_equal(got, want)
 
 
+def test_f64_to_f16_rounds_once_and_matches_numpy(ref):
+    """The conversion the scale of Eq. 4 goes through: binary64 straight to binary16.  numpy's float64 -> float16 cast
+    rounds once; values just beside a middle between two binary16 neighbours tell one rounding from two."""
+    rng = np.random.default_rng(2)
+    vals = [0.0, -0.0, 1.0, 65504.0, 65519.999999, 65520.0, 1e6, -1e6, float("inf"), float("-inf"), 2.0**-24, 2.0**-25,
+            2.0**-25 * (1 + 2.0**-40), 2.0**-26, 3 * 2.0**-25, 2.0**-14, 2.0**-14 - 2.0**-25, 1e-300, 1.6e-3, 7.98e-4]
+    vals += list(rng.standard_normal(4000) * 0.002)
+    vals += list(np.exp(rng.uniform(-20, 12, 4000)) * rng.choice([-1, 1], 4000))
+    h = np.arange(0, 0x7BFF, 5, dtype=np.uint16)
+    lo = h.view(np.float16).astype(np.float64)
+    hi = (h + 1).astype(np.uint16).view(np.float16).astype(np.float64)
+    mid = (lo + hi) / 2
+    ulp32 = np.spacing(mid.astype(np.float32)).astype(np.float64)
+    # the middle itself (tie -> even), and a quarter of a binary32 step to either side: binary32 would swallow it
+    vals += list(mid) + list(mid + ulp32 / 4) + list(mid - ulp32 / 4)
+    arr = np.array(vals, dtype=np.float64)
+    with np.errstate(over="ignore"):
+        want = arr.astype(np.float16).view(np.uint16)
+    got = np.array([ref.f64_to_f16(float(v)) for v in arr], dtype=np.uint16)
+    assert np.array_equal(got, want)
+    # and the two-step conversion really differs on those: the test would see a detour through binary32
+    two_step = np.array([ref.f32_to_f16(float(np.float32(v))) for v in mid + ulp32 / 4], dtype=np.uint16)
+    one_step = np.array([ref.f64_to_f16(float(v)) for v in mid + ulp32 / 4], dtype=np.uint16)
+    assert (two_step != one_step).sum() > len(mid) // 3
+
+
+def midpoint_scale_matrices():
+    """A (base, fine-tuned) pair of 1 x 64 whose mean |Delta| is 1 + 2^-11 + 2^-29: a hair above the middle between the
+    binary16 neighbours 1 and 1 + 2^-10.  One rounding gives 1 + 2^-10; by way of binary32 (which rounds the mean onto
+    the middle, a tie) it would give 1."""
+    base = np.zeros((1, 64), dtype=np.float16)
+    ft = np.ones((1, 64), dtype=np.float16)
+    ft[0, :32] = np.float16(1.0 + 2.0**-10)
+    base[0, 63] = np.float16(-(2.0**-23))            # Delta = 1 + 2^-23, exact in binary32
+    return base, ft
+
+
+def test_scale_is_rounded_once_at_a_binary16_middle(ref):
+    base, ft = midpoint_scale_matrices()
+    packed, alpha, mean = ref.compress(base, ft)
+    assert mean == 1.0 + 2.0**-11 + 2.0**-29                      # the binary64 mean is exact here
+    assert float(np.float32(mean)) == 1.0 + 2.0**-11              # binary32 would put it ON the middle
+    assert alpha == 1.0 + 2.0**-10                                # one rounding: up
+    assert alpha == float(np.float64(mean).astype(np.float16))
+    assert np.all(packed == 0xFFFFFFFF)
+
+
 def test_f32_to_f16_nan_stays_nan(ref):
     h = ref.f32_to_f16(float("nan"))
     assert (h & 0x7C00) == 0x7C00 and (h & 0x3FF) != 0
