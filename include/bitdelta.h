@@ -234,6 +234,22 @@ bd_status bd_compress_iterated(const uint16_t* w_base_f16, const uint16_t* w_ft_
                                uint32_t* packed, float* alpha,
                                void* workspace, size_t workspace_bytes, void* stream);
 
+/* Eq. 6 with k planes per tenant on the row-major tensors (the k-plane form of bd_linear_multitenant):
+ *   y[t] = x[t] W_base^T + sum_{j<k} alpha[e*k+j] * (x[t] S_{e,j}^T),   e = tenant_of_token[t]
+ *   planes_by_tenant  DEVICE array [n_tenants * k] of device pointers, entry e*k + j = plane j of tenant e as
+ *                     bd_compress_iterated writes it ([out, in/32] words)
+ *   alpha_by_tenant   device [n_tenants * k]
+ * Runs on the matrix-core decode kernel only: in % 128 == 0 and a base below 4 GiB, else BD_ERR_UNSUPPORTED.
+ * A token occupies k of a launch's 32 columns; more tokens run as several launches.  Other arguments and errors as
+ * bd_linear_multitenant; k outside 1..BD_MAX_PLANES gives BD_ERR_SHAPE.  Needs no workspace. */
+bd_status bd_linear_multitenant_kbit(const uint16_t* x_f16, const uint16_t* w_base_f16,
+                                     const uint32_t* const* planes_by_tenant,
+                                     const float* alpha_by_tenant,
+                                     const int32_t* tenant_of_token,
+                                     uint16_t* y_f16,
+                                     int64_t T, int64_t out, int64_t in, int32_t n_tenants, int32_t k,
+                                     void* stream);
+
 /* Eq. 6 with k planes per tenant over the serving layout:
  *   y[t] = x[t] W_base^T + sum_{j<k} alpha[e*k+j] * (x[t] S_{e,j}^T),   e = tenant_of_token[t]
  * (each +-1 sum accumulated in binary32, scaled, added to the base product; one rounding to fp16).

@@ -31,7 +31,7 @@ EXPORTS = ["bd_status_string", "bd_version", "bd_workspace_bytes", "bd_pack_sign
            "bd_delta_image_build", "bd_delta_image_check", "bd_delta_image_entry", "bd_delta_file_write",
            "bd_delta_file_bytes", "bd_delta_file_read", "bd_delta_upload", "bd_delta_install", "bd_quantize_base_q8",
            "bd_compress_q8", "bd_tiled_base_q8_bytes", "bd_tile_base_q8", "bd_linear_multitenant_tiled_q8",
-           "bd_linear_multitenant_tiled_group_q8"]
+           "bd_linear_multitenant_tiled_group_q8", "bd_linear_multitenant_kbit"]
 
 
 class BitDeltaError(RuntimeError):
@@ -99,6 +99,7 @@ def lib() -> ctypes.CDLL:
         L.bd_linear_multitenant_tiled_q8.argtypes = [vp, vp, pvp, vp, pi, vp, i64, i64, i64, i32, vp]
         L.bd_linear_multitenant_tiled_group_q8.argtypes = [i32, vp, pvp, pvp, pvp, pi, pvp, i64, pi64, i64, i32, vp]
         L.bd_compress_iterated.argtypes = [vp, vp, i64, i64, i32, vp, vp, vp, sz, vp]
+        L.bd_linear_multitenant_kbit.argtypes = [vp, vp, vp, vp, pi, vp, i64, i64, i64, i32, i32, vp]
         L.bd_compress_batch.argtypes = [i32, pvp, pvp, pi64, pi64, pvp, vp, vp, sz, vp]
         L.bd_compress_batch.restype = ctypes.c_int
         L.bd_linear_multitenant_tiled_kbit.argtypes = [vp, vp, pvp, vp, pi, vp, i64, i64, i64, i32, i32, vp]
@@ -444,6 +445,43 @@ def linear_multitenant_tiled(x: torch.Tensor, w_tiled: torch.Tensor, out: int, t
     _check(lib().bd_linear_multitenant_tiled(_ptr(x), _ptr(w_tiled), tenants.host_ptrs, _ptr(tenants.alpha), tok,
                                              _ptr(y), T, out, inn, tenants.n_tenants, _stream(stream)),
            "bd_linear_multitenant_tiled")
+    return y
+
+
+class PlaneTable:
+    """Device-side arrays of bd_linear_multitenant_kbit: pointers to every tenant's k row-major planes (entry
+    tenant * k + plane) and the scales [n_tenants * k].  planes_by_tenant: list of int32 tensors [k, out, in/32]."""
+
+    def __init__(self, planes_by_tenant: Sequence[torch.Tensor], alpha_by_tenant: torch.Tensor):
+        self.planes = list(planes_by_tenant)
+        self.k = int(self.planes[0].shape[0])
+        for p in self.planes:
+            _dev(p, torch.int32, "planes")
+            if p.shape[0] != self.k:
+                raise ValueError("every tenant needs the same number of planes")
+        dev = self.planes[0].device
+        self.ptrs = torch.tensor([p[j].data_ptr() for p in self.planes for j in range(self.k)], dtype=torch.int64, device=dev)
+        self.alpha = alpha_by_tenant.to(device=dev, dtype=torch.float32).reshape(-1).contiguous()
+        if self.alpha.numel() != len(self.planes) * self.k:
+            raise ValueError("one alpha per tenant and plane")
+
+    @property
+    def n_tenants(self) -> int:
+        return len(self.planes)
+
+
+def linear_multitenant_kbit(x: torch.Tensor, w_base: torch.Tensor, tenants: PlaneTable, tenant_of_token: Sequence[int],
+                            y: Optional[torch.Tensor] = None, stream=None, tok_array=None) -> torch.Tensor:
+    """bd_linear_multitenant_kbit: y fp16 [T, out] from the row-major base and k row-major planes per tenant."""
+    _dev(x, torch.float16, "x")
+    _dev(w_base, torch.float16, "w_base")
+    T, inn = x.shape
+    out = w_base.shape[0]
+    if y is None:
+        y = torch.empty((T, out), dtype=torch.float16, device=x.device)
+    tok = tok_array if tok_array is not None else _tok_array(tenant_of_token)
+    _check(lib().bd_linear_multitenant_kbit(_ptr(x), _ptr(w_base), _ptr(tenants.ptrs), _ptr(tenants.alpha), tok, _ptr(y), T, out,
+                                            inn, tenants.n_tenants, tenants.k, _stream(stream)), "bd_linear_multitenant_kbit")
     return y
 
 

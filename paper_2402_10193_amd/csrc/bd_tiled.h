@@ -61,8 +61,9 @@ struct TiledArgs {
     // when y is written and only the first contributes the base product.  One plane: all 1.
     int32_t col_span[kTiledMaxCt][kTiledMaxTokens];
     int32_t planes;                                           // k: 1 = plain 1-bit deltas
-    // Row-major entry point only (wt[0] = W [out, in] row-major, signs[][][] unused): the caller's DEVICE table of
-    // tenants' packed deltas [out, in/32] and the tenant of every job slot (slots beyond the jobs repeat slot 0's).
+    // Row-major entry points only (wt[0] = W [out, in] row-major, signs[][][] unused): the caller's DEVICE table of
+    // packed deltas [out, in/32], entry tenant * planes + plane, and the table index of every job slot (slots beyond
+    // the jobs repeat slot 0's).
     const uint32_t* const* packed_by_tenant;
     int32_t job_tenant[kTiledMaxCt][kTiledMaxJobs];
 };

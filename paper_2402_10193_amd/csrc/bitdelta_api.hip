@@ -459,7 +459,7 @@ bd_status tiled_linear_impl(int32_t n_mats, const uint16_t* x_f16, const uint16_
                             int64_t in, int32_t n_tenants, int32_t k, void* stream, bool q8,
                             const uint32_t* const* packed_rowmajor_dev) {
     const bool rm = packed_rowmajor_dev != nullptr;
-    if (rm && (n_mats != 1 || k != 1 || q8 || in % 128 != 0)) return BD_ERR_UNSUPPORTED;
+    if (rm && (n_mats != 1 || q8 || in % 128 != 0)) return BD_ERR_UNSUPPORTED;
     if (n_mats < 1 || n_mats > bd::kTiledMaxMats) return BD_ERR_SHAPE;
     if (k < 1 || k > bd::kTiledMaxPlanes) return BD_ERR_SHAPE;
     if (!out) return BD_ERR_NULL;
@@ -559,7 +559,7 @@ bd_status tiled_linear_impl(int32_t n_mats, const uint16_t* x_f16, const uint16_
             max_jobs = std::max(max_jobs, n_jobs);
             for (int sl = 0; sl < bd::kTiledMaxJobs; ++sl) {   // slots beyond the jobs repeat slot 0 (never selected)
                 const int s = sl < n_jobs ? sl : 0;
-                a.job_tenant[ct][sl] = run_tenant[s / k];
+                a.job_tenant[ct][sl] = run_tenant[s / k] * k + s % k;   // index into the caller's table: (tenant, plane)
                 for (int mi = 0; mi < mats && !rm; ++mi)
                     a.signs[ct][mi][sl] = tiled_by_mat_tenant[((size_t)mat_of[mi] * n_tenants + run_tenant[s / k]) * k + s % k];
             }
@@ -664,6 +664,20 @@ bd_status bd_linear_multitenant_tiled_group_kbit(int32_t n_mats, const uint16_t*
                                                  int32_t n_tenants, int32_t k, void* stream) {
     return tiled_linear_impl(n_mats, x_f16, w_tiled, planes_by_mat_tenant, alpha_by_mat, tenant_of_token, y_f16, T, out, in,
                              n_tenants, k, stream, false, nullptr);
+}
+
+bd_status bd_linear_multitenant_kbit(const uint16_t* x_f16, const uint16_t* w_base_f16, const uint32_t* const* planes_by_tenant,
+                                     const float* alpha_by_tenant, const int32_t* tenant_of_token, uint16_t* y_f16, int64_t T,
+                                     int64_t out, int64_t in, int32_t n_tenants, int32_t k, void* stream) {
+    if (k < 1 || k > bd::kTiledMaxPlanes) return BD_ERR_SHAPE;
+    const bd_status st = check_linear_args(x_f16, w_base_f16, planes_by_tenant, alpha_by_tenant, tenant_of_token, y_f16, T, out, in,
+                                           n_tenants);
+    if (st != BD_OK) return st;
+    if (T == 0 || out == 0) return BD_OK;
+    // the matrix-core kernel on the row-major tensors: whole groups of four sign words, 32-bit byte offsets
+    if (in % 128 != 0 || in == 0 || (uint64_t)out * (uint64_t)in * 2 >= ((uint64_t)1 << 32)) return BD_ERR_UNSUPPORTED;
+    return tiled_linear_impl(1, x_f16, &w_base_f16, nullptr, &alpha_by_tenant, tenant_of_token, &y_f16, T, &out, in, n_tenants, k,
+                             stream, false, planes_by_tenant);
 }
 
 bd_status bd_linear_multitenant_tiled_kbit(const uint16_t* x_f16, const uint16_t* w_tiled,

@@ -95,6 +95,16 @@ __device__ __forceinline__ void prefill_big_tile(
     unsigned char* const lut = lds + 2 * kBgBufBytes;
 
     constexpr int kThreads = 256 * WM, kWaveM = TM / WM, MI = kWaveM / 32;
+    // mfma_in_place hides the accumulators from the compiler's hazard bookkeeping, so the schedule itself has to keep
+    // an accumulator's uses apart.  A k slice issues, for every (i, j), one MFMA into accb[i][j] and one into accd[i][j]:
+    // 4 MI MFMAs, each accumulator once, always in the same order, so 4 MI - 1 other MFMAs (each 8 passes = 32 cycles of
+    // the matrix pipe) lie between two uses of one accumulator.  The dependent-accumulate hazard of the 8-pass
+    // instructions is below 20 cycles; 7 MFMAs (MI = 2: 64-row halves, or two wavefronts per SIMD) are 224.
+    // The epilogue reads the accumulators with vector instructions after two `s_nop 15` (32 wait states; the rule for
+    // reading the result of an 8-pass MFMA asks for 18).  Every instantiation has a full-output parity test.
+    constexpr int kMfmasBetweenUses = 4 * MI - 1;
+    static_assert(MI == 2 || MI == 4, "the slice schedule below is written for 2 or 4 token blocks per wavefront");
+    static_assert(kMfmasBetweenUses >= 7, "an accumulator would be used again while its last MFMA may still be in the pipe");
     constexpr int kBgXPer = TM * 8 / kThreads, kBgWPer = kBgN * 8 / kThreads;   // 16-byte chunks per thread and step
     constexpr int kSets = WM == 1 ? 2 : 1;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;

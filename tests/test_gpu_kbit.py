@@ -119,6 +119,28 @@ def test_kbit_linear_matches_oracle(ref, case):
         assert torch.equal(bd.linear_multitenant_tiled(x, prob.w_tiled, out, tt, tok), y)
 
 
+@pytest.mark.parametrize("case", range(len(KBIT_CASES)))
+def test_kbit_linear_on_row_major_tensors_matches_oracle_and_tiled_call(ref, case):
+    """bd_linear_multitenant_kbit: the same k-plane linear read from the row-major base and planes.  Same arithmetic as the
+    tiled call (same kernel, same order of additions): the same bits; shapes the row-major kernel cannot run are refused."""
+    out, inn, nt, k, tok = KBIT_CASES[case]
+    _p(f"kbit row-major case={case} out={out} in={inn} tenants={nt} k={k} T={len(tok)}")
+    prob = PlaneProblem(ref, out, inn, nt, k, tag=("klin", case))
+    x = prob.x(len(tok))
+    planes = [torch.stack([packed_to_device(p, DEV) for p in pl]).contiguous() for pl in prob.planes_np]
+    table = bd.PlaneTable(planes, torch.from_numpy(prob.alpha_np).to(DEV))
+    if inn % 128 != 0:
+        with pytest.raises(bd.BitDeltaError) as e:
+            bd.linear_multitenant_kbit(x, prob.w_base, table, tok)
+        assert e.value.status == 7
+        return
+    y = bd.linear_multitenant_kbit(x, prob.w_base, table, tok)
+    torch.cuda.synchronize()
+    _, y32 = ref.linear_multitenant_kbit(to_np(x), prob.w_base_np, prob.planes_np, prob.alpha_np, tok)
+    check_close(y, y32, f"kbit row-major case {case}")
+    assert torch.equal(y, bd.linear_multitenant_tiled_kbit(x, prob.w_tiled, out, prob.table, tok))
+
+
 def test_kbit_more_planes_come_closer_to_the_fine_tuned_weight(ref):
     """The point of the extension: y with k planes approaches x W_fine^T as k grows."""
     out, inn, T = 64, 2048, 4

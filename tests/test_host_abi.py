@@ -103,6 +103,16 @@ def test_compress_and_pack_argument_errors(bd):
     assert L.bd_materialize(A, 2 * A, 0, 3 * A, 16, 64, 0) == 1
 
 
+def test_linear_kbit_row_major_argument_errors(bd):
+    f = bd.lib().bd_linear_multitenant_kbit
+    assert f(A, 2 * A, 3 * A, 4 * A, _tok(0), 5 * A, 1, 16, 128, 1, 0, 0) == 2      # k out of range
+    assert f(A, 2 * A, 3 * A, 4 * A, _tok(0), 5 * A, 1, 16, 128, 1, 9, 0) == 2
+    assert f(A, 2 * A, 0, 4 * A, _tok(0), 5 * A, 1, 16, 128, 1, 2, 0) == 1
+    assert f(A, 2 * A, 3 * A, 4 * A, _tok(1), 5 * A, 1, 16, 128, 1, 2, 0) == 4
+    assert f(A, 2 * A, 3 * A, 4 * A, _tok(0), 5 * A, 1, 16, 96, 1, 2, 0) == 7       # in % 128: no kernel for it
+    assert f(A, 2 * A, 3 * A, 4 * A, _tok(0), 5 * A, 0, 16, 128, 1, 2, 0) == 0      # no tokens: nothing to do
+
+
 def test_compress_noalloc_argument_errors(bd):
     """Errors of the entry point that brings its own scratch are host-side and come before any launch or look-up."""
     c = bd.lib().bd_compress_noalloc
