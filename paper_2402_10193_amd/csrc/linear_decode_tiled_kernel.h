@@ -388,8 +388,10 @@ __global__ __launch_bounds__(kMaxWavesTiled * kWave) void linear_decode_tiled_ke
     // last column tile of a (row block, k tile) only.  xr: this task's x in operand order; with
     // streamed x the next task's (kt_next, next column tile) is fetched into xnext during the task
     // and replaces xr at its end.
+    // (always_inline on the lambdas: left to its own judgement the compiler may keep one a function, and everything it
+    // captures by reference -- every register array of the kernel -- then lives in scratch)
     auto task = [&](auto more_tag, auto ct_tag, u32x4 (&xr)[8], const int kt_cur, const int rb_next, const int kt_next,
-                    u32x4 (&xnext)[8]) {
+                    u32x4 (&xnext)[8]) __attribute__((always_inline)) {
         constexpr bool MORE = decltype(more_tag)::value;
         constexpr int CT = decltype(ct_tag)::value;
         constexpr int CT_NEXT = (CT + 1) % NCT;
@@ -429,7 +431,7 @@ __global__ __launch_bounds__(kMaxWavesTiled * kWave) void linear_decode_tiled_ke
         constexpr int kLookAhead = (NCT == 2 || (RM && NJ == 16)) ? 4 : 6, kRing = kLookAhead + 2, kPairs = 8 * NJ;
         u32x4 ring[kRing];
         float4v sel = {0.f, 0.f, 0.f, 0.f};   // the job owning this lane's column, this tile
-        auto look_up = [&](const int i) {      // i = 8 * job + slice
+        auto look_up = [&](const int i) __attribute__((always_inline)) {      // i = 8 * job + slice
             const int j = i >> 3, v = i & 7;
             if constexpr (RM) {
                 if (v == 0) sr[j] = rm_gather_sign_bytes(sr[j]);
@@ -502,7 +504,7 @@ __global__ __launch_bounds__(kMaxWavesTiled * kWave) void linear_decode_tiled_ke
         // where the requests go after this row block's last task
         int m_nx = m_req, rb_nx = 0;
         if (!last_rb) mat_of(r0 + rbi + 1, m_nx, rb_nx);
-        auto cross = [&]() {   // requests move on to the next row block: switch the pointers if it is in another matrix
+        auto cross = [&]() __attribute__((always_inline)) {   // requests move on to the next row block: switch the pointers if it is in another matrix
             if constexpr (RM) rm_lane_offsets(rb_nx);
             if (m_nx != m_req) {
                 wt = (const unsigned char*)a.wt[m_nx];
@@ -613,9 +615,14 @@ static hipError_t launch_tiled_t(const TiledArgs& args, int n_jobs, hipStream_t 
         cus = (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0) ? v : 256;
         cus_of[dev & 63].store(cus, std::memory_order_relaxed);
     }
-    // persistent grid: one workgroup per compute unit, never more workgroups than row blocks;
+    // Persistent grid: at most one workgroup per compute unit, never more workgroups than row blocks -- and of the
+    // grids that need the same number of rounds (row blocks per workgroup, rounded up) the SMALLEST: 1376 row blocks
+    // (gate,up of Llama-2-7B) on 256 units are 6 rounds either way, but 256 workgroups leave 160 units idle during the
+    // sixth while 230 workgroups of 6 (four of them 5) keep all of theirs streaming to the end.  The launch is bound by
+    // HBM, not by the number of units, so it then takes the time of 5.4 rounds instead of 6.
     // 8 wavefronts, never more than k tiles (an empty reduction, KT == 0, never gets here: the host writes y = 0)
-    const unsigned grid = (unsigned)(rb_total < cus ? rb_total : cus);
+    const int rounds = (rb_total + cus - 1) / cus;
+    const unsigned grid = (unsigned)((rb_total + rounds - 1) / rounds);
     int n_waves = kMaxWavesTiled;
     while (n_waves > 1 && n_waves > args.KT) n_waves >>= 1;
     if (args.n_ct == 2) {   // 17..32 tokens: two column tiles, streamed x
