@@ -14,7 +14,7 @@ namespace {
 using bd::DecodeMeta;
 using bd::kMaxDecodeTokens;
 
-constexpr int kVersion = 211;   // 0.2.11
+constexpr int kVersion = 212;   // 0.2.12
 constexpr int kVariantRowWave = 1;
 constexpr int kVariantRowMajorMfma = 2;   // the matrix-core decode kernel on the row-major tensors (in % 128 == 0)
 constexpr int kVariantPrefillSmall = 4;   // T > 32 with a workspace: the 128 x 128 tile GEMM
@@ -144,9 +144,9 @@ hipError_t run_prefill(const uint16_t* x, const uint16_t* w, const uint32_t* con
 // never mix tenants (a tenant with 3 tokens still costs a whole tile), or decode launches of 32 tokens each, which
 // re-read the base per launch but spend nothing on empty rows.  Rough model from measured rates (MI355X, graph
 // replay): a 128 x 256 tile takes 1.45 us per 64-wide k step plus 10 us around the loop, one tile per compute unit at
-// a time; a decode launch of the matrix-core kernel on the row-major tensors takes 6 us plus its base bytes at
-// 4.2 TB/s plus its sign bytes at 2.15 TB/s (7B shapes, 1 to 16 tenants: 21 to 46 us per launch); the vector-ALU
-// kernel streams everything at 1.3 TB/s plus 8 us.  A wrong guess costs time, never correctness.
+// a time; a decode launch of the matrix-core kernel on the row-major tensors takes 7 us plus its base bytes at
+// 6.2 TB/s plus the sign bytes of its job slots (4, 8 or 16: at least 4 are multiplied) at 3.1 TB/s (7B shapes,
+// 1 to 16 tenants: 20 to 35 us per launch); the vector-ALU kernel streams everything at 1.3 TB/s plus 8 us.  A wrong guess costs time, never correctness.
 bool prefill_gemm_pays(const int32_t* tenant_of_token, int64_t T, int64_t out, int64_t in, int32_t n_tenants, bool big,
                        bool decode_on_matrix_cores) {
     std::vector<int32_t> count((size_t)n_tenants, 0);
@@ -177,7 +177,7 @@ bool prefill_gemm_pays(const int32_t* tenant_of_token, int64_t T, int64_t out, i
             }
         }
         const double elems = (double)out * (double)in;
-        decode_us += decode_on_matrix_cores ? 6.0 + 2.0 * elems / 4.2e6 + (double)distinct * elems / 8.0 / 2.15e6
+        decode_us += decode_on_matrix_cores ? 7.0 + 2.0 * elems / 6.2e6 + (double)std::max(distinct, 4) * elems / 8.0 / 3.1e6
                                             : 8.0 + elems * (2.0 + (double)distinct / 8.0) / 1.3e6;
     }
     return gemm_us < decode_us;

@@ -166,8 +166,12 @@ __global__ __launch_bounds__(kMaxWavesTiled * kWave) void linear_decode_tiled_ke
     const int r0 = (int)((int64_t)blockIdx.x * rb_total / gridDim.x);
     const int r1 = (int)((int64_t)(blockIdx.x + 1) * rb_total / gridDim.x);
     const int n_rb = r1 - r0;
-    const int kb = wave * KT / nw, ke = (wave + 1) * KT / nw;   // this wavefront's k tiles
-    const int steps = XSTEPS > 0 ? XSTEPS : ke - kb;
+    // This wavefront's k tiles: kb, kb + kstride, ... (`steps` of them).  Tiled tensors: a contiguous range.  Row-major: every
+    // nw-th tile, so that the wavefronts of a workgroup are on neighbouring tiles at the same time: a 128-byte line of a
+    // row's signs covers four k tiles, and taken by one wavefront in four consecutive tasks it would come from HBM four times.
+    const int kb = RM ? wave : wave * KT / nw;
+    const int kstride = RM ? nw : 1;
+    const int steps = XSTEPS > 0 ? XSTEPS : (RM ? (KT - wave + nw - 1) / nw : (wave + 1) * KT / nw - kb);
     const bool have_work = n_rb > 0 && steps > 0;
 
     auto mat_of = [&](const int rbg, int& m, int& rb) {
@@ -346,7 +350,7 @@ __global__ __launch_bounds__(kMaxWavesTiled * kWave) void linear_decode_tiled_ke
         const uint32_t soff0 = s_lane_off(s_off(rb_req, kb), lane8, kb);
 #pragma unroll
         for (int j = 0; j < NJ; ++j) sr[j] = ld_s(sign_ptr(0, j), soff0);
-        if constexpr (XSTEPS == 2) x_fetch(xraw[1], kb + 1);
+        if constexpr (XSTEPS == 2) x_fetch(xraw[1], kb + kstride);
     }
 
     // this lane's column: owning job, tenant (for the scale)
@@ -492,55 +496,34 @@ __global__ __launch_bounds__(kMaxWavesTiled * kWave) void linear_decode_tiled_ke
 
     int slot = 0, flush_base = r0;
     int m_cur = m_req;
-    for (int rbi = 0; rbi < n_rb; ++rbi) {
-        const bool last_rb = rbi + 1 == n_rb;
-        float4v sc = {1.f, 1.f, 1.f, 1.f};   // 8-bit base: the scales of this lane's 4 output rows, asked for a row block ahead of their use
+    int rbi = 0;            // the row block being multiplied: r0 + rbi
+    bool last_rb = false;
+    float4v sc = {1.f, 1.f, 1.f, 1.f};   // 8-bit base: the scales of this lane's 4 output rows, asked for a row block ahead of their use
+    int m_nx = m_req, rb_nx = 0;         // where the requests go after this row block's last task
+    auto begin_rb = [&]() __attribute__((always_inline)) {
+        last_rb = rbi + 1 == n_rb;
         if constexpr (Q8) {
             int m_c, rb_c;
             mat_of(r0 + rbi, m_c, rb_c);
             const float* ws = m_c == 0 ? a.wscale[0] : (m_c == 1 ? a.wscale[1] : a.wscale[2]);
             sc = *(const float4v*)(ws + rb_c * kTileRows + 4 * g);   // the scale array is padded to whole row blocks
         }
-        // where the requests go after this row block's last task
-        int m_nx = m_req, rb_nx = 0;
+        m_nx = m_req;
+        rb_nx = 0;
         if (!last_rb) mat_of(r0 + rbi + 1, m_nx, rb_nx);
-        auto cross = [&]() __attribute__((always_inline)) {   // requests move on to the next row block: switch the pointers if it is in another matrix
-            if constexpr (RM) rm_lane_offsets(rb_nx);
-            if (m_nx != m_req) {
-                wt = (const unsigned char*)a.wt[m_nx];
+    };
+    auto cross = [&]() __attribute__((always_inline)) {   // requests move on to the next row block: switch the pointers if it is in another matrix
+        if constexpr (RM) rm_lane_offsets(rb_nx);
+        if (m_nx != m_req) {
+            wt = (const unsigned char*)a.wt[m_nx];
 #pragma unroll
-                for (int ct = 0; ct < NCT; ++ct)
+            for (int ct = 0; ct < NCT; ++ct)
 #pragma unroll
-                    for (int j = 0; j < NJ; ++j) sp[ct][j] = (const unsigned char*)a.signs[ct][m_nx][j];
-            }
-        };
-        using Ct0 = std::integral_constant<int, 0>;
-        using CtL = std::integral_constant<int, NCT - 1>;
-        if constexpr (XSTEPS > 0) {
-#pragma unroll
-            for (int ki = 0; ki < XSTEPS; ++ki) {
-                if (ki + 1 < XSTEPS) {
-                    task(std::true_type{}, Ct0{}, xs[ki], kb + ki, rb_req, kb + ki + 1, xraw[0]);
-                } else if (!last_rb) {
-                    cross();
-                    task(std::true_type{}, Ct0{}, xs[ki], kb + ki, rb_nx, kb, xraw[0]);
-                } else {
-                    task(std::false_type{}, Ct0{}, xs[ki], kb + ki, 0, 0, xraw[0]);
-                }
-            }
-        } else {
-            for (int ki = 0; ki < steps; ++ki) {
-                const bool inner = ki + 1 < steps;
-                // all but the last column tile: the next task stays on this tile (same k tile, next columns)
-                if constexpr (NCT == 2) task(std::true_type{}, Ct0{}, xs[0], kb + ki, rb_req, kb + ki, xraw[0]);
-                if (!inner && !last_rb) cross();
-                if (inner || !last_rb)
-                    task(std::true_type{}, CtL{}, xs[0], kb + ki, inner ? rb_req : rb_nx, inner ? kb + ki + 1 : kb, xraw[0]);
-                else
-                    task(std::false_type{}, CtL{}, xs[0], kb + ki, 0, 0, xraw[0]);
-            }
+                for (int j = 0; j < NJ; ++j) sp[ct][j] = (const unsigned char*)a.signs[ct][m_nx][j];
         }
-        // ---- row block done: this wavefront's partial tiles -> slots
+    };
+    // row block done: this wavefront's partial tiles -> slots; the slots are added up and written when they are full
+    auto end_rb = [&]() __attribute__((always_inline)) {
 #pragma unroll
         for (int ct = 0; ct < NCT; ++ct) {
             const float al = m_cur == 0 ? alpha_m[ct][0] : (m_cur == 1 ? alpha_m[ct][1] : alpha_m[ct][2]);
@@ -570,6 +553,53 @@ __global__ __launch_bounds__(kMaxWavesTiled * kWave) void linear_decode_tiled_ke
         m_cur = m_nx;
         m_req = m_nx;
         rb_req = rb_nx;
+        ++rbi;
+    };
+    using Ct0 = std::integral_constant<int, 0>;
+    using CtL = std::integral_constant<int, NCT - 1>;
+    if constexpr (XSTEPS > 0) {
+        while (rbi < n_rb) {
+            begin_rb();
+#pragma unroll
+            for (int ki = 0; ki < XSTEPS; ++ki) {
+                if (ki + 1 < XSTEPS) {
+                    task(std::true_type{}, Ct0{}, xs[ki], kb + ki * kstride, rb_req, kb + (ki + 1) * kstride, xraw[0]);
+                } else if (!last_rb) {
+                    cross();
+                    task(std::true_type{}, Ct0{}, xs[ki], kb + ki * kstride, rb_nx, kb, xraw[0]);
+                } else {
+                    task(std::false_type{}, Ct0{}, xs[ki], kb + ki * kstride, 0, 0, xraw[0]);
+                }
+            }
+            end_rb();
+        }
+    } else {
+        // Streamed x: ONE loop over all (row block, k tile) pairs but the last, with a single copy of the task that requests
+        // its successor, and the last task after the loop.  (As a loop nest with the last task inside it, the compiler
+        // kept two sets of registers for the requested tiles, copied one into the other at the end of every task and
+        // waited there for every outstanding load: nothing was in flight across a task boundary.)
+        begin_rb();
+        int ki = 0;
+        const int total = n_rb * steps;
+        for (int t = 0; t + 1 < total; ++t) {
+            const bool inner = ki + 1 < steps;
+            const int kt = kb + ki * kstride;
+            // all but the last column tile: the next task stays on this tile (same k tile, next columns)
+            if constexpr (NCT == 2) task(std::true_type{}, Ct0{}, xs[0], kt, rb_req, kt, xraw[0]);
+            if (!inner) cross();
+            task(std::true_type{}, CtL{}, xs[0], kt, inner ? rb_req : rb_nx, inner ? kt + kstride : kb, xraw[0]);
+            if (inner) {
+                ++ki;
+            } else {
+                end_rb();
+                begin_rb();
+                ki = 0;
+            }
+        }
+        const int kt = kb + ki * kstride;
+        if constexpr (NCT == 2) task(std::true_type{}, Ct0{}, xs[0], kt, rb_req, kt, xraw[0]);
+        task(std::false_type{}, CtL{}, xs[0], kt, 0, 0, xraw[0]);
+        end_rb();
     }
 }
 

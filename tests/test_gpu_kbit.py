@@ -122,7 +122,8 @@ def test_kbit_linear_matches_oracle(ref, case):
 @pytest.mark.parametrize("case", range(len(KBIT_CASES)))
 def test_kbit_linear_on_row_major_tensors_matches_oracle_and_tiled_call(ref, case):
     """bd_linear_multitenant_kbit: the same k-plane linear read from the row-major base and planes.  Same arithmetic as the
-    tiled call (same kernel, same order of additions): the same bits; shapes the row-major kernel cannot run are refused."""
+    tiled call up to the order of additions (the k tiles are dealt to the wavefronts differently): the same bits from call to
+    call, at most a rounding step from the tiled call's; shapes the row-major kernel cannot run are refused."""
     out, inn, nt, k, tok = KBIT_CASES[case]
     _p(f"kbit row-major case={case} out={out} in={inn} tenants={nt} k={k} T={len(tok)}")
     prob = PlaneProblem(ref, out, inn, nt, k, tag=("klin", case))
@@ -138,7 +139,10 @@ def test_kbit_linear_on_row_major_tensors_matches_oracle_and_tiled_call(ref, cas
     torch.cuda.synchronize()
     _, y32 = ref.linear_multitenant_kbit(to_np(x), prob.w_base_np, prob.planes_np, prob.alpha_np, tok)
     check_close(y, y32, f"kbit row-major case {case}")
-    assert torch.equal(y, bd.linear_multitenant_tiled_kbit(x, prob.w_tiled, out, prob.table, tok))
+    assert torch.equal(y, bd.linear_multitenant_kbit(x, prob.w_base, table, tok))   # reproducible
+    y_tiled = bd.linear_multitenant_tiled_kbit(x, prob.w_tiled, out, prob.table, tok)
+    check_close(y, to_np(y_tiled).astype(np.float32), f"kbit row-major against tiled, case {case}")
+    assert np.mean(to_np(y) == to_np(y_tiled)) > 0.9   # most sums round to the same binary16 either way
 
 
 def test_kbit_more_planes_come_closer_to_the_fine_tuned_weight(ref):
