@@ -316,19 +316,23 @@ __global__ __launch_bounds__(kMaxWavesTiled * kWave) void linear_decode_tiled_ke
         for (int i = 0; i < kTiledMaxTokens; ++i) tok_c = (c == i && i < a.T[ct]) ? a.col_token[ct][i] : tok_c;
         xlane[ct] = (uint32_t)tok_c * row_bytes + (uint32_t)g * 16u;
     }
-    auto x_fetch_operands = [&](u32x4 (&xop)[8], const int kt, const int ct) {
+    // A slice that lies beyond `in` (ragged tile only) reads the row's first bytes instead, valid memory, and x_zero_beyond
+    // replaces it by zeros once it has arrived: every path issues the same eight loads, so the count of loads in
+    // flight at any later point is known at compile time and nothing has to wait for more than it needs.
+    auto x_fetch_operands = [&](u32x4 (&xop)[8], const int kt, const int ct) __attribute__((always_inline)) {
         uint32_t xl = ct == 0 ? xlane[0] : xlane[NCT - 1];
         asm volatile("" : "+v"(xl));
         const uint32_t off = xl + (uint32_t)kt * (uint32_t)(kTileK * 2);
-        if (kt != k_ragged) {
+        const int k_lane = kt * kTileK + 8 * g;
+        const int k_end = kt == k_ragged ? a.in : kt * kTileK + kTileK;
 #pragma unroll
-            for (int v = 0; v < 8; ++v) xop[v] = ldg16(xg, off + v * 64);
-        } else {
+        for (int v = 0; v < 8; ++v) xop[v] = ldg16(xg, k_lane + 32 * v < k_end ? off + v * 64 : xl);
+    };
+    auto x_zero_beyond = [&](u32x4 (&xop)[8], const int kt) __attribute__((always_inline)) {
+        if (kt == k_ragged) {
 #pragma unroll
-            for (int v = 0; v < 8; ++v) {
-                xop[v] = u32x4{0u, 0u, 0u, 0u};
-                if (kt * kTileK + 32 * v + 8 * g < a.in) xop[v] = ldg16(xg, off + v * 64);
-            }
+            for (int v = 0; v < 8; ++v)
+                if (kt * kTileK + 32 * v + 8 * g >= a.in) xop[v] = u32x4{0u, 0u, 0u, 0u};
         }
     };
     unsigned char* const region = smem + kLutBytes + wave * Plan::kRegion;
@@ -370,6 +374,13 @@ __global__ __launch_bounds__(kMaxWavesTiled * kWave) void linear_decode_tiled_ke
     }
 
     if (!have_work) return;   // uniform per workgroup (n_rb) / never true for steps (host: waves <= k tiles)
+    if constexpr (XSTEPS == 0) {
+        x_zero_beyond(xs[0], kb);
+        // Everything requested so far (the first task's tiles, the scales) has to be there before the first delta job
+        // anyway.  Waiting for it here, once, keeps the compiler from putting a wait for a register of the prologue at
+        // the top of the task loop, where it would drain the loads in flight at every task.
+        __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
+    }
 #pragma unroll
     for (int i = 0; i < (XSTEPS > 0 ? XR : 0); ++i) x_to_operands(xraw[i], xs[i]);
     const uint32_t lanebits = (uint32_t)c << 4;
@@ -431,8 +442,9 @@ __global__ __launch_bounds__(kMaxWavesTiled * kWave) void linear_decode_tiled_ke
         // ---- delta jobs.  The 8 NJ (job, slice) pairs of the task form one sequence; the table
         // look-up of pair i + kLookAhead is issued before the MFMA of pair i, through a ring of
         // operand registers, and a job's sign words are re-requested as soon as its last address exists.
-        // (row-major with 16 jobs: a shorter ring, so that the two registers the row offsets take do not end up in scratch)
-        constexpr int kLookAhead = (NCT == 2 || (RM && NJ == 16)) ? 4 : 6, kRing = kLookAhead + 2, kPairs = 8 * NJ;
+        // (row-major with 16 jobs and resident x: a shorter ring, so that the two registers the row offsets take do not end up
+        // in scratch.  Measured with rings of 4 to 14 look-ups ahead: the depth does not change the time of a task.)
+        constexpr int kLookAhead = (RM && NJ == 16 && XSTEPS > 0) ? 4 : 6, kRing = kLookAhead + 2, kPairs = 8 * NJ;
         u32x4 ring[kRing];
         float4v sel = {0.f, 0.f, 0.f, 0.f};   // the job owning this lane's column, this tile
         auto look_up = [&](const int i) __attribute__((always_inline)) {      // i = 8 * job + slice
@@ -468,6 +480,7 @@ __global__ __launch_bounds__(kMaxWavesTiled * kWave) void linear_decode_tiled_ke
         }
         dsel[CT] += sel;
         if constexpr (MORE && XSTEPS == 0) {   // this task's x is spent: move the next one in
+            x_zero_beyond(xnext, kt_next);
 #pragma unroll
             for (int v = 0; v < 8; ++v) xr[v] = xnext[v];
         }
@@ -491,7 +504,13 @@ __global__ __launch_bounds__(kMaxWavesTiled * kWave) void linear_decode_tiled_ke
                 a.y[m][(int64_t)a.col_token[ct][col] * out + n_row] = f2h_rne(s);
             }
         }
-        if (more_follow) __syncthreads();
+        if (more_follow) {
+            // The stores of y must not be outstanding when the task loop goes on: loads and stores share one counter,
+            // and with both kinds in flight the compiler can only wait for all of them -- it would put that wait at
+            // the top of the task loop, where it drains the requested tiles at every task.
+            if constexpr (XSTEPS == 0) __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
+            __syncthreads();
+        }
     };
 
     int slot = 0, flush_base = r0;
@@ -523,7 +542,13 @@ __global__ __launch_bounds__(kMaxWavesTiled * kWave) void linear_decode_tiled_ke
         }
     };
     // row block done: this wavefront's partial tiles -> slots; the slots are added up and written when they are full
-    auto end_rb = [&]() __attribute__((always_inline)) {
+    // more_tag: std::true_type / std::false_type where the caller knows whether another row block follows, RbDynamic
+    // where last_rb tells
+    struct RbDynamic {};
+    auto end_rb = [&](auto more_tag) __attribute__((always_inline)) {
+        bool last;
+        if constexpr (std::is_same<decltype(more_tag), RbDynamic>::value) last = last_rb;
+        else last = !decltype(more_tag)::value;
 #pragma unroll
         for (int ct = 0; ct < NCT; ++ct) {
             const float al = m_cur == 0 ? alpha_m[ct][0] : (m_cur == 1 ? alpha_m[ct][1] : alpha_m[ct][2]);
@@ -545,8 +570,8 @@ __global__ __launch_bounds__(kMaxWavesTiled * kWave) void linear_decode_tiled_ke
             accb[ct] = dsel[ct] = accs[ct] = float4v{0.f, 0.f, 0.f, 0.f};
         }
         slot += NCT;
-        if (slot == Plan::kRedSlots || last_rb) {
-            flush(flush_base, slot, !last_rb);
+        if (slot == Plan::kRedSlots || last) {
+            flush(flush_base, slot, !last);
             flush_base += slot / NCT;
             slot = 0;
         }
@@ -571,7 +596,7 @@ __global__ __launch_bounds__(kMaxWavesTiled * kWave) void linear_decode_tiled_ke
                     task(std::false_type{}, Ct0{}, xs[ki], kb + ki * kstride, 0, 0, xraw[0]);
                 }
             }
-            end_rb();
+            end_rb(RbDynamic{});
         }
     } else {
         // Streamed x: ONE loop over all (row block, k tile) pairs but the last, with a single copy of the task that requests
@@ -591,7 +616,7 @@ __global__ __launch_bounds__(kMaxWavesTiled * kWave) void linear_decode_tiled_ke
             if (inner) {
                 ++ki;
             } else {
-                end_rb();
+                end_rb(std::true_type{});
                 begin_rb();
                 ki = 0;
             }
@@ -599,7 +624,7 @@ __global__ __launch_bounds__(kMaxWavesTiled * kWave) void linear_decode_tiled_ke
         const int kt = kb + ki * kstride;
         if constexpr (NCT == 2) task(std::true_type{}, Ct0{}, xs[0], kt, rb_req, kt, xraw[0]);
         task(std::false_type{}, CtL{}, xs[0], kt, 0, 0, xraw[0]);
-        end_rb();
+        end_rb(std::false_type{});
     }
 }
 
