@@ -73,6 +73,9 @@ def parse():
                     help="int8: 8-bit round-to-nearest base weights (one scale per output row), deltas taken against them")
     ap.add_argument("--planes", type=int, default=1,
                     help="sign planes per tenant (iterated compression); a token then takes that many of a launch's columns")
+    ap.add_argument("--shared-signs", action="store_true",
+                    help="diagnostic: every tenant's table entry points at tenant 0's sign tensors (same launches, same arithmetic, "
+                         "same requests to L2, a third of the HBM bytes at B = 16); the reported GB/s stay the nominal ones")
     ap.add_argument("--calibrate", action="store_true",
                     help="only run a 1 GiB copy and a 1 GiB read three times: known sizes against which the "
                          "profiler's HBM byte counters are scaled")
@@ -82,7 +85,7 @@ def parse():
 MFMA_F16_PEAK_TFLOPS = 2500.0
 
 
-def run_prefill(args, torch, bd, synth, dev):
+def run_prefill(args, torch, bd, synth, dev, with_variants=False):
     """8 tenants x 512 tokens through bd_linear_multitenant on an up- and a down-projection of Llama-2-7B: one
     step = both linears; reports TFLOP/s of the two products (base and delta) against the dense fp16 MFMA peak."""
     B, per = 8, 512
@@ -119,7 +122,44 @@ def run_prefill(args, torch, bd, synth, dev):
     ms = e0.elapsed_time(e1) / args.steps
     flops = sum(2.0 * 2.0 * T * inn * out for *_, out, inn in mats)      # base + delta products
     tflops = flops / (ms * 1e-3) / 1e12
+    variants = None
+    if with_variants:
+        # the 128 x 128 tile GEMM on the up projection: one plane (variant 4), two planes per tenant, the 8-bit base
+        x, base, table, y, ws, out, inn = mats[0]
+        ws_g = bd.new_workspace(bd.workspace_bytes(bd.OP_LINEAR_GEMM, T, out, inn, B), dev)
+        planes, alphas = [], []
+        for t in range(B):
+            ft = synth.finetuned_weight(base, tag=("pf", "up", t))
+            p, a = bd.compress_iterated(base, ft, 2, workspace=ws_c)
+            planes.append(p)
+            alphas.append(a)
+        ptable = bd.PlaneTable(planes, torch.stack(alphas))
+        q, qs = bd.quantize_base_q8(base)
+        qp, qa = [], []
+        for t in range(B):
+            ft = synth.finetuned_weight(base, tag=("pf", "up", t))
+            p, a = bd.compress_q8(q, qs, ft, workspace=ws_c)
+            qp.append(p)
+            qa.append(a)
+        qtable = bd.TenantTable(qp, qa)
+        calls = {
+            "one_plane_128x128": lambda: bd.linear_multitenant(x, base, table, tok, y=y, tok_array=tok_arr, workspace=ws, variant=4),
+            "two_planes_128x128": lambda: bd.linear_multitenant_gemm_kbit(x, base, ptable, tok, y=y, workspace=ws_g, tok_array=tok_arr),
+            "int8_base_128x128": lambda: bd.linear_multitenant_gemm_q8(x, q, qs, qtable, tok, y=y, workspace=ws_g, tok_array=tok_arr),
+        }
+        variants = {}
+        for name, fn in calls.items():
+            fn()
+            torch.cuda.synchronize()
+            e0.record()
+            for _ in range(args.steps):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            us = e0.elapsed_time(e1) / args.steps * 1e3
+            variants[name] = {"us_per_launch": round(us, 1), "TFLOP/s": round(2.0 * 2.0 * T * inn * out / (us * 1e-6) / 1e12, 1)}
     return {
+        **({"variants_up_projection": variants} if variants else {}),
         "metric": "prefill tokens/s, fused fp16 base + 1-bit delta linear, 8 tenants x 512 tokens",
         "value": round(T / (ms * 1e-3), 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
@@ -239,7 +279,10 @@ def build_stack(args, torch, bd, synth, dev, shapes, sigma, n_layers, n_res, k, 
                 base = None
             else:
                 wt = bd.tile_base_q8(qb, qscale) if q8 else bd.tile_base(base)
-                ttable = bd.TiledTenantTable([bd.tile_signs(p, out, inn) for p in packed], table.alpha)
+                tiles = [bd.tile_signs(p, out, inn) for p in packed]
+                if getattr(args, "shared_signs", False):
+                    tiles = [tiles[0]] * len(tiles)
+                ttable = bd.TiledTenantTable(tiles, table.alpha)
                 if li >= keep_rowmajor:
                     base = table = None
             mats.append((name, out, inn, base, table, wt, ttable))
@@ -369,7 +412,7 @@ def main():
         print(json.dumps({"calibrate": "3 x bd_probe_copy and bd_probe_read of 1 GiB"}))
         return
     if args.workload == "prefill":
-        print(json.dumps(run_prefill(args, torch, bd, synth, dev)))
+        print(json.dumps(run_prefill(args, torch, bd, synth, dev, with_variants=True)))
         return
     B, n_layers = args.tenants, args.layers
     shapes = synth.LLAMA2_7B_LAYER if args.model == "7b" else synth.LLAMA2_70B_LAYER
@@ -451,6 +494,7 @@ def main():
             "layers": n_layers, "launches_per_step": launches_per_step,
             "launch": "hip graph replay" if graph is not None else "eager",
             "path": args.path, "kernel_variant": args.variant,
+            **({"shared_signs": True} if args.shared_signs else {}),
         },
         "roofline": {
             "bound": "hbm",
@@ -458,7 +502,7 @@ def main():
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
             "frac": round(achieved_gbs / HBM_PEAK_GBS, 4),
-            "traffic": measured_traffic(args.model, B, args.path, bd.version()) if n_layers == 32 and not args.mix and k == 1 and not q8 else None,
+            "traffic": measured_traffic(args.model, B, args.path, bd.version()) if n_layers == 32 and not args.mix and k == 1 and not q8 and not args.shared_signs else None,
             "kernel": kernel_name,
             "bytes_per_launch": round(bytes_per_step / launches_per_step, 1),
             "avg_launch_us": round(ms_per_step * 1e3 / launches_per_step, 3),

@@ -56,7 +56,8 @@ typedef enum bd_status {
 typedef enum bd_op {
     BD_OP_PACK_SIGNS = 0,
     BD_OP_COMPRESS = 1,
-    BD_OP_LINEAR_MULTITENANT = 2
+    BD_OP_LINEAR_MULTITENANT = 2,
+    BD_OP_LINEAR_GEMM = 3            /* bd_linear_multitenant_gemm_kbit / _gemm_q8: the token tables, any T >= 1 */
 } bd_op;
 
 /* Text for a status code (static storage, never NULL). */
@@ -249,6 +250,30 @@ bd_status bd_linear_multitenant_kbit(const uint16_t* x_f16, const uint16_t* w_ba
                                      uint16_t* y_f16,
                                      int64_t T, int64_t out, int64_t in, int32_t n_tenants, int32_t k,
                                      void* stream);
+
+/* The GEMM form (the prefill regime of Sec. 4.3, many tokens per tenant) of the two extensions of Sec. 4.2, for any
+ * T >= 1 (T <= 65535): tokens are sorted by tenant and cut into tiles of 128 rows that never mix tenants, every tile
+ * is a matrix-core GEMM over `in` (128 x 128 tiles of y).  Tensors row-major as bd_compress_iterated /
+ * bd_quantize_base_q8 + bd_compress_q8 write them; in % 32 == 0.
+ *   workspace   bd_workspace_bytes(BD_OP_LINEAR_GEMM, T, out, in, n_tenants) bytes, 256-byte aligned, device memory;
+ *               holds the token tables of this call until the launch has run (one call at a time per workspace)
+ * _gemm_kbit (fidelity of Delta, k planes): y[t] = x[t] W_base^T + x[t] D_e^T with D_e = sum_j alpha[e*k+j] S_{e,j}
+ *   added up in fp16 in ascending j (one rounding per plane; 2^-11 of the delta term against the exact sum);
+ *   planes_by_tenant, alpha_by_tenant as for bd_linear_multitenant_kbit; k outside 1..BD_MAX_PLANES: BD_ERR_SHAPE.
+ * _gemm_q8 (quantized base models): y[t,n] = wscale[n] * sum_k x[t,k] q[n,k] + alpha[e] * (x[t] S_e^T)[n];
+ *   q [out, in] int8, wscale [out] binary32 (device), packed_by_tenant / alpha_by_tenant as for bd_linear_multitenant.
+ * Errors as bd_linear_multitenant, BD_ERR_WORKSPACE for a missing, small or misaligned workspace, BD_ERR_UNSUPPORTED
+ * for in == 0.  Asynchronous. */
+bd_status bd_linear_multitenant_gemm_kbit(const uint16_t* x_f16, const uint16_t* w_base_f16,
+                                          const uint32_t* const* planes_by_tenant, const float* alpha_by_tenant,
+                                          const int32_t* tenant_of_token, uint16_t* y_f16,
+                                          int64_t T, int64_t out, int64_t in, int32_t n_tenants, int32_t k,
+                                          void* workspace, size_t workspace_bytes, void* stream);
+bd_status bd_linear_multitenant_gemm_q8(const uint16_t* x_f16, const int8_t* q, const float* wscale,
+                                        const uint32_t* const* packed_by_tenant, const float* alpha_by_tenant,
+                                        const int32_t* tenant_of_token, uint16_t* y_f16,
+                                        int64_t T, int64_t out, int64_t in, int32_t n_tenants,
+                                        void* workspace, size_t workspace_bytes, void* stream);
 
 /* Eq. 6 with k planes per tenant over the serving layout:
  *   y[t] = x[t] W_base^T + sum_{j<k} alpha[e*k+j] * (x[t] S_{e,j}^T),   e = tenant_of_token[t]

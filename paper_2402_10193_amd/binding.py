@@ -19,7 +19,7 @@ BD_OK = 0
 STATUS_NAMES = {0: "BD_OK", 1: "BD_ERR_NULL", 2: "BD_ERR_SHAPE", 3: "BD_ERR_ALIGN", 4: "BD_ERR_TENANT",
                 5: "BD_ERR_WORKSPACE", 6: "BD_ERR_DEVICE", 7: "BD_ERR_UNSUPPORTED", 8: "BD_ERR_ALIAS",
                 9: "BD_ERR_FORMAT", 10: "BD_ERR_IO", 11: "BD_ERR_TOO_LARGE"}
-OP_PACK_SIGNS, OP_COMPRESS, OP_LINEAR_MULTITENANT = 0, 1, 2
+OP_PACK_SIGNS, OP_COMPRESS, OP_LINEAR_MULTITENANT, OP_LINEAR_GEMM = 0, 1, 2, 3
 
 # every symbol include/bitdelta.h declares
 EXPORTS = ["bd_status_string", "bd_version", "bd_workspace_bytes", "bd_pack_signs", "bd_compress", "bd_compress_noalloc", "bd_compress_batch",
@@ -31,7 +31,8 @@ EXPORTS = ["bd_status_string", "bd_version", "bd_workspace_bytes", "bd_pack_sign
            "bd_delta_image_build", "bd_delta_image_check", "bd_delta_image_entry", "bd_delta_file_write",
            "bd_delta_file_bytes", "bd_delta_file_read", "bd_delta_upload", "bd_delta_install", "bd_quantize_base_q8",
            "bd_compress_q8", "bd_tiled_base_q8_bytes", "bd_tile_base_q8", "bd_linear_multitenant_tiled_q8",
-           "bd_linear_multitenant_tiled_group_q8", "bd_linear_multitenant_kbit"]
+           "bd_linear_multitenant_tiled_group_q8", "bd_linear_multitenant_kbit", "bd_linear_multitenant_gemm_kbit",
+           "bd_linear_multitenant_gemm_q8"]
 
 
 class BitDeltaError(RuntimeError):
@@ -100,6 +101,8 @@ def lib() -> ctypes.CDLL:
         L.bd_linear_multitenant_tiled_group_q8.argtypes = [i32, vp, pvp, pvp, pvp, pi, pvp, i64, pi64, i64, i32, vp]
         L.bd_compress_iterated.argtypes = [vp, vp, i64, i64, i32, vp, vp, vp, sz, vp]
         L.bd_linear_multitenant_kbit.argtypes = [vp, vp, vp, vp, pi, vp, i64, i64, i64, i32, i32, vp]
+        L.bd_linear_multitenant_gemm_kbit.argtypes = [vp, vp, vp, vp, pi, vp, i64, i64, i64, i32, i32, vp, sz, vp]
+        L.bd_linear_multitenant_gemm_q8.argtypes = [vp, vp, vp, vp, vp, pi, vp, i64, i64, i64, i32, vp, sz, vp]
         L.bd_compress_batch.argtypes = [i32, pvp, pvp, pi64, pi64, pvp, vp, vp, sz, vp]
         L.bd_compress_batch.restype = ctypes.c_int
         L.bd_linear_multitenant_tiled_kbit.argtypes = [vp, vp, pvp, vp, pi, vp, i64, i64, i64, i32, i32, vp]
@@ -482,6 +485,45 @@ def linear_multitenant_kbit(x: torch.Tensor, w_base: torch.Tensor, tenants: Plan
     tok = tok_array if tok_array is not None else _tok_array(tenant_of_token)
     _check(lib().bd_linear_multitenant_kbit(_ptr(x), _ptr(w_base), _ptr(tenants.ptrs), _ptr(tenants.alpha), tok, _ptr(y), T, out,
                                             inn, tenants.n_tenants, tenants.k, _stream(stream)), "bd_linear_multitenant_kbit")
+    return y
+
+
+def linear_multitenant_gemm_kbit(x: torch.Tensor, w_base: torch.Tensor, tenants: PlaneTable, tenant_of_token: Sequence[int],
+                                 y: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None, stream=None,
+                                 tok_array=None) -> torch.Tensor:
+    """bd_linear_multitenant_gemm_kbit: the GEMM form (any T >= 1) with k row-major planes per tenant."""
+    _dev(x, torch.float16, "x")
+    _dev(w_base, torch.float16, "w_base")
+    T, inn = x.shape
+    out = w_base.shape[0]
+    if y is None:
+        y = torch.empty((T, out), dtype=torch.float16, device=x.device)
+    if workspace is None:
+        workspace = new_workspace(workspace_bytes(OP_LINEAR_GEMM, T, out, inn, tenants.n_tenants), x.device)
+    tok = tok_array if tok_array is not None else _tok_array(tenant_of_token)
+    _check(lib().bd_linear_multitenant_gemm_kbit(_ptr(x), _ptr(w_base), _ptr(tenants.ptrs), _ptr(tenants.alpha), tok, _ptr(y), T,
+                                                 out, inn, tenants.n_tenants, tenants.k, _ptr(workspace), workspace.numel(),
+                                                 _stream(stream)), "bd_linear_multitenant_gemm_kbit")
+    return y
+
+
+def linear_multitenant_gemm_q8(x: torch.Tensor, q: torch.Tensor, scale: torch.Tensor, tenants: "TenantTable",
+                               tenant_of_token: Sequence[int], y: Optional[torch.Tensor] = None,
+                               workspace: Optional[torch.Tensor] = None, stream=None, tok_array=None) -> torch.Tensor:
+    """bd_linear_multitenant_gemm_q8: the GEMM form (any T >= 1) on the row-major 8-bit base (q int8 [out, in], scale [out])."""
+    _dev(x, torch.float16, "x")
+    _dev(q, torch.int8, "q")
+    _dev(scale, torch.float32, "scale")
+    T, inn = x.shape
+    out = q.shape[0]
+    if y is None:
+        y = torch.empty((T, out), dtype=torch.float16, device=x.device)
+    if workspace is None:
+        workspace = new_workspace(workspace_bytes(OP_LINEAR_GEMM, T, out, inn, tenants.n_tenants), x.device)
+    tok = tok_array if tok_array is not None else _tok_array(tenant_of_token)
+    _check(lib().bd_linear_multitenant_gemm_q8(_ptr(x), _ptr(q), _ptr(scale), _ptr(tenants.ptrs), _ptr(tenants.alpha), tok, _ptr(y),
+                                               T, out, inn, tenants.n_tenants, _ptr(workspace), workspace.numel(),
+                                               _stream(stream)), "bd_linear_multitenant_gemm_q8")
     return y
 
 

@@ -46,9 +46,12 @@ constexpr int kPrefillTile = 128;   // tile of y: 128 tokens x 128 output featur
 constexpr int kPrefillK = 64;       // reduction elements per step
 struct PrefillMetaChunk { int32_t v[960]; };
 hipError_t launch_prefill_meta(const PrefillMetaChunk& chunk, int32_t* dst, int n, hipStream_t st);
-hipError_t launch_linear_prefill(const uint16_t* x, const uint16_t* w, const uint32_t* const* packed_by_tenant,
-                                 const float* alpha_by_tenant, const int32_t* row_token, const int32_t* tile_tenant,
-                                 int n_mtiles, uint16_t* y, int64_t out, int64_t in, hipStream_t st);
+// k_planes = 0: one plane per tenant (tables indexed by tenant); k_planes = 1..8: tables indexed by tenant * k_planes +
+// plane.  wscale != nullptr: w is the row-major int8 base ([out, in] bytes) and wscale its per-row scales.
+hipError_t launch_linear_prefill(const uint16_t* x, const void* w, const uint32_t* const* packed_by_tenant,
+                                 const float* alpha_by_tenant, const float* wscale, const int32_t* row_token,
+                                 const int32_t* tile_tenant, int n_mtiles, uint16_t* y, int64_t out, int64_t in,
+                                 int k_planes, hipStream_t st);
 // the 128 x 256 tile GEMM of linear_prefill_big.hip; T = rows of x; halve_last_round (4 wavefronts only): the tiles of a
 // last round that would occupy at most half of the compute units run as two workgroups of 64 token rows each
 bool prefill_big_fits(int64_t T, int64_t out, int64_t in);

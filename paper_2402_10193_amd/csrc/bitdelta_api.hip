@@ -14,7 +14,7 @@ namespace {
 using bd::DecodeMeta;
 using bd::kMaxDecodeTokens;
 
-constexpr int kVersion = 212;   // 0.2.12
+constexpr int kVersion = 213;   // 0.2.13
 constexpr int kVariantRowWave = 1;
 constexpr int kVariantRowMajorMfma = 2;   // the matrix-core decode kernel on the row-major tensors (in % 128 == 0)
 constexpr int kVariantPrefillSmall = 4;   // T > 32 with a workspace: the 128 x 128 tile GEMM
@@ -94,8 +94,13 @@ bd_status check_linear_args(const void* x, const void* w, const void* packed_by_
 
 // Prefill (T > 32): the token permutation and the tenant of every 128-row tile live in the workspace.
 // At most ceil(T / 128) full tiles plus one ragged tile per tenant that has a token.
+size_t prefill_table_bytes(int64_t T, int32_t n_tenants);
 size_t prefill_workspace_bytes(int64_t T, int32_t n_tenants) {
     if (T <= kMaxDecodeTokens || n_tenants < 0) return 0;
+    return prefill_table_bytes(T, n_tenants);
+}
+size_t prefill_table_bytes(int64_t T, int32_t n_tenants) {
+    if (T < 1 || n_tenants < 0) return 0;
     const int64_t tiles = (T + bd::kPrefillTile - 1) / bd::kPrefillTile + std::min<int64_t>(n_tenants, T);
     const size_t bytes = (size_t)tiles * (bd::kPrefillTile + 1) * sizeof(int32_t);
     return (bytes + 255) & ~(size_t)255;
@@ -103,9 +108,12 @@ size_t prefill_workspace_bytes(int64_t T, int32_t n_tenants) {
 
 // Sorts the tokens by tenant (stable), cuts them into tiles of 128 rows that never mix tenants, writes
 // the two tables into the workspace (through kernel arguments: no host-to-device copy call) and runs the GEMM.
-hipError_t run_prefill(const uint16_t* x, const uint16_t* w, const uint32_t* const* packed_by_tenant,
+// k_planes = 0: one plane per tenant; 1..8: tables indexed by tenant * k_planes + plane.  wscale: the 8-bit base's row
+// scales (w is then the int8 tensor).  Both go through the 128 x 128 tiles (big_waves = 0).
+hipError_t run_prefill(const uint16_t* x, const void* w, const uint32_t* const* packed_by_tenant,
                        const float* alpha_by_tenant, const int32_t* tenant_of_token, uint16_t* y, int64_t T, int64_t out,
-                       int64_t in, void* workspace, hipStream_t st, int big_waves, bool halve_last_round) {
+                       int64_t in, void* workspace, hipStream_t st, int big_waves, bool halve_last_round,
+                       int k_planes = 0, const float* wscale = nullptr) {
     std::vector<int32_t> order((size_t)T);
     for (int64_t i = 0; i < T; ++i) order[(size_t)i] = (int32_t)i;
     std::stable_sort(order.begin(), order.end(),
@@ -134,10 +142,10 @@ hipError_t run_prefill(const uint16_t* x, const uint16_t* w, const uint32_t* con
         if (e != hipSuccess) return e;
     }
     if (big_waves)
-        return bd::launch_linear_prefill_big(x, w, packed_by_tenant, alpha_by_tenant, dst, dst + row_token.size(), n_mtiles, y,
-                                             T, out, in, big_waves, halve_last_round, st);
-    return bd::launch_linear_prefill(x, w, packed_by_tenant, alpha_by_tenant, dst, dst + row_token.size(), n_mtiles, y, out,
-                                     in, st);
+        return bd::launch_linear_prefill_big(x, (const uint16_t*)w, packed_by_tenant, alpha_by_tenant, dst,
+                                             dst + row_token.size(), n_mtiles, y, T, out, in, big_waves, halve_last_round, st);
+    return bd::launch_linear_prefill(x, w, packed_by_tenant, alpha_by_tenant, wscale, dst, dst + row_token.size(), n_mtiles, y,
+                                     out, in, k_planes, st);
 }
 
 // Which way is quicker for T > 32 tokens when both are possible: one GEMM launch, whose tiles of 128 token rows
@@ -213,6 +221,7 @@ size_t bd_workspace_bytes(bd_op op, int64_t T, int64_t out, int64_t in, int32_t 
         case BD_OP_COMPRESS: return (size_t)bd::kCompressMaxBlocks * sizeof(double);
         case BD_OP_PACK_SIGNS: return 0;
         case BD_OP_LINEAR_MULTITENANT: return prefill_workspace_bytes(T, n_tenants);
+        case BD_OP_LINEAR_GEMM: return prefill_table_bytes(T, n_tenants);
     }
     return 0;
 }
@@ -678,6 +687,44 @@ bd_status bd_linear_multitenant_kbit(const uint16_t* x_f16, const uint16_t* w_ba
     if (in % 128 != 0 || in == 0 || (uint64_t)out * (uint64_t)in * 2 >= ((uint64_t)1 << 32)) return BD_ERR_UNSUPPORTED;
     return tiled_linear_impl(1, x_f16, &w_base_f16, nullptr, &alpha_by_tenant, tenant_of_token, &y_f16, T, &out, in, n_tenants, k,
                              stream, false, planes_by_tenant);
+}
+
+// The GEMM form for any T >= 1 with k planes per tenant or the 8-bit base (128 x 128 tiles).
+static bd_status gemm_entry(const uint16_t* x_f16, const void* w, size_t w_bytes_per_el, const uint32_t* const* packed_by_tenant,
+                            const float* alpha_by_tenant, const float* wscale, const int32_t* tenant_of_token, uint16_t* y_f16,
+                            int64_t T, int64_t out, int64_t in, int32_t n_tenants, int k_planes, void* workspace,
+                            size_t workspace_bytes, void* stream) {
+    const bd_status st = check_linear_args(x_f16, w, packed_by_tenant, alpha_by_tenant, tenant_of_token, y_f16, T, out, in,
+                                           n_tenants);
+    if (st != BD_OK) return st;
+    if (T == 0 || out == 0) return BD_OK;
+    if (overlaps(y_f16, (size_t)T * out * 2, w, (size_t)out * in * w_bytes_per_el)) return BD_ERR_ALIAS;
+    if (in == 0) return BD_ERR_UNSUPPORTED;   // the empty reduction (y = 0) is bd_linear_multitenant's
+    const size_t need = prefill_table_bytes(T, n_tenants);
+    if (!workspace || workspace_bytes < need || misaligned(workspace, 256)) return BD_ERR_WORKSPACE;
+    return run_prefill(x_f16, w, packed_by_tenant, alpha_by_tenant, tenant_of_token, y_f16, T, out, in, workspace,
+                       (hipStream_t)stream, 0, false, k_planes, wscale) == hipSuccess
+               ? BD_OK
+               : BD_ERR_DEVICE;
+}
+
+bd_status bd_linear_multitenant_gemm_kbit(const uint16_t* x_f16, const uint16_t* w_base_f16,
+                                          const uint32_t* const* planes_by_tenant, const float* alpha_by_tenant,
+                                          const int32_t* tenant_of_token, uint16_t* y_f16, int64_t T, int64_t out, int64_t in,
+                                          int32_t n_tenants, int32_t k, void* workspace, size_t workspace_bytes, void* stream) {
+    if (k < 1 || k > bd::kTiledMaxPlanes) return BD_ERR_SHAPE;
+    return gemm_entry(x_f16, w_base_f16, 2, planes_by_tenant, alpha_by_tenant, nullptr, tenant_of_token, y_f16, T, out, in,
+                      n_tenants, k, workspace, workspace_bytes, stream);
+}
+
+bd_status bd_linear_multitenant_gemm_q8(const uint16_t* x_f16, const int8_t* q, const float* wscale,
+                                        const uint32_t* const* packed_by_tenant, const float* alpha_by_tenant,
+                                        const int32_t* tenant_of_token, uint16_t* y_f16, int64_t T, int64_t out, int64_t in,
+                                        int32_t n_tenants, void* workspace, size_t workspace_bytes, void* stream) {
+    if (T > 0 && out > 0 && !wscale) return BD_ERR_NULL;
+    if (misaligned(wscale, 4)) return BD_ERR_ALIGN;
+    return gemm_entry(x_f16, q, 1, packed_by_tenant, alpha_by_tenant, wscale, tenant_of_token, y_f16, T, out, in, n_tenants, 0,
+                      workspace, workspace_bytes, stream);
 }
 
 bd_status bd_linear_multitenant_tiled_kbit(const uint16_t* x_f16, const uint16_t* w_tiled,

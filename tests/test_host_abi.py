@@ -113,6 +113,32 @@ def test_linear_kbit_row_major_argument_errors(bd):
     assert f(A, 2 * A, 3 * A, 4 * A, _tok(0), 5 * A, 0, 16, 128, 1, 2, 0) == 0      # no tokens: nothing to do
 
 
+def test_gemm_variants_argument_errors(bd):
+    """bd_linear_multitenant_gemm_kbit / _gemm_q8: every error is found on the host before anything is launched."""
+    L = bd.lib()
+    f, g = L.bd_linear_multitenant_gemm_kbit, L.bd_linear_multitenant_gemm_q8
+    W = 0x100000   # a fake, 256-byte aligned workspace address
+    # the token tables: (ceil(T / 128) + min(tenants, T)) tiles x 129 ints, for any T >= 1
+    assert bd.workspace_bytes(bd.OP_LINEAR_GEMM, 1, 64, 64, 3) == (2 * 129 * 4 + 255) // 256 * 256
+    assert bd.workspace_bytes(bd.OP_LINEAR_GEMM, 4096, 11008, 4096, 8) == (40 * 129 * 4 + 255) // 256 * 256
+    assert bd.workspace_bytes(bd.OP_LINEAR_GEMM, 0, 64, 64, 3) == 0
+    assert f(A, 2 * A, 3 * A, 4 * A, _tok(0), 5 * A, 1, 16, 128, 1, 0, W, 4096, 0) == 2     # k out of range
+    assert f(A, 2 * A, 3 * A, 4 * A, _tok(0), 5 * A, 1, 16, 128, 1, 9, W, 4096, 0) == 2
+    assert f(A, 2 * A, 3 * A, 4 * A, _tok(0), 5 * A, 1, 16, 100, 1, 2, W, 4096, 0) == 2     # in % 32
+    assert f(A, 2 * A, 0, 4 * A, _tok(0), 5 * A, 1, 16, 128, 1, 2, W, 4096, 0) == 1
+    assert f(A, 2 * A, 3 * A, 4 * A, _tok(1), 5 * A, 1, 16, 128, 1, 2, W, 4096, 0) == 4
+    assert f(A, 2 * A, 3 * A, 4 * A, _tok(0), 5 * A, 1, 16, 128, 1, 2, 0, 0, 0) == 5         # no workspace
+    assert f(A, 2 * A, 3 * A, 4 * A, _tok(0), 5 * A, 1, 16, 128, 1, 2, W, 16, 0) == 5        # too small
+    assert f(A, 2 * A, 3 * A, 4 * A, _tok(0), 5 * A, 1, 16, 128, 1, 2, W + 64, 4096, 0) == 5  # misaligned
+    assert f(A, 2 * A, 3 * A, 4 * A, _tok(0), 5 * A, 1, 16, 0, 1, 2, W, 4096, 0) == 7        # empty reduction: not here
+    assert f(A, 2 * A, 3 * A, 4 * A, _tok(0), 5 * A, 0, 16, 128, 1, 2, 0, 0, 0) == 0         # no tokens: nothing to do
+    assert g(A, 2 * A, 0, 3 * A, 4 * A, _tok(0), 5 * A, 1, 16, 128, 1, W, 4096, 0) == 1      # scales missing
+    assert g(A, 2 * A, 6 * A + 2, 3 * A, 4 * A, _tok(0), 5 * A, 1, 16, 128, 1, W, 4096, 0) == 3
+    assert g(A, 2 * A, 6 * A, 3 * A, 4 * A, _tok(2), 5 * A, 1, 16, 128, 2, W, 4096, 0) == 4
+    assert g(A, 2 * A, 6 * A, 3 * A, 4 * A, _tok(0), 5 * A, 1, 16, 128, 1, 0, 0, 0) == 5
+    assert g(A, A, 6 * A, 3 * A, 4 * A, _tok(0), A, 1, 16, 128, 1, W, 4096, 0) == 8          # y on top of x
+
+
 def test_compress_noalloc_argument_errors(bd):
     """Errors of the entry point that brings its own scratch are host-side and come before any launch or look-up."""
     c = bd.lib().bd_compress_noalloc
