@@ -285,6 +285,8 @@ def build_stack(args, torch, bd, synth, dev, shapes, sigma, n_layers, n_res, k, 
                 ttable = bd.TiledTenantTable(tiles, table.alpha)
                 if li >= keep_rowmajor:
                     base = table = None
+                elif q8:
+                    base = (qb, qscale)   # the row-major 8-bit base: what bd_linear_multitenant_q8 takes
             mats.append((name, out, inn, base, table, wt, ttable))
         layers.append(mats)
     return layers, incoming
@@ -296,7 +298,11 @@ def make_plans(args, bd, layers, xs, ys, tok, tok_arr, path, k, q8):
     for mats in layers:
         by = {m[0]: m for m in mats}
         plan = []
-        if path == "rowmajor":
+        if path == "rowmajor" and q8:
+            for name, out, inn, base, table, _, _ in mats:
+                plan.append(lambda inn=inn, base=base, table=table, y=ys[(name, out)]: bd.linear_multitenant_q8(
+                    xs[inn], base[0], base[1], table, tok, y=y, tok_array=tok_arr))
+        elif path == "rowmajor":
             for name, out, inn, base, table, _, _ in mats:
                 plan.append(lambda inn=inn, base=base, table=table, y=ys[(name, out)]: bd.linear_multitenant(
                     xs[inn], base, table, tok, y=y, variant=args.variant, tok_array=tok_arr))
@@ -427,7 +433,7 @@ def main():
     k = args.planes
     q8 = args.base == "int8"
     if q8:
-        assert args.path == "tiled-fused" and k == 1 and args.workload == "decode", "--base int8: tiled-fused decode, one plane"
+        assert args.path in ("tiled-fused", "rowmajor") and k == 1 and args.workload == "decode", "--base int8: tiled-fused or rowmajor decode, one plane"
         args.no_extras = args.no_cpu = True
     if k != 1:
         assert args.path == "tiled-fused", "--planes needs the tiled-fused path"

@@ -251,6 +251,18 @@ bd_status bd_linear_multitenant_kbit(const uint16_t* x_f16, const uint16_t* w_ba
                                      int64_t T, int64_t out, int64_t in, int32_t n_tenants, int32_t k,
                                      void* stream);
 
+/* Eq. 6 over the 8-bit base (Sec. 4.2, quantized base models) on the row-major tensors, the decode form:
+ *   y[t,n] = wscale[n] * sum_k x[t,k] q[n,k] + alpha[e] * (x[t] S_e^T)[n],   e = tenant_of_token[t]
+ *   q [out, in] int8 and wscale [out] binary32 as bd_quantize_base_q8 writes them, packed_by_tenant / alpha_by_tenant as
+ *   for bd_linear_multitenant (deltas from bd_compress_q8).  Runs on the matrix-core decode kernel: in % 128 == 0 and
+ *   out * in < 2^32, else BD_ERR_UNSUPPORTED; 32 tokens per launch, more tokens run as several launches (many tokens
+ *   per tenant: bd_linear_multitenant_gemm_q8).  Needs no workspace.  Other arguments and errors as
+ *   bd_linear_multitenant. */
+bd_status bd_linear_multitenant_q8(const uint16_t* x_f16, const int8_t* q, const float* wscale,
+                                   const uint32_t* const* packed_by_tenant, const float* alpha_by_tenant,
+                                   const int32_t* tenant_of_token, uint16_t* y_f16,
+                                   int64_t T, int64_t out, int64_t in, int32_t n_tenants, void* stream);
+
 /* The GEMM form (the prefill regime of Sec. 4.3, many tokens per tenant) of the two extensions of Sec. 4.2, for any
  * T >= 1 (T <= 65535): tokens are sorted by tenant and cut into tiles of 128 rows that never mix tenants, every tile
  * is a matrix-core GEMM over `in` (128 x 128 tiles of y).  Tensors row-major as bd_compress_iterated /

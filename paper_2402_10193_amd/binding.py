@@ -32,7 +32,7 @@ EXPORTS = ["bd_status_string", "bd_version", "bd_workspace_bytes", "bd_pack_sign
            "bd_delta_file_bytes", "bd_delta_file_read", "bd_delta_upload", "bd_delta_install", "bd_quantize_base_q8",
            "bd_compress_q8", "bd_tiled_base_q8_bytes", "bd_tile_base_q8", "bd_linear_multitenant_tiled_q8",
            "bd_linear_multitenant_tiled_group_q8", "bd_linear_multitenant_kbit", "bd_linear_multitenant_gemm_kbit",
-           "bd_linear_multitenant_gemm_q8"]
+           "bd_linear_multitenant_gemm_q8", "bd_linear_multitenant_q8"]
 
 
 class BitDeltaError(RuntimeError):
@@ -103,6 +103,7 @@ def lib() -> ctypes.CDLL:
         L.bd_linear_multitenant_kbit.argtypes = [vp, vp, vp, vp, pi, vp, i64, i64, i64, i32, i32, vp]
         L.bd_linear_multitenant_gemm_kbit.argtypes = [vp, vp, vp, vp, pi, vp, i64, i64, i64, i32, i32, vp, sz, vp]
         L.bd_linear_multitenant_gemm_q8.argtypes = [vp, vp, vp, vp, vp, pi, vp, i64, i64, i64, i32, vp, sz, vp]
+        L.bd_linear_multitenant_q8.argtypes = [vp, vp, vp, vp, vp, pi, vp, i64, i64, i64, i32, vp]
         L.bd_compress_batch.argtypes = [i32, pvp, pvp, pi64, pi64, pvp, vp, vp, sz, vp]
         L.bd_compress_batch.restype = ctypes.c_int
         L.bd_linear_multitenant_tiled_kbit.argtypes = [vp, vp, pvp, vp, pi, vp, i64, i64, i64, i32, i32, vp]
@@ -504,6 +505,23 @@ def linear_multitenant_gemm_kbit(x: torch.Tensor, w_base: torch.Tensor, tenants:
     _check(lib().bd_linear_multitenant_gemm_kbit(_ptr(x), _ptr(w_base), _ptr(tenants.ptrs), _ptr(tenants.alpha), tok, _ptr(y), T,
                                                  out, inn, tenants.n_tenants, tenants.k, _ptr(workspace), workspace.numel(),
                                                  _stream(stream)), "bd_linear_multitenant_gemm_kbit")
+    return y
+
+
+def linear_multitenant_q8(x: torch.Tensor, q: torch.Tensor, scale: torch.Tensor, tenants: "TenantTable",
+                          tenant_of_token: Sequence[int], y: Optional[torch.Tensor] = None, stream=None,
+                          tok_array=None) -> torch.Tensor:
+    """bd_linear_multitenant_q8: decode launches on the row-major 8-bit base (q int8 [out, in], scale [out])."""
+    _dev(x, torch.float16, "x")
+    _dev(q, torch.int8, "q")
+    _dev(scale, torch.float32, "scale")
+    T, inn = x.shape
+    out = q.shape[0]
+    if y is None:
+        y = torch.empty((T, out), dtype=torch.float16, device=x.device)
+    tok = tok_array if tok_array is not None else _tok_array(tenant_of_token)
+    _check(lib().bd_linear_multitenant_q8(_ptr(x), _ptr(q), _ptr(scale), _ptr(tenants.ptrs), _ptr(tenants.alpha), tok, _ptr(y), T,
+                                          out, inn, tenants.n_tenants, _stream(stream)), "bd_linear_multitenant_q8")
     return y
 
 

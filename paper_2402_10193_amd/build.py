@@ -12,7 +12,7 @@ CSRC = os.path.join(PKG, "csrc")
 OBJ = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "libbitdelta.so")
 
-SOURCES = ["bitdelta_api.hip", "compress_kernels.hip", "linear_rowwave.hip", "linear_decode_rowmajor.hip",
+SOURCES = ["bitdelta_api.hip", "compress_kernels.hip", "linear_rowwave.hip", "linear_decode_rowmajor.hip", "linear_decode_rowmajor_q8.hip",
            "linear_decode_tiled.hip", "linear_decode_tiled_q8.hip", "tile_kernels.hip", "linear_prefill.hip", "linear_prefill_big.hip", "baseline_kernels.hip", "delta_image.hip"]
 
 HIPCC_FLAGS = [

@@ -77,6 +77,8 @@ hipError_t launch_linear_decode_tiled(const TiledArgs& args, int n_jobs, hipStre
 hipError_t launch_linear_decode_rowmajor(const TiledArgs& args, int n_jobs, hipStream_t st);
 // the same over an 8-bit base: args.wt point at base8 tiles, args.wscale at their scales
 hipError_t launch_linear_decode_tiled_q8(const TiledArgs& args, int n_jobs, hipStream_t st);
+// the row-major 8-bit base: args.wt[0] = q [out, in] int8, args.wscale[0] = the `out` scales (one matrix)
+hipError_t launch_linear_decode_rowmajor_q8(const TiledArgs& args, int n_jobs, hipStream_t st);
 // q [out, in] int8, scale [out] -> base8 tiles followed by the padded scales
 hipError_t launch_tile_base_q8(const int8_t* q, const float* scale, int64_t out, int64_t in, unsigned char* wq, hipStream_t st);
 

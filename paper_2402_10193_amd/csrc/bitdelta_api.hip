@@ -76,7 +76,7 @@ void build_meta(const int32_t* tenant_of_token, int64_t t0, int n, DecodeMeta* m
 
 bd_status check_linear_args(const void* x, const void* w, const void* packed_by_tenant, const void* alpha_by_tenant,
                             const int32_t* tenant_of_token, const void* y, int64_t T, int64_t out, int64_t in,
-                            int32_t n_tenants) {
+                            int32_t n_tenants, size_t w_bytes_per_el = 2) {
     if (T < 0 || out < 0 || in < 0 || n_tenants < 0 || T > 65535) return BD_ERR_SHAPE;
     if (in % 32 != 0) return BD_ERR_SHAPE;
     if (out > (int64_t)1 << 31 || in > (int64_t)1 << 31) return BD_ERR_SHAPE;
@@ -88,7 +88,7 @@ bd_status check_linear_args(const void* x, const void* w, const void* packed_by_
     for (int64_t t = 0; t < T; ++t)
         if (tenant_of_token[t] < 0 || tenant_of_token[t] >= n_tenants) return BD_ERR_TENANT;
     const size_t ybytes = (size_t)T * out * 2;
-    if (overlaps(y, ybytes, x, (size_t)T * in * 2) || overlaps(y, ybytes, w, (size_t)out * in * 2)) return BD_ERR_ALIAS;
+    if (overlaps(y, ybytes, x, (size_t)T * in * 2) || overlaps(y, ybytes, w, (size_t)out * in * w_bytes_per_el)) return BD_ERR_ALIAS;
     return BD_OK;
 }
 
@@ -341,7 +341,7 @@ bd_status tiled_linear_impl(int32_t n_mats, const uint16_t* x_f16, const uint16_
                             const uint32_t* const* tiled_by_mat_tenant, const float* const* alpha_by_mat,
                             const int32_t* tenant_of_token, uint16_t* const* y_f16, int64_t T, const int64_t* out,
                             int64_t in, int32_t n_tenants, int32_t k, void* stream, bool q8,
-                            const uint32_t* const* packed_rowmajor_dev);
+                            const uint32_t* const* packed_rowmajor_dev, const float* wscale_rowmajor = nullptr);
 }
 
 bd_status bd_linear_multitenant_variant(const uint16_t* x_f16, const uint16_t* w_base_f16,
@@ -466,9 +466,9 @@ bd_status tiled_linear_impl(int32_t n_mats, const uint16_t* x_f16, const uint16_
                             const uint32_t* const* tiled_by_mat_tenant, const float* const* alpha_by_mat,
                             const int32_t* tenant_of_token, uint16_t* const* y_f16, int64_t T, const int64_t* out,
                             int64_t in, int32_t n_tenants, int32_t k, void* stream, bool q8,
-                            const uint32_t* const* packed_rowmajor_dev) {
+                            const uint32_t* const* packed_rowmajor_dev, const float* wscale_rowmajor) {
     const bool rm = packed_rowmajor_dev != nullptr;
-    if (rm && (n_mats != 1 || q8 || in % 128 != 0)) return BD_ERR_UNSUPPORTED;
+    if (rm && (n_mats != 1 || in % 128 != 0 || (q8 && (!wscale_rowmajor || k != 1)))) return BD_ERR_UNSUPPORTED;
     if (n_mats < 1 || n_mats > bd::kTiledMaxMats) return BD_ERR_SHAPE;
     if (k < 1 || k > bd::kTiledMaxPlanes) return BD_ERR_SHAPE;
     if (!out) return BD_ERR_NULL;
@@ -498,7 +498,7 @@ bd_status tiled_linear_impl(int32_t n_mats, const uint16_t* x_f16, const uint16_
         if (!w_tiled[m] || !alpha_by_mat[m] || !y_f16[m]) return BD_ERR_NULL;
         if (misaligned(w_tiled[m], 16) || misaligned(y_f16[m], 2) || misaligned(alpha_by_mat[m], 4)) return BD_ERR_ALIGN;
         const size_t ybytes = (size_t)T * out[m] * 2;
-        const size_t wbytes = rm ? (size_t)out[m] * in * 2 : (q8 ? bd_tiled_base_q8_bytes(out[m], in) : bd_tiled_base_bytes(out[m], in));
+        const size_t wbytes = rm ? (size_t)out[m] * in * (q8 ? 1 : 2) : (q8 ? bd_tiled_base_q8_bytes(out[m], in) : bd_tiled_base_bytes(out[m], in));
         if (overlaps(y_f16[m], ybytes, x_f16, (size_t)T * in * 2) || overlaps(y_f16[m], ybytes, w_tiled[m], wbytes))
             return BD_ERR_ALIAS;
         for (int64_t t = 0; t < T && !rm; ++t)
@@ -534,7 +534,9 @@ bd_status tiled_linear_impl(int32_t n_mats, const uint16_t* x_f16, const uint16_
             a.wt[mats] = w_tiled[m];
             a.y[mats] = y_f16[m];
             a.alpha[mats] = alpha_by_mat[m];
-            if (q8)   // the scales follow the tiles
+            if (q8 && rm)
+                a.wscale[mats] = wscale_rowmajor;
+            else if (q8)   // the scales follow the tiles
                 a.wscale[mats] = (const float*)((const unsigned char*)w_tiled[m] +
                                                 (size_t)(bd::tiled_row_blocks(out[m]) * bd::tiled_k_tiles(in)) * bd::kTileBaseQ8Bytes);
             a.out[mats] = (int32_t)out[m];
@@ -573,7 +575,8 @@ bd_status tiled_linear_impl(int32_t n_mats, const uint16_t* x_f16, const uint16_
                     a.signs[ct][mi][sl] = tiled_by_mat_tenant[((size_t)mat_of[mi] * n_tenants + run_tenant[s / k]) * k + s % k];
             }
         }
-        const hipError_t e = rm   ? bd::launch_linear_decode_rowmajor(a, max_jobs, (hipStream_t)stream)
+        const hipError_t e = rm   ? (q8 ? bd::launch_linear_decode_rowmajor_q8(a, max_jobs, (hipStream_t)stream)
+                                        : bd::launch_linear_decode_rowmajor(a, max_jobs, (hipStream_t)stream))
                              : q8 ? bd::launch_linear_decode_tiled_q8(a, max_jobs, (hipStream_t)stream)
                                   : bd::launch_linear_decode_tiled(a, max_jobs, (hipStream_t)stream);
         if (e != hipSuccess) return BD_ERR_DEVICE;
@@ -695,10 +698,9 @@ static bd_status gemm_entry(const uint16_t* x_f16, const void* w, size_t w_bytes
                             int64_t T, int64_t out, int64_t in, int32_t n_tenants, int k_planes, void* workspace,
                             size_t workspace_bytes, void* stream) {
     const bd_status st = check_linear_args(x_f16, w, packed_by_tenant, alpha_by_tenant, tenant_of_token, y_f16, T, out, in,
-                                           n_tenants);
+                                           n_tenants, w_bytes_per_el);
     if (st != BD_OK) return st;
     if (T == 0 || out == 0) return BD_OK;
-    if (overlaps(y_f16, (size_t)T * out * 2, w, (size_t)out * in * w_bytes_per_el)) return BD_ERR_ALIAS;
     if (in == 0) return BD_ERR_UNSUPPORTED;   // the empty reduction (y = 0) is bd_linear_multitenant's
     const size_t need = prefill_table_bytes(T, n_tenants);
     if (!workspace || workspace_bytes < need || misaligned(workspace, 256)) return BD_ERR_WORKSPACE;
@@ -725,6 +727,23 @@ bd_status bd_linear_multitenant_gemm_q8(const uint16_t* x_f16, const int8_t* q, 
     if (misaligned(wscale, 4)) return BD_ERR_ALIGN;
     return gemm_entry(x_f16, q, 1, packed_by_tenant, alpha_by_tenant, wscale, tenant_of_token, y_f16, T, out, in, n_tenants, 0,
                       workspace, workspace_bytes, stream);
+}
+
+bd_status bd_linear_multitenant_q8(const uint16_t* x_f16, const int8_t* q, const float* wscale,
+                                   const uint32_t* const* packed_by_tenant, const float* alpha_by_tenant,
+                                   const int32_t* tenant_of_token, uint16_t* y_f16, int64_t T, int64_t out, int64_t in,
+                                   int32_t n_tenants, void* stream) {
+    const bd_status st = check_linear_args(x_f16, q, packed_by_tenant, alpha_by_tenant, tenant_of_token, y_f16, T, out, in,
+                                           n_tenants, 1);
+    if (st != BD_OK) return st;
+    if (T == 0 || out == 0) return BD_OK;
+    if (!wscale) return BD_ERR_NULL;
+    if (misaligned(wscale, 4)) return BD_ERR_ALIGN;
+    // the matrix-core kernel on the row-major tensors: whole groups of four sign words, 32-bit byte offsets
+    if (in % 128 != 0 || in == 0 || (uint64_t)out * (uint64_t)in >= ((uint64_t)1 << 32)) return BD_ERR_UNSUPPORTED;
+    const uint16_t* w = (const uint16_t*)q;
+    return tiled_linear_impl(1, x_f16, &w, nullptr, &alpha_by_tenant, tenant_of_token, &y_f16, T, &out, in, n_tenants, 1, stream,
+                             true, packed_by_tenant, wscale);
 }
 
 bd_status bd_linear_multitenant_tiled_kbit(const uint16_t* x_f16, const uint16_t* w_tiled,

@@ -117,6 +117,21 @@ __device__ __forceinline__ u32x2 rm_gather_sign_bytes(const u32x2 w) {
     const auto f = __builtin_amdgcn_permlane16_swap(u, t, false, false);
     return u32x2{f[0], f[1]};
 }
+// Row-major 8-bit base.  In: the 16 bytes lane (r, g) loaded, q[row r][64 i + 16 g ..] (two's complement).  Out: the
+// lane's 8 bytes of slice 2 i in words 0, 1 and of slice 2 i + 1 in words 2, 3, as u = q + 128 (what the tiled 8-bit base
+// holds).  The four lanes of a row hold [lo, hi] halves; lane g' needs half g' % 2 of lane g' / 2 (slice 2 i) and of
+// lane 2 + g' / 2 (slice 2 i + 1): a swap between neighbouring rows of 16 lanes, then one between the wavefront's halves.
+__device__ __forceinline__ u32x4 rm_gather_q8(const u32x4 w) {
+    u32x4 r;
+#pragma unroll
+    for (int d = 0; d < 2; ++d) {
+        const auto s16 = __builtin_amdgcn_permlane16_swap(w[d], w[2 + d], false, false);
+        const auto s32 = __builtin_amdgcn_permlane32_swap(s16[0], s16[1], false, false);
+        r[d] = s32[0] ^ 0x80808080u;
+        r[2 + d] = s32[1] ^ 0x80808080u;
+    }
+    return r;
+}
 // slice v of the gathered bytes: word (v / 2) % 2, byte v % 2 + 2 * (v / 4)
 __device__ __forceinline__ u32x4 lut_read_rm(const u32x2 s, const int v, const uint32_t lanebits) {
     const uint32_t addr = __builtin_amdgcn_perm(s[(v >> 1) & 1], lanebits, 0x0C0C0000u | ((4u + ((v & 1) | ((v & 4) >> 1))) << 8));
@@ -129,10 +144,10 @@ __device__ __forceinline__ u32x4 lut_read_rm(const u32x2 s, const int v, const u
 // XSTEPS = 0: any number of k tiles per wavefront, x double-buffered per task.
 // NCT = 2 (streamed x only): 17..32 tokens as two column tiles; the tasks of one (row block, k tile)
 // then come in pairs that share the base registers, so the base is still read once.
-// RM: row-major W and packed signs (one matrix, fp16 base, in % 128 == 0) instead of the tiled tensors.
+// RM: row-major W (fp16, or the int8 q of the 8-bit base with its `out` scales) and packed signs (one matrix,
+// in % 128 == 0) instead of the tiled tensors.
 template <int NJ, int XSTEPS, int NCT, bool Q8, bool RM = false>
 __global__ __launch_bounds__(kMaxWavesTiled * kWave) void linear_decode_tiled_kernel(const TiledArgs a) {
-    static_assert(!(RM && Q8), "the 8-bit base exists in the tiled layout only");
     constexpr uint32_t kWTile = Q8 ? kTileBaseQ8Bytes : kTileBaseBytes;   // bytes of one base tile
     constexpr int kWLoads = Q8 ? 4 : 8;                                   // 1 KiB loads per base tile
     extern __shared__ __align__(16) unsigned char smem[];   // [0, 64 KiB): table; then one region per wavefront
@@ -222,12 +237,12 @@ __global__ __launch_bounds__(kMaxWavesTiled * kWave) void linear_decode_tiled_ke
     uint32_t lane16 = (uint32_t)lane * 16u, lane8 = (uint32_t)lane * 8u;
     auto rm_lane_offsets = [&](const int rb) {
         const int row = min(rb * kTileRows + c, a.out[0] - 1);
-        lane16 = (uint32_t)row * ((uint32_t)a.in * 2u) + (uint32_t)g * 16u;
+        lane16 = (uint32_t)row * ((uint32_t)a.in * (Q8 ? 1u : 2u)) + (uint32_t)g * 16u;
         lane8 = (uint32_t)row * ((uint32_t)a.in >> 3) + (uint32_t)g * 8u;
     };
     if constexpr (RM) rm_lane_offsets(rb_req);
     auto w_off = [&](const int rb, const int kt) {   // uniform byte offset of tile (rb, kt) of the base
-        return RM ? (uint32_t)kt * (uint32_t)(kTileK * 2) : (uint32_t)(rb * KT + kt) * kWTile;
+        return RM ? (uint32_t)kt * (uint32_t)(kTileK * (Q8 ? 1 : 2)) : (uint32_t)(rb * KT + kt) * kWTile;
     };
     auto s_off = [&](const int rb, const int kt) {   // ... of a tenant's signs
         return RM ? (uint32_t)kt * (uint32_t)(kTileK / 8) : (uint32_t)(rb * KT + kt) * (uint32_t)kTileSignBytes;
@@ -247,7 +262,7 @@ __global__ __launch_bounds__(kMaxWavesTiled * kWave) void linear_decode_tiled_ke
     // their x is zero).  All of it is uniform arithmetic per task, no branch around a load.
     const int kt_short = (RM && (a.in % kTileK) != 0) ? KT - 1 : -1;
     auto w_base_hi = [&](const int kt) {   // the pointer slices 4..7 of tile kt are read through
-        return (RM && kt == kt_short) ? wt - 4 * kSliceStride : wt;
+        return (RM && kt == kt_short) ? wt - (kWLoads / 2) * kSliceStride : wt;
     };
     auto s_lane_off = [&](const uint32_t off_u, const uint32_t l8, const int kt) {
         uint32_t off = off_u + l8;
@@ -262,7 +277,7 @@ __global__ __launch_bounds__(kMaxWavesTiled * kWave) void linear_decode_tiled_ke
         const uint32_t woff0 = w_off(rb_req, kb) + lane16;
         const unsigned char* const wt_hi0 = w_base_hi(kb);
 #pragma unroll
-        for (int v = 0; v < kWLoads; ++v) wr[v] = ld_w(v >= 4 ? wt_hi0 : wt, woff0 + (uint32_t)v * kSliceStride);
+        for (int v = 0; v < kWLoads; ++v) wr[v] = ld_w(v >= kWLoads / 2 ? wt_hi0 : wt, woff0 + (uint32_t)v * kSliceStride);
     }
 
     // ---- the table: entry b, copy cp at 256 b + 16 cp; element e = bit e of b ? +1.0 : -1.0.
@@ -422,11 +437,14 @@ __global__ __launch_bounds__(kMaxWavesTiled * kWave) void linear_decode_tiled_ke
 #pragma unroll
         for (int v = 0; v < 8; ++v) {
             if constexpr (Q8) {
+                if constexpr (RM && CT == 0) {   // the first column tile finds the registers as loaded; the second, gathered
+                    if ((v & 1) == 0) wr[v >> 1] = rm_gather_q8(wr[v >> 1]);
+                }
                 accb[CT] = __builtin_amdgcn_mfma_f32_16x16x32_f16(q8_operand(wr[v >> 1], v & 1),
                                                                   __builtin_bit_cast(half8, xr[v]), accb[CT], 0, 0, 0);
                 accs[CT] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ones, __builtin_bit_cast(half8, xr[v]), accs[CT], 0, 0, 0);
                 if constexpr (MORE && NEW_BASE) {
-                    if (v & 1) wr[v >> 1] = ldg16_stream(wt, woff + (v >> 1) * 1024);
+                    if (v & 1) wr[v >> 1] = ld_w((v >> 1) >= kWLoads / 2 ? wt_hi : wt, woff + (uint32_t)(v >> 1) * kSliceStride);
                 }
             } else {
                 u32x4 wv = wr[v];
@@ -525,7 +543,12 @@ __global__ __launch_bounds__(kMaxWavesTiled * kWave) void linear_decode_tiled_ke
             int m_c, rb_c;
             mat_of(r0 + rbi, m_c, rb_c);
             const float* ws = m_c == 0 ? a.wscale[0] : (m_c == 1 ? a.wscale[1] : a.wscale[2]);
-            sc = *(const float4v*)(ws + rb_c * kTileRows + 4 * g);   // the scale array is padded to whole row blocks
+            if constexpr (RM) {   // the caller's array of `out` scales: rows beyond `out` read the last one (never stored)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) sc[i] = ws[min(rb_c * kTileRows + 4 * g + i, a.out[0] - 1)];
+            } else {
+                sc = *(const float4v*)(ws + rb_c * kTileRows + 4 * g);   // the scale array is padded to whole row blocks
+            }
         }
         m_nx = m_req;
         rb_nx = 0;

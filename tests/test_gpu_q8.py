@@ -111,6 +111,54 @@ def test_q8_linear_matches_oracle(ref, case):
     assert torch.equal(bd.linear_multitenant_tiled_q8(x, prob.wq, out, prob.table, tok), y)
 
 
+@pytest.mark.parametrize("case", range(len(Q8_CASES)))
+def test_q8_linear_on_row_major_tensors_matches_oracle(ref, case):
+    """bd_linear_multitenant_q8: the same linear read from the row-major int8 base and its `out` scales."""
+    out, inn, nt, tok = Q8_CASES[case]
+    _p(f"q8 row-major case={case} out={out} in={inn} tenants={nt} T={len(tok)}")
+    prob = Q8Problem(ref, out, inn, nt, ("q8lin", case))
+    x = prob.x(len(tok))
+    q = torch.from_numpy(prob.q_np).to(DEV)
+    s = torch.from_numpy(prob.s_np).to(DEV)
+    table = bd.TenantTable([packed_to_device(p, DEV) for p in prob.packed_np],
+                           torch.tensor(prob.alpha_np, dtype=torch.float32, device=DEV))
+    if inn % 128 != 0:
+        with pytest.raises(bd.BitDeltaError) as e:
+            bd.linear_multitenant_q8(x, q, s, table, tok)
+        assert e.value.status == 7
+        return
+    y = bd.linear_multitenant_q8(x, q, s, table, tok)
+    torch.cuda.synchronize()
+    _, y32 = ref.linear_multitenant_q8(to_np(x), prob.q_np, prob.s_np, prob.packed_np, prob.alpha_np, tok)
+    check_close(y, y32, f"q8 row-major case {case}")
+    assert torch.equal(y, bd.linear_multitenant_q8(x, q, s, table, tok))   # reproducible
+    y_tiled = bd.linear_multitenant_tiled_q8(x, prob.wq, out, prob.table, tok)
+    check_close(y, to_np(y_tiled).astype(np.float32), f"q8 row-major against tiled, case {case}")
+
+
+def test_q8_row_major_output_right_behind_the_int8_base(ref):
+    """y may start right where the out * in BYTES of q end (the alias check must not take q for an fp16 tensor)."""
+    out, inn, nt, tok = 50, 640, 3, [2, 0, 1]
+    prob = Q8Problem(ref, out, inn, nt, ("q8adj",))
+    x = prob.x(len(tok))
+    buf = torch.empty(out * inn + len(tok) * out * 2, dtype=torch.uint8, device=DEV)
+    q = buf[:out * inn].view(torch.int8).view(out, inn)
+    q.copy_(torch.from_numpy(prob.q_np).to(DEV))
+    y = buf[out * inn:].view(torch.float16).view(len(tok), out)
+    s = torch.from_numpy(prob.s_np).to(DEV)
+    table = bd.TenantTable([packed_to_device(p, DEV) for p in prob.packed_np],
+                           torch.tensor(prob.alpha_np, dtype=torch.float32, device=DEV))
+    _, y32 = ref.linear_multitenant_q8(to_np(x), prob.q_np, prob.s_np, prob.packed_np, prob.alpha_np, tok)
+    bd.linear_multitenant_q8(x, q, s, table, tok, y=y)
+    check_close(y, y32, "y behind q, decode")
+    y.zero_()
+    bd.linear_multitenant_gemm_q8(x, q, s, table, tok, y=y)
+    check_close(y, y32, "y behind q, gemm")
+    with pytest.raises(bd.BitDeltaError) as e:   # and one byte earlier it does overlap
+        bd.linear_multitenant_q8(x, q, s, table, tok, y=buf[out * inn - 16:out * inn - 16 + len(tok) * out * 2].view(torch.float16).view(len(tok), out))
+    assert e.value.status == 8
+
+
 def test_q8_group_and_errors(ref):
     inn, nt = 1024, 3
     probs = [Q8Problem(ref, o, inn, nt, ("q8grp", i)) for i, o in enumerate((48, 80, 32))]

@@ -137,6 +137,12 @@ def test_gemm_variants_argument_errors(bd):
     assert g(A, 2 * A, 6 * A, 3 * A, 4 * A, _tok(2), 5 * A, 1, 16, 128, 2, W, 4096, 0) == 4
     assert g(A, 2 * A, 6 * A, 3 * A, 4 * A, _tok(0), 5 * A, 1, 16, 128, 1, 0, 0, 0) == 5
     assert g(A, A, 6 * A, 3 * A, 4 * A, _tok(0), A, 1, 16, 128, 1, W, 4096, 0) == 8          # y on top of x
+    d = L.bd_linear_multitenant_q8                                                          # the decode form
+    assert d(A, 2 * A, 0, 3 * A, 4 * A, _tok(0), 5 * A, 1, 16, 128, 1, 0) == 1
+    assert d(A, 2 * A, 6 * A, 3 * A, 4 * A, _tok(1), 5 * A, 1, 16, 128, 1, 0) == 4
+    assert d(A, 2 * A, 6 * A, 3 * A, 4 * A, _tok(0), 5 * A, 1, 16, 96, 1, 0) == 7           # in % 128: no kernel for it
+    assert d(A, 2 * A, 6 * A, 3 * A, 4 * A, _tok(0), 5 * A, 1, 16, 100, 1, 0) == 2
+    assert d(A, 2 * A, 6 * A, 3 * A, 4 * A, _tok(0), 5 * A, 0, 16, 128, 1, 0) == 0
 
 
 def test_compress_noalloc_argument_errors(bd):
