@@ -331,17 +331,23 @@ __global__ __launch_bounds__(kMaxWavesTiled * kWave) void linear_decode_tiled_ke
         for (int i = 0; i < kTiledMaxTokens; ++i) tok_c = (c == i && i < a.T[ct]) ? a.col_token[ct][i] : tok_c;
         xlane[ct] = (uint32_t)tok_c * row_bytes + (uint32_t)g * 16u;
     }
-    // A slice that lies beyond `in` (ragged tile only) reads the row's first bytes instead, valid memory, and x_zero_beyond
-    // replaces it by zeros once it has arrived: every path issues the same eight loads, so the count of loads in
-    // flight at any later point is known at compile time and nothing has to wait for more than it needs.
+    // A slice that lies beyond `in` (ragged tile only) reads the lane's last slice inside the row again (or the row's first
+    // bytes if it has none), valid memory, and x_zero_beyond replaces it by zeros once it has arrived: both paths issue the
+    // same eight loads, so the count of loads in flight at any later point is known at compile time and nothing has to
+    // wait for more than it needs.  The common path keeps its constant offsets (no address arithmetic per slice).
     auto x_fetch_operands = [&](u32x4 (&xop)[8], const int kt, const int ct) __attribute__((always_inline)) {
         uint32_t xl = ct == 0 ? xlane[0] : xlane[NCT - 1];
         asm volatile("" : "+v"(xl));
         const uint32_t off = xl + (uint32_t)kt * (uint32_t)(kTileK * 2);
-        const int k_lane = kt * kTileK + 8 * g;
-        const int k_end = kt == k_ragged ? a.in : kt * kTileK + kTileK;
+        if (kt != k_ragged) {
 #pragma unroll
-        for (int v = 0; v < 8; ++v) xop[v] = ldg16(xg, k_lane + 32 * v < k_end ? off + v * 64 : xl);
+            for (int v = 0; v < 8; ++v) xop[v] = ldg16(xg, off + v * 64);
+        } else {
+            const int n_in = (a.in - kt * kTileK - 8 * g + 31) >> 5;   // this lane's slices inside the row (may be <= 0)
+            const uint32_t last = n_in > 0 ? off + (uint32_t)(n_in - 1) * 64u : xl;
+#pragma unroll
+            for (int v = 0; v < 8; ++v) xop[v] = ldg16(xg, min(off + (uint32_t)v * 64u, last));
+        }
     };
     auto x_zero_beyond = [&](u32x4 (&xop)[8], const int kt) __attribute__((always_inline)) {
         if (kt == k_ragged) {
