@@ -270,33 +270,6 @@ __global__ __launch_bounds__(kMaxWavesTiled * kWave) void linear_decode_tiled_ke
         return off;
     };
 
-    // ---- requests of the first task: base first, (table,) then x, then the signs
-    u32x4 wr[kWLoads];   // fp16 base: slice v; 8-bit base: slices 2 i and 2 i + 1 (8 bytes each)
-    u32x2 sr[NJ];
-    if (have_work) {
-        const uint32_t woff0 = w_off(rb_req, kb) + lane16;
-        const unsigned char* const wt_hi0 = w_base_hi(kb);
-#pragma unroll
-        for (int v = 0; v < kWLoads; ++v) wr[v] = ld_w(v >= kWLoads / 2 ? wt_hi0 : wt, woff0 + (uint32_t)v * kSliceStride);
-    }
-
-    // ---- the table: entry b, copy cp at 256 b + 16 cp; element e = bit e of b ? +1.0 : -1.0.
-    // Built (and the workgroup synchronised) while only the first base requests are in flight: the
-    // later requests queue up behind the memory system, and a barrier behind them would hold the
-    // first multiplications back by microseconds.
-    // Consecutive lanes write consecutive 16-byte copies (16 per entry), a wavefront 1 KiB at a stretch: with a
-    // lane per entry the writes of a wavefront were 128 bytes apart, eight of them on every bank.
-    for (int q = threadIdx.x; q < 256 * 16; q += blockDim.x) {
-        const uint32_t b = (uint32_t)q >> 4;
-        u32x4 e;
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-            e[i] = 0xBC00BC00u ^ (((b >> (2 * i)) & 1u) << 15) ^ (((b >> (2 * i + 1)) & 1u) << 31);
-        *(u32x4*)(smem + q * 16) = e;
-    }
-    __syncthreads();
-
-
     // x of one k tile is a [16 tokens][256] fp16 block.  It is fetched with loads whose lanes are
     // contiguous in memory (load i: token rows 2i and 2i+1, 512 B each) and brought into B-operand
     // order (lane (c, g): row c, elements 32 v + 8 g ..) through this wavefront's LDS staging rows:
@@ -356,6 +329,44 @@ __global__ __launch_bounds__(kMaxWavesTiled * kWave) void linear_decode_tiled_ke
                 if (kt * kTileK + 32 * v + 8 * g >= a.in) xop[v] = u32x4{0u, 0u, 0u, 0u};
         }
     };
+    // ---- requests of the first task: x first, then the base, (the table,) then the signs.  x is small and every
+    // workgroup asks for the same lines; asked for behind the first base tiles of all compute units (16 MB) it arrives
+    // microseconds after them and the first base product waits for it.  (Measured: 1.3 % on launches of one matrix, nothing
+    // on the grouped launches, whose end is set by the stream.)
+    constexpr int XR = XSTEPS > 0 ? XSTEPS : 1;   // x register sets in operand order
+    u32x4 xs[XR][8];
+    u32x4 xraw[XR][8];                            // resident x as fetched; streamed x: the next task's operands
+    if (have_work) {
+        if constexpr (XSTEPS > 0) x_fetch(xraw[0], kb);
+        else x_fetch_operands(xs[0], kb, 0);
+        if constexpr (XSTEPS == 2) x_fetch(xraw[1], kb + kstride);
+    }
+    u32x4 wr[kWLoads];   // fp16 base: slice v; 8-bit base: slices 2 i and 2 i + 1 (8 bytes each)
+    u32x2 sr[NJ];
+    if (have_work) {
+        const uint32_t woff0 = w_off(rb_req, kb) + lane16;
+        const unsigned char* const wt_hi0 = w_base_hi(kb);
+#pragma unroll
+        for (int v = 0; v < kWLoads; ++v) wr[v] = ld_w(v >= kWLoads / 2 ? wt_hi0 : wt, woff0 + (uint32_t)v * kSliceStride);
+    }
+
+    // ---- the table: entry b, copy cp at 256 b + 16 cp; element e = bit e of b ? +1.0 : -1.0.
+    // Built (and the workgroup synchronised) while only the first base requests are in flight: the
+    // later requests queue up behind the memory system, and a barrier behind them would hold the
+    // first multiplications back by microseconds.
+    // Consecutive lanes write consecutive 16-byte copies (16 per entry), a wavefront 1 KiB at a stretch: with a
+    // lane per entry the writes of a wavefront were 128 bytes apart, eight of them on every bank.
+    for (int q = threadIdx.x; q < 256 * 16; q += blockDim.x) {
+        const uint32_t b = (uint32_t)q >> 4;
+        u32x4 e;
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            e[i] = 0xBC00BC00u ^ (((b >> (2 * i)) & 1u) << 15) ^ (((b >> (2 * i + 1)) & 1u) << 31);
+        *(u32x4*)(smem + q * 16) = e;
+    }
+    __syncthreads();
+
+
     unsigned char* const region = smem + kLutBytes + wave * Plan::kRegion;
     auto x_to_operands = [&](const u32x4 (&xraw)[8], u32x4 (&xop)[8]) {
         lds_wave_sync();   // earlier reads of the staging rows are done
@@ -366,16 +377,10 @@ __global__ __launch_bounds__(kMaxWavesTiled * kWave) void linear_decode_tiled_ke
         for (int v = 0; v < 8; ++v) xop[v] = *(const u32x4*)(region + c * kStageRowBytes + 64 * v + 16 * g);
     };
 
-    constexpr int XR = XSTEPS > 0 ? XSTEPS : 1;   // x register sets in operand order
-    u32x4 xs[XR][8];
-    u32x4 xraw[XR][8];                            // resident x as fetched; streamed x: the next task's operands
     if (have_work) {
-        if constexpr (XSTEPS > 0) x_fetch(xraw[0], kb);
-        else x_fetch_operands(xs[0], kb, 0);
         const uint32_t soff0 = s_lane_off(s_off(rb_req, kb), lane8, kb);
 #pragma unroll
         for (int j = 0; j < NJ; ++j) sr[j] = ld_s(sign_ptr(0, j), soff0);
-        if constexpr (XSTEPS == 2) x_fetch(xraw[1], kb + kstride);
     }
 
     // this lane's column: owning job, tenant (for the scale)
