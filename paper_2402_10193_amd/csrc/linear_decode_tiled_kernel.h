@@ -71,7 +71,9 @@ constexpr int kStageBytes = 16 * kStageRowBytes;
 template <int XSTEPS> struct LdsPlan {
     static constexpr int kRedSlots = 8;   // 16 x 16 tiles; a row block takes one per column tile
     static constexpr int kRegion = (XSTEPS > 0 && kStageBytes > kRedSlots * kRedBytesPerWave) ? kStageBytes : kRedSlots * kRedBytesPerWave;
-    static constexpr int kTotal = kLutBytes + kMaxWavesTiled * kRegion;
+    // behind the regions: (span, token) of every column of both column tiles, for the threads that write y
+    static constexpr int kMeta = kLutBytes + kMaxWavesTiled * kRegion;
+    static constexpr int kTotal = kMeta + kTiledMaxCt * kTiledMaxTokens * 8;
 };
 static_assert(LdsPlan<0>::kTotal <= 160 * 1024 && LdsPlan<2>::kTotal <= 160 * 1024, "LDS budget");
 
@@ -364,6 +366,13 @@ __global__ __launch_bounds__(kMaxWavesTiled * kWave) void linear_decode_tiled_ke
             e[i] = 0xBC00BC00u ^ (((b >> (2 * i)) & 1u) << 15) ^ (((b >> (2 * i + 1)) & 1u) << 31);
         *(u32x4*)(smem + q * 16) = e;
     }
+    // What the write of y needs per column, read from the kernel arguments with a lane's own index (a load from memory)
+    // here, where it waits with everything else, and from LDS when a row block is finished: at the end of a launch a trip
+    // to memory for it would be added to the launch's time.
+    if (threadIdx.x < kTiledMaxCt * kTiledMaxTokens) {
+        const int ct = threadIdx.x / kTiledMaxTokens, col = threadIdx.x % kTiledMaxTokens;
+        *(u32x2*)(smem + Plan::kMeta + threadIdx.x * 8) = u32x2{(uint32_t)a.col_span[ct][col], (uint32_t)a.col_token[ct][col]};
+    }
     __syncthreads();
 
 
@@ -524,13 +533,14 @@ __global__ __launch_bounds__(kMaxWavesTiled * kWave) void linear_decode_tiled_ke
             int m, rb;
             mat_of(rbg0 + slot / NCT, m, rb);
             const int out = a.out[m], n_row = rb * kTileRows + row;
-            const int span = a.col_span[ct][col];   // columns of this token (its planes); 0: not a token's first column
+            const u32x2 meta = *(const u32x2*)(smem + Plan::kMeta + (ct * kTiledMaxTokens + col) * 8);
+            const int span = (int)meta[0];   // columns of this token (its planes); 0: not a token's first column
             if (col < a.T[ct] && n_row < out && span > 0) {
                 float s = 0.f;
                 for (int p = 0; p < span; ++p)
                     for (int wv = 0; wv < nw; ++wv)
                         s += *(const float*)(smem + kLutBytes + wv * Plan::kRegion + (slot * 256 + e + p * 16) * 4);
-                a.y[m][(int64_t)a.col_token[ct][col] * out + n_row] = f2h_rne(s);
+                a.y[m][(int64_t)(int)meta[1] * out + n_row] = f2h_rne(s);
             }
         }
         if (more_follow) {

@@ -136,6 +136,23 @@ def test_q8_linear_on_row_major_tensors_matches_oracle(ref, case):
     check_close(y, to_np(y_tiled).astype(np.float32), f"q8 row-major against tiled, case {case}")
 
 
+def test_q8_row_major_more_tokens_than_one_launch(ref):
+    """75 tokens of 5 tenants: three decode launches of the row-major 8-bit kernel, tokens grouped by tenant across them."""
+    out, inn, nt = 80, 1152, 5
+    rng = np.random.default_rng(5)
+    tok = [int(t) for t in rng.integers(0, nt, size=75)]
+    prob = Q8Problem(ref, out, inn, nt, ("q8many",))
+    x = prob.x(len(tok))
+    q = torch.from_numpy(prob.q_np).to(DEV)
+    s = torch.from_numpy(prob.s_np).to(DEV)
+    table = bd.TenantTable([packed_to_device(p, DEV) for p in prob.packed_np],
+                           torch.tensor(prob.alpha_np, dtype=torch.float32, device=DEV))
+    y = bd.linear_multitenant_q8(x, q, s, table, tok)
+    _, y32 = ref.linear_multitenant_q8(to_np(x), prob.q_np, prob.s_np, prob.packed_np, prob.alpha_np, tok)
+    check_close(y, y32, "q8 row-major, 75 tokens")
+    check_close(bd.linear_multitenant_gemm_q8(x, q, s, table, tok), y32, "q8 gemm, 75 tokens")
+
+
 def test_q8_row_major_output_right_behind_the_int8_base(ref):
     """y may start right where the out * in BYTES of q end (the alias check must not take q for an fp16 tensor)."""
     out, inn, nt, tok = 50, 640, 3, [2, 0, 1]
