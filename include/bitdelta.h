@@ -135,7 +135,12 @@ bd_status bd_compress_batch(int32_t n, const uint16_t* const* w_base_f16, const 
  * (256-byte aligned; it receives the token permutation).  With a NULL or smaller workspace the same
  * result is produced by ceil(T / 32) decode launches, each re-reading the base; with a workspace the
  * library takes whichever of the two a cost estimate on the host says is quicker (GEMM tiles hold one
- * tenant's tokens only, so a batch with a few tokens per tenant is cheaper as decode launches). */
+ * tenant's tokens only, so a batch with a few tokens per tenant is cheaper as decode launches).
+ * Speed: this call reads the tensors in the canonical row-major layout, which costs a decode launch four times the
+ * cache accesses per byte of the serving layout; a decode step through it runs at about two thirds of the rate of
+ * bd_linear_multitenant_tiled on the same matrices (and the grouped tiled call saves three launches per layer on top).
+ * A server re-tiles once (bd_tile_base, bd_tile_signs) and decodes through the tiled calls; this call is the one that
+ * needs no preparation. */
 bd_status bd_linear_multitenant(const uint16_t* x_f16, const uint16_t* w_base_f16,
                                 const uint32_t* const* packed_by_tenant,
                                 const float* alpha_by_tenant,
