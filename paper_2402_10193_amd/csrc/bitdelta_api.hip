@@ -14,7 +14,7 @@ namespace {
 using bd::DecodeMeta;
 using bd::kMaxDecodeTokens;
 
-constexpr int kVersion = 216;   // 0.2.16
+constexpr int kVersion = 217;   // 0.2.17
 constexpr int kVariantRowWave = 1;
 constexpr int kVariantRowMajorMfma = 2;   // the matrix-core decode kernel on the row-major tensors (in % 128 == 0)
 constexpr int kVariantPrefillSmall = 4;   // T > 32 with a workspace: the 128 x 128 tile GEMM
