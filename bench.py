@@ -15,7 +15,8 @@ Prints ONE JSON line: decode tokens/s, the HBM roofline of the decode kernel, an
 host cores on one layer of the same workload.
 
 Other workloads and options (each prints one JSON line of its own):
-  --workload prefill   8 tenants x 512 tokens through the matrix-core GEMM (--variant 4/5/6/7 picks the kernel)
+  --workload prefill   8 tenants x 512 tokens through the matrix-core GEMM (--variant 4/5/6/7 picks the kernel; the
+                       merged one-product form, variant 8, is timed beside it)
   --workload hotswap   one tenant's delta set from pinned host memory into the serving layout while B tenants decode
   --mix 6,4,3,1,1,1    a mixed decode batch (tokens per active tenant; the other resident tenants idle)
   --planes K           K sign planes per tenant (iterated compression)
@@ -83,6 +84,7 @@ def parse():
 
 
 MFMA_F16_PEAK_TFLOPS = 2500.0
+MERGED_VARIANT = 8
 
 
 def run_prefill(args, torch, bd, synth, dev, with_variants=False):
@@ -107,21 +109,31 @@ def run_prefill(args, torch, bd, synth, dev, with_variants=False):
         ws = bd.new_workspace(bd.workspace_bytes(bd.OP_LINEAR_MULTITENANT, T, out, inn, B), dev)
         mats.append((x, base, bd.TenantTable(packed, alphas), y, ws, out, inn))
 
-    def step():
-        for x, base, table, y, ws, _, _ in mats:
-            bd.linear_multitenant(x, base, table, tok, y=y, tok_array=tok_arr, workspace=ws, variant=args.variant)
-    for _ in range(max(args.warmup, 1)):
-        step()
-    torch.cuda.synchronize()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record()
-    for _ in range(args.steps):
-        step()
-    e1.record()
-    torch.cuda.synchronize()
-    ms = e0.elapsed_time(e1) / args.steps
+
+    def time_steps(variant):
+        def step():
+            for x, base, table, y, ws, _, _ in mats:
+                bd.linear_multitenant(x, base, table, tok, y=y, tok_array=tok_arr, workspace=ws, variant=variant)
+        for _ in range(max(args.warmup, 1)):
+            step()
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(args.steps):
+            step()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / args.steps
+    ms = time_steps(args.variant)
     flops = sum(2.0 * 2.0 * T * inn * out for *_, out, inn in mats)      # base + delta products
     tflops = flops / (ms * 1e-3) / 1e12
+    # The same two linears as ONE product each on W + alpha S, the sum formed in fp16 on the way to the matrix cores
+    # (variant 8): half the flops, and a result that differs from the two-product form by one fp16 rounding per weight.
+    ms_m = time_steps(MERGED_VARIANT)
+    merged = {"ms_per_step": round(ms_m, 4), "tokens_per_s": round(T / (ms_m * 1e-3), 1),
+              "TFLOP/s": round(flops / 2 / (ms_m * 1e-3) / 1e12, 1),
+              "frac": round(flops / 2 / (ms_m * 1e-3) / 1e12 / MFMA_F16_PEAK_TFLOPS, 4),
+              "note": "one GEMM on W + alpha S (fp16 sum): the flops of a dense fine-tuned model only"}
     variants = None
     if with_variants:
         # the 128 x 128 tile GEMM on the up projection: one plane (variant 4), two planes per tenant, the 8-bit base
@@ -160,6 +172,7 @@ def run_prefill(args, torch, bd, synth, dev, with_variants=False):
             variants[name] = {"us_per_launch": round(us, 1), "TFLOP/s": round(2.0 * 2.0 * T * inn * out / (us * 1e-6) / 1e12, 1)}
     return {
         **({"variants_up_projection": variants} if variants else {}),
+        "merged_form": merged,
         "metric": "prefill tokens/s, fused fp16 base + 1-bit delta linear, 8 tenants x 512 tokens",
         "value": round(T / (ms * 1e-3), 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
@@ -418,7 +431,7 @@ def main():
         print(json.dumps({"calibrate": "3 x bd_probe_copy and bd_probe_read of 1 GiB"}))
         return
     if args.workload == "prefill":
-        print(json.dumps(run_prefill(args, torch, bd, synth, dev, with_variants=True)))
+        print(json.dumps(run_prefill(args, torch, bd, synth, dev, with_variants=not args.no_extras)))
         return
     B, n_layers = args.tenants, args.layers
     shapes = synth.LLAMA2_7B_LAYER if args.model == "7b" else synth.LLAMA2_70B_LAYER
@@ -688,7 +701,8 @@ def main():
             extras["prefill_8x512"] = {"tokens_per_s": pf["value"], "ms_per_step": pf["ms_per_step"],
                                        "TFLOP/s": pf["roofline"]["achieved"], "frac": pf["roofline"]["frac"],
                                        "TFLOP/s_fine_tuned_model_only": pf["roofline"]["achieved_useful"],
-                                       "frac_fine_tuned_model_only": pf["roofline"]["frac_useful"]}
+                                       "frac_fine_tuned_model_only": pf["roofline"]["frac_useful"],
+                                       "merged_form": pf["merged_form"]}
     result["extras"] = extras
 
     # ---- the oracle on the host cores, one layer of the same workload

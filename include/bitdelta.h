@@ -158,7 +158,13 @@ bd_status bd_linear_multitenant(const uint16_t* x_f16, const uint16_t* w_base_f1
  *   variant 4, 5, 6  the prefill GEMM with 128 x 128 tiles / 128 x 256 tiles and 4 wavefronts / 128 x 256
  *              tiles and 8 wavefronts (T > 32 and a workspace as for variant 0, else BD_ERR_UNSUPPORTED /
  *              BD_ERR_WORKSPACE; 5, 6 and 7 need in % 64 == 0)
- *   variant 7  as 5, but every tile whole (5 runs the tiles of a last, sparsely filled round as halves) */
+ *   variant 7  as 5, but every tile whole (5 runs the tiles of a last, sparsely filled round as halves)
+ *   variant 8  the left-hand side of Eq. 6 as ONE matrix product: a workgroup rebuilds the fine-tuned weight
+ *              W + alpha S of its tile on the way to the matrix cores (alpha rounded to binary16, the sum rounded
+ *              once to binary16, as a per-tenant fp16 model would store it) and multiplies once, 256 x 256
+ *              tiles.  Half the matrix-core work of variants 4 to 7; the result differs from theirs by that
+ *              rounding of the weights (about 2e-4 of the largest output at in = 4096) and equals, up to
+ *              summation order, bd_linear_naive on bd_materialize'd weights.  Same conditions as 5. */
 bd_status bd_linear_multitenant_variant(const uint16_t* x_f16, const uint16_t* w_base_f16,
                                         const uint32_t* const* packed_by_tenant,
                                         const float* alpha_by_tenant,

@@ -14,13 +14,14 @@ namespace {
 using bd::DecodeMeta;
 using bd::kMaxDecodeTokens;
 
-constexpr int kVersion = 217;   // 0.2.17
+constexpr int kVersion = 218;   // 0.2.18
 constexpr int kVariantRowWave = 1;
 constexpr int kVariantRowMajorMfma = 2;   // the matrix-core decode kernel on the row-major tensors (in % 128 == 0)
 constexpr int kVariantPrefillSmall = 4;   // T > 32 with a workspace: the 128 x 128 tile GEMM
 constexpr int kVariantPrefillBig = 5;     // ... the 128 x 256 tile GEMM (in % 64 == 0), one wavefront per SIMD
 constexpr int kVariantPrefillBig8 = 6;    // ... the same tile with two wavefronts per SIMD
 constexpr int kVariantPrefillBigWhole = 7;   // ... as 5, but never cutting the tiles of the last round in two
+constexpr int kVariantPrefillMerged = 8;     // ... one product on W + alpha S, formed in fp16 on the way to the matrix cores (256 x 256 tiles)
 
 inline bool misaligned(const void* p, size_t a) { return ((uintptr_t)p & (a - 1)) != 0; }
 
@@ -94,26 +95,33 @@ bd_status check_linear_args(const void* x, const void* w, const void* packed_by_
 
 // Prefill (T > 32): the token permutation and the tenant of every 128-row tile live in the workspace.
 // At most ceil(T / 128) full tiles plus one ragged tile per tenant that has a token.
-size_t prefill_table_bytes(int64_t T, int32_t n_tenants);
+size_t prefill_table_bytes(int64_t T, int32_t n_tenants, bool merged_too = false);
 size_t prefill_workspace_bytes(int64_t T, int32_t n_tenants) {
     if (T <= kMaxDecodeTokens || n_tenants < 0) return 0;
-    return prefill_table_bytes(T, n_tenants);
+    return prefill_table_bytes(T, n_tenants, true);
 }
-size_t prefill_table_bytes(int64_t T, int32_t n_tenants) {
+// The token tables of the GEMM: tiles of 128 rows (merged_too: or of the 256 rows of the one-product form, whichever
+// table is larger); every tenant with a token ends in one partly filled tile at most.
+size_t prefill_table_bytes(int64_t T, int32_t n_tenants, bool merged_too) {
     if (T < 1 || n_tenants < 0) return 0;
-    const int64_t tiles = (T + bd::kPrefillTile - 1) / bd::kPrefillTile + std::min<int64_t>(n_tenants, T);
-    const size_t bytes = (size_t)tiles * (bd::kPrefillTile + 1) * sizeof(int32_t);
+    size_t bytes = 0;
+    for (const int64_t rows : {(int64_t)bd::kPrefillTile, (int64_t)bd::kPrefillMergedTile}) {
+        if (rows != bd::kPrefillTile && !merged_too) continue;
+        const int64_t tiles = (T + rows - 1) / rows + std::min<int64_t>(n_tenants, T);
+        bytes = std::max(bytes, (size_t)tiles * (size_t)(rows + 1) * sizeof(int32_t));
+    }
     return (bytes + 255) & ~(size_t)255;
 }
 
-// Sorts the tokens by tenant (stable), cuts them into tiles of 128 rows that never mix tenants, writes
+// Sorts the tokens by tenant (stable), cuts them into tiles of 128 rows (merged: 256) that never mix tenants, writes
 // the two tables into the workspace (through kernel arguments: no host-to-device copy call) and runs the GEMM.
 // k_planes = 0: one plane per tenant; 1..8: tables indexed by tenant * k_planes + plane.  wscale: the 8-bit base's row
 // scales (w is then the int8 tensor).  Both go through the 128 x 128 tiles (big_waves = 0).
 hipError_t run_prefill(const uint16_t* x, const void* w, const uint32_t* const* packed_by_tenant,
                        const float* alpha_by_tenant, const int32_t* tenant_of_token, uint16_t* y, int64_t T, int64_t out,
                        int64_t in, void* workspace, hipStream_t st, int big_waves, bool halve_last_round,
-                       int k_planes = 0, const float* wscale = nullptr) {
+                       int k_planes = 0, const float* wscale = nullptr, bool merged = false) {
+    const int64_t tile_rows = merged ? bd::kPrefillMergedTile : bd::kPrefillTile;
     std::vector<int32_t> order((size_t)T);
     for (int64_t i = 0; i < T; ++i) order[(size_t)i] = (int32_t)i;
     std::stable_sort(order.begin(), order.end(),
@@ -123,9 +131,9 @@ hipError_t run_prefill(const uint16_t* x, const void* w, const uint32_t* const* 
         const int32_t tenant = tenant_of_token[order[(size_t)i]];
         int64_t e = i;
         while (e < T && tenant_of_token[order[(size_t)e]] == tenant) ++e;
-        for (int64_t t0 = i; t0 < e; t0 += bd::kPrefillTile) {
+        for (int64_t t0 = i; t0 < e; t0 += tile_rows) {
             tile_tenant.push_back(tenant);
-            for (int64_t rrow = 0; rrow < bd::kPrefillTile; ++rrow)
+            for (int64_t rrow = 0; rrow < tile_rows; ++rrow)
                 row_token.push_back(t0 + rrow < e ? order[(size_t)(t0 + rrow)] : -1);
         }
         i = e;
@@ -141,6 +149,9 @@ hipError_t run_prefill(const uint16_t* x, const void* w, const uint32_t* const* 
         const hipError_t e = bd::launch_prefill_meta(c, dst + off, n, st);
         if (e != hipSuccess) return e;
     }
+    if (merged)
+        return bd::launch_linear_prefill_merged(x, (const uint16_t*)w, packed_by_tenant, alpha_by_tenant, dst,
+                                                dst + row_token.size(), n_mtiles, y, T, out, in, halve_last_round, st);
     if (big_waves)
         return bd::launch_linear_prefill_big(x, (const uint16_t*)w, packed_by_tenant, alpha_by_tenant, dst,
                                              dst + row_token.size(), n_mtiles, y, T, out, in, big_waves, halve_last_round, st);
@@ -352,7 +363,9 @@ bd_status bd_linear_multitenant_variant(const uint16_t* x_f16, const uint16_t* w
     const bd_status st = check_linear_args(x_f16, w_base_f16, packed_by_tenant, alpha_by_tenant, tenant_of_token, y_f16,
                                            T, out, in, n_tenants);
     if (st != BD_OK) return st;
-    const bool big_variant = variant == kVariantPrefillBig || variant == kVariantPrefillBig8 || variant == kVariantPrefillBigWhole;
+    const bool merged_variant = variant == kVariantPrefillMerged;
+    const bool big_variant = variant == kVariantPrefillBig || variant == kVariantPrefillBig8 || variant == kVariantPrefillBigWhole ||
+                             merged_variant;
     const bool prefill_variant = variant == kVariantPrefillSmall || big_variant;
     if (variant != 0 && variant != kVariantRowWave && variant != kVariantRowMajorMfma && !prefill_variant)
         return BD_ERR_UNSUPPORTED;
@@ -377,11 +390,11 @@ bd_status bd_linear_multitenant_variant(const uint16_t* x_f16, const uint16_t* w
         // the large tile (one workgroup per CU, 256 output features wide) pays off when there are at least that many
         int big_waves = 0;
         if (variant == kVariantPrefillBig8) big_waves = 8;
-        if (variant == kVariantPrefillBig || variant == kVariantPrefillBigWhole ||
+        if (variant == kVariantPrefillBig || variant == kVariantPrefillBigWhole || variant == kVariantPrefillMerged ||
             (variant == 0 && big_default))
             big_waves = 4;
         return run_prefill(x_f16, w_base_f16, packed_by_tenant, alpha_by_tenant, tenant_of_token, y_f16, T, out, in,
-                           workspace, hs, big_waves, variant != kVariantPrefillBigWhole) == hipSuccess
+                           workspace, hs, big_waves, variant != kVariantPrefillBigWhole, 0, nullptr, merged_variant) == hipSuccess
                    ? BD_OK
                    : BD_ERR_DEVICE;
     }

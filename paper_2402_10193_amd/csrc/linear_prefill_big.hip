@@ -28,18 +28,34 @@ namespace bd {
 namespace {
 
 constexpr int kBgM = 128, kBgN = 256, kBgK = 64;
+constexpr int kMergedTile = kPrefillMergedTile;          // token rows of a tile of the merged form
 constexpr int kBgRowBytes = kBgK * 2;                    // 128
-constexpr int kBgXBytes = kBgM * kBgRowBytes;            // 16384
 constexpr int kBgWBytes = kBgN * kBgRowBytes;            // 32768
 constexpr int kBgSBytes = kBgN * 8;                      // 2048
-constexpr int kBgBufBytes = kBgXBytes + kBgWBytes + kBgSBytes;
-constexpr int kBgLutBytes = 256 * 8 * 16;
-constexpr int kBgTokBytes = kBgM * 4;                    // the tile's token of every row
-constexpr int kBgLdsBytes = 2 * kBgBufBytes + kBgLutBytes + kBgTokBytes;   // 135680
+// LDS of a tile of TM token rows: [2 buffers: x, W, sign words][byte table][the tile's token of every row].  The x
+// tile is laid out for 128 rows (half tiles use the first 64) or for 256; beside the larger one the table keeps
+// 4 copies of every entry instead of 8.
+template <int TM>
+struct BgLds {
+    static constexpr int kRows = TM > kBgM ? TM : kBgM;
+    static constexpr int kX = kRows * kBgRowBytes;              // 16384 | 32768
+    static constexpr int kBuf = kX + kBgWBytes + kBgSBytes;
+    static constexpr int kLutCopies = TM > kBgM ? 4 : 8;
+    static constexpr int kLutEntry = kLutCopies * 16;
+    static constexpr int kLut = 256 * kLutEntry;
+    static constexpr int kTok = kRows * 4;
+    static constexpr int kTotal = 2 * kBuf + kLut + kTok;       // 135680 | 152576
+    // 128 rows: buffer 1 follows buffer 0 (x, W, signs | x, W, signs), 51200 bytes on.  256 rows: x | x | W | W |
+    // signs | signs, so that the distance between a region's two buffers still fits the 16-bit offset of an LDS instruction.
+    static constexpr bool kByRegion = TM > kBgM;
+    static constexpr int kXStride = kByRegion ? kX : kBuf;
+    static constexpr int kWBase = kByRegion ? 2 * kX : kX, kWStride = kByRegion ? kBgWBytes : kBuf;
+    static constexpr int kSBase = kByRegion ? 2 * kX + 2 * kBgWBytes : kX + kBgWBytes, kSStride = kByRegion ? kBgSBytes : kBuf;
+};
+constexpr int kBgLdsBytes = BgLds<kBgM>::kTotal;
 // Epilogue: a wavefront's rows of y as fp16, 64 features + 16 B of padding each (rows 4 apart, which one LDS
 // instruction writes together, then fall into different banks), in the tile buffers, which are free by then.
 constexpr int kBgOutRowBytes = 64 * 2 + 16;
-static_assert(kBgM * kBgOutRowBytes * 4 <= 2 * kBgBufBytes, "the result rows of all wavefronts fit the tile buffers");
 constexpr int kBgPanel = 4, kBgChunk = 32, kBgXcds = 8;  // launch order: 8 x 4 tiles (1024 tokens x 1024 features) per XCD at a time
 
 __device__ __forceinline__ int bg_off(const int row, const int chunk) {
@@ -82,16 +98,26 @@ __device__ __forceinline__ void mfma_in_place(float16v& acc, const half8 a, cons
 
 }  // namespace
 
-// One tile: TM token rows r0 .. r0 + TM of the 128-row token tile mt, output features 256 nt .. + 256.
+// One tile: TM token rows r0 .. r0 + TM of token tile mt (whose rows' tokens are tile_tokens[]), output features
+// 256 nt .. + 256.
 // WM = 1: 4 wavefronts (1 x 4), each TM tokens x 64 features, alone on its SIMD; two sets of staging registers
 // (loads two steps ahead).  WM = 2: 8 wavefronts (2 x 4), each TM / 2 x 64, two per SIMD; one set (one step ahead).
 // TM = 128, or 64 (WM = 1 only): half a tile, for the tiles of a last round that would leave most units idle.
-template <int WM, int TM>
+// MERGED: one product instead of two.  The table holds +-alpha (alpha rounded to fp16) instead of +-1, a lane adds
+// its sign operand to its W operand in fp16 (one rounding per weight: the fine-tuned weight W + alpha S as an fp16
+// model would store it, the left-hand side of Eq. 6) and multiplies once: half the matrix-core work, and a result
+// that differs from the two-product form by that rounding of the weights.
+template <int WM, int TM, bool MERGED>
 __device__ __forceinline__ void prefill_big_tile(
     const uint16_t* __restrict__ x, const uint16_t* __restrict__ w, const uint32_t* const* __restrict__ packed_by_tenant,
-    const float* __restrict__ alpha_by_tenant, const int32_t* __restrict__ row_token, const int32_t* __restrict__ tile_tenant,
+    const float* __restrict__ alpha_by_tenant, const int32_t* __restrict__ tile_tokens, const int32_t* __restrict__ tile_tenant,
     uint16_t* __restrict__ y, const int64_t out, const int64_t in, const int mt, const int nt, const int r0) {
     extern __shared__ __align__(16) unsigned char lds[];   // [2 buffers: x, W, sign words][table][tokens]
+    using Lds = BgLds<TM>;
+    constexpr int kBgBufBytes = Lds::kBuf, kBgLutBytes = Lds::kLut;
+    // the result rows of all wavefronts fit in front of the tokens (the merged form's last table reads are issued
+    // before the last barrier, so its table may be overwritten as well)
+    static_assert(TM * kBgOutRowBytes * 4 <= 2 * kBgBufBytes + (MERGED ? kBgLutBytes : 0), "the epilogue's rows overlap the tokens");
     unsigned char* const lut = lds + 2 * kBgBufBytes;
 
     constexpr int kThreads = 256 * WM, kWaveM = TM / WM, MI = kWaveM / 32;
@@ -102,11 +128,13 @@ __device__ __forceinline__ void prefill_big_tile(
     // instructions is below 20 cycles; 7 MFMAs (MI = 2: 64-row halves, or two wavefronts per SIMD) are 224.
     // The epilogue reads the accumulators with vector instructions after two `s_nop 15` (32 wait states; the rule for
     // reading the result of an 8-pass MFMA asks for 18).  Every instantiation has a full-output parity test.
-    constexpr int kMfmasBetweenUses = 4 * MI - 1;
-    static_assert(MI == 2 || MI == 4, "the slice schedule below is written for 2 or 4 token blocks per wavefront");
-    static_assert(kMfmasBetweenUses >= 7, "an accumulator would be used again while its last MFMA may still be in the pipe");
+    // (MERGED: 2 MI MFMAs per slice, each accumulator once: 3 or 7 others, 96 cycles or more, between two uses.)
+    constexpr int kMfmasBetweenUses = (MERGED ? 2 : 4) * MI - 1;
+    static_assert(MI == 2 || MI == 4 || (MERGED && MI == 8), "the slice schedules below are written for these token blocks per wavefront");
+    static_assert(kMfmasBetweenUses >= (MERGED ? 3 : 7), "an accumulator would be used again while its last MFMA may still be in the pipe");
     constexpr int kBgXPer = TM * 8 / kThreads, kBgWPer = kBgN * 8 / kThreads;   // 16-byte chunks per thread and step
-    constexpr int kSets = WM == 1 ? 2 : 1;
+    constexpr int kSets = (WM == 1 && TM <= kBgM) ? 2 : 1;   // (256 rows: the registers hold one set)
+    static_assert(!MERGED || WM == 1, "the merged form runs one wavefront per SIMD");
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 2, wn = wave & 3;
     const int64_t n0 = (int64_t)nt * kBgN;
@@ -133,35 +161,42 @@ __device__ __forceinline__ void prefill_big_tile(
         const int q = tid + kThreads * i, row = q >> 3, c8 = q & 7;
         const int64_t wrow = n0 + row < out ? row : out - 1 - n0;
         wsrc[i] = (uint32_t)(wrow * in * 2) + c8 * 16;
-        wdst[i] = lds_at(kBgXBytes + bg_off(row, c8));
+        wdst[i] = lds_at(Lds::kWBase + bg_off(row, c8));
         asm volatile("" : "+v"(wdst[i]));   // a register of its own: derived from xdst[i], it would cost an addition per use
         set0.wg[i] = *(const u32x4*)(wbase + wsrc[i]);
     }
     const int tenant = tile_tenant[mt];
     int tokv[kBgXPer];
 #pragma unroll
-    for (int i = 0; i < kBgXPer; ++i) tokv[i] = row_token[mt * kBgM + r0 + ((tid + kThreads * i) >> 3)];
+    for (int i = 0; i < kBgXPer; ++i) tokv[i] = tile_tokens[r0 + ((tid + kThreads * i) >> 3)];
     if (kSets == 2) {
 #pragma unroll
         for (int i = 0; i < kBgWPer; ++i) set1.wg[i] = *(const u32x4*)(wbase + (int64_t)step_b * kBgRowBytes + wsrc[i]);
     }
     __builtin_amdgcn_sched_barrier(0);
 
-    // byte -> 8 fp16 (+1.0 where the bit is set, else -1.0), element e = bit e; entry [byte][copy].  Consecutive lanes
-    // write consecutive 16-byte copies (a wavefront 1 KiB at a stretch; a lane per entry would put its writes 128
-    // bytes apart, several of them on every bank).
-    for (int q = tid; q < 256 * 8; q += kThreads) {
-        const uint32_t bb = (uint32_t)q >> 3;
+    // byte -> 8 fp16 (+1.0 where the bit is set, else -1.0; MERGED: +alpha, -alpha), element e = bit e; entry
+    // [byte][copy].  Consecutive lanes write consecutive 16-byte copies (a wavefront 1 KiB at a stretch; a lane per
+    // entry would put its writes 128 bytes apart, several of them on every bank).
+    float alpha = 0.f;
+    uint32_t minus = 0xBC00BC00u;
+    if constexpr (MERGED) {
+        alpha = alpha_by_tenant[tenant];
+        const uint32_t h = (uint32_t)f2h_rne(alpha) ^ 0x8000u;
+        minus = h | (h << 16);
+    }
+    for (int q = tid; q < 256 * Lds::kLutCopies; q += kThreads) {
+        const uint32_t bb = (uint32_t)q / Lds::kLutCopies;
         u32x4 e;
 #pragma unroll
         for (int i = 0; i < 4; ++i)
-            e[i] = 0xBC00BC00u ^ (((bb >> (2 * i)) & 1u) << 15) ^ (((bb >> (2 * i + 1)) & 1u) << 31);
+            e[i] = minus ^ (((bb >> (2 * i)) & 1u) << 15) ^ (((bb >> (2 * i + 1)) & 1u) << 31);
         *(u32x4*)(lut + q * 16) = e;
     }
-    const lds_bytes lut_lane = lds_at(2 * kBgBufBytes + (lane & 7) * 16);
+    const lds_bytes lut_lane = lds_at(2 * kBgBufBytes + (lane & (Lds::kLutCopies - 1)) * 16);
     __builtin_amdgcn_sched_barrier(0);
 
-    const float alpha = alpha_by_tenant[tenant];
+    if constexpr (!MERGED) alpha = alpha_by_tenant[tenant];
     // sign words: 256 threads take a row's two words each, 512 threads one word each
     const int s_row = WM == 1 ? tid : tid >> 1, s_word = WM == 1 ? 0 : tid & 1;
     const int64_t srow = n0 + s_row < out ? n0 + s_row : out - 1;
@@ -183,7 +218,7 @@ __device__ __forceinline__ void prefill_big_tile(
         if (WM == 1) set1.s1 = ssrc[2 * step_b + 1];
     }
 
-    const lds_bytes sdst = lds_at(kBgXBytes + kBgWBytes + tid * (WM == 1 ? 8 : 4));
+    const lds_bytes sdst = lds_at(Lds::kSBase + tid * (WM == 1 ? 8 : 4));
     // items: the x chunks, the W chunks, the sign word(s)
     constexpr int kItems = kBgXPer + kBgWPer + 1;
     auto fetch_item = [&](Staged& st, const int step, const int item) {
@@ -201,11 +236,10 @@ __device__ __forceinline__ void prefill_big_tile(
         }
     };
     auto stage_item = [&](const Staged& st, const int buf, const int item) {
-        const int b = buf * kBgBufBytes;
-        if (item < kBgXPer) lds_put<u32x4>(xdst[item] + b, st.xg[item]);
-        else if (item < kBgXPer + kBgWPer) lds_put<u32x4>(wdst[item - kBgXPer] + b, st.wg[item - kBgXPer]);
-        else if (WM == 1) lds_put<u32x2>(sdst + b, u32x2{st.s0, st.s1});
-        else lds_put<uint32_t>(sdst + b, st.s0);
+        if (item < kBgXPer) lds_put<u32x4>(xdst[item] + buf * Lds::kXStride, st.xg[item]);
+        else if (item < kBgXPer + kBgWPer) lds_put<u32x4>(wdst[item - kBgXPer] + buf * Lds::kWStride, st.wg[item - kBgXPer]);
+        else if (WM == 1) lds_put<u32x2>(sdst + buf * Lds::kSStride, u32x2{st.s0, st.s1});
+        else lds_put<uint32_t>(sdst + buf * Lds::kSStride, st.s0);
     };
     auto fetch = [&](Staged& st, const int step) {
 #pragma unroll
@@ -233,21 +267,21 @@ __device__ __forceinline__ void prefill_big_tile(
     for (int sl = 0; sl < 4; ++sl) {
         const int cho = ((2 * sl + hi) ^ mask) << 4;
         xrd[sl] = lds_at((wm * kWaveM + r32) * kBgRowBytes + cho);
-        wrd[sl] = lds_at(kBgXBytes + (wn * 64 + r32) * kBgRowBytes + cho);
+        wrd[sl] = lds_at(Lds::kWBase + (wn * 64 + r32) * kBgRowBytes + cho);
         asm volatile("" : "+v"(xrd[sl]), "+v"(wrd[sl]));
     }
-    const lds_bytes srd = lds_at(kBgXBytes + kBgWBytes + (wn * 64 + r32) * 8);
+    const lds_bytes srd = lds_at(Lds::kSBase + (wn * 64 + r32) * 8);
     half8 a[2][MI], bw[2][2], bs[2][2];   // operands of two k slices: one being multiplied, one being read
     u32x2 sw[2];                         // this lane's row of the 2 feature blocks: the step's 8 sign bytes each
     auto read_signs = [&](const int buf) {
 #pragma unroll
-        for (int j = 0; j < 2; ++j) sw[j] = lds_get<u32x2>(srd + buf * kBgBufBytes + j * 32 * 8);
+        for (int j = 0; j < 2; ++j) sw[j] = lds_get<u32x2>(srd + buf * Lds::kSStride + j * 32 * 8);
     };
     // The MI + 4 operand reads of a k slice, in the order the MFMAs of the slice need them.
     constexpr int kReads = MI + 4;
     const uint32_t sh[2] = {8u * hi, 16u + 8u * hi};   // bit position of the lane's sign byte in the word: slice 2 w + (0 | 1)
     auto read_item = [&](const int buf, const int sl, const int set, const int r) {
-        const int b = buf * kBgBufBytes;
+        const int b = buf * kBgBufBytes;   // (128 rows: the stride of every region)
         // r: 0 W(0), 1 signs(0), 2 x(0), 3 W(1), 4 signs(1), 5.. x(1..)
         if (r == 0 || r == 3) {
             const int j = r / 3;
@@ -255,7 +289,7 @@ __device__ __forceinline__ void prefill_big_tile(
         } else if (r == 1 || r == 4) {
             const int j = r / 3;
             const uint32_t byte = __builtin_amdgcn_ubfe(sl < 2 ? sw[j][0] : sw[j][1], sh[sl & 1], 8u);   // byte 2 sl + hi of the row's 8
-            bs[set][j] = lds_get<half8>(lut_lane + (byte << 7));
+            bs[set][j] = lds_get<half8>(lut_lane + byte * Lds::kLutEntry);
         } else {
             const int i = r == 2 ? 0 : r - 4;
             a[set][i] = lds_get<half8>(xrd[sl] + (b + i * 32 * kBgRowBytes));
@@ -264,6 +298,32 @@ __device__ __forceinline__ void prefill_big_tile(
     auto read_slice = [&](const int buf, const int sl, const int set) {
 #pragma unroll
         for (int r = 0; r < kReads; ++r) read_item(buf, sl, set, r);
+    };
+
+    // MERGED.  The MFMAs of a slice run feature block 0 first (slots 0 .. MI-1), then block 1 (slots MI .. 2 MI-1).
+    // Behind the first slots the next slice's W(0), signs(0), W(1), signs(1) are read (8 token blocks: behind every
+    // other one); behind slot MI + i, the last one that uses x operand i, that operand of the next slice.  W(0) +
+    // signs(0) of the next slice are added up in the second half of this slice and W(1) + signs(1) in the first
+    // half of the next one.  With 8 token blocks the step's LDS writes and global loads alternate over the slots
+    // 0 .. 2 kItems - 1, so that no slot carries more than one of them.
+    auto read_item_m = [&](const int buf, const int sl, const int set, const int r) {
+        if (r < 4) {
+            const int j = r >> 1;
+            if ((r & 1) == 0) {
+                bw[set][j] = lds_get<half8>(wrd[sl] + (buf * Lds::kWStride + j * 32 * kBgRowBytes));
+            } else {
+                const uint32_t byte = __builtin_amdgcn_ubfe(sl < 2 ? sw[j][0] : sw[j][1], sh[sl & 1], 8u);
+                bs[set][j] = lds_get<half8>(lut_lane + byte * Lds::kLutEntry);
+            }
+        } else {
+            // one set of x operands: a[i] is read again right behind the last MFMA of the slice that uses it
+            a[0][r - 4] = lds_get<half8>(xrd[sl] + (buf * Lds::kXStride + (r - 4) * 32 * kBgRowBytes));
+        }
+    };
+    auto merge_word = [&](const int set, const int j, const int m) {   // one packed addition
+        const half2v sum = half2v{bw[set][j][2 * m], bw[set][j][2 * m + 1]} + half2v{bs[set][j][2 * m], bs[set][j][2 * m + 1]};
+        bw[set][j][2 * m] = sum[0];
+        bw[set][j][2 * m + 1] = sum[1];
     };
 
     // While step `step` is multiplied, the tiles of step + 1 (in `next`) go into the other buffer and `next` is
@@ -313,17 +373,75 @@ __device__ __forceinline__ void prefill_big_tile(
         }
     };
 
+    auto do_step_merged = [&](const int step, const int buf, Staged& next) {
+        const int step3 = step + 1 + kSets < last ? step + 1 + kSets : last;
+#pragma unroll
+        for (int sl = 0; sl < 4; ++sl) {                        // k slice: 2 MI MFMAs
+            const int cur = sl & 1;
+            if (sl == 3) {
+                bg_barrier();
+                read_signs(buf ^ 1);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+                for (int i = 0; i < MI; ++i) {
+                    // through the builtin: the compiler keeps the distance that the matrix cores need behind the packed
+                    // additions that write bw
+                    accb[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[0][i], bw[cur][j], accb[i][j], 0, 0, 0);
+                    const int q = j * MI + i;   // slot of the slice
+                    // reads of the next slice's operands
+                    const int r_lo = q >= MI ? 4 + q - MI : (MI == 2 ? 2 * q : (MI == 4 ? q : q / 2));
+                    const int r_hi = q >= MI ? r_lo + 1 : (MI == 2 ? r_lo + 2 : (MI == 4 || (q & 1) == 0 ? r_lo + 1 : r_lo));
+#pragma unroll
+                    for (int r = r_lo; r < r_hi; ++r) {
+                        if (sl < 3) read_item_m(buf, sl + 1, cur ^ 1, r);
+                        else read_item_m(buf ^ 1, 0, 0, r);
+                    }
+#pragma unroll
+                    for (int m = 0; m < 4; ++m) {
+                        if (q == m * MI / 4) merge_word(cur, 1, m);              // this slice's feature block 1
+                        if (q == MI + m * MI / 4) merge_word(cur ^ 1, 0, m);     // the next slice's feature block 0
+                    }
+                    const int p = sl * MI * 2 + q;
+                    if constexpr (MI == 8) {
+                        static_assert(MI != 8 || 2 * kItems <= 3 * MI * 2, "all items are staged before the barrier slice");
+                        if ((p & 1) == 0 && p / 2 < kItems) stage_item(next, buf ^ 1, p / 2);
+                        if ((p & 1) == 1 && p / 2 < kItems) fetch_item(next, step3, p / 2);
+                    } else {
+                        if (p < kItems) stage_item(next, buf ^ 1, p);
+                        if (p >= kLag && p - kLag < kItems) fetch_item(next, step3, p - kLag);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+
     stage(set0, 0);   // both sets were requested at the top
     fetch(set0, kSets < last ? kSets : last);
     bg_barrier();       // the table and the tiles of step 0 are complete
     read_signs(0);
-    read_slice(0, 0, 0);
     int step = 0;
-    for (; step + 1 < n_steps; step += 2) {
-        do_step(step, 0, kSets == 2 ? set1 : set0);
-        do_step(step + 1, 1, set0);
+    if constexpr (MERGED) {
+#pragma unroll
+        for (int r = 0; r < kReads; ++r) read_item_m(0, 0, 0, r);
+#pragma unroll
+        for (int m = 0; m < 4; ++m) merge_word(0, 0, m);
+        for (; step + 1 < n_steps; step += 2) {
+            do_step_merged(step, 0, kSets == 2 ? set1 : set0);
+            do_step_merged(step + 1, 1, set0);
+        }
+        if (step < n_steps) do_step_merged(step, 0, kSets == 2 ? set1 : set0);
+    } else {
+        read_slice(0, 0, 0);
+        for (; step + 1 < n_steps; step += 2) {
+            do_step(step, 0, kSets == 2 ? set1 : set0);
+            do_step(step + 1, 1, set0);
+        }
+        if (step < n_steps) do_step(step, 0, kSets == 2 ? set1 : set0);
     }
-    if (step < n_steps) do_step(step, 0, kSets == 2 ? set1 : set0);
 
     asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");   // the last MFMAs have left the pipe before their results are read
     // Every wavefront has passed the last step's barrier, so nobody reads the tiles or the table any more (the
@@ -339,7 +457,8 @@ __device__ __forceinline__ void prefill_big_tile(
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
                 const int row = 32 * i + 8 * (e >> 2) + 4 * hi + (e & 3);
-                lds_put<uint16_t>(orow + row * kBgOutRowBytes + (32 * j + r32) * 2, f2h_rne(accb[i][j][e] + alpha * accd[i][j][e]));
+                lds_put<uint16_t>(orow + row * kBgOutRowBytes + (32 * j + r32) * 2,
+                                  f2h_rne(MERGED ? accb[i][j][e] : accb[i][j][e] + alpha * accd[i][j][e]));
             }
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
@@ -365,30 +484,61 @@ __device__ __forceinline__ void prefill_big_tile(
 
 // Launch order -> tile.  Tiles are numbered in panels of 8 N tiles, row-major inside, and an XCD takes chunks of 32
 // consecutive numbers, so that the workgroups it runs together form a compact block of tiles.  The tiles from n_full
-// on are run as two workgroups of half a tile each (n_full = all of them: none).
+// on are run as two workgroups of half a tile each (n_full = all of them: none).  Returns false for a surplus workgroup.
+__device__ __forceinline__ bool bg_tile_of_block(const int n_mtiles, const int n_ntiles, const int n_full, int* mt, int* nt,
+                                                 int* half) {
+    const int L = blockIdx.x, xcd = L % kBgXcds, slot = L / kBgXcds;
+    const int chunk = (slot / kBgChunk) * kBgXcds + xcd;
+    const int v = chunk * kBgChunk + slot % kBgChunk;
+    const int n_tiles = n_mtiles * n_ntiles;
+    if (v >= n_full + 2 * (n_tiles - n_full)) return false;
+    const int t = v < n_full ? v : n_full + ((v - n_full) >> 1);
+    const int per_panel = n_mtiles * kBgPanel;
+    const int panel = t / per_panel, tp = t - panel * per_panel;
+    const int width = n_ntiles - panel * kBgPanel < kBgPanel ? n_ntiles - panel * kBgPanel : kBgPanel;
+    *mt = tp / width;
+    *nt = panel * kBgPanel + tp % width;
+    *half = v < n_full ? -1 : (v - n_full) & 1;
+    return true;
+}
+
 template <int WM>
 __global__ __launch_bounds__(256 * WM, 1) void linear_prefill_big_kernel(
     const uint16_t* __restrict__ x, const uint16_t* __restrict__ w, const uint32_t* const* __restrict__ packed_by_tenant,
     const float* __restrict__ alpha_by_tenant, const int32_t* __restrict__ row_token, const int32_t* __restrict__ tile_tenant,
     uint16_t* __restrict__ y, const int64_t out, const int64_t in, const int n_mtiles, const int n_ntiles, const int n_full) {
-    const int L = blockIdx.x, xcd = L % kBgXcds, slot = L / kBgXcds;
-    const int chunk = (slot / kBgChunk) * kBgXcds + xcd;
-    const int v = chunk * kBgChunk + slot % kBgChunk;
-    const int n_tiles = n_mtiles * n_ntiles;
-    if (v >= n_full + 2 * (n_tiles - n_full)) return;
-    const int t = v < n_full ? v : n_full + ((v - n_full) >> 1);
-    const int per_panel = n_mtiles * kBgPanel;
-    const int panel = t / per_panel, tp = t - panel * per_panel;
-    const int width = n_ntiles - panel * kBgPanel < kBgPanel ? n_ntiles - panel * kBgPanel : kBgPanel;
-    const int mt = tp / width, nt = panel * kBgPanel + tp % width;
+    int mt, nt, half;
+    if (!bg_tile_of_block(n_mtiles, n_ntiles, n_full, &mt, &nt, &half)) return;
+    const int32_t* const tile_tokens = row_token + mt * kBgM;
     if constexpr (WM == 1) {
-        if (v >= n_full) {
-            prefill_big_tile<1, kBgM / 2>(x, w, packed_by_tenant, alpha_by_tenant, row_token, tile_tenant, y, out, in, mt, nt,
-                                          ((v - n_full) & 1) * (kBgM / 2));
+        if (half >= 0) {
+            prefill_big_tile<1, kBgM / 2, false>(x, w, packed_by_tenant, alpha_by_tenant, tile_tokens, tile_tenant, y, out, in, mt, nt,
+                                                 half * (kBgM / 2));
             return;
         }
     }
-    prefill_big_tile<WM, kBgM>(x, w, packed_by_tenant, alpha_by_tenant, row_token, tile_tenant, y, out, in, mt, nt, 0);
+    prefill_big_tile<WM, kBgM, false>(x, w, packed_by_tenant, alpha_by_tenant, tile_tokens, tile_tenant, y, out, in, mt, nt, 0);
+}
+
+// The merged form on token tiles of 256 rows (row_token holds 256 entries per tile): a wavefront multiplies 256
+// tokens x 64 features per operand of W that it reads, looks up and adds, which is what lets the matrix cores run
+// most of the time although every such operand costs eight instructions.  A tile whose upper 128 rows are empty (a
+// tenant's last tile; the rows of a tile are filled from the top) runs as 128 rows; the tiles from n_full on run as
+// two workgroups of 128 rows each.
+__global__ __launch_bounds__(256, 1) void linear_prefill_merged_kernel(
+    const uint16_t* __restrict__ x, const uint16_t* __restrict__ w, const uint32_t* const* __restrict__ packed_by_tenant,
+    const float* __restrict__ alpha_by_tenant, const int32_t* __restrict__ row_token, const int32_t* __restrict__ tile_tenant,
+    uint16_t* __restrict__ y, const int64_t out, const int64_t in, const int n_mtiles, const int n_ntiles, const int n_full) {
+    int mt, nt, half;
+    if (!bg_tile_of_block(n_mtiles, n_ntiles, n_full, &mt, &nt, &half)) return;
+    const int32_t* const tile_tokens = row_token + mt * kMergedTile;
+    if (half >= 0 || tile_tokens[kBgM] < 0) {
+        const int r0 = half > 0 ? kBgM : 0;
+        if (tile_tokens[r0] < 0) return;   // nothing in this half
+        prefill_big_tile<1, kBgM, true>(x, w, packed_by_tenant, alpha_by_tenant, tile_tokens, tile_tenant, y, out, in, mt, nt, r0);
+        return;
+    }
+    prefill_big_tile<1, kMergedTile, true>(x, w, packed_by_tenant, alpha_by_tenant, tile_tokens, tile_tenant, y, out, in, mt, nt, 0);
 }
 
 // T: rows of x (its byte offsets and those inside one 256-row band of W must fit 32 bits)
@@ -397,40 +547,48 @@ bool prefill_big_fits(int64_t T, int64_t out, int64_t in) {
            (uint64_t)kBgN * (uint64_t)in * 2 < ((uint64_t)1 << 32);
 }
 
-template <int WM>
-static hipError_t launch_big_t(const uint16_t* x, const uint16_t* w, const uint32_t* const* packed_by_tenant,
-                               const float* alpha_by_tenant, const int32_t* row_token, const int32_t* tile_tenant,
-                               int n_mtiles, int n_ntiles, uint16_t* y, int64_t out, int64_t in, bool halve_last_round,
-                               hipStream_t st) {
-    auto kernel = linear_prefill_big_kernel<WM>;
-    static PerDeviceOnce lds_limit;
+namespace {
+
+// One workgroup per compute unit at a time: when the last round of tiles would keep at most half of the units
+// busy, its tiles are cut in two, which takes little more than half the time of a round.
+hipError_t whole_tiles(int64_t tiles, bool halve_last_round, int64_t* n_full) {
+    *n_full = tiles;
+    if (!halve_last_round) return hipSuccess;
+    int cus = 0;
+    const hipError_t ec = device_cu_count(&cus);
+    if (ec != hipSuccess) return ec;
+    const int64_t r = tiles % cus;
+    if (r != 0 && 2 * r <= cus) *n_full = tiles - r;
+    return hipSuccess;
+}
+
+template <typename Kernel>
+hipError_t launch_tiles(Kernel kernel, PerDeviceOnce& lds_limit, int lds_bytes, int threads, const uint16_t* x, const uint16_t* w,
+                        const uint32_t* const* packed_by_tenant, const float* alpha_by_tenant, const int32_t* row_token,
+                        const int32_t* tile_tenant, int n_mtiles, int n_ntiles, uint16_t* y, int64_t out, int64_t in,
+                        bool halve_last_round, hipStream_t st) {
     const hipError_t ea = lds_limit.run([&] {
         hipFuncAttributes fa;
         const hipError_t e = hipFuncGetAttributes(&fa, (const void*)kernel);
         if (e != hipSuccess) return e;
         if (fa.sharedSizeBytes != 0) return hipErrorInvalidValue;   // the kernel addresses its dynamic LDS from 0
-        return hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kBgLdsBytes);
+        return hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
     });
     if (ea != hipSuccess) return ea;
     const int64_t tiles = (int64_t)n_mtiles * n_ntiles, round = (int64_t)kBgChunk * kBgXcds;
-    // One workgroup per compute unit at a time: when the last round of tiles would keep at most half of the units
-    // busy, its tiles are cut in two (64 token rows each), which takes little more than half the time of a round.
     int64_t n_full = tiles;
-    if (WM == 1 && halve_last_round) {
-        int cus = 0;
-        const hipError_t ec = device_cu_count(&cus);
-        if (ec != hipSuccess) return ec;
-        const int64_t r = tiles % cus;
-        if (r != 0 && 2 * r <= cus) n_full = tiles - r;
-    }
+    const hipError_t ew = whole_tiles(tiles, halve_last_round, &n_full);
+    if (ew != hipSuccess) return ew;
     const int64_t n_virtual = n_full + 2 * (tiles - n_full);
     const unsigned grid = (unsigned)((n_virtual + round - 1) / round * round);   // surplus workgroups return at once
-    hipLaunchKernelGGL(kernel, dim3(grid), dim3(256 * WM), kBgLdsBytes, st, x, w, packed_by_tenant, alpha_by_tenant, row_token,
+    hipLaunchKernelGGL(kernel, dim3(grid), dim3(threads), lds_bytes, st, x, w, packed_by_tenant, alpha_by_tenant, row_token,
                        tile_tenant, y, out, in, n_mtiles, n_ntiles, (int)n_full);
     return hipGetLastError();
 }
 
-// waves: 4 (one wavefront per SIMD) or 8 (two)
+}  // namespace
+
+// waves: 4 (one wavefront per SIMD) or 8 (two); row_token: 128 entries per token tile
 hipError_t launch_linear_prefill_big(const uint16_t* x, const uint16_t* w, const uint32_t* const* packed_by_tenant,
                                      const float* alpha_by_tenant, const int32_t* row_token, const int32_t* tile_tenant,
                                      int n_mtiles, uint16_t* y, int64_t T, int64_t out, int64_t in, int waves, bool halve_last_round,
@@ -439,10 +597,27 @@ hipError_t launch_linear_prefill_big(const uint16_t* x, const uint16_t* w, const
     const int n_ntiles = (int)((out + kBgN - 1) / kBgN);
     const int64_t tiles = (int64_t)n_mtiles * n_ntiles;
     if (tiles < 1 || tiles > (int64_t)1 << 30) return hipErrorInvalidValue;
+    static PerDeviceOnce once4, once8;
     if (waves == 4)
-        return launch_big_t<1>(x, w, packed_by_tenant, alpha_by_tenant, row_token, tile_tenant, n_mtiles, n_ntiles, y, out, in,
-                               halve_last_round, st);
-    return launch_big_t<2>(x, w, packed_by_tenant, alpha_by_tenant, row_token, tile_tenant, n_mtiles, n_ntiles, y, out, in, false, st);
+        return launch_tiles(linear_prefill_big_kernel<1>, once4, kBgLdsBytes, 256, x, w, packed_by_tenant, alpha_by_tenant, row_token,
+                            tile_tenant, n_mtiles, n_ntiles, y, out, in, halve_last_round, st);
+    return launch_tiles(linear_prefill_big_kernel<2>, once8, kBgLdsBytes, 512, x, w, packed_by_tenant, alpha_by_tenant, row_token,
+                        tile_tenant, n_mtiles, n_ntiles, y, out, in, false, st);
+}
+
+// One product on W + alpha S (formed in fp16 on the way to the matrix cores); row_token: kPrefillMergedTile = 256
+// entries per token tile.
+hipError_t launch_linear_prefill_merged(const uint16_t* x, const uint16_t* w, const uint32_t* const* packed_by_tenant,
+                                        const float* alpha_by_tenant, const int32_t* row_token, const int32_t* tile_tenant,
+                                        int n_mtiles, uint16_t* y, int64_t T, int64_t out, int64_t in, bool halve_last_round,
+                                        hipStream_t st) {
+    if (!prefill_big_fits(T, out, in)) return hipErrorInvalidValue;
+    const int n_ntiles = (int)((out + kBgN - 1) / kBgN);
+    const int64_t tiles = (int64_t)n_mtiles * n_ntiles;
+    if (tiles < 1 || tiles > (int64_t)1 << 30) return hipErrorInvalidValue;
+    static PerDeviceOnce once;
+    return launch_tiles(linear_prefill_merged_kernel, once, BgLds<kMergedTile>::kTotal, 256, x, w, packed_by_tenant, alpha_by_tenant,
+                        row_token, tile_tenant, n_mtiles, n_ntiles, y, out, in, halve_last_round, st);
 }
 
 }  // namespace bd

@@ -50,7 +50,8 @@ class TiledProblem(Problem):
         self.ttable = bd.TiledTenantTable([bd.tile_signs(p, out, inn) for p in self.table.packed], self.table.alpha)
 
 
-def check_close(y_gpu: torch.Tensor, y_ref32: np.ndarray, what=""):
+def check_close(y_gpu: torch.Tensor, y_ref32: np.ndarray, what="", elementwise=True):
+    """max |y - y_ref| / max |y_ref| <= REL_TOL, and (elementwise) every element within REL_TOL |y_ref| + 1e-3 rms(y_ref)."""
     y = to_np(y_gpu).astype(np.float64)
     r = y_ref32.astype(np.float64)
     assert y.shape == r.shape, (y.shape, r.shape)
@@ -60,6 +61,8 @@ def check_close(y_gpu: torch.Tensor, y_ref32: np.ndarray, what=""):
     scale = np.max(np.abs(r))
     err = np.max(np.abs(y - r)) / scale
     assert err <= REL_TOL, f"{what}: max rel err {err:.3e} > {REL_TOL}"
+    if not elementwise:
+        return err
     rms = np.sqrt(np.mean(r * r))
     bad = np.abs(y - r) > REL_TOL * np.abs(r) + 1e-3 * rms
     assert not bad.any(), f"{what}: {bad.sum()} elements outside the element-wise bound"

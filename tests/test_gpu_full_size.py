@@ -188,6 +188,14 @@ def test_prefill_8_tenants_x_512_tokens_sampled_rows(ref, name, out, inn):
     _, y32 = ref.linear_multitenant(to_np(x), base_np, packed, alphas, tok)
     err = check_close(y[:, rows.to(DEV)], y32, f"prefill {name}")
     print(f"   max rel err {err:.2e}", flush=True)
+    # the one-product form (W + alpha S rounded to fp16, 256 x 256 tiles) against the oracle's materialised weights
+    y8 = bd.linear_multitenant(x, base, table, tok, variant=8)
+    torch.cuda.synchronize()
+    w_ft = [ref.materialise_f16(base_np, packed[t], alphas[t]) for t in range(B)]
+    _, n32 = ref.linear_naive(to_np(x), w_ft, tok)
+    err8 = check_close(y8[:, rows.to(DEV)], n32, f"prefill {name}, one product")
+    err86 = check_close(y8[:, rows.to(DEV)], y32, f"prefill {name}, one product against the two products", elementwise=False)
+    print(f"   one product: max rel err {err8:.2e} (materialised weights)  {err86:.2e} (two products)", flush=True)
 
 
 @pytest.mark.timeout(900)

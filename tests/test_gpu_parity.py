@@ -150,13 +150,14 @@ PREFILL_CASES = [
     (64, 32, 4, [9, 9, 9, 9]),                   # a single k step
     (520, 192, 3, [40, 3, 90]),                  # three 64-wide steps (odd), three 256-wide N tiles with a ragged one
     (256, 64, 2, [33, 1]),                       # one 64-wide step
+    (300, 320, 4, [257, 512, 130, 128]),         # five steps (odd); tiles of 256 rows: whole ones, short ones, a single row
 ]
 
 
 @pytest.mark.parametrize("case", range(len(PREFILL_CASES)))
 def test_prefill_gemm_matches_oracle(ref, case):
     """More than 32 tokens with a workspace: the library picks one matrix-core GEMM launch or decode launches, whichever
-    its cost model says is quicker; without a workspace: decode launches; variants 4..7 force a GEMM.  Same oracle."""
+    its cost model says is quicker; without a workspace: decode launches; variants 4..8 force a GEMM.  Same oracle."""
     out, inn, nt, counts = PREFILL_CASES[case]
     tok = [t for t, c in enumerate(counts) for _ in range(c)]
     perm = torch.randperm(len(tok), generator=torch.Generator().manual_seed(case)).tolist()
@@ -185,6 +186,16 @@ def test_prefill_gemm_matches_oracle(ref, case):
             by_variant[v] = y5
         # half tiles add up every element in the same order as whole tiles
         assert torch.equal(by_variant[5], by_variant[7])
+        # variant 8: one product on W + alpha S rounded to fp16 -- the naive per-tenant model's arithmetic (the oracle's
+        # materialised fp16 weights through its plain linear); within the same bound of the two-product form as well
+        w_ft = [ref.materialise_f16(prob.w_base_np, prob.packed_np[t], prob.alpha_np[t]) for t in range(nt)]
+        _, n32 = ref.linear_naive(to_np(x), w_ft, tok)
+        y8 = bd.linear_multitenant(x, prob.w_base, prob.table, tok, variant=8)
+        check_close(y8, n32, f"prefill case {case}, one product, against the materialised weights")
+        # (the weights' own fp16 rounding separates it from the two products: the bar on the largest error holds, the
+        # element-wise one is asked against the materialised weights only)
+        check_close(y8, y32, f"prefill case {case}, one product, against the two products", elementwise=False)
+        assert torch.equal(bd.linear_multitenant(x, prob.w_base, prob.table, tok, variant=8), y8)
     else:
         with pytest.raises(bd.BitDeltaError) as e:
             bd.linear_multitenant(x, prob.w_base, prob.table, tok, variant=5)

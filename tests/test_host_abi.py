@@ -47,9 +47,10 @@ def test_workspace_bytes(bd):
     assert bd.workspace_bytes(bd.OP_COMPRESS, 0, 4096, 4096, 1) >= 2048 * 8
     assert bd.workspace_bytes(bd.OP_LINEAR_MULTITENANT, 16, 4096, 4096, 16) == 0
     assert bd.workspace_bytes(bd.OP_LINEAR_MULTITENANT, 32, 4096, 4096, 16) == 0
-    # prefill: (ceil(T / 128) + min(tenants, T)) tiles x 129 ints, rounded up to 256 bytes
-    assert bd.workspace_bytes(bd.OP_LINEAR_MULTITENANT, 4096, 11008, 4096, 8) == (40 * 129 * 4 + 255) // 256 * 256
-    assert bd.workspace_bytes(bd.OP_LINEAR_MULTITENANT, 33, 64, 64, 100) == (34 * 129 * 4 + 255) // 256 * 256
+    # prefill: (ceil(T / rows) + min(tenants, T)) tiles x (rows + 1) ints for token tiles of rows = 128 and of 256 rows
+    # (the one-product form), the larger of the two, rounded up to 256 bytes
+    assert bd.workspace_bytes(bd.OP_LINEAR_MULTITENANT, 4096, 11008, 4096, 8) == (max(40 * 129, 24 * 257) * 4 + 255) // 256 * 256
+    assert bd.workspace_bytes(bd.OP_LINEAR_MULTITENANT, 33, 64, 64, 100) == (max(34 * 129, 34 * 257) * 4 + 255) // 256 * 256
     assert bd.workspace_bytes(bd.OP_PACK_SIGNS, 0, 4096, 4096, 1) == 0
     assert bd.workspace_bytes(bd.OP_COMPRESS, 0, 4096, 4100, 1) == 0   # rejected shape
 
@@ -81,6 +82,14 @@ def test_linear_argument_errors_are_caught_on_the_host(bd):
     fv = L.bd_linear_multitenant_variant
     assert fv(A, 2 * A, 3 * A, 4 * A, _tok(0), 5 * A, 1, 16, 128, 1, 0, 0, 0, 99) == 7
     assert fv(A, 2 * A, 3 * A, 4 * A, _tok(0), 5 * A, 1, 16, 96, 1, 0, 0, 0, 3) == 7
+    # the GEMM variants: one decode launch worth of tokens, no workspace, a reduction length the large tiles cannot run
+    many = _tok(*([0] * 64))
+    for v in (4, 5, 6, 7, 8):
+        assert fv(A, 2 * A, 3 * A, 4 * A, _tok(0), 5 * A, 1, 16, 128, 1, 0, 0, 0, v) == 7
+        assert fv(A, 2 * A, 3 * A, 4 * A, many, 5 * A, 64, 16, 128, 1, 0, 0, 0, v) == 5
+    for v in (5, 6, 7, 8):
+        assert fv(A, 2 * A, 3 * A, 4 * A, many, 5 * A, 64, 16, 96, 1, 6 * A, 1 << 20, 0, v) == 7
+    assert fv(A, 2 * A, 3 * A, 4 * A, many, 5 * A, 64, 16, 128, 1, 6 * A, 1 << 20, 0, 9) == 7
 
 
 def test_compress_and_pack_argument_errors(bd):
