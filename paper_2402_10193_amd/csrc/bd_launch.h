@@ -46,6 +46,8 @@ constexpr int kPrefillTile = 128;   // tile of y: 128 tokens x 128 output featur
 constexpr int kPrefillK = 64;       // reduction elements per step
 struct PrefillMetaChunk { int32_t v[960]; };
 hipError_t launch_prefill_meta(const PrefillMetaChunk& chunk, int32_t* dst, int n, hipStream_t st);
+// the same from runs: triples (first index in dst, first value, n: n > 0 values counting up, n < 0: -n copies), at most 320 per launch
+hipError_t launch_prefill_meta_runs(const PrefillMetaChunk& chunk, int32_t* dst, int n_runs, hipStream_t st);
 // k_planes = 0: one plane per tenant (tables indexed by tenant); k_planes = 1..8: tables indexed by tenant * k_planes +
 // plane.  wscale != nullptr: w is the row-major int8 base ([out, in] bytes) and wscale its per-row scales.
 hipError_t launch_linear_prefill(const uint16_t* x, const void* w, const uint32_t* const* packed_by_tenant,

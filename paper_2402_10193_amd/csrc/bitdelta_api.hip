@@ -14,7 +14,7 @@ namespace {
 using bd::DecodeMeta;
 using bd::kMaxDecodeTokens;
 
-constexpr int kVersion = 218;   // 0.2.18
+constexpr int kVersion = 219;   // 0.2.19
 constexpr int kVariantRowWave = 1;
 constexpr int kVariantRowMajorMfma = 2;   // the matrix-core decode kernel on the row-major tensors (in % 128 == 0)
 constexpr int kVariantPrefillSmall = 4;   // T > 32 with a workspace: the 128 x 128 tile GEMM
@@ -142,12 +142,33 @@ hipError_t run_prefill(const uint16_t* x, const void* w, const uint32_t* const* 
     std::vector<int32_t> all(row_token);
     all.insert(all.end(), tile_tenant.begin(), tile_tenant.end());
     int32_t* dst = (int32_t*)workspace;
-    for (size_t off = 0; off < all.size(); off += 960) {
-        bd::PrefillMetaChunk c;
-        const int n = (int)std::min<size_t>(960, all.size() - off);
-        std::memcpy(c.v, all.data() + off, (size_t)n * sizeof(int32_t));
-        const hipError_t e = bd::launch_prefill_meta(c, dst + off, n, st);
-        if (e != hipSuccess) return e;
+    // The tables as runs of values that count up or repeat (tokens that arrive grouped by tenant: a few runs for the
+    // whole batch), where that takes fewer launches than the values themselves.
+    std::vector<int32_t> runs;   // triples: first index, first value, n (> 0 counting up, < 0 repeated)
+    for (size_t i = 0; i < all.size();) {
+        size_t e = i + 1;
+        const int32_t step = e < all.size() ? all[e] - all[i] : 0;
+        if (step == 0 || step == 1)
+            while (e < all.size() && all[e] - all[e - 1] == step) ++e;
+        runs.insert(runs.end(), {(int32_t)i, all[i], step == 1 ? (int32_t)(e - i) : -(int32_t)(e - i)});
+        i = e;
+    }
+    if ((runs.size() / 3 + 319) / 320 < (all.size() + 959) / 960) {
+        for (size_t off = 0; off < runs.size(); off += 960) {
+            bd::PrefillMetaChunk c;
+            const int n = (int)std::min<size_t>(960, runs.size() - off);
+            std::memcpy(c.v, runs.data() + off, (size_t)n * sizeof(int32_t));
+            const hipError_t e = bd::launch_prefill_meta_runs(c, dst, n / 3, st);
+            if (e != hipSuccess) return e;
+        }
+    } else {
+        for (size_t off = 0; off < all.size(); off += 960) {
+            bd::PrefillMetaChunk c;
+            const int n = (int)std::min<size_t>(960, all.size() - off);
+            std::memcpy(c.v, all.data() + off, (size_t)n * sizeof(int32_t));
+            const hipError_t e = bd::launch_prefill_meta(c, dst + off, n, st);
+            if (e != hipSuccess) return e;
+        }
     }
     if (merged)
         return bd::launch_linear_prefill_merged(x, (const uint16_t*)w, packed_by_tenant, alpha_by_tenant, dst,

@@ -56,6 +56,17 @@ __global__ __launch_bounds__(256) void prefill_meta_kernel(const PrefillMetaChun
     for (int i = threadIdx.x; i < n; i += blockDim.x) dst[i] = c.v[i];
 }
 
+// The same tables written from runs: triple r = (first index, first value, n) stands for n values first, first + 1, ...
+// (n > 0) or -n copies of the value (n < 0).  A batch whose tokens arrive grouped by tenant is a handful of runs.
+__global__ __launch_bounds__(256) void prefill_meta_runs_kernel(const PrefillMetaChunk c, int32_t* __restrict__ dst, const int n_runs) {
+    for (int r = 0; r < n_runs; ++r) {
+        const int first = c.v[3 * r], value = c.v[3 * r + 1], n = c.v[3 * r + 2];
+        const int count = n < 0 ? -n : n;
+        for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < count; i += gridDim.x * blockDim.x)
+            dst[first + i] = n > 0 ? value + i : value;
+    }
+}
+
 typedef _Float16 half2v __attribute__((ext_vector_type(2)));
 constexpr int kPfMaxPlanes = 8;
 
@@ -282,6 +293,11 @@ __global__ __launch_bounds__(256, 2) void linear_prefill_kernel(
 
 hipError_t launch_prefill_meta(const PrefillMetaChunk& chunk, int32_t* dst, int n, hipStream_t st) {
     hipLaunchKernelGGL(prefill_meta_kernel, dim3(1), dim3(256), 0, st, chunk, dst, n);
+    return hipGetLastError();
+}
+
+hipError_t launch_prefill_meta_runs(const PrefillMetaChunk& chunk, int32_t* dst, int n_runs, hipStream_t st) {
+    hipLaunchKernelGGL(prefill_meta_runs_kernel, dim3(8), dim3(256), 0, st, chunk, dst, n_runs);
     return hipGetLastError();
 }
 

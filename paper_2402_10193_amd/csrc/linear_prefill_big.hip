@@ -20,6 +20,9 @@
 // then, so that the first reads of the next step overlap those MFMAs.  The finished tile leaves
 // through LDS as fp16 rows, in 16-byte stores.
 // Used when in % 64 == 0; other shapes take the 128 x 128 kernel.
+// The same tile body also runs the left-hand side of Eq. 6, X (W + alpha S) with the bracket rounded to
+// fp16, as ONE product on tiles of 256 tokens x 256 features (linear_prefill_merged_kernel; the caller
+// asks for it by name): see MERGED at prefill_big_tile.
 #include "bd_device.h"
 #include "bd_launch.h"
 

@@ -202,6 +202,23 @@ def test_prefill_gemm_matches_oracle(ref, case):
         assert e.value.status == 7
 
 
+def test_prefill_token_tables_written_from_runs(ref):
+    """Tokens that arrive grouped by tenant: the library writes the GEMM's token tables from a few runs (values counting
+    up, padding and tenant ids repeated) instead of value by value; a batch with one stray token in the middle mixes both."""
+    out, inn, nt, counts = 300, 512, 5, [70, 1, 0, 129, 300]
+    grouped = [t for t, c in enumerate(counts) for _ in range(c)]
+    stray = list(grouped)
+    stray[100], stray[400] = stray[400], stray[100]
+    prob = Problem(ref, out, inn, nt, tag=("pf", "runs"))
+    for name, tok in (("grouped", grouped), ("one stray pair", stray)):
+        _p(f"prefill tables from runs: {name}, T={len(tok)}")
+        x = prob.x(len(tok))
+        _, y32 = ref.linear_multitenant(to_np(x), prob.w_base_np, prob.packed_np, prob.alpha_np, tok)
+        for v in (4, 5, 8):
+            y = bd.linear_multitenant(x, prob.w_base, prob.table, tok, variant=v)
+            check_close(y, y32, f"tables from runs, {name}, variant {v}", elementwise=v != 8)
+
+
 @pytest.mark.parametrize("variant", VARIANTS)
 def test_linear_special_inputs(ref, variant):
     """alpha = 0, all-ones / all-zero sign words, one-hot x: exact consequences of Eq. 6."""
