@@ -126,7 +126,8 @@ def run_prefill(args, torch, bd, synth, dev, with_variants=False):
         return e0.elapsed_time(e1) / args.steps
     ms = time_steps(args.variant)
     flops = sum(2.0 * 2.0 * T * inn * out for *_, out, inn in mats)      # base + delta products
-    tflops = flops / (ms * 1e-3) / 1e12
+    one_product = args.variant == MERGED_VARIANT                          # asked for by name: its own flops only
+    tflops = (flops / 2 if one_product else flops) / (ms * 1e-3) / 1e12
     # The same two linears as ONE product each on W + alpha S, the sum formed in fp16 on the way to the matrix cores
     # (variant 8): half the flops, and a result that differs from the two-product form by one fp16 rounding per weight.
     ms_m = time_steps(MERGED_VARIANT)
@@ -180,11 +181,14 @@ def run_prefill(args, torch, bd, synth, dev, with_variants=False):
         "config": {"workload": "prefill: 8 tenants x 512 tokens, linears 4096->11008 and 11008->4096 (one step = both)",
                    "tenants": B, "tokens": T},
         "roofline": {"bound": "mfma", "achieved": round(tflops, 1), "peak": MFMA_F16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                     "frac": round(tflops / MFMA_F16_PEAK_TFLOPS, 4), "traffic": None, "kernel": "linear_prefill_big_kernel" if args.variant != 4 else "linear_prefill_kernel",
-                     "flops_per_launch": flops / 2, "avg_launch_us": round(ms * 1e3 / 2, 2),
+                     "frac": round(tflops / MFMA_F16_PEAK_TFLOPS, 4), "traffic": None, "kernel": {4: "linear_prefill_kernel", MERGED_VARIANT: "linear_prefill_merged_kernel"}.get(args.variant, "linear_prefill_big_kernel"),
+                     "flops_per_launch": flops / (4 if one_product else 2), "avg_launch_us": round(ms * 1e3 / 2, 2),
                      # counting only the flops of a dense fine-tuned model (2 T in out per linear): half of the above
-                     "achieved_useful": round(tflops / 2, 1), "frac_useful": round(tflops / 2 / MFMA_F16_PEAK_TFLOPS, 4),
-                     "useful_fraction_note": "half of the flops are the base product, half the +-1 delta product"},
+                     # (all of it for the one-product kernel)
+                     "achieved_useful": round(tflops if one_product else tflops / 2, 1),
+                     "frac_useful": round((tflops if one_product else tflops / 2) / MFMA_F16_PEAK_TFLOPS, 4),
+                     "useful_fraction_note": "one product on W + alpha S" if one_product else
+                                             "half of the flops are the base product, half the +-1 delta product"},
     }
 
 
