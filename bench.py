@@ -135,6 +135,32 @@ def run_prefill(args, torch, bd, synth, dev, with_variants=False):
               "TFLOP/s": round(flops / 2 / (ms_m * 1e-3) / 1e12, 1),
               "frac": round(flops / 2 / (ms_m * 1e-3) / 1e12 / MFMA_F16_PEAK_TFLOPS, 4),
               "note": "one GEMM on W + alpha S (fp16 sum): the flops of a dense fine-tuned model only"}
+    # The same step on the serving layout of the decode path (bd_linear_multitenant_tiled_gemm): one copy of the base and
+    # of every delta for decode and prefill.
+    tiled_mats = []
+    for x, base, table, y, ws, out, inn in mats:
+        ttable = bd.TiledTenantTable([bd.tile_signs(p, out, inn) for p in table.packed], table.alpha)
+        ws_t = bd.new_workspace(bd.workspace_bytes(bd.OP_LINEAR_TILED_GEMM, T, out, inn, B), dev)
+        tiled_mats.append((x, bd.tile_base(base), ttable, y, ws_t, out))
+
+    def time_tiled(one_product):
+        def step():
+            for x, wt, ttable, y, ws_t, out in tiled_mats:
+                bd.linear_multitenant_tiled_gemm(x, wt, out, ttable, tok, one_product=one_product, y=y, workspace=ws_t, tok_array=tok_arr)
+        for _ in range(max(args.warmup, 1)):
+            step()
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(args.steps):
+            step()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / args.steps
+    ms_t2, ms_t1 = time_tiled(False), time_tiled(True)
+    serving_layout = {"two_products_ms_per_step": round(ms_t2, 4), "two_products_TFLOP/s": round(flops / (ms_t2 * 1e-3) / 1e12, 1),
+                      "one_product_ms_per_step": round(ms_t1, 4), "one_product_tokens_per_s": round(T / (ms_t1 * 1e-3), 1),
+                      "note": "bd_linear_multitenant_tiled_gemm: W and signs read from the tiled tensors the decode kernel uses"}
+    del tiled_mats
     variants = None
     if with_variants:
         # the 128 x 128 tile GEMM on the up projection: one plane (variant 4), two planes per tenant, the 8-bit base
@@ -174,6 +200,7 @@ def run_prefill(args, torch, bd, synth, dev, with_variants=False):
     return {
         **({"variants_up_projection": variants} if variants else {}),
         "merged_form": merged,
+        "serving_layout": serving_layout,
         "metric": "prefill tokens/s, fused fp16 base + 1-bit delta linear, 8 tenants x 512 tokens",
         "value": round(T / (ms * 1e-3), 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
@@ -706,7 +733,7 @@ def main():
                                        "TFLOP/s": pf["roofline"]["achieved"], "frac": pf["roofline"]["frac"],
                                        "TFLOP/s_fine_tuned_model_only": pf["roofline"]["achieved_useful"],
                                        "frac_fine_tuned_model_only": pf["roofline"]["frac_useful"],
-                                       "merged_form": pf["merged_form"]}
+                                       "merged_form": pf["merged_form"], "serving_layout": pf["serving_layout"]}
     result["extras"] = extras
 
     # ---- the oracle on the host cores, one layer of the same workload

@@ -57,7 +57,8 @@ typedef enum bd_op {
     BD_OP_PACK_SIGNS = 0,
     BD_OP_COMPRESS = 1,
     BD_OP_LINEAR_MULTITENANT = 2,
-    BD_OP_LINEAR_GEMM = 3            /* bd_linear_multitenant_gemm_kbit / _gemm_q8: the token tables, any T >= 1 */
+    BD_OP_LINEAR_GEMM = 3,           /* bd_linear_multitenant_gemm_kbit / _gemm_q8: the token tables, any T >= 1 */
+    BD_OP_LINEAR_TILED_GEMM = 4      /* bd_linear_multitenant_tiled_gemm: token tables and the tenants' pointer table */
 } bd_op;
 
 /* Text for a status code (static storage, never NULL). */
@@ -213,6 +214,27 @@ bd_status bd_linear_multitenant_tiled(const uint16_t* x_f16, const uint16_t* w_t
                                       uint16_t* y_f16,
                                       int64_t T, int64_t out, int64_t in, int32_t n_tenants,
                                       void* stream);
+
+/* The prefill regime of Sec. 4.3 (many tokens per tenant) on the SAME serving layout, so that one copy of the base and
+ * of every delta serves both decode and prefill: all T tokens (1 <= T <= 65535) in ONE matrix-core GEMM launch, tokens
+ * sorted by tenant and cut into tiles that never mix tenants (as bd_linear_multitenant does with a workspace).
+ *   one_product == 0  Eq. 6 as written: base product and +-1 product in separate binary32 accumulators, alpha applied to
+ *                     the finished sum (128 x 256 tiles; the arithmetic of bd_linear_multitenant's GEMM)
+ *   one_product != 0  its left-hand side, X (W + alpha S) with the bracket rounded once to binary16 (256 x 256 tiles;
+ *                     the arithmetic of variant 8 of bd_linear_multitenant_variant): half the matrix-core work
+ *   tiled_by_tenant   HOST array of n_tenants DEVICE pointers (bd_tile_signs); NULL allowed for tenants without a token
+ *   workspace         bd_workspace_bytes(BD_OP_LINEAR_TILED_GEMM, T, out, in, n_tenants) bytes, 256-byte aligned, device
+ *                     memory: receives the token tables and the pointer table of this call (one call at a time per workspace)
+ * in % 64 == 0 (else BD_ERR_UNSUPPORTED); y must not overlap x or w_tiled.  A batch with few tokens per tenant is
+ * cheaper through bd_linear_multitenant_tiled (a GEMM tile holds one tenant's tokens only).  Asynchronous. */
+bd_status bd_linear_multitenant_tiled_gemm(const uint16_t* x_f16, const uint16_t* w_tiled,
+                                           const uint32_t* const* tiled_by_tenant,
+                                           const float* alpha_by_tenant,
+                                           const int32_t* tenant_of_token,
+                                           uint16_t* y_f16,
+                                           int64_t T, int64_t out, int64_t in, int32_t n_tenants,
+                                           int32_t one_product,
+                                           void* workspace, size_t workspace_bytes, void* stream);
 
 /* Up to 3 linears that read the same activations (q, k, v or gate, up of one decoder layer) in
  * ONE launch: y_m = Eq. 6 with matrix m's base, deltas and scales, for m < n_mats.

@@ -19,14 +19,15 @@ BD_OK = 0
 STATUS_NAMES = {0: "BD_OK", 1: "BD_ERR_NULL", 2: "BD_ERR_SHAPE", 3: "BD_ERR_ALIGN", 4: "BD_ERR_TENANT",
                 5: "BD_ERR_WORKSPACE", 6: "BD_ERR_DEVICE", 7: "BD_ERR_UNSUPPORTED", 8: "BD_ERR_ALIAS",
                 9: "BD_ERR_FORMAT", 10: "BD_ERR_IO", 11: "BD_ERR_TOO_LARGE"}
-OP_PACK_SIGNS, OP_COMPRESS, OP_LINEAR_MULTITENANT, OP_LINEAR_GEMM = 0, 1, 2, 3
+OP_PACK_SIGNS, OP_COMPRESS, OP_LINEAR_MULTITENANT, OP_LINEAR_GEMM, OP_LINEAR_TILED_GEMM = 0, 1, 2, 3, 4
 
 # every symbol include/bitdelta.h declares
 EXPORTS = ["bd_status_string", "bd_version", "bd_workspace_bytes", "bd_pack_signs", "bd_compress", "bd_compress_noalloc", "bd_compress_batch",
            "bd_group_tokens",
            "bd_linear_multitenant", "bd_linear_multitenant_variant", "bd_materialize", "bd_linear_naive",
            "bd_probe_read", "bd_probe_copy", "bd_tiled_base_bytes", "bd_tiled_signs_bytes", "bd_tile_base",
-           "bd_tile_signs", "bd_linear_multitenant_tiled", "bd_linear_multitenant_tiled_group", "bd_compress_iterated",
+           "bd_tile_signs", "bd_linear_multitenant_tiled", "bd_linear_multitenant_tiled_gemm", "bd_linear_multitenant_tiled_group",
+           "bd_compress_iterated",
            "bd_linear_multitenant_tiled_kbit", "bd_linear_multitenant_tiled_group_kbit", "bd_delta_image_bytes",
            "bd_delta_image_build", "bd_delta_image_check", "bd_delta_image_entry", "bd_delta_file_write",
            "bd_delta_file_bytes", "bd_delta_file_read", "bd_delta_upload", "bd_delta_install", "bd_quantize_base_q8",
@@ -81,6 +82,8 @@ def lib() -> ctypes.CDLL:
         pvp, pi64 = ctypes.POINTER(vp), ctypes.POINTER(i64)
         L.bd_linear_multitenant_tiled.argtypes = [vp, vp, pvp, vp, pi, vp, i64, i64, i64, i32, vp]
         L.bd_linear_multitenant_tiled_group.argtypes = [i32, vp, pvp, pvp, pvp, pi, pvp, i64, pi64, i64, i32, vp]
+        L.bd_linear_multitenant_tiled_gemm.argtypes = [vp, vp, pvp, vp, pi, vp, i64, i64, i64, i32, i32, vp, sz, vp]
+        L.bd_linear_multitenant_tiled_gemm.restype = ctypes.c_int
         psz = ctypes.POINTER(sz)
         L.bd_delta_image_bytes.restype = sz
         L.bd_delta_image_bytes.argtypes = [i32, pi64, pi64, i32]
@@ -449,6 +452,26 @@ def linear_multitenant_tiled(x: torch.Tensor, w_tiled: torch.Tensor, out: int, t
     _check(lib().bd_linear_multitenant_tiled(_ptr(x), _ptr(w_tiled), tenants.host_ptrs, _ptr(tenants.alpha), tok,
                                              _ptr(y), T, out, inn, tenants.n_tenants, _stream(stream)),
            "bd_linear_multitenant_tiled")
+    return y
+
+
+def linear_multitenant_tiled_gemm(x: torch.Tensor, w_tiled: torch.Tensor, out: int, tenants: TiledTenantTable,
+                                  tenant_of_token: Sequence[int], one_product: bool = False, y: Optional[torch.Tensor] = None,
+                                  workspace: Optional[torch.Tensor] = None, stream=None, tok_array=None) -> torch.Tensor:
+    """bd_linear_multitenant_tiled_gemm: all tokens in one matrix-core GEMM launch on the serving layout; y fp16 [T, out].
+    workspace: a caller-owned uint8 tensor of bd_workspace_bytes(OP_LINEAR_TILED_GEMM, ...) bytes, or None to allocate one."""
+    _dev(x, torch.float16, "x")
+    _dev(w_tiled, torch.float16, "w_tiled")
+    T, inn = x.shape
+    if y is None:
+        y = torch.empty((T, out), dtype=torch.float16, device=x.device)
+    _dev(y, torch.float16, "y")
+    if workspace is None:
+        workspace = new_workspace(workspace_bytes(OP_LINEAR_TILED_GEMM, T, out, inn, tenants.n_tenants), x.device)
+    tok = tok_array if tok_array is not None else _tok_array(tenant_of_token)
+    _check(lib().bd_linear_multitenant_tiled_gemm(_ptr(x), _ptr(w_tiled), tenants.host_ptrs, _ptr(tenants.alpha), tok, _ptr(y), T,
+                                                  out, inn, tenants.n_tenants, 1 if one_product else 0, _ptr(workspace),
+                                                  workspace.numel(), _stream(stream)), "bd_linear_multitenant_tiled_gemm")
     return y
 
 

@@ -55,19 +55,20 @@ hipError_t launch_linear_prefill(const uint16_t* x, const void* w, const uint32_
                                  const int32_t* tile_tenant, int n_mtiles, uint16_t* y, int64_t out, int64_t in,
                                  int k_planes, hipStream_t st);
 // the 128 x 256 tile GEMM of linear_prefill_big.hip; T = rows of x; halve_last_round (4 wavefronts only): the tiles of a
-// last round that would occupy at most half of the compute units run as two workgroups of 64 token rows each
+// last round that would occupy at most half of the compute units run as two workgroups of 64 token rows each;
+// tiled (4 wavefronts only): w and the tenants' sign tensors are in the serving layout (bd_tile_base / bd_tile_signs)
 bool prefill_big_fits(int64_t T, int64_t out, int64_t in);
 hipError_t launch_linear_prefill_big(const uint16_t* x, const uint16_t* w, const uint32_t* const* packed_by_tenant,
                                      const float* alpha_by_tenant, const int32_t* row_token, const int32_t* tile_tenant,
                                      int n_mtiles, uint16_t* y, int64_t T, int64_t out, int64_t in, int waves, bool halve_last_round,
-                                     hipStream_t st);
+                                     bool tiled, hipStream_t st);
 // the same product as one GEMM on W + alpha S, the sum formed in fp16 on the way to the matrix cores; its token tiles
 // (row_token, tile_tenant) have kPrefillMergedTile rows; halve_last_round: as above, with halves of 128 rows
 constexpr int kPrefillMergedTile = 256;
 hipError_t launch_linear_prefill_merged(const uint16_t* x, const uint16_t* w, const uint32_t* const* packed_by_tenant,
                                         const float* alpha_by_tenant, const int32_t* row_token, const int32_t* tile_tenant,
                                         int n_mtiles, uint16_t* y, int64_t T, int64_t out, int64_t in, bool halve_last_round,
-                                        hipStream_t st);
+                                        bool tiled, hipStream_t st);
 
 // 8-bit round-to-nearest base: q [out, in] int8 and one binary32 scale per row; the compressor against scale * q
 hipError_t launch_quantize_rtn8(const uint16_t* w, int64_t out, int64_t in, int8_t* q, float* scale, hipStream_t st);

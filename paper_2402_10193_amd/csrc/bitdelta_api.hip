@@ -14,7 +14,7 @@ namespace {
 using bd::DecodeMeta;
 using bd::kMaxDecodeTokens;
 
-constexpr int kVersion = 219;   // 0.2.19
+constexpr int kVersion = 220;   // 0.2.20
 constexpr int kVariantRowWave = 1;
 constexpr int kVariantRowMajorMfma = 2;   // the matrix-core decode kernel on the row-major tensors (in % 128 == 0)
 constexpr int kVariantPrefillSmall = 4;   // T > 32 with a workspace: the 128 x 128 tile GEMM
@@ -100,6 +100,7 @@ size_t prefill_workspace_bytes(int64_t T, int32_t n_tenants) {
     if (T <= kMaxDecodeTokens || n_tenants < 0) return 0;
     return prefill_table_bytes(T, n_tenants, true);
 }
+size_t tiled_gemm_workspace_bytes(int64_t T, int32_t n_tenants);
 // The token tables of the GEMM: tiles of 128 rows (merged_too: or of the 256 rows of the one-product form, whichever
 // table is larger); every tenant with a token ends in one partly filled tile at most.
 size_t prefill_table_bytes(int64_t T, int32_t n_tenants, bool merged_too) {
@@ -113,6 +114,13 @@ size_t prefill_table_bytes(int64_t T, int32_t n_tenants, bool merged_too) {
     return (bytes + 255) & ~(size_t)255;
 }
 
+// bd_linear_multitenant_tiled_gemm: the token tables and, behind them, the table of the tenants' sign pointers
+size_t tiled_gemm_workspace_bytes(int64_t T, int32_t n_tenants) {
+    const size_t tables = prefill_table_bytes(T, n_tenants, true);
+    if (tables == 0) return 0;
+    return tables + (((size_t)n_tenants * 8 + 8 + 255) & ~(size_t)255);
+}
+
 // Sorts the tokens by tenant (stable), cuts them into tiles of 128 rows (merged: 256) that never mix tenants, writes
 // the two tables into the workspace (through kernel arguments: no host-to-device copy call) and runs the GEMM.
 // k_planes = 0: one plane per tenant; 1..8: tables indexed by tenant * k_planes + plane.  wscale: the 8-bit base's row
@@ -120,7 +128,8 @@ size_t prefill_table_bytes(int64_t T, int32_t n_tenants, bool merged_too) {
 hipError_t run_prefill(const uint16_t* x, const void* w, const uint32_t* const* packed_by_tenant,
                        const float* alpha_by_tenant, const int32_t* tenant_of_token, uint16_t* y, int64_t T, int64_t out,
                        int64_t in, void* workspace, hipStream_t st, int big_waves, bool halve_last_round,
-                       int k_planes = 0, const float* wscale = nullptr, bool merged = false) {
+                       int k_planes = 0, const float* wscale = nullptr, bool merged = false,
+                       const uint32_t* const* tiled_by_tenant_host = nullptr, int32_t n_tenants = 0) {
     const int64_t tile_rows = merged ? bd::kPrefillMergedTile : bd::kPrefillTile;
     std::vector<int32_t> order((size_t)T);
     for (int64_t i = 0; i < T; ++i) order[(size_t)i] = (int32_t)i;
@@ -141,6 +150,19 @@ hipError_t run_prefill(const uint16_t* x, const void* w, const uint32_t* const* 
     const int n_mtiles = (int)tile_tenant.size();
     std::vector<int32_t> all(row_token);
     all.insert(all.end(), tile_tenant.begin(), tile_tenant.end());
+    // Serving layout: the tenants' sign pointers come as a host array; the GEMM reads them from a device table, which
+    // travels behind the token tables (8-byte aligned).
+    const bool tiled = tiled_by_tenant_host != nullptr;
+    size_t pointer_table_at = 0;
+    if (tiled) {
+        if (all.size() & 1) all.push_back(0);
+        pointer_table_at = all.size();
+        for (int32_t t = 0; t < n_tenants; ++t) {
+            const uint64_t p = (uint64_t)(uintptr_t)tiled_by_tenant_host[t];
+            all.push_back((int32_t)(uint32_t)p);
+            all.push_back((int32_t)(uint32_t)(p >> 32));
+        }
+    }
     int32_t* dst = (int32_t*)workspace;
     // The tables as runs of values that count up or repeat (tokens that arrive grouped by tenant: a few runs for the
     // whole batch), where that takes fewer launches than the values themselves.
@@ -170,12 +192,14 @@ hipError_t run_prefill(const uint16_t* x, const void* w, const uint32_t* const* 
             if (e != hipSuccess) return e;
         }
     }
+    if (tiled) packed_by_tenant = (const uint32_t* const*)(dst + pointer_table_at);
     if (merged)
         return bd::launch_linear_prefill_merged(x, (const uint16_t*)w, packed_by_tenant, alpha_by_tenant, dst,
-                                                dst + row_token.size(), n_mtiles, y, T, out, in, halve_last_round, st);
+                                                dst + row_token.size(), n_mtiles, y, T, out, in, halve_last_round, tiled, st);
     if (big_waves)
         return bd::launch_linear_prefill_big(x, (const uint16_t*)w, packed_by_tenant, alpha_by_tenant, dst,
-                                             dst + row_token.size(), n_mtiles, y, T, out, in, big_waves, halve_last_round, st);
+                                             dst + row_token.size(), n_mtiles, y, T, out, in, big_waves, halve_last_round, tiled, st);
+    if (tiled) return hipErrorInvalidValue;   // the 128 x 128 tiles read the row-major tensors only
     return bd::launch_linear_prefill(x, w, packed_by_tenant, alpha_by_tenant, wscale, dst, dst + row_token.size(), n_mtiles, y,
                                      out, in, k_planes, st);
 }
@@ -254,6 +278,7 @@ size_t bd_workspace_bytes(bd_op op, int64_t T, int64_t out, int64_t in, int32_t 
         case BD_OP_PACK_SIGNS: return 0;
         case BD_OP_LINEAR_MULTITENANT: return prefill_workspace_bytes(T, n_tenants);
         case BD_OP_LINEAR_GEMM: return prefill_table_bytes(T, n_tenants);
+        case BD_OP_LINEAR_TILED_GEMM: return tiled_gemm_workspace_bytes(T, n_tenants);
     }
     return 0;
 }
@@ -701,6 +726,33 @@ bd_status bd_linear_multitenant_tiled(const uint16_t* x_f16, const uint16_t* w_t
                                       int32_t n_tenants, void* stream) {
     return tiled_linear_impl(1, x_f16, &w_tiled, tiled_by_tenant, &alpha_by_tenant, tenant_of_token, &y_f16, T, &out, in,
                              n_tenants, 1, stream, false, nullptr);
+}
+
+bd_status bd_linear_multitenant_tiled_gemm(const uint16_t* x_f16, const uint16_t* w_tiled, const uint32_t* const* tiled_by_tenant,
+                                           const float* alpha_by_tenant, const int32_t* tenant_of_token, uint16_t* y_f16,
+                                           int64_t T, int64_t out, int64_t in, int32_t n_tenants, int32_t one_product,
+                                           void* workspace, size_t workspace_bytes, void* stream) {
+    if (T < 0 || n_tenants < 0 || T > 65535 || !tiled_shape_ok(out, in)) return BD_ERR_SHAPE;
+    if ((uint64_t)T * (uint64_t)in * 2 >= ((uint64_t)1 << 32)) return BD_ERR_SHAPE;   // 32-bit byte offsets into x
+    if (T == 0 || out == 0) return BD_OK;
+    if (!x_f16 || !w_tiled || !tiled_by_tenant || !alpha_by_tenant || !tenant_of_token || !y_f16) return BD_ERR_NULL;
+    if (misaligned(x_f16, 16) || misaligned(w_tiled, 16) || misaligned(y_f16, 2) || misaligned(alpha_by_tenant, 4)) return BD_ERR_ALIGN;
+    for (int64_t t = 0; t < T; ++t) {
+        const int32_t e = tenant_of_token[t];
+        if (e < 0 || e >= n_tenants) return BD_ERR_TENANT;
+        if (!tiled_by_tenant[e]) return BD_ERR_NULL;          // a tenant with a token needs its delta
+        if (misaligned(tiled_by_tenant[e], 16)) return BD_ERR_ALIGN;
+    }
+    const size_t ybytes = (size_t)T * (size_t)out * 2;
+    if (overlaps(y_f16, ybytes, x_f16, (size_t)T * (size_t)in * 2) || overlaps(y_f16, ybytes, w_tiled, bd_tiled_base_bytes(out, in)))
+        return BD_ERR_ALIAS;
+    if (in == 0 || !bd::prefill_big_fits(T, out, in)) return BD_ERR_UNSUPPORTED;   // whole k steps of 64
+    const size_t need = tiled_gemm_workspace_bytes(T, n_tenants);
+    if (!workspace || workspace_bytes < need || misaligned(workspace, 256)) return BD_ERR_WORKSPACE;
+    return run_prefill(x_f16, w_tiled, nullptr, alpha_by_tenant, tenant_of_token, y_f16, T, out, in, workspace, (hipStream_t)stream, 4,
+                       true, 0, nullptr, one_product != 0, tiled_by_tenant, n_tenants) == hipSuccess
+               ? BD_OK
+               : BD_ERR_DEVICE;
 }
 
 bd_status bd_linear_multitenant_tiled_group_kbit(int32_t n_mats, const uint16_t* x_f16, const uint16_t* const* w_tiled,

@@ -73,6 +73,7 @@ __device__ __forceinline__ void bg_barrier() {
 }
 
 typedef const uint32_t __attribute__((address_space(1)))* bg_global_words;
+typedef const uint16_t __attribute__((address_space(1)))* bg_global_halfwords;
 
 // LDS through pointers in the LDS address space, made from byte offsets.  The kernel has no static LDS, so its
 // dynamic LDS starts at address 0 (the host checks that): no instruction is spent on adding the (relocated, zero)
@@ -110,7 +111,10 @@ __device__ __forceinline__ void mfma_in_place(float16v& acc, const half8 a, cons
 // its sign operand to its W operand in fp16 (one rounding per weight: the fine-tuned weight W + alpha S as an fp16
 // model would store it, the left-hand side of Eq. 6) and multiplies once: half the matrix-core work, and a result
 // that differs from the two-product form by that rounding of the weights.
-template <int WM, int TM, bool MERGED>
+// TILED: W and the signs are read from the serving layout of the decode kernel (tiles of 16 rows x 256 k in
+// matrix-core operand order, bd_tile_base / bd_tile_signs): a 16-byte chunk of a row is a 16-byte chunk there too,
+// 2 KiB per row block and step in one piece, and a row's sign bytes of a step are four 2-byte pieces 128 bytes apart.
+template <int WM, int TM, bool MERGED, bool TILED>
 __device__ __forceinline__ void prefill_big_tile(
     const uint16_t* __restrict__ x, const uint16_t* __restrict__ w, const uint32_t* const* __restrict__ packed_by_tenant,
     const float* __restrict__ alpha_by_tenant, const int32_t* __restrict__ tile_tokens, const int32_t* __restrict__ tile_tenant,
@@ -138,6 +142,7 @@ __device__ __forceinline__ void prefill_big_tile(
     constexpr int kBgXPer = TM * 8 / kThreads, kBgWPer = kBgN * 8 / kThreads;   // 16-byte chunks per thread and step
     constexpr int kSets = (WM == 1 && TM <= kBgM) ? 2 : 1;   // (256 rows: the registers hold one set)
     static_assert(!MERGED || WM == 1, "the merged form runs one wavefront per SIMD");
+    static_assert(!TILED || WM == 1, "the tiled sources are written for one row of signs per thread");
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 2, wn = wave & 3;
     const int64_t n0 = (int64_t)nt * kBgN;
@@ -150,12 +155,15 @@ __device__ __forceinline__ void prefill_big_tile(
     // The prologue asks for things in the order in which their addresses become known, so that the trips to memory
     // overlap: W (kernel arguments only), then the tile's tenant and tokens; behind those x, the sign pointer, the signs.
     const unsigned char* const xbase = (const unsigned char*)x;
-    const unsigned char* const wbase = (const unsigned char*)(w + n0 * in);
+    const int64_t k_tiles = (in + 255) >> 8;                       // of the serving layout
+    constexpr int kWStep = TILED ? 2048 : kBgRowBytes;              // bytes a thread's W address advances per step
+    const unsigned char* const wbase = TILED ? (const unsigned char*)w + (n0 >> 4) * k_tiles * 8192 : (const unsigned char*)(w + n0 * in);
     uint32_t xsrc[kBgXPer], wsrc[kBgWPer];
     lds_bytes xdst[kBgXPer], wdst[kBgWPer];   // in buffer 0
     struct Staged {
         u32x4 xg[kBgXPer], wg[kBgWPer];
-        uint32_t s0, s1;
+        uint32_t s0, s1;      // row-major signs: the row's two words of the step
+        uint32_t su[4];       // tiled signs: the 2 bytes (slices 2 (step % 4), + 1) of the row's lanes g = 0..3
     };
     Staged set0, set1;
     const int step_b = 1 < last ? 1 : last;   // what the second set holds first
@@ -163,7 +171,9 @@ __device__ __forceinline__ void prefill_big_tile(
     for (int i = 0; i < kBgWPer; ++i) {
         const int q = tid + kThreads * i, row = q >> 3, c8 = q & 7;
         const int64_t wrow = n0 + row < out ? row : out - 1 - n0;
-        wsrc[i] = (uint32_t)(wrow * in * 2) + c8 * 16;
+        // tiled: row block wrow / 16, slice c8 / 4 of the step's two, lane (wrow % 16, c8 % 4)
+        wsrc[i] = TILED ? (uint32_t)((wrow >> 4) * k_tiles * 8192) + (c8 >> 2) * 1024 + (c8 & 3) * 256 + (uint32_t)(wrow & 15) * 16
+                        : (uint32_t)(wrow * in * 2) + c8 * 16;
         wdst[i] = lds_at(Lds::kWBase + bg_off(row, c8));
         asm volatile("" : "+v"(wdst[i]));   // a register of its own: derived from xdst[i], it would cost an addition per use
         set0.wg[i] = *(const u32x4*)(wbase + wsrc[i]);
@@ -174,7 +184,7 @@ __device__ __forceinline__ void prefill_big_tile(
     for (int i = 0; i < kBgXPer; ++i) tokv[i] = tile_tokens[r0 + ((tid + kThreads * i) >> 3)];
     if (kSets == 2) {
 #pragma unroll
-        for (int i = 0; i < kBgWPer; ++i) set1.wg[i] = *(const u32x4*)(wbase + (int64_t)step_b * kBgRowBytes + wsrc[i]);
+        for (int i = 0; i < kBgWPer; ++i) set1.wg[i] = *(const u32x4*)(wbase + (int64_t)step_b * kWStep + wsrc[i]);
     }
     __builtin_amdgcn_sched_barrier(0);
 
@@ -203,7 +213,19 @@ __device__ __forceinline__ void prefill_big_tile(
     // sign words: 256 threads take a row's two words each, 512 threads one word each
     const int s_row = WM == 1 ? tid : tid >> 1, s_word = WM == 1 ? 0 : tid & 1;
     const int64_t srow = n0 + s_row < out ? n0 + s_row : out - 1;
-    const bg_global_words ssrc = (bg_global_words)(packed_by_tenant[tenant] + srow * words_per_row) + s_word;
+    const uint32_t* const tenant_signs = packed_by_tenant[tenant];
+    const bg_global_words ssrc = (bg_global_words)(tenant_signs + srow * words_per_row) + s_word;
+    const bg_global_halfwords ssrc_tiled = (bg_global_halfwords)((const unsigned char*)tenant_signs + (srow >> 4) * k_tiles * 512 + (srow & 15) * 8);
+    auto fetch_signs = [&](Staged& st, const int step) {
+        if constexpr (TILED) {
+            const int at = (step >> 2) * 256 + (step & 3);   // in 2-byte units: tile step / 4, slices 2 (step % 4), + 1
+#pragma unroll
+            for (int g = 0; g < 4; ++g) st.su[g] = ssrc_tiled[at + g * 64];
+        } else {
+            st.s0 = ssrc[2 * step];
+            if (WM == 1) st.s1 = ssrc[2 * step + 1];
+        }
+    };
 #pragma unroll
     for (int i = 0; i < kBgXPer; ++i) {
         const int q = tid + kThreads * i, row = q >> 3, c8 = q & 7;
@@ -214,12 +236,8 @@ __device__ __forceinline__ void prefill_big_tile(
         set0.xg[i] = *(const u32x4*)(xbase + xsrc[i]);
         if (kSets == 2) set1.xg[i] = *(const u32x4*)(xbase + (int64_t)step_b * kBgRowBytes + xsrc[i]);
     }
-    set0.s0 = ssrc[0];
-    if (WM == 1) set0.s1 = ssrc[1];
-    if (kSets == 2) {
-        set1.s0 = ssrc[2 * step_b];
-        if (WM == 1) set1.s1 = ssrc[2 * step_b + 1];
-    }
+    fetch_signs(set0, 0);
+    if (kSets == 2) fetch_signs(set1, step_b);
 
     const lds_bytes sdst = lds_at(Lds::kSBase + tid * (WM == 1 ? 8 : 4));
     // items: the x chunks, the W chunks, the sign word(s)
@@ -232,16 +250,20 @@ __device__ __forceinline__ void prefill_big_tile(
             st.xg[item] = *(const u32x4*)(xbase + (int64_t)step * kBgRowBytes + xsrc[item]);
         } else if (item < kBgXPer + kBgWPer) {
             asm volatile("" : "+v"(wsrc[item - kBgXPer]));
-            st.wg[item - kBgXPer] = *(const u32x4*)(wbase + (int64_t)step * kBgRowBytes + wsrc[item - kBgXPer]);
+            st.wg[item - kBgXPer] = *(const u32x4*)(wbase + (int64_t)step * kWStep + wsrc[item - kBgXPer]);
         } else {
-            st.s0 = ssrc[2 * step];
-            if (WM == 1) st.s1 = ssrc[2 * step + 1];
+            fetch_signs(st, step);
         }
     };
     auto stage_item = [&](const Staged& st, const int buf, const int item) {
         if (item < kBgXPer) lds_put<u32x4>(xdst[item] + buf * Lds::kXStride, st.xg[item]);
         else if (item < kBgXPer + kBgWPer) lds_put<u32x4>(wdst[item - kBgXPer] + buf * Lds::kWStride, st.wg[item - kBgXPer]);
-        else if (WM == 1) lds_put<u32x2>(sdst + buf * Lds::kSStride, u32x2{st.s0, st.s1});
+        else if (TILED) {
+            // su[g] = (byte of slice v, byte of slice v + 1) of lane g: the row's words are (v: g = 0..3), (v + 1: g = 0..3)
+            const uint32_t lo = st.su[0] | (st.su[1] << 16), hi = st.su[2] | (st.su[3] << 16);
+            lds_put<u32x2>(sdst + buf * Lds::kSStride,
+                           u32x2{__builtin_amdgcn_perm(hi, lo, 0x06040200u), __builtin_amdgcn_perm(hi, lo, 0x07050301u)});
+        } else if (WM == 1) lds_put<u32x2>(sdst + buf * Lds::kSStride, u32x2{st.s0, st.s1});
         else lds_put<uint32_t>(sdst + buf * Lds::kSStride, st.s0);
     };
     auto fetch = [&](Staged& st, const int step) {
@@ -505,7 +527,7 @@ __device__ __forceinline__ bool bg_tile_of_block(const int n_mtiles, const int n
     return true;
 }
 
-template <int WM>
+template <int WM, bool TILED>
 __global__ __launch_bounds__(256 * WM, 1) void linear_prefill_big_kernel(
     const uint16_t* __restrict__ x, const uint16_t* __restrict__ w, const uint32_t* const* __restrict__ packed_by_tenant,
     const float* __restrict__ alpha_by_tenant, const int32_t* __restrict__ row_token, const int32_t* __restrict__ tile_tenant,
@@ -515,12 +537,12 @@ __global__ __launch_bounds__(256 * WM, 1) void linear_prefill_big_kernel(
     const int32_t* const tile_tokens = row_token + mt * kBgM;
     if constexpr (WM == 1) {
         if (half >= 0) {
-            prefill_big_tile<1, kBgM / 2, false>(x, w, packed_by_tenant, alpha_by_tenant, tile_tokens, tile_tenant, y, out, in, mt, nt,
+            prefill_big_tile<1, kBgM / 2, false, TILED>(x, w, packed_by_tenant, alpha_by_tenant, tile_tokens, tile_tenant, y, out, in, mt, nt,
                                                  half * (kBgM / 2));
             return;
         }
     }
-    prefill_big_tile<WM, kBgM, false>(x, w, packed_by_tenant, alpha_by_tenant, tile_tokens, tile_tenant, y, out, in, mt, nt, 0);
+    prefill_big_tile<WM, kBgM, false, TILED>(x, w, packed_by_tenant, alpha_by_tenant, tile_tokens, tile_tenant, y, out, in, mt, nt, 0);
 }
 
 // The merged form on token tiles of 256 rows (row_token holds 256 entries per tile): a wavefront multiplies 256
@@ -528,6 +550,7 @@ __global__ __launch_bounds__(256 * WM, 1) void linear_prefill_big_kernel(
 // most of the time although every such operand costs eight instructions.  A tile whose upper 128 rows are empty (a
 // tenant's last tile; the rows of a tile are filled from the top) runs as 128 rows; the tiles from n_full on run as
 // two workgroups of 128 rows each.
+template <bool TILED>
 __global__ __launch_bounds__(256, 1) void linear_prefill_merged_kernel(
     const uint16_t* __restrict__ x, const uint16_t* __restrict__ w, const uint32_t* const* __restrict__ packed_by_tenant,
     const float* __restrict__ alpha_by_tenant, const int32_t* __restrict__ row_token, const int32_t* __restrict__ tile_tenant,
@@ -538,10 +561,10 @@ __global__ __launch_bounds__(256, 1) void linear_prefill_merged_kernel(
     if (half >= 0 || tile_tokens[kBgM] < 0) {
         const int r0 = half > 0 ? kBgM : 0;
         if (tile_tokens[r0] < 0) return;   // nothing in this half
-        prefill_big_tile<1, kBgM, true>(x, w, packed_by_tenant, alpha_by_tenant, tile_tokens, tile_tenant, y, out, in, mt, nt, r0);
+        prefill_big_tile<1, kBgM, true, TILED>(x, w, packed_by_tenant, alpha_by_tenant, tile_tokens, tile_tenant, y, out, in, mt, nt, r0);
         return;
     }
-    prefill_big_tile<1, kMergedTile, true>(x, w, packed_by_tenant, alpha_by_tenant, tile_tokens, tile_tenant, y, out, in, mt, nt, 0);
+    prefill_big_tile<1, kMergedTile, true, TILED>(x, w, packed_by_tenant, alpha_by_tenant, tile_tokens, tile_tenant, y, out, in, mt, nt, 0);
 }
 
 // T: rows of x (its byte offsets and those inside one 256-row band of W must fit 32 bits)
@@ -591,20 +614,24 @@ hipError_t launch_tiles(Kernel kernel, PerDeviceOnce& lds_limit, int lds_bytes, 
 
 }  // namespace
 
-// waves: 4 (one wavefront per SIMD) or 8 (two); row_token: 128 entries per token tile
+// waves: 4 (one wavefront per SIMD) or 8 (two); row_token: 128 entries per token tile; tiled (4 wavefronts only): w and
+// the tenants' signs in the serving layout
 hipError_t launch_linear_prefill_big(const uint16_t* x, const uint16_t* w, const uint32_t* const* packed_by_tenant,
                                      const float* alpha_by_tenant, const int32_t* row_token, const int32_t* tile_tenant,
                                      int n_mtiles, uint16_t* y, int64_t T, int64_t out, int64_t in, int waves, bool halve_last_round,
-                                     hipStream_t st) {
-    if (!prefill_big_fits(T, out, in) || (waves != 4 && waves != 8)) return hipErrorInvalidValue;
+                                     bool tiled, hipStream_t st) {
+    if (!prefill_big_fits(T, out, in) || (waves != 4 && waves != 8) || (tiled && waves != 4)) return hipErrorInvalidValue;
     const int n_ntiles = (int)((out + kBgN - 1) / kBgN);
     const int64_t tiles = (int64_t)n_mtiles * n_ntiles;
     if (tiles < 1 || tiles > (int64_t)1 << 30) return hipErrorInvalidValue;
-    static PerDeviceOnce once4, once8;
+    static PerDeviceOnce once4, once8, once4t;
+    if (tiled)
+        return launch_tiles(linear_prefill_big_kernel<1, true>, once4t, kBgLdsBytes, 256, x, w, packed_by_tenant, alpha_by_tenant,
+                            row_token, tile_tenant, n_mtiles, n_ntiles, y, out, in, halve_last_round, st);
     if (waves == 4)
-        return launch_tiles(linear_prefill_big_kernel<1>, once4, kBgLdsBytes, 256, x, w, packed_by_tenant, alpha_by_tenant, row_token,
-                            tile_tenant, n_mtiles, n_ntiles, y, out, in, halve_last_round, st);
-    return launch_tiles(linear_prefill_big_kernel<2>, once8, kBgLdsBytes, 512, x, w, packed_by_tenant, alpha_by_tenant, row_token,
+        return launch_tiles(linear_prefill_big_kernel<1, false>, once4, kBgLdsBytes, 256, x, w, packed_by_tenant, alpha_by_tenant,
+                            row_token, tile_tenant, n_mtiles, n_ntiles, y, out, in, halve_last_round, st);
+    return launch_tiles(linear_prefill_big_kernel<2, false>, once8, kBgLdsBytes, 512, x, w, packed_by_tenant, alpha_by_tenant, row_token,
                         tile_tenant, n_mtiles, n_ntiles, y, out, in, false, st);
 }
 
@@ -613,13 +640,16 @@ hipError_t launch_linear_prefill_big(const uint16_t* x, const uint16_t* w, const
 hipError_t launch_linear_prefill_merged(const uint16_t* x, const uint16_t* w, const uint32_t* const* packed_by_tenant,
                                         const float* alpha_by_tenant, const int32_t* row_token, const int32_t* tile_tenant,
                                         int n_mtiles, uint16_t* y, int64_t T, int64_t out, int64_t in, bool halve_last_round,
-                                        hipStream_t st) {
+                                        bool tiled, hipStream_t st) {
     if (!prefill_big_fits(T, out, in)) return hipErrorInvalidValue;
     const int n_ntiles = (int)((out + kBgN - 1) / kBgN);
     const int64_t tiles = (int64_t)n_mtiles * n_ntiles;
     if (tiles < 1 || tiles > (int64_t)1 << 30) return hipErrorInvalidValue;
-    static PerDeviceOnce once;
-    return launch_tiles(linear_prefill_merged_kernel, once, BgLds<kMergedTile>::kTotal, 256, x, w, packed_by_tenant, alpha_by_tenant,
+    static PerDeviceOnce once, once_t;
+    if (tiled)
+        return launch_tiles(linear_prefill_merged_kernel<true>, once_t, BgLds<kMergedTile>::kTotal, 256, x, w, packed_by_tenant,
+                            alpha_by_tenant, row_token, tile_tenant, n_mtiles, n_ntiles, y, out, in, halve_last_round, st);
+    return launch_tiles(linear_prefill_merged_kernel<false>, once, BgLds<kMergedTile>::kTotal, 256, x, w, packed_by_tenant, alpha_by_tenant,
                         row_token, tile_tenant, n_mtiles, n_ntiles, y, out, in, halve_last_round, st);
 }
 

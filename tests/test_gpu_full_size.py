@@ -196,6 +196,11 @@ def test_prefill_8_tenants_x_512_tokens_sampled_rows(ref, name, out, inn):
     err8 = check_close(y8[:, rows.to(DEV)], n32, f"prefill {name}, one product")
     err86 = check_close(y8[:, rows.to(DEV)], y32, f"prefill {name}, one product against the two products", elementwise=False)
     print(f"   one product: max rel err {err8:.2e} (materialised weights)  {err86:.2e} (two products)", flush=True)
+    # the same two launches reading the serving layout: same arithmetic in the same order, so the same bits
+    ttable = bd.TiledTenantTable([bd.tile_signs(p, out, inn) for p in table.packed], table.alpha)
+    w_tiled = bd.tile_base(base)
+    assert torch.equal(bd.linear_multitenant_tiled_gemm(x, w_tiled, out, ttable, tok), y)
+    assert torch.equal(bd.linear_multitenant_tiled_gemm(x, w_tiled, out, ttable, tok, one_product=True), y8)
 
 
 @pytest.mark.timeout(900)

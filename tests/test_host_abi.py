@@ -92,6 +92,32 @@ def test_linear_argument_errors_are_caught_on_the_host(bd):
     assert fv(A, 2 * A, 3 * A, 4 * A, many, 5 * A, 64, 16, 128, 1, 6 * A, 1 << 20, 0, 9) == 7
 
 
+def test_tiled_gemm_argument_errors(bd):
+    """bd_linear_multitenant_tiled_gemm: every error is found on the host before anything is launched."""
+    L = bd.lib()
+    f = L.bd_linear_multitenant_tiled_gemm
+    ptrs = (ctypes.c_void_p * 2)(3 * A, 6 * A)
+    tok = _tok(*([0] * 40))
+    W = 0x100000   # a fake, 256-byte aligned workspace address
+    need = bd.workspace_bytes(bd.OP_LINEAR_TILED_GEMM, 40, 64, 128, 2)
+    # the token tables of either tile height (1 + 2 tiles x 129 ints, or x 257) and the table of 2 pointers
+    assert need == (3 * 257 * 4 + 255) // 256 * 256 + 256
+    assert bd.workspace_bytes(bd.OP_LINEAR_TILED_GEMM, 0, 64, 128, 2) == 0
+
+    def call(x=A, w=2 * A, p=ptrs, al=4 * A, t=tok, y=5 * A, T=40, out=64, inn=128, nt=2, ws=W, nb=need):
+        return f(x, w, p, al, t, y, T, out, inn, nt, 0, ws, nb, 0)
+
+    assert call(inn=100) == 2 and call(T=-1) == 2 and call(T=70000) == 2
+    assert call(x=0) == 1 and call(w=0) == 1 and call(al=0) == 1 and call(y=0) == 1 and call(p=None) == 1
+    assert call(p=(ctypes.c_void_p * 2)(None, 6 * A)) == 1            # tenant 0 has tokens but no delta
+    assert call(x=A + 2) == 3 and call(p=(ctypes.c_void_p * 2)(3 * A + 4, 6 * A)) == 3
+    assert call(t=_tok(*([0] * 39 + [2]))) == 4 and call(t=_tok(*([0] * 39 + [-1]))) == 4
+    assert call(y=A + 64) == 8 and call(y=2 * A + 1024) == 8
+    assert call(inn=96) == 7                                          # no whole step of 64
+    assert call(ws=0, nb=0) == 5 and call(nb=need - 1) == 5 and call(ws=W + 16) == 5
+    assert call(T=0, x=0, y=0) == 0 and call(out=0, w=0, y=0) == 0
+
+
 def test_compress_and_pack_argument_errors(bd):
     L = bd.lib()
     need = bd.workspace_bytes(bd.OP_COMPRESS, 0, 16, 128, 1)
