@@ -569,6 +569,8 @@ def main():
         per = {}
         for name, out, inn in [s for s in shapes if s[0] in ("q", "k", "gate", "down")]:
             mats = [(m[3], m[4]) for L in layers for m in L if m[0] == name and m[3] is not None]
+            if not mats:    # the row-major tensors are kept only with --path rowmajor
+                continue
             for base, table in mats[:2]:
                 bd.linear_multitenant(xs[inn], base, table, tok, y=ys[(name, out)], variant=args.variant, tok_array=tok_arr)
             torch.cuda.synchronize()
