@@ -219,6 +219,46 @@ def test_prefill_token_tables_written_from_runs(ref):
             check_close(y, y32, f"tables from runs, {name}, variant {v}", elementwise=v != 8)
 
 
+def test_one_product_gemm_special_inputs(ref):
+    """Variant 8 on scales and weights at the edges: alpha = 0 (W itself: bit for bit the two-product form), a negative
+    and a large scale, a scale that is not a binary16 number (the kernel rounds it first), one-hot x (the materialised
+    weight itself, exactly), and non-finite weights (they stay where the oracle puts them)."""
+    out, inn, T = 272, 192, 140
+    prob = Problem(ref, out, inn, 1, tag=("pf", "special"))
+    x = prob.x(T)
+    tok = [0] * T
+    packed = prob.table.packed[0]
+
+    def table(alpha):
+        return bd.TenantTable([packed], torch.tensor([alpha], dtype=torch.float32, device=DEV))
+    _p("one product: alpha = 0")
+    y0 = bd.linear_multitenant(x, prob.w_base, table(0.0), tok, variant=8)
+    assert torch.equal(y0, bd.linear_multitenant(x, prob.w_base, table(0.0), tok, variant=5))
+    for alpha in (-0.003, 0.5, 0.0017):                       # 0.0017 is no binary16 number
+        _p(f"one product: alpha = {alpha}")
+        a16 = float(np.float16(alpha))
+        w_ft = ref.materialise_f16(prob.w_base_np, prob.packed_np[0], a16)
+        _, n32 = ref.linear_naive(to_np(x), [w_ft], tok)
+        check_close(bd.linear_multitenant(x, prob.w_base, table(alpha), tok, variant=8), n32, f"alpha {alpha}")
+    _p("one product: one-hot x")
+    xe = torch.zeros((inn, inn), dtype=torch.float16, device=DEV)
+    xe[torch.arange(inn), torch.arange(inn)] = 1.0
+    w_ft = ref.materialise_f16(prob.w_base_np, prob.packed_np[0], prob.alpha_np[0])
+    y = bd.linear_multitenant(xe, prob.w_base, prob.table, [0] * inn, variant=8)
+    assert np.array_equal(to_np(y).view(np.uint16), np.ascontiguousarray(w_ft.T).view(np.uint16))
+    _p("one product: non-finite weights")
+    w = prob.w_base.clone()
+    w[3, 5], w[100, 77], w[271, 191], w[8, 0] = float("inf"), float("-inf"), float("nan"), 6e-8   # and a subnormal
+    w_ft = ref.materialise_f16(to_np(w), prob.packed_np[0], prob.alpha_np[0])
+    _, n32 = ref.linear_naive(to_np(x), [w_ft], tok)
+    y = to_np(bd.linear_multitenant(x, w, prob.table, tok, variant=8)).astype(np.float32)
+    assert np.array_equal(np.isnan(y), np.isnan(n32)) and np.array_equal(np.isinf(y), np.isinf(n32))
+    fin = np.isfinite(n32)
+    assert np.array_equal(np.sign(y[~fin & ~np.isnan(n32)]), np.sign(n32[~fin & ~np.isnan(n32)]))
+    rows = [r for r in range(out) if r not in (3, 100, 271)]
+    check_close(torch.from_numpy(y[:, rows]), n32[:, rows], "rows without non-finite weights")
+
+
 @pytest.mark.parametrize("variant", VARIANTS)
 def test_linear_special_inputs(ref, variant):
     """alpha = 0, all-ones / all-zero sign words, one-hot x: exact consequences of Eq. 6."""
